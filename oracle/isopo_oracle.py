@@ -1,0 +1,279 @@
+"""CPU fp64 oracle for the ISOPO layer step.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain definition of what the layer step computes.
+It is imported by the tests, by the smoke check and by the benchmark's
+cpu_baseline leg, and by nothing else: the product path (the HIP library and
+its binding) never calls it and shares no code with it.
+
+Everything is numpy float64.  Every per-sequence gradient is materialised
+explicitly; there is no blocking, fusion or reordering beyond what the paper's
+definitions state.  Notation follows the paper:
+
+    X      act_in   [N, d_in]     token activations of one linear layer
+    Delta  grad_out [N, d_out]    back-propagated gradient of sum(log_prob)
+    G_i    seq_logprob_grad       = Delta_i^T X_i, shape [d_out, d_in]
+    K      ntk      [m, m]        K = J J^T, J_i = vec(G_i)
+    A      advantages [m]
+    c      per-sequence coefficients applied to the G_i
+
+Pins (tests/test_oracle_pins.py): autograd brute force, the ghost double sum,
+rank-one closed form, unit Fisher norm, the orthogonal-gradient reduction,
+solve residual and the eigendecomposition route, the MinSR property, the
+large-regulariser limit, equivariances, the one-sequence closed form, the
+token-by-token contraction, and duplicate sequences.  Every public function
+below is pinned by at least one of them; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+REG_ABSOLUTE = 0
+REG_REL_TRACE = 1
+
+
+def widen(a) -> np.ndarray:
+    """Exact widening of an input buffer to float64.
+
+    uint16 arrays are taken as bfloat16 bit patterns (the upper half of an
+    IEEE float32); float32/float64 arrays are widened as they are.  No value
+    changes, so input quantisation is never part of an error budget.
+    """
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if a.dtype in (np.float32, np.float64):
+        return a.astype(np.float64)
+    raise TypeError(f"unsupported input dtype {a.dtype}")
+
+
+def check_offsets(seq_offsets, n_tokens: int) -> np.ndarray:
+    off = np.asarray(seq_offsets, dtype=np.int64)
+    if off.ndim != 1 or off.size < 2:
+        raise ValueError("seq_offsets needs at least two entries")
+    if off[0] != 0 or off[-1] != n_tokens or np.any(np.diff(off) < 0):
+        raise ValueError("seq_offsets must start at 0, end at N and be non-decreasing")
+    return off
+
+
+def seq_logprob_grads(X, Delta, seq_offsets, rows=None) -> np.ndarray:
+    """G_i = Delta_i^T X_i for every sequence (non-interacting and interacting
+    listings: `seq_logprob_grad = grad_out.T @ act_in` over one sequence's rows).
+
+    Returns [m, d_out, d_in]; with rows=(r0, r1) only output rows r0:r1 of each
+    G_i are formed, [m, r1-r0, d_in] (used to bound memory on large layers).
+    An empty sequence gives G_i = 0.
+    """
+    X = widen(X)
+    Delta = widen(Delta)
+    off = check_offsets(seq_offsets, X.shape[0])
+    if Delta.shape[0] != X.shape[0]:
+        raise ValueError("X and Delta must have the same number of token rows")
+    r0, r1 = (0, Delta.shape[1]) if rows is None else rows
+    m = off.size - 1
+    G = np.zeros((m, r1 - r0, X.shape[1]), dtype=np.float64)
+    for i in range(m):
+        s, e = off[i], off[i + 1]
+        if e > s:
+            G[i] = Delta[s:e, r0:r1].T @ X[s:e]
+    return G
+
+
+def ntk_from_seq_grads(G) -> np.ndarray:
+    """K_ij = sum(G_i * G_j) for i <= j, mirrored (interacting listing's
+    double loop; K = J J^T of the interacting-variant section)."""
+    m = G.shape[0]
+    K = np.empty((m, m), dtype=np.float64)
+    for i in range(m):
+        for j in range(i, m):
+            K[i, j] = np.sum(G[i] * G[j])
+            K[j, i] = K[i, j]
+    return K
+
+
+def ntk_ghost(X, Delta, seq_offsets) -> np.ndarray:
+    """The same K from the rank-one structure of token gradients
+    (efficient-implementation paragraph: each token gradient is the outer
+    product grad_out[t] act_in[t]^T, so <g^(t), g^(s)> = (x_t.x_s)(d_t.d_s)):
+
+        K_ij = sum_{t in i} sum_{s in j} (x_t . x_s) (delta_t . delta_s).
+
+    No G_i is formed.  Quadratic in N: small inputs only.
+    """
+    X = widen(X)
+    Delta = widen(Delta)
+    off = check_offsets(seq_offsets, X.shape[0])
+    H = (X @ X.T) * (Delta @ Delta.T)
+    m = off.size - 1
+    K = np.zeros((m, m), dtype=np.float64)
+    for i in range(m):
+        for j in range(m):
+            K[i, j] = np.sum(H[off[i]:off[i + 1], off[j]:off[j + 1]])
+    return K
+
+
+def layer_ntk(X, Delta, seq_offsets, chunk_rows=None) -> np.ndarray:
+    """K for one layer.  For large layers the G_i are held d_out-rows-chunk by
+    chunk (all sequences at once) and K accumulates over the chunks; every
+    chunk of every G_i is still materialised."""
+    d_out = np.asarray(Delta).shape[1]
+    if chunk_rows is None or chunk_rows >= d_out:
+        return ntk_from_seq_grads(seq_logprob_grads(X, Delta, seq_offsets))
+    Xw, Dw = widen(X), widen(Delta)
+    m = len(seq_offsets) - 1
+    K = np.zeros((m, m), dtype=np.float64)
+    for r0 in range(0, d_out, chunk_rows):
+        r1 = min(d_out, r0 + chunk_rows)
+        K += ntk_from_seq_grads(seq_logprob_grads(Xw, Dw, seq_offsets, rows=(r0, r1)))
+    return K
+
+
+def ntk_entry(X, Delta, seq_offsets, i: int, j: int) -> float:
+    """One entry K_ij = <G_i, G_j>_F, forming only G_i and G_j."""
+    X = widen(X)
+    Delta = widen(Delta)
+    off = check_offsets(seq_offsets, X.shape[0])
+    Gi = Delta[off[i]:off[i + 1]].T @ X[off[i]:off[i + 1]]
+    Gj = Gi if j == i else Delta[off[j]:off[j + 1]].T @ X[off[j]:off[j + 1]]
+    return float(np.sum(Gi * Gj))
+
+
+def effective_reg(K, lam: float, reg_mode: int = REG_ABSOLUTE) -> float:
+    """The regulariser actually added.  ABSOLUTE: lam itself (the Tikhonov c of
+    v = J^T (K + cI)^-1 A).  REL_TRACE: lam * tr(K)/m, the current batch's
+    mean eigenvalue standing in for the trailing mean the interacting
+    experiment uses (regulariser = factor * E[mean(D)])."""
+    K = np.asarray(K, dtype=np.float64)
+    if reg_mode == REG_ABSOLUTE:
+        return float(lam)
+    if reg_mode == REG_REL_TRACE:
+        return float(lam) * float(np.trace(K)) / K.shape[0]
+    raise ValueError("unknown reg_mode")
+
+
+def fisher_norm_sq(K) -> np.ndarray:
+    """||g_i||_F^2 ~= (1/n) sum_j (g_i . g_j)^2 = (1/m) sum_j K_ij^2
+    (eq. F-norm-basic with v = g_i and the batch's reduced gradients as the
+    samples, j = i included)."""
+    K = np.asarray(K, dtype=np.float64)
+    return np.sum(K * K, axis=1) / K.shape[0]
+
+
+def coeff_fisher(K, A, lam: float, reg_mode: int = REG_ABSOLUTE) -> np.ndarray:
+    """Non-interacting update's coefficients:
+    c_i = A_i / sqrt(||g_i||_F^2 + reg)   (layer-wise update u_l; rescaling()
+    of the non-interacting listing).  A zero denominator (empty sequence with
+    reg = 0) gives c_i = 0 by convention."""
+    A = np.asarray(A, dtype=np.float64)
+    den = fisher_norm_sq(K) + effective_reg(K, lam, reg_mode)
+    c = np.zeros_like(A)
+    nz = den > 0
+    c[nz] = A[nz] / np.sqrt(den[nz])
+    return c
+
+
+def coeff_interacting(K, A, lam: float, reg_mode: int = REG_ABSOLUTE):
+    """Interacting update's coefficients c = (K + reg I)^-1 A, so that
+    v = J^T c (interacting-variant section).  Returns (c, info): info = 0 on
+    success, k > 0 if the k-th leading minor of K + reg I is not positive
+    (no pseudo-inverse, no clamping; c is then NaN)."""
+    K = np.asarray(K, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    m = K.shape[0]
+    M = K + effective_reg(K, lam, reg_mode) * np.eye(m)
+    # Cholesky by the textbook column recurrence, so the failing pivot is known.
+    L = np.zeros_like(M)
+    for k in range(m):
+        d = M[k, k] - np.dot(L[k, :k], L[k, :k])
+        if not d > 0.0:
+            return np.full(m, np.nan), k + 1
+        L[k, k] = np.sqrt(d)
+        for r in range(k + 1, m):
+            L[r, k] = (M[r, k] - np.dot(L[r, :k], L[k, :k])) / L[k, k]
+    y = np.zeros(m)
+    for k in range(m):
+        y[k] = (A[k] - np.dot(L[k, :k], y[:k])) / L[k, k]
+    c = np.zeros(m)
+    for k in range(m - 1, -1, -1):
+        c[k] = (y[k] - np.dot(L[k + 1:, k], c[k + 1:])) / L[k, k]
+    return c, 0
+
+
+def coeff_interacting_eigh(K, A, lam: float, reg_mode: int = REG_ABSOLUTE) -> np.ndarray:
+    """The same coefficients by the route the interacting listing takes:
+    D, U = eigh(K); c = U ((1/(D + reg)) * (U^T A))."""
+    K = np.asarray(K, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    D, U = np.linalg.eigh(K)
+    pre = 1.0 / (D + effective_reg(K, lam, reg_mode))
+    return U @ (pre * (U.T @ A))
+
+
+def weighted_grad(G, c, dW_in=None, beta: float = 0.0) -> np.ndarray:
+    """dW = beta * dW_in + sum_i c_i G_i   (`grad += advantages[i] * scale_i *
+    seq_logprob_grad`; `stack(seq_grads, -1) @ advantages_preconditioned`;
+    `mod.grad += grad`)."""
+    c = np.asarray(c, dtype=np.float64)
+    dW = np.zeros(G.shape[1:], dtype=np.float64)
+    for i in range(G.shape[0]):
+        dW += c[i] * G[i]
+    if dW_in is not None and beta != 0.0:
+        dW += beta * np.asarray(dW_in, dtype=np.float64)
+    return dW
+
+
+def weighted_grad_tokens(X, Delta, seq_offsets, c, rows=None) -> np.ndarray:
+    """The same contraction written over token rows:
+    dW = Delta^T diag(c_tok) X with c_tok[t] = c_{seq(t)}."""
+    X = widen(X)
+    Delta = widen(Delta)
+    off = check_offsets(seq_offsets, X.shape[0])
+    c = np.asarray(c, dtype=np.float64)
+    c_tok = np.repeat(c, np.diff(off))
+    r0, r1 = (0, Delta.shape[1]) if rows is None else rows
+    return (Delta[:, r0:r1] * c_tok[:, None]).T @ X
+
+
+def weighted_grad_entry(X, Delta, seq_offsets, c, o: int, k: int) -> float:
+    """One element dW[o, k] = sum_t c_tok[t] Delta[t, o] X[t, k]."""
+    off = check_offsets(seq_offsets, np.asarray(X).shape[0])
+    c_tok = np.repeat(np.asarray(c, dtype=np.float64), np.diff(off))
+    return float(np.sum(c_tok * widen(np.asarray(Delta)[:, o]) * widen(np.asarray(X)[:, k])))
+
+
+def layer_step(X, Delta, seq_offsets, A, variant: str, lam: float,
+               reg_mode: int = REG_ABSOLUTE, dW_in=None, beta: float = 0.0,
+               chunk_rows=None) -> dict:
+    """The whole layer step: K, c, dW and the plain REINFORCE gradient
+    dW_R = sum_i A_i G_i that ISOPO is compared with.
+
+    variant: "fisher" (non-interacting) or "interacting".
+    With chunk_rows the G_i are held chunk_rows output rows at a time: one
+    sweep accumulates K, a second sweep (after c is known) forms dW.
+    """
+    Xw, Dw = widen(X), widen(Delta)
+    off = check_offsets(seq_offsets, Xw.shape[0])
+    A = np.asarray(A, dtype=np.float64)
+    d_out = Dw.shape[1]
+    step = d_out if chunk_rows is None else int(chunk_rows)
+    K = layer_ntk(Xw, Dw, off, chunk_rows=chunk_rows)
+    info = 0
+    if variant == "fisher":
+        c = coeff_fisher(K, A, lam, reg_mode)
+    elif variant == "interacting":
+        c, info = coeff_interacting(K, A, lam, reg_mode)
+    else:
+        raise ValueError("variant must be 'fisher' or 'interacting'")
+    dW = np.zeros((d_out, Xw.shape[1]), dtype=np.float64)
+    dW_R = np.zeros_like(dW)
+    if info == 0:
+        for r0 in range(0, d_out, step):
+            r1 = min(d_out, r0 + step)
+            G = seq_logprob_grads(Xw, Dw, off, rows=(r0, r1))
+            dW[r0:r1] = weighted_grad(G, c)
+            dW_R[r0:r1] = weighted_grad(G, A)
+        if dW_in is not None and beta != 0.0:
+            dW += beta * np.asarray(dW_in, dtype=np.float64)
+    else:
+        dW[:] = np.nan
+    return {"K": K, "c": c, "info": info, "dW": dW, "dW_reinforce": dW_R,
+            "reg_eff": effective_reg(K, lam, reg_mode)}

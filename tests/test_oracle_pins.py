@@ -1,0 +1,325 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+The paper prints no worked example, so every pin is a hand-worked fixture, a
+closed form, an invariant, brute force or autograd.  Each test is chosen so a
+plausible mistake in the oracle (dropped term, wrong sign or index,
+transposed operand, missing 1/n) fails it.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import isopo_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_layer(rng, lengths, d_in, d_out, sx=1.0, sd=0.1):
+    n = int(np.sum(lengths))
+    X = rng.standard_normal((n, d_in)) * sx
+    D = rng.standard_normal((n, d_out)) * sd
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    return X, D, off
+
+
+def test_hand_worked_fixture():
+    """Hand-derived 2-sequence example: G, K, Fisher norms, both coefficient
+    variants, dW and the REINFORCE gradient."""
+    with open(os.path.join(GOLDEN, "hand_worked_two_sequences.json")) as f:
+        g = json.load(f)
+    X, D, off = np.array(g["X"], float), np.array(g["Delta"], float), g["seq_offsets"]
+    A = np.array(g["A"], float)
+    G = orc.seq_logprob_grads(X, D, off)
+    np.testing.assert_array_equal(G, np.array(g["G"], float))
+    K = orc.ntk_from_seq_grads(G)
+    np.testing.assert_array_equal(K, np.array(g["K"], float))
+    np.testing.assert_allclose(orc.fisher_norm_sq(K), g["fisher_norm_sq"], rtol=1e-15)
+    np.testing.assert_allclose(orc.coeff_fisher(K, A, g["fisher_reg"]), g["c_fisher"], rtol=1e-13)
+    c, info = orc.coeff_interacting(K, A, g["interacting_reg"])
+    assert info == 0
+    np.testing.assert_allclose(c * 69, g["c_interacting_times_69"], rtol=1e-13)
+    np.testing.assert_allclose(orc.weighted_grad(G, c) * 69, g["dW_interacting_times_69"], rtol=1e-13)
+    np.testing.assert_allclose(orc.weighted_grad(G, A), g["dW_reinforce"], rtol=1e-15)
+    step = orc.layer_step(X, D, off, A, "interacting", g["interacting_reg"])
+    np.testing.assert_allclose(step["dW"] * 69, g["dW_interacting_times_69"], rtol=1e-13)
+    np.testing.assert_allclose(step["dW_reinforce"], g["dW_reinforce"], rtol=1e-15)
+
+
+def test_p1_autograd_brute_force():
+    """A tiny softmax policy logits = W x_t: autograd's d/dW of each sequence's
+    summed log-prob equals Delta_i^T X_i with Delta_t = onehot(y_t) - softmax.
+    Pins the per-sequence gradient and its d_out x d_in orientation, then K and
+    the interacting update via autograd Jacobian rows."""
+    torch.manual_seed(0)
+    d_in, d_out = 5, 7
+    lengths = [3, 1, 4]
+    n = sum(lengths)
+    W = torch.randn(d_out, d_in, dtype=torch.float64, requires_grad=True)
+    X = torch.randn(n, d_in, dtype=torch.float64)
+    y = torch.randint(0, d_out, (n,))
+    off = np.concatenate([[0], np.cumsum(lengths)])
+    J = []
+    for i in range(len(lengths)):
+        s, e = off[i], off[i + 1]
+        logp = torch.log_softmax(X[s:e] @ W.T, dim=1)
+        obj = logp[torch.arange(e - s), y[s:e]].sum()
+        (gW,) = torch.autograd.grad(obj, W)
+        J.append(gW.numpy().copy())
+    J = np.stack(J)
+    with torch.no_grad():
+        Delta = (torch.nn.functional.one_hot(y, d_out).double() - torch.softmax(X @ W.T, dim=1)).numpy()
+    G = orc.seq_logprob_grads(X.numpy(), Delta, off)
+    np.testing.assert_allclose(G, J, rtol=1e-12, atol=1e-14)
+    Jm = J.reshape(len(lengths), -1)
+    K = orc.layer_ntk(X.numpy(), Delta, off)
+    np.testing.assert_allclose(K, Jm @ Jm.T, rtol=1e-12)
+    A = np.array([0.5, -1.0, 2.0])
+    lam = 0.3
+    v = Jm.T @ np.linalg.solve(K + lam * np.eye(3), A)      # v = J^T (K + cI)^-1 A
+    step = orc.layer_step(X.numpy(), Delta, off, A, "interacting", lam)
+    np.testing.assert_allclose(step["dW"].ravel(), v, rtol=1e-11)
+
+
+def test_p2_two_formulas_one_K():
+    """Frobenius definition and ghost double sum agree (independent code)."""
+    rng = np.random.default_rng(1)
+    X, D, off = _rand_layer(rng, [5, 1, 9, 0, 3], 11, 6)
+    K1 = orc.layer_ntk(X, D, off)
+    K2 = orc.ntk_ghost(X, D, off)
+    np.testing.assert_allclose(K1, K2, rtol=1e-11, atol=1e-13 * np.abs(K1).max())
+    # chunked accumulation equals the unchunked one
+    np.testing.assert_allclose(orc.layer_ntk(X, D, off, chunk_rows=4), K1, rtol=1e-12)
+    for (i, j) in [(0, 0), (0, 2), (4, 1), (3, 3)]:
+        np.testing.assert_allclose(orc.ntk_entry(X, D, off, i, j), K1[i, j], rtol=1e-12, atol=1e-18)
+
+
+def test_p3_symmetry_psd_diagonal():
+    rng = np.random.default_rng(2)
+    X, D, off = _rand_layer(rng, [4, 7, 2, 6, 3, 5], 8, 9)
+    G = orc.seq_logprob_grads(X, D, off)
+    K = orc.ntk_from_seq_grads(G)
+    assert np.array_equal(K, K.T)
+    assert np.linalg.eigvalsh(K).min() >= -1e-12 * np.trace(K)
+    np.testing.assert_allclose(np.diag(K), [np.sum(g * g) for g in G], rtol=1e-14)
+    # more sequences than parameters: K is rank-deficient but still PSD
+    X, D, off = _rand_layer(rng, [2] * 8, 2, 3)
+    K = orc.layer_ntk(X, D, off)
+    ev = np.linalg.eigvalsh(K)
+    assert ev.min() >= -1e-12 * np.trace(K) and (ev < 1e-10 * ev.max()).sum() >= 2
+
+
+def test_p4_rank_one_closed_form():
+    """Every sequence one token long: K_ij = (x_i . x_j)(delta_i . delta_j)."""
+    rng = np.random.default_rng(3)
+    X, D, off = _rand_layer(rng, [1] * 6, 5, 4)
+    K = orc.layer_ntk(X, D, off)
+    np.testing.assert_allclose(K, (X @ X.T) * (D @ D.T), rtol=1e-12)
+
+
+def test_p5_unit_fisher_norm():
+    """With reg = 0 each rescaled sequence gradient w_i = G_i / F_i has
+    (1/m) sum_j <w_i, G_j>^2 = 1."""
+    rng = np.random.default_rng(4)
+    X, D, off = _rand_layer(rng, [6, 3, 8, 5], 7, 5)
+    G = orc.seq_logprob_grads(X, D, off)
+    K = orc.ntk_from_seq_grads(G)
+    c = orc.coeff_fisher(K, np.ones(4), 0.0)
+    for i in range(4):
+        w = c[i] * G[i]
+        fn = np.mean([np.sum(w * G[j]) ** 2 for j in range(4)])
+        assert abs(fn - 1.0) < 1e-12
+    # the regulariser enters under the square root, added to the squared norm
+    c_reg = orc.coeff_fisher(K, np.ones(4), 2.5)
+    np.testing.assert_allclose(1.0 / c_reg ** 2 - 1.0 / c ** 2, 2.5, rtol=1e-10)
+
+
+def test_p6_orthogonal_reduction():
+    """Exactly orthogonal G_i (each sequence owns a disjoint block of input
+    channels): K is diagonal; at reg 0 c_fisher = sqrt(m) c_interacting; for
+    reg > 0 the interacting coefficients are A_i / (k_i + reg)."""
+    rng = np.random.default_rng(5)
+    m, blk, d_out = 4, 3, 5
+    lengths = [3, 5, 2, 4]
+    X, D, off = _rand_layer(rng, lengths, m * blk, d_out)
+    for i in range(m):
+        mask = np.zeros(m * blk)
+        mask[i * blk:(i + 1) * blk] = 1.0
+        X[off[i]:off[i + 1]] *= mask
+    K = orc.layer_ntk(X, D, off)
+    assert np.abs(K - np.diag(np.diag(K))).max() == 0.0
+    A = rng.standard_normal(m)
+    cf = orc.coeff_fisher(K, A, 0.0)
+    ci, info = orc.coeff_interacting(K, A, 0.0)
+    assert info == 0
+    np.testing.assert_allclose(cf, np.sqrt(m) * ci, rtol=1e-12)
+    lam = 0.7
+    ci, _ = orc.coeff_interacting(K, A, lam)
+    np.testing.assert_allclose(ci, A / (np.diag(K) + lam), rtol=1e-12)
+    np.testing.assert_allclose(orc.coeff_fisher(K, A, lam), A / np.sqrt(np.diag(K) ** 2 / m + lam), rtol=1e-12)
+
+
+def test_p7_solve_residual_and_eigh_route():
+    rng = np.random.default_rng(6)
+    X, D, off = _rand_layer(rng, [4, 6, 3, 7, 5], 6, 6)
+    K = orc.layer_ntk(X, D, off)
+    A = rng.standard_normal(5)
+    for lam, mode in [(1e-3, orc.REG_ABSOLUTE), (0.5, orc.REG_REL_TRACE)]:
+        c, info = orc.coeff_interacting(K, A, lam, mode)
+        assert info == 0
+        le = orc.effective_reg(K, lam, mode)
+        r = (K + le * np.eye(5)) @ c - A
+        assert np.linalg.norm(r) <= 1e-12 * np.linalg.norm(A) * np.linalg.cond(K + le * np.eye(5))
+        np.testing.assert_allclose(c, orc.coeff_interacting_eigh(K, A, lam, mode), rtol=1e-9)
+    assert orc.effective_reg(K, 0.5, orc.REG_REL_TRACE) == pytest.approx(0.5 * np.trace(K) / 5)
+
+
+def test_p8_minsr_property():
+    """<dW, G_i> = (K c)_i = A_i - reg c_i."""
+    rng = np.random.default_rng(7)
+    X, D, off = _rand_layer(rng, [5, 4, 6], 9, 8)
+    A = rng.standard_normal(3)
+    lam = 0.01
+    step = orc.layer_step(X, D, off, A, "interacting", lam)
+    G = orc.seq_logprob_grads(X, D, off)
+    lhs = np.array([np.sum(step["dW"] * G[i]) for i in range(3)])
+    np.testing.assert_allclose(lhs, A - lam * step["c"], rtol=1e-10)
+
+
+def test_p9_large_reg_limit_is_reinforce():
+    rng = np.random.default_rng(8)
+    X, D, off = _rand_layer(rng, [5, 4, 6, 2], 7, 6)
+    A = rng.standard_normal(4)
+    K = orc.layer_ntk(X, D, off)
+    lam = 1e9 * np.linalg.norm(K, 2)
+    step = orc.layer_step(X, D, off, A, "interacting", lam)
+    np.testing.assert_allclose(lam * step["dW"], step["dW_reinforce"], rtol=1e-8)
+    G = orc.seq_logprob_grads(X, D, off)
+    np.testing.assert_allclose(step["dW_reinforce"], sum(A[i] * G[i] for i in range(4)), rtol=1e-13)
+
+
+def test_p10_equivariances():
+    rng = np.random.default_rng(9)
+    lengths = [4, 6, 3, 5]
+    X, D, off = _rand_layer(rng, lengths, 6, 5)
+    A = rng.standard_normal(4)
+    base = {v: orc.layer_step(X, D, off, A, v, 0.05) for v in ("fisher", "interacting")}
+    # permute sequences
+    perm = [2, 0, 3, 1]
+    Xp = np.concatenate([X[off[i]:off[i + 1]] for i in perm])
+    Dp = np.concatenate([D[off[i]:off[i + 1]] for i in perm])
+    offp = np.concatenate([[0], np.cumsum([lengths[i] for i in perm])])
+    for v in base:
+        s = orc.layer_step(Xp, Dp, offp, A[perm], v, 0.05)
+        np.testing.assert_allclose(s["K"], base[v]["K"][np.ix_(perm, perm)], rtol=1e-12)
+        np.testing.assert_allclose(s["c"], base[v]["c"][perm], rtol=1e-10)
+        np.testing.assert_allclose(s["dW"], base[v]["dW"], rtol=1e-10, atol=1e-14)
+    # permute tokens inside a sequence
+    Xq, Dq = X.copy(), D.copy()
+    idx = off[1] + rng.permutation(lengths[1])
+    Xq[off[1]:off[2]], Dq[off[1]:off[2]] = X[idx], D[idx]
+    np.testing.assert_allclose(orc.layer_ntk(Xq, Dq, off), base["fisher"]["K"], rtol=1e-12)
+    # scaling Delta by alpha: K scales by alpha^2, dW by 1/alpha (reg 0)
+    alpha = 3.0
+    for v in base:
+        s0 = orc.layer_step(X, D, off, A, v, 0.0)
+        s1 = orc.layer_step(X, alpha * D, off, A, v, 0.0)
+        np.testing.assert_allclose(s1["K"], alpha ** 2 * s0["K"], rtol=1e-12)
+        np.testing.assert_allclose(s1["dW"], s0["dW"] / alpha, rtol=1e-9, atol=1e-13)
+    # splitting a sequence: G_i = G_i' + G_i''
+    off_split = np.array([0, 4, 7, 10, 13, 18])
+    Ks = orc.layer_ntk(X, D, off_split)
+    K = base["fisher"]["K"]
+    assert Ks[1, 1] + 2 * Ks[1, 2] + Ks[2, 2] == pytest.approx(K[1, 1], rel=1e-12)
+    assert Ks[0, 1] + Ks[0, 2] == pytest.approx(K[0, 1], rel=1e-10)
+
+
+def test_p11_single_sequence_closed_form():
+    rng = np.random.default_rng(10)
+    X, D, off = _rand_layer(rng, [7], 5, 4)
+    G = D.T @ X
+    g2 = np.sum(G * G)
+    a, lam = -1.3, 0.2
+    s = orc.layer_step(X, D, off, np.array([a]), "interacting", lam)
+    np.testing.assert_allclose(s["dW"], a * G / (g2 + lam), rtol=1e-12)
+    s = orc.layer_step(X, D, off, np.array([a]), "fisher", lam)
+    np.testing.assert_allclose(s["dW"], a * G / np.sqrt(g2 ** 2 + lam), rtol=1e-12)
+
+
+def test_p12_weighted_grad_two_ways():
+    rng = np.random.default_rng(11)
+    X, D, off = _rand_layer(rng, [3, 0, 5, 4], 6, 7)
+    c = rng.standard_normal(4)
+    G = orc.seq_logprob_grads(X, D, off)
+    dW = orc.weighted_grad(G, c)
+    np.testing.assert_allclose(orc.weighted_grad_tokens(X, D, off, c), dW, rtol=1e-12, atol=1e-15)
+    brute = np.zeros((7, 6))
+    for i in range(4):
+        for t in range(off[i], off[i + 1]):
+            brute += c[i] * np.outer(D[t], X[t])
+    np.testing.assert_allclose(dW, brute, rtol=1e-12, atol=1e-15)
+    assert orc.weighted_grad_entry(X, D, off, c, 2, 3) == pytest.approx(dW[2, 3], rel=1e-12)
+    np.testing.assert_allclose(orc.weighted_grad_tokens(X, D, off, c, rows=(2, 5)), dW[2:5], rtol=1e-12, atol=1e-15)
+    dW0 = rng.standard_normal((7, 6))
+    np.testing.assert_allclose(orc.weighted_grad(G, c, dW0, 0.5), dW + 0.5 * dW0, rtol=1e-13)
+
+
+def test_p13_interacting_listing_in_torch():
+    """The interacting hook restated with torch fp64 ops (per-sequence
+    grad_out.T @ act_in, pairwise sums, eigh, stack @ coefficients) and the
+    non-interacting update with the reduced-gradient Fisher estimate."""
+    rng = np.random.default_rng(12)
+    lengths = [32] * 4
+    X, D, off = _rand_layer(rng, lengths, 64, 128, sd=1e-2)
+    A = rng.standard_normal(4)
+    reg = 1e-3
+    Xt, Dt, At = torch.from_numpy(X), torch.from_numpy(D), torch.from_numpy(A)
+    grads = [Dt[off[i]:off[i + 1]].T @ Xt[off[i]:off[i + 1]] for i in range(4)]
+    ntk = torch.tensor([[torch.sum(gi * gj).item() for gj in grads] for gi in grads], dtype=torch.float64)
+    ev, U = torch.linalg.eigh(ntk)
+    coef = U @ ((1.0 / (ev + reg)) * (U.T @ At))
+    upd = torch.stack(grads, dim=-1) @ coef
+    s = orc.layer_step(X, D, off, A, "interacting", reg)
+    np.testing.assert_allclose(s["K"], ntk.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(s["dW"], upd.numpy(), rtol=1e-8, atol=1e-12)
+    upd = sum(At[i] * grads[i] / torch.sqrt(torch.mean(ntk[i] ** 2) + reg) for i in range(4))
+    s = orc.layer_step(X, D, off, A, "fisher", reg)
+    np.testing.assert_allclose(s["dW"], upd.numpy(), rtol=1e-11, atol=1e-14)
+
+
+def test_p14_duplicate_sequences_and_not_pd():
+    rng = np.random.default_rng(13)
+    X, D, off = _rand_layer(rng, [4, 4, 5], 6, 5)
+    X[4:8], D[4:8] = X[0:4], D[0:4]
+    K = orc.layer_ntk(X, D, off)
+    A = np.array([1.0, -0.5, 0.3])
+    lam = 0.1
+    c, info = orc.coeff_interacting(K, A, lam)
+    assert info == 0 and np.all(np.isfinite(c))
+    assert c[0] - c[1] == pytest.approx((A[0] - A[1]) / lam, rel=1e-9)
+    # singular K with reg 0: the second pivot is not positive -> reported, not clamped
+    Kd = np.array([[4.0, 2.0, 0.0], [2.0, 1.0, 0.0], [0.0, 0.0, 1.0]])
+    c, info = orc.coeff_interacting(Kd, A, 0.0)
+    assert info == 2 and np.all(np.isnan(c))
+    c, info = orc.coeff_interacting(-np.eye(3), A, 0.5)
+    assert info == 1
+    # an empty sequence with reg 0 in the fisher variant gives c_i = 0, not inf
+    X, D, off = _rand_layer(rng, [3, 0, 4], 5, 4)
+    K = orc.layer_ntk(X, D, off)
+    assert np.all(K[1] == 0) and np.all(K[:, 1] == 0)
+    c = orc.coeff_fisher(K, np.ones(3), 0.0)
+    assert c[1] == 0.0 and np.all(np.isfinite(c))
+
+
+def test_widen_bf16_bits_exact():
+    x = torch.randn(257, dtype=torch.float32).to(torch.bfloat16)
+    bits = x.view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(orc.widen(bits), x.to(torch.float64).numpy())
+    with pytest.raises(TypeError):
+        orc.widen(np.zeros(3, dtype=np.int32))
+    with pytest.raises(ValueError):
+        orc.check_offsets([0, 3, 2, 5], 5)
+    with pytest.raises(ValueError):
+        orc.check_offsets([1, 5], 5)
