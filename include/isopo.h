@@ -1,0 +1,143 @@
+/*
+ * isopo.h - C ABI of the MI355X (gfx950) ISOPO layer-step library.
+ *
+ * One linear layer of a policy network sees, per microbatch, token activations
+ * X = act_in [N, d_in] and back-propagated output gradients Delta = grad_out
+ * [N, d_out] of sum(log_prob), grouped into m = n_seq contiguous sequences.
+ * The per-sequence log-probability gradient is G_i = Delta_i^T X_i
+ * [d_out, d_in] (both hook listings: `grad_out.T @ act_in`).  The layer step is
+ *
+ *   1. isopo_layer_gram     K_ij = <G_i, G_j>_F          (K = J J^T, interacting-
+ *                                                         variant section)
+ *   2. isopo_transform      c from K and the advantages A: Fisher-normalised
+ *                           (non-interacting update u_l with eq. F-norm-basic)
+ *                           or c = (K + reg I)^-1 A (interacting update)
+ *   3. isopo_weighted_grad  dW = beta dW + sum_i c_i G_i
+ *                              = beta dW + Delta^T diag(c_tok) X
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless the name ends in _host.
+ *     The caller owns every buffer; the library never allocates or frees
+ *     device memory and never synchronises the stream or the device.
+ *   - Matrices are dense row-major.  X, Delta are fp32 or bf16 (isopo_dtype);
+ *     K, A, c, dW are fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     all work is enqueued on it in order.
+ *   - Errors a host check can see return a non-zero isopo_status and enqueue
+ *     nothing.  Conditions only the device can see are reported through
+ *     info_dev (isopo_transform).
+ *   - d_in and d_out must be multiples of 8 (bf16) or 4 (fp32) so token rows
+ *     are 16-byte aligned; X, Delta, stash and workspace pointers must be
+ *     16-byte aligned (256 for workspace).
+ *   - n_seq <= ISOPO_MAX_SEQ.  A zero-length sequence is legal: its G_i is 0,
+ *     its row and column of K are 0.
+ */
+#ifndef ISOPO_H
+#define ISOPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ISOPO_MAX_SEQ 1024
+
+typedef enum {
+  ISOPO_OK = 0,
+  ISOPO_ERR_INVALID_ARG = 1,        /* null pointer, non-positive size, bad enum, misalignment */
+  ISOPO_ERR_BAD_OFFSETS = 2,        /* host offsets not 0-based, not non-decreasing or not ending at n_tokens */
+  ISOPO_ERR_UNSUPPORTED = 3,        /* dtype / shape the kernels do not cover */
+  ISOPO_ERR_WORKSPACE_TOO_SMALL = 4,
+  ISOPO_ERR_HIP = 5                 /* a HIP launch or query failed */
+} isopo_status;
+
+typedef enum { ISOPO_F32 = 0, ISOPO_BF16 = 1 } isopo_dtype;
+
+/* How K is formed.  GHOST: K_ij = sum_{t in i, s in j} (x_t.x_s)(delta_t.delta_s),
+ * from the rank-one structure of token gradients (efficient-implementation
+ * paragraph); no G_i exists.  MATERIALISED: every G_i is written to a stash and
+ * K is its Gram matrix (interacting listing).  AUTO lets the cost model pick. */
+typedef enum { ISOPO_GRAM_AUTO = 0, ISOPO_GRAM_GHOST = 1, ISOPO_GRAM_MATERIALISED = 2 } isopo_gram_path;
+
+typedef enum {
+  ISOPO_VARIANT_FISHER = 0,         /* c_i = A_i / sqrt((1/m) sum_j K_ij^2 + reg) */
+  ISOPO_VARIANT_INTERACTING = 1     /* c = (K + reg I)^-1 A */
+} isopo_variant;
+
+typedef enum {
+  ISOPO_REG_ABSOLUTE = 0,           /* reg = lambda (the Tikhonov constant as printed) */
+  ISOPO_REG_REL_TRACE = 1           /* reg = lambda * tr(K)/m (relative to the mean eigenvalue,
+                                       as the interacting experiment's regulariser is) */
+} isopo_reg_mode;
+
+/* One ragged layer problem.  All pointers caller-owned. */
+typedef struct {
+  const void* X;                    /* device [n_tokens, d_in]  */
+  const void* Delta;                /* device [n_tokens, d_out] */
+  isopo_dtype dtype;                /* of X and Delta */
+  int64_t n_tokens;                 /* N, < 2^31 */
+  int32_t d_in, d_out, n_seq;
+  const int32_t* seq_offsets_dev;   /* device [n_seq+1]: 0 = off[0] <= ... <= off[n_seq] = n_tokens */
+  const int32_t* seq_offsets_host;  /* the same values on the host (validation, path choice, grid sizing) */
+} isopo_layer;
+
+/* What isopo_layer_gram would do for `requested` and how much workspace it
+ * wants.  Pure host function.
+ *   *chosen       the path taken (never AUTO)
+ *   *ws_full      bytes that hold the whole stash [n_seq, d_out, d_in] (needed for keep_stash)
+ *   *ws_min       the smallest workspace the call accepts (the stash is then
+ *                 formed and consumed in chunks of output rows)
+ * Any out pointer may be NULL. */
+isopo_status isopo_layer_gram_plan(const isopo_layer* layer, isopo_gram_path requested,
+                                   isopo_gram_path* chosen, size_t* ws_full, size_t* ws_min);
+
+/* Modelled cost (seconds on one MI355X) of forming K by each path; the AUTO
+ * choice is the smaller.  Pure host function; exposed for tests. */
+isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, double* t_materialised);
+
+/* K [n_seq, n_seq] fp32, both triangles written, bit-symmetric.
+ *   workspace/ws_bytes  device scratch, >= ws_min of the plan.
+ *   keep_stash          non-zero: leave the per-sequence gradients in the
+ *                       workspace, starting at its first byte, as
+ *                       [n_seq, d_out, d_in] in the stash dtype (bf16 for bf16
+ *                       inputs, fp32 for fp32 inputs), for isopo_weighted_grad.
+ *                       Needs ws_bytes >= ws_full and the MATERIALISED path
+ *                       (forced, or AUTO resolving to it); otherwise
+ *                       ISOPO_ERR_WORKSPACE_TOO_SMALL / ISOPO_ERR_INVALID_ARG. */
+isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, float* K,
+                              void* workspace, size_t ws_bytes, int keep_stash, void* stream);
+
+/* Bytes of device workspace isopo_transform needs (0 for n_seq <= 128). */
+size_t isopo_transform_workspace(int32_t n_seq, int32_t batch);
+
+/* Coefficients from K and A, for `batch` independent problems laid out
+ * back to back: K [batch, n_seq, n_seq], A [batch, n_seq] -> c [batch, n_seq].
+ *   info_dev  device int32 [batch] or NULL.  0: ok.  k > 0 (INTERACTING only):
+ *             the k-th pivot of K + reg I was not positive; c of that problem
+ *             is then filled with NaN.  FISHER: a zero denominator gives
+ *             c_i = 0. */
+isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int32_t batch,
+                             isopo_variant variant, float lambda, isopo_reg_mode reg_mode,
+                             float* c, int32_t* info_dev, void* workspace, size_t ws_bytes,
+                             void* stream);
+
+/* dW [d_out, d_in] fp32 = beta * dW + sum_i c_i G_i.
+ *   stash  NULL: contract X and Delta again, dW = Delta^T diag(c_tok) X (with
+ *          c = A this is the plain REINFORCE gradient).  bf16 inputs: the
+ *          scaled rows c_tok[t] * Delta[t,:] are rounded to bf16 before the
+ *          MFMA, as a bf16 pre-scaling of Delta would.
+ *          non-NULL: the stash isopo_layer_gram left (keep_stash), read once. */
+isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash,
+                                 float beta, float* dW, void* stream);
+
+const char* isopo_status_string(isopo_status s);
+
+/* Library version, "major.minor". */
+const char* isopo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ISOPO_H */

@@ -128,12 +128,13 @@ def layer_ntk(X, Delta, seq_offsets, chunk_rows=None) -> np.ndarray:
 
 
 def ntk_entry(X, Delta, seq_offsets, i: int, j: int) -> float:
-    """One entry K_ij = <G_i, G_j>_F, forming only G_i and G_j."""
-    X = widen(X)
-    Delta = widen(Delta)
+    """One entry K_ij = <G_i, G_j>_F, forming only G_i and G_j (only the rows
+    of the two sequences are widened)."""
+    X = np.asarray(X)
+    Delta = np.asarray(Delta)
     off = check_offsets(seq_offsets, X.shape[0])
-    Gi = Delta[off[i]:off[i + 1]].T @ X[off[i]:off[i + 1]]
-    Gj = Gi if j == i else Delta[off[j]:off[j + 1]].T @ X[off[j]:off[j + 1]]
+    Gi = widen(Delta[off[i]:off[i + 1]]).T @ widen(X[off[i]:off[i + 1]])
+    Gj = Gi if j == i else widen(Delta[off[j]:off[j + 1]]).T @ widen(X[off[j]:off[j + 1]])
     return float(np.sum(Gi * Gj))
 
 

@@ -1,0 +1,259 @@
+// C ABI of the ISOPO layer-step library: argument checks, the Gram-path cost
+// model, workspace layout and kernel sequencing.  No arithmetic of the method
+// lives here; every step runs in the kernels.
+#include "../../include/isopo.h"
+
+#include <cstdlib>
+#include <cstring>
+
+#include "kernels.h"
+
+namespace {
+
+using namespace isopo;
+
+constexpr size_t kAlign = 256;
+constexpr int kTileRows = 256;        // output rows per tile of the contraction kernel
+constexpr int kMaterialisedMaxSeq = 128;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t elem_size(isopo_dtype t) { return t == ISOPO_BF16 ? 2 : 4; }
+
+isopo_status check_layer(const isopo_layer* l, bool need_dev) {
+  if (!l) return ISOPO_ERR_INVALID_ARG;
+  if (l->dtype != ISOPO_F32 && l->dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  if (l->d_in <= 0 || l->d_out <= 0 || l->n_seq <= 0 || l->n_tokens < 0) return ISOPO_ERR_INVALID_ARG;
+  if (l->n_tokens >= (int64_t)1 << 31) return ISOPO_ERR_UNSUPPORTED;
+  if (l->n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  const int vec = l->dtype == ISOPO_BF16 ? 8 : 4;
+  if (l->d_in % vec || l->d_out % vec) return ISOPO_ERR_UNSUPPORTED;
+  if (!l->seq_offsets_host) return ISOPO_ERR_INVALID_ARG;
+  const int32_t* off = l->seq_offsets_host;
+  if (off[0] != 0 || off[l->n_seq] != l->n_tokens) return ISOPO_ERR_BAD_OFFSETS;
+  for (int i = 0; i < l->n_seq; ++i)
+    if (off[i + 1] < off[i]) return ISOPO_ERR_BAD_OFFSETS;
+  if (need_dev) {
+    if (!l->seq_offsets_dev) return ISOPO_ERR_INVALID_ARG;
+    if (l->n_tokens > 0 && (!l->X || !l->Delta)) return ISOPO_ERR_INVALID_ARG;
+    if (!aligned16(l->X) || !aligned16(l->Delta)) return ISOPO_ERR_INVALID_ARG;
+  }
+  return ISOPO_OK;
+}
+
+// Rates of this library's own kernels on one MI355X, used only to rank the two
+// Gram paths.  The materialised path runs the tiled MFMA contraction once and
+// then streams the stash (one write, one read); the ghost path is two
+// token-by-token Gram matrices whose fragments come straight from cache.
+constexpr double kRateContraction = 6.0e14;   // flop/s, per-sequence gradient kernel
+constexpr double kRateGhost = 1.2e14;         // flop/s, ghost kernel
+constexpr double kRateStash = 3.0e12;         // B/s, stash write / read
+constexpr double kLaunch = 6.0e-6;            // s per kernel launch in the chain
+
+void cost_model(const isopo_layer* l, double* t_ghost, double* t_mat) {
+  const double n = (double)l->n_tokens, di = l->d_in, d_o = l->d_out, b = l->n_seq;
+  const double D = di * d_o;
+  // ghost: N^2/2 token pairs (symmetry), 2 flops per multiply-add, over d_in + d_out features;
+  // the kernel works on 64-token tiles, so a short batch still pays whole tiles
+  const double nt = (double)((l->n_tokens + 63) / 64) * 64.0;
+  *t_ghost = nt * nt * (di + d_o) / kRateGhost + 4 * kLaunch;
+  // materialised: every tile is padded to whole 32-token blocks per sequence
+  double n_pad = 0;
+  for (int i = 0; i < l->n_seq; ++i) {
+    const int len = l->seq_offsets_host[i + 1] - l->seq_offsets_host[i];
+    n_pad += (double)((len + 31) / 32) * 32.0;
+  }
+  (void)n;
+  const double es = (double)elem_size(l->dtype);
+  *t_mat = 2.0 * n_pad * D / kRateContraction + 2.0 * b * D * es / kRateStash + 3 * kLaunch;
+}
+
+size_t stash_bytes(const isopo_layer* l, int rows) {
+  return (size_t)l->n_seq * (size_t)rows * (size_t)l->d_in * elem_size(l->dtype);
+}
+
+size_t partial_bytes(const isopo_layer* l) {
+  return align_up((size_t)stash_gram_slots() * stash_gram_slot_floats(l->n_seq) * sizeof(float));
+}
+
+size_t ghost_bytes(const isopo_layer* l) {
+  return align_up((size_t)l->n_seq * l->n_seq * sizeof(double)) + align_up((size_t)l->n_tokens * sizeof(int32_t));
+}
+
+isopo_gram_path resolve(const isopo_layer* l, isopo_gram_path req) {
+  if (req != ISOPO_GRAM_AUTO) return req;
+  if (l->n_seq > kMaterialisedMaxSeq) return ISOPO_GRAM_GHOST;
+  double tg, tm;
+  cost_model(l, &tg, &tm);
+  return tg < tm ? ISOPO_GRAM_GHOST : ISOPO_GRAM_MATERIALISED;
+}
+
+// Optional cap (MiB) on the stash bytes formed per pass, so that the Gram pass
+// over a chunk finds it still in the memory-side cache.  0 = no cap.
+size_t chunk_cap_bytes() {
+  static const size_t cap = [] {
+    const char* e = std::getenv("ISOPO_STASH_CHUNK_MB");
+    return e ? (size_t)std::strtoull(e, nullptr, 10) << 20 : (size_t)0;
+  }();
+  return cap;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* isopo_version(void) { return "0.1"; }
+
+const char* isopo_status_string(isopo_status s) {
+  switch (s) {
+    case ISOPO_OK: return "ok";
+    case ISOPO_ERR_INVALID_ARG: return "invalid argument";
+    case ISOPO_ERR_BAD_OFFSETS: return "bad sequence offsets";
+    case ISOPO_ERR_UNSUPPORTED: return "unsupported dtype or shape";
+    case ISOPO_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case ISOPO_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, double* t_materialised) {
+  isopo_status st = check_layer(layer, false);
+  if (st != ISOPO_OK) return st;
+  double tg, tm;
+  cost_model(layer, &tg, &tm);
+  if (t_ghost) *t_ghost = tg;
+  if (t_materialised) *t_materialised = tm;
+  return ISOPO_OK;
+}
+
+isopo_status isopo_layer_gram_plan(const isopo_layer* layer, isopo_gram_path requested, isopo_gram_path* chosen,
+                                   size_t* ws_full, size_t* ws_min) {
+  isopo_status st = check_layer(layer, false);
+  if (st != ISOPO_OK) return st;
+  if (requested != ISOPO_GRAM_AUTO && requested != ISOPO_GRAM_GHOST && requested != ISOPO_GRAM_MATERIALISED)
+    return ISOPO_ERR_INVALID_ARG;
+  const isopo_gram_path path = resolve(layer, requested);
+  if (path == ISOPO_GRAM_MATERIALISED && layer->n_seq > kMaterialisedMaxSeq) return ISOPO_ERR_UNSUPPORTED;
+  if (chosen) *chosen = path;
+  if (path == ISOPO_GRAM_GHOST) {
+    if (ws_full) *ws_full = ghost_bytes(layer);
+    if (ws_min) *ws_min = ghost_bytes(layer);
+  } else {
+    const int min_rows = layer->d_out < kTileRows ? layer->d_out : kTileRows;
+    if (ws_full) *ws_full = align_up(stash_bytes(layer, layer->d_out)) + partial_bytes(layer);
+    if (ws_min) *ws_min = align_up(stash_bytes(layer, min_rows)) + partial_bytes(layer);
+  }
+  return ISOPO_OK;
+}
+
+isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, float* K, void* workspace,
+                              size_t ws_bytes, int keep_stash, void* stream) {
+  isopo_status st = check_layer(layer, true);
+  if (st != ISOPO_OK) return st;
+  if (!K || !workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1))) return ISOPO_ERR_INVALID_ARG;
+  isopo_gram_path chosen;
+  size_t ws_full, ws_min;
+  st = isopo_layer_gram_plan(layer, path, &chosen, &ws_full, &ws_min);
+  if (st != ISOPO_OK) return st;
+  if (ws_bytes < ws_min) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool bf16 = layer->dtype == ISOPO_BF16;
+  char* ws = static_cast<char*>(workspace);
+
+  if (chosen == ISOPO_GRAM_GHOST) {
+    if (keep_stash) return ISOPO_ERR_INVALID_ARG;
+    GhostArgs g;
+    g.X = layer->X; g.Delta = layer->Delta; g.off = layer->seq_offsets_dev;
+    g.n_tokens = (int)layer->n_tokens; g.d_in = layer->d_in; g.d_out = layer->d_out; g.n_seq = layer->n_seq;
+    g.bf16 = bf16;
+    g.K64 = reinterpret_cast<double*>(ws);
+    g.tok_seq = reinterpret_cast<int32_t*>(ws + align_up((size_t)layer->n_seq * layer->n_seq * sizeof(double)));
+    g.K = K;
+    return launch_ghost_gram(g, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+  }
+
+  if (keep_stash && ws_bytes < ws_full) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  const size_t pbytes = partial_bytes(layer);
+  const size_t row_bytes = stash_bytes(layer, 1);
+  // rows of d_out whose gradients are formed and reduced per pass
+  size_t rows_fit = (ws_bytes - pbytes) / row_bytes;
+  const bool whole = rows_fit >= (size_t)layer->d_out;
+  if (whole) rows_fit = layer->d_out;
+  size_t chunk_rows = rows_fit;
+  const size_t cap = chunk_cap_bytes();
+  if (cap && chunk_rows * row_bytes > cap) chunk_rows = cap / row_bytes;
+  if (chunk_rows < (size_t)layer->d_out) {
+    chunk_rows = chunk_rows / kTileRows * kTileRows;
+    if (chunk_rows < (size_t)kTileRows) chunk_rows = kTileRows;
+    if (chunk_rows > rows_fit) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  }
+  // With the whole stash resident, chunk c lives at its final place (rows r0.. of
+  // every sequence); otherwise every chunk reuses the front of the workspace.
+  const long long seq_stride = whole ? (long long)layer->d_out * layer->d_in : (long long)chunk_rows * layer->d_in;
+  float* partials = reinterpret_cast<float*>(ws + (whole ? align_up(stash_bytes(layer, layer->d_out))
+                                                         : align_up(stash_bytes(layer, (int)chunk_rows))));
+  if (reinterpret_cast<char*>(partials) + pbytes > ws + ws_bytes) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+
+  for (int r0 = 0; r0 < layer->d_out; r0 += (int)chunk_rows) {
+    const int rows = (layer->d_out - r0) < (int)chunk_rows ? (layer->d_out - r0) : (int)chunk_rows;
+    SeqGradArgs a;
+    a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.c = nullptr;
+    a.out = ws; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq;
+    a.row0 = r0; a.rows = rows; a.out_row0 = whole ? 0 : r0; a.out_seq_stride = seq_stride;
+    a.beta = 0.f; a.per_sequence = true; a.bf16 = bf16;
+    if (launch_seq_grad(a, s) != hipSuccess) return ISOPO_ERR_HIP;
+    StashGramArgs g;
+    g.stash = ws; g.seq_stride = seq_stride;
+    g.p0 = whole ? (long long)r0 * layer->d_in : 0;
+    g.p1 = g.p0 + (long long)rows * layer->d_in;
+    g.n_seq = layer->n_seq; g.bf16 = bf16; g.first = (r0 == 0); g.partials = partials;
+    if (launch_stash_gram(g, s) != hipSuccess) return ISOPO_ERR_HIP;
+  }
+  return launch_stash_gram_finish(partials, layer->n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+size_t isopo_transform_workspace(int32_t n_seq, int32_t batch) {
+  if (n_seq <= kTransformLdsMax || batch <= 0) return 0;
+  return (size_t)batch * ((size_t)n_seq * n_seq + n_seq) * sizeof(double);
+}
+
+isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int32_t batch, isopo_variant variant,
+                             float lambda, isopo_reg_mode reg_mode, float* c, int32_t* info_dev, void* workspace,
+                             size_t ws_bytes, void* stream) {
+  if (!K || !A || !c || n_seq <= 0 || batch <= 0) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  if (variant != ISOPO_VARIANT_FISHER && variant != ISOPO_VARIANT_INTERACTING) return ISOPO_ERR_INVALID_ARG;
+  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE) return ISOPO_ERR_INVALID_ARG;
+  if (!(lambda >= 0.f)) return ISOPO_ERR_INVALID_ARG;
+  if (variant == ISOPO_VARIANT_INTERACTING) {
+    const size_t need = isopo_transform_workspace(n_seq, batch);
+    if (need && (!workspace || ws_bytes < need)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+    if (need && (reinterpret_cast<uintptr_t>(workspace) & 15u)) return ISOPO_ERR_INVALID_ARG;
+  }
+  TransformArgs t;
+  t.K = K; t.A = A; t.n_seq = n_seq; t.batch = batch; t.variant = (int)variant; t.reg_mode = (int)reg_mode;
+  t.lambda = lambda; t.c = c; t.info = info_dev; t.workspace = static_cast<double*>(workspace);
+  return launch_transform(t, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash, float beta, float* dW,
+                                 void* stream) {
+  isopo_status st = check_layer(layer, true);
+  if (st != ISOPO_OK) return st;
+  if (!c || !dW || !aligned16(dW) || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool bf16 = layer->dtype == ISOPO_BF16;
+  const long long D = (long long)layer->d_out * layer->d_in;
+  if (stash) {
+    return launch_stash_weighted_sum(stash, bf16, D, D, layer->n_seq, c, beta, dW, s) == hipSuccess ? ISOPO_OK
+                                                                                                      : ISOPO_ERR_HIP;
+  }
+  SeqGradArgs a;
+  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.c = c; a.out = dW;
+  a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq;
+  a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0; a.out_seq_stride = 0;
+  a.beta = beta; a.per_sequence = false; a.bf16 = bf16;
+  return launch_seq_grad(a, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+}  // extern "C"

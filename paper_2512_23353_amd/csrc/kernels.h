@@ -1,0 +1,76 @@
+// Host-callable launchers of the gfx950 kernels.  Internal to the library: the
+// public surface is include/isopo.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace isopo {
+
+// Token-reduction contraction  out[o][k] = sum_t scale(t) * Delta[t][o] * X[t][k].
+//   per_sequence = true :  one output per sequence (the stash of G_i), scale = 1
+//   per_sequence = false:  one output (dW), scale = c[seq(t)], out = beta*out + sum
+struct SeqGradArgs {
+  const void* X;
+  const void* Delta;
+  const int32_t* off;        // device [n_seq+1]
+  const float* c;            // device [n_seq] (weighted mode only)
+  void* out;                 // stash (input dtype) or dW (fp32)
+  int d_in, d_out, n_seq;
+  int row0, rows;            // output rows [row0, row0+rows) of d_out handled by this launch
+  int out_row0;              // output row o is stored at row (o - out_row0)
+  long long out_seq_stride;  // elements between consecutive sequences' outputs (per_sequence)
+  float beta;
+  bool per_sequence;
+  bool bf16;
+};
+hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s);
+
+// K partials from the stash:  for p in [p0, p1):  acc[i][j] += S[i][p] * S[j][p].
+struct StashGramArgs {
+  const void* stash;         // [n_seq][seq_stride] elements, input dtype
+  long long seq_stride;
+  long long p0, p1;          // element range inside each sequence's gradient
+  int n_seq;
+  bool bf16;
+  bool first;                // overwrite the partial slots instead of adding to them
+  float* partials;           // [stash_gram_slots()][stash_gram_slot_floats(n_seq)]
+};
+int stash_gram_slots();
+size_t stash_gram_slot_floats(int n_seq);
+hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s);
+// K[i][j] = K[j][i] = sum over slots (fixed order) of the (i<=j) entry.
+hipError_t launch_stash_gram_finish(const float* partials, int n_seq, float* K, hipStream_t s);
+
+// dW[p] = beta*dW[p] + sum_i c[i] * stash[i][p],  p in [0, n_elem).
+hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq_stride, long long n_elem,
+                                     int n_seq, const float* c, float beta, float* dW, hipStream_t s);
+
+// Ghost Gram: K_ij = sum_{t in i, s in j} (x_t.x_s)(delta_t.delta_s).
+struct GhostArgs {
+  const void* X;
+  const void* Delta;
+  const int32_t* off;
+  int n_tokens, d_in, d_out, n_seq;
+  bool bf16;
+  int32_t* tok_seq;          // workspace [n_tokens]
+  double* K64;               // workspace [n_seq*n_seq]
+  float* K;
+};
+hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s);
+
+struct TransformArgs {
+  const float* K;
+  const float* A;
+  int n_seq, batch;
+  int variant, reg_mode;
+  float lambda;
+  float* c;
+  int32_t* info;
+  double* workspace;         // [batch][n_seq*n_seq] when n_seq > kTransformLdsMax, else unused
+};
+constexpr int kTransformLdsMax = 128;
+hipError_t launch_transform(const TransformArgs& a, hipStream_t s);
+
+}  // namespace isopo

@@ -1,0 +1,224 @@
+// Gram matrix and weighted sum over the stash of per-sequence gradients.
+//
+//   K_ij = sum_p S[i][p] * S[j][p]          (interacting listing: ntk[i, j] =
+//                                            sum(seq_grads[i] * seq_grads[j]))
+//   dW[p] = beta dW[p] + sum_i c_i S[i][p]  (stack(seq_grads, -1) @ coefficients)
+//
+// Both read the stash once and are bound by HBM.  For the Gram matrix the
+// reduction index p is the fast index of every S[i], which is the register
+// layout the MFMA wants for both operands, and since K = S S^T the A and B
+// fragments are the same registers: a wave loads one 16-byte piece per lane and
+// row block and issues mfma(a_i, a_j) for every block pair i <= j.
+//
+// Determinism: every wave owns one slot of a partial buffer, the p -> wave
+// assignment is a fixed formula, and the finishing kernel adds the slots in
+// index order; K is bit-reproducible and exactly symmetric.
+#include "common.h"
+#include "kernels.h"
+
+namespace isopo {
+namespace {
+
+constexpr int kGramBlocks = 512;            // workgroups of the streaming kernel
+constexpr int kGramWaves = 4;               // waves per workgroup
+constexpr int kGramSlots = kGramBlocks * kGramWaves;
+constexpr int kMaxRowBlocks = 4;            // 32-row blocks a single wave keeps pairs for (n_seq <= 128)
+
+__host__ __device__ constexpr int tri(int nb) { return nb * (nb + 1) / 2; }
+// index of block pair (bi <= bj) in row-major upper-triangular order
+__host__ __device__ inline int pair_index(int bi, int bj, int nb) { return bi * nb - bi * (bi - 1) / 2 + (bj - bi); }
+
+struct GramParams {
+  const void* stash;
+  long long seq_stride, p0, p1;
+  int n_seq;
+  int first;
+  float* partials;
+  long long slot_floats;
+};
+
+// One wave handles "super steps" of 4 consecutive 32-byte-per-row pieces (128 B
+// of every row), so each row's cache line is consumed by one wave.
+template <int NB, bool BF16>
+__global__ __launch_bounds__(256) void stash_gram_kernel(GramParams p) {
+  constexpr int kElemPerVec = BF16 ? 8 : 4;           // per 16-byte lane load
+  constexpr int kStepElems = 2 * kElemPerVec;         // per row and micro step (two lane halves)
+  constexpr int kSuper = 4;                           // micro steps per super step
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const long long slot = (long long)blockIdx.x * kGramWaves + wave;
+  const long long n_slots = (long long)gridDim.x * kGramWaves;
+
+  f32x16 acc[tri(NB)];
+#pragma unroll
+  for (int q = 0; q < tri(NB); ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+
+  const char* base[NB];
+  bool row_ok[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int r = b * 32 + row;
+    row_ok[b] = r < p.n_seq;
+    base[b] = static_cast<const char*>(p.stash) + (size_t)(row_ok[b] ? r : 0) * p.seq_stride * (BF16 ? 2 : 4);
+  }
+
+  const long long n_elems = p.p1 - p.p0;
+  const long long n_super = (n_elems + kSuper * kStepElems - 1) / (kSuper * kStepElems);
+  for (long long u = slot; u < n_super; u += n_slots) {
+    uint4 frag[NB][kSuper];
+#pragma unroll
+    for (int q = 0; q < kSuper; ++q) {
+      const long long e = p.p0 + (u * kSuper + q) * kStepElems + half * kElemPerVec;
+      const bool in = e < p.p1;     // p1 - p0 is a multiple of the vector width
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        frag[b][q] = (in && row_ok[b]) ? *reinterpret_cast<const uint4*>(base[b] + e * (BF16 ? 2 : 4))
+                                       : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int q = 0; q < kSuper; ++q) {
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int bj = bi; bj < NB; ++bj) {
+          f32x16& a = acc[pair_index(bi, bj, NB)];
+          if constexpr (BF16) {
+            a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[bi][q]),
+                                                        __builtin_bit_cast(bf16x8, frag[bj][q]), a, 0, 0, 0);
+          } else {
+            const float4 fa = __builtin_bit_cast(float4, frag[bi][q]);
+            const float4 fb = __builtin_bit_cast(float4, frag[bj][q]);
+            a = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.x, fb.x, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.y, fb.y, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.z, fb.z, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.w, fb.w, a, 0, 0, 0);
+          }
+        }
+    }
+  }
+
+  // slot layout: [pair][v][lane]
+  float* out = p.partials + slot * p.slot_floats;
+#pragma unroll
+  for (int q = 0; q < tri(NB); ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      float* o = out + (q * 16 + v) * 64 + lane;
+      *o = (p.first ? 0.f : *o) + acc[q][v];
+    }
+}
+
+__global__ void stash_gram_finish_kernel(const float* __restrict__ partials, int n_slots, long long slot_floats,
+                                         int n_seq, int nb, float* __restrict__ K) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_seq * n_seq) return;
+  const int i = idx / n_seq, j = idx % n_seq;
+  if (i > j) return;
+  const int bi = i >> 5, bj = j >> 5, ri = i & 31, cj = j & 31;
+  const int v = 4 * (ri >> 3) + (ri & 3), lane = cj + 32 * ((ri >> 2) & 1);
+  const float* src = partials + ((long long)pair_index(bi, bj, nb) * 16 + v) * 64 + lane;
+  float s = 0.f;
+  for (int w = 0; w < n_slots; ++w) s += src[(long long)w * slot_floats];
+  K[(size_t)i * n_seq + j] = s;
+  K[(size_t)j * n_seq + i] = s;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __restrict__ stash, long long seq_stride,
+                                                                 long long n_vec, int n_seq,
+                                                                 const float* __restrict__ c, float beta,
+                                                                 float* __restrict__ dW) {
+  constexpr int kV = BF16 ? 8 : 4;
+  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < n_vec;
+       vi += (long long)gridDim.x * blockDim.x) {
+    float s[kV];
+#pragma unroll
+    for (int e = 0; e < kV; ++e) s[e] = 0.f;
+    const char* src = static_cast<const char*>(stash) + vi * 16;
+    for (int i = 0; i < n_seq; ++i) {
+      const float ci = c[i];
+      const uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)i * seq_stride * (BF16 ? 2 : 4));
+      if constexpr (BF16) {
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          s[2 * e] += ci * __builtin_bit_cast(float, w[e] << 16);
+          s[2 * e + 1] += ci * __builtin_bit_cast(float, w[e] & 0xffff0000u);
+        }
+      } else {
+        const float4 f = __builtin_bit_cast(float4, v);
+        s[0] += ci * f.x; s[1] += ci * f.y; s[2] += ci * f.z; s[3] += ci * f.w;
+      }
+    }
+    float* o = dW + vi * kV;
+#pragma unroll
+    for (int e = 0; e < kV; e += 4) {
+      float4 r = make_float4(s[e], s[e + 1], s[e + 2], s[e + 3]);
+      if (beta != 0.f) {
+        const float4 old = *reinterpret_cast<const float4*>(o + e);
+        r.x += beta * old.x; r.y += beta * old.y; r.z += beta * old.z; r.w += beta * old.w;
+      }
+      *reinterpret_cast<float4*>(o + e) = r;
+    }
+  }
+}
+
+template <int NB>
+hipError_t launch_gram_nb(const GramParams& p, bool bf16, hipStream_t s) {
+  if (bf16)
+    hipLaunchKernelGGL((stash_gram_kernel<NB, true>), dim3(kGramBlocks), dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((stash_gram_kernel<NB, false>), dim3(kGramBlocks), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int stash_gram_slots() { return kGramSlots; }
+
+size_t stash_gram_slot_floats(int n_seq) {
+  const int nb = (n_seq + 31) / 32;
+  return (size_t)tri(nb) * 1024;
+}
+
+hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s) {
+  const int nb = (a.n_seq + 31) / 32;
+  if (nb > kMaxRowBlocks) return hipErrorInvalidValue;
+  GramParams p;
+  p.stash = a.stash; p.seq_stride = a.seq_stride; p.p0 = a.p0; p.p1 = a.p1;
+  p.n_seq = a.n_seq; p.first = a.first ? 1 : 0; p.partials = a.partials;
+  p.slot_floats = (long long)stash_gram_slot_floats(a.n_seq);
+  switch (nb) {
+    case 1: return launch_gram_nb<1>(p, a.bf16, s);
+    case 2: return launch_gram_nb<2>(p, a.bf16, s);
+    case 3: return launch_gram_nb<3>(p, a.bf16, s);
+    default: return launch_gram_nb<4>(p, a.bf16, s);
+  }
+}
+
+hipError_t launch_stash_gram_finish(const float* partials, int n_seq, float* K, hipStream_t s) {
+  const int nb = (n_seq + 31) / 32;
+  const int n = n_seq * n_seq;
+  hipLaunchKernelGGL(stash_gram_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partials, kGramSlots,
+                     (long long)stash_gram_slot_floats(n_seq), n_seq, nb, K);
+  return hipGetLastError();
+}
+
+hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq_stride, long long n_elem, int n_seq,
+                                     const float* c, float beta, float* dW, hipStream_t s) {
+  const long long n_vec = n_elem / (bf16 ? 8 : 4);
+  if (n_vec <= 0) return hipSuccess;
+  long long blocks = (n_vec + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (bf16)
+    hipLaunchKernelGGL((stash_weighted_sum_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
+                       n_vec, n_seq, c, beta, dW);
+  else
+    hipLaunchKernelGGL((stash_weighted_sum_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
+                       n_vec, n_seq, c, beta, dW);
+  return hipGetLastError();
+}
+
+}  // namespace isopo

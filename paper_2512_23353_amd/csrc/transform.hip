@@ -1,0 +1,133 @@
+// Per-sequence coefficients from the layer's Gram matrix K and the advantages A.
+//
+//   FISHER       c_i = A_i / sqrt(||g_i||_F^2 + reg),  ||g_i||_F^2 = (1/m) sum_j K_ij^2
+//                (non-interacting update u_l, with the Fisher norm of eq.
+//                F-norm-basic taken over the batch's reduced gradients, j = i
+//                included)
+//   INTERACTING  c = (K + reg I)^-1 A          (v = J^T (K + cI)^-1 A)
+//
+// reg = lambda, or lambda * tr(K)/m.  The m x m problem is tiny next to the
+// contractions around it, so one workgroup per problem works in fp64: a
+// right-looking Cholesky factorisation in LDS (m <= 128) or in a caller-provided
+// global scratch (larger m), then two triangular solves.  The result is the
+// unique solution; the eigendecomposition the interacting listing uses reaches
+// the same vector.  A non-positive pivot is reported, never clamped.
+#include "common.h"
+#include "kernels.h"
+
+namespace isopo {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ double block_sum(double x, double* red /* [kThreads/64] */) {
+  x = wave_sum(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  double s = 0.0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) s += red[w];
+  return s;
+}
+
+__global__ __launch_bounds__(kThreads) void transform_kernel(const float* __restrict__ Kb, const float* __restrict__ Ab,
+                                                             int m, int variant, int reg_mode, float lambda,
+                                                             float* __restrict__ cb, int32_t* __restrict__ info,
+                                                             double* __restrict__ gws) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ double red[kThreads / 64];
+  const int prob = blockIdx.x, tid = threadIdx.x;
+  const float* K = Kb + (size_t)prob * m * m;
+  const float* A = Ab + (size_t)prob * m;
+  float* c = cb + (size_t)prob * m;
+
+  double reg = (double)lambda;
+  if (reg_mode == 1) {
+    double tr = 0.0;
+    for (int i = tid; i < m; i += kThreads) tr += (double)K[(size_t)i * m + i];
+    reg = (double)lambda * block_sum(tr, red) / (double)m;
+  }
+
+  if (variant == 0) {
+    for (int i = tid; i < m; i += kThreads) {
+      double s = 0.0;
+      for (int j = 0; j < m; ++j) {
+        const double k = (double)K[(size_t)i * m + j];
+        s += k * k;
+      }
+      const double den = s / (double)m + reg;
+      c[i] = den > 0.0 ? (float)((double)A[i] / sqrt(den)) : 0.f;
+    }
+    if (info && tid == 0) info[prob] = 0;
+    return;
+  }
+
+  // M = K + reg I (lower triangle), y, in LDS or global scratch.
+  double* M = gws ? gws + (size_t)prob * ((size_t)m * m + m) : reinterpret_cast<double*>(smem);
+  double* y = M + (size_t)m * m;
+  for (int e = tid; e < m * m; e += kThreads) {
+    const int r = e / m, q = e % m;
+    if (q <= r) M[e] = (double)K[e] + (r == q ? reg : 0.0);
+  }
+  for (int i = tid; i < m; i += kThreads) y[i] = (double)A[i];
+  __syncthreads();
+
+  for (int k = 0; k < m; ++k) {
+    const double d = M[(size_t)k * m + k];
+    if (!(d > 0.0)) {                       // uniform: every thread reads the same value
+      for (int i = tid; i < m; i += kThreads) c[i] = __builtin_nanf("");
+      if (info && tid == 0) info[prob] = k + 1;
+      return;
+    }
+    const double inv = 1.0 / sqrt(d);
+    __syncthreads();                        // everyone has read the pivot
+    for (int r = k + tid; r < m; r += kThreads) M[(size_t)r * m + k] *= inv;   // column k of L (M[k][k] -> sqrt(d))
+    __syncthreads();
+    const int rem = m - k - 1;              // trailing lower triangle, rows/cols k+1..m-1
+    for (int e = tid; e < rem * rem; e += kThreads) {
+      const int r = k + 1 + e / rem, q = k + 1 + e % rem;
+      if (q <= r) M[(size_t)r * m + q] -= M[(size_t)r * m + k] * M[(size_t)q * m + k];
+    }
+    __syncthreads();
+  }
+  // forward: L y = A
+  for (int k = 0; k < m; ++k) {
+    const double yk = y[k] / M[(size_t)k * m + k];
+    __syncthreads();
+    if (tid == 0) y[k] = yk;
+    for (int r = k + 1 + tid; r < m; r += kThreads) y[r] -= M[(size_t)r * m + k] * yk;
+    __syncthreads();
+  }
+  // backward: L^T c = y
+  for (int k = m - 1; k >= 0; --k) {
+    const double ck = y[k] / M[(size_t)k * m + k];
+    __syncthreads();
+    if (tid == 0) y[k] = ck;
+    for (int r = tid; r < k; r += kThreads) y[r] -= M[(size_t)k * m + r] * ck;
+    __syncthreads();
+  }
+  for (int i = tid; i < m; i += kThreads) c[i] = (float)y[i];
+  if (info && tid == 0) info[prob] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_transform(const TransformArgs& a, hipStream_t s) {
+  const bool lds = a.n_seq <= kTransformLdsMax;
+  size_t smem = 0;
+  if (a.variant == 1 && lds) smem = ((size_t)a.n_seq * a.n_seq + a.n_seq) * sizeof(double);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const int max_smem = (int)(((size_t)kTransformLdsMax * kTransformLdsMax + kTransformLdsMax) * sizeof(double));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(transform_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, max_smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(transform_kernel, dim3(a.batch), dim3(kThreads), smem, s, a.K, a.A, a.n_seq, a.variant,
+                     a.reg_mode, a.lambda, a.c, a.info, (a.variant == 1 && !lds) ? a.workspace : nullptr);
+  return hipGetLastError();
+}
+
+}  // namespace isopo

@@ -1,0 +1,223 @@
+"""Thin ctypes binding over the C-ABI library (include/isopo.h).
+
+Argument marshalling only: every step of the layer step runs in the library's
+kernels.  torch supplies device memory and the stream.  There is no CPU
+fallback: if libisopo.so is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libisopo.so")
+_lib = None
+
+OK = 0
+F32, BF16 = 0, 1
+GRAM_AUTO, GRAM_GHOST, GRAM_MATERIALISED = 0, 1, 2
+VARIANT_FISHER, VARIANT_INTERACTING = 0, 1
+REG_ABSOLUTE, REG_REL_TRACE = 0, 1
+MAX_SEQ = 1024
+
+_VARIANTS = {"fisher": VARIANT_FISHER, "interacting": VARIANT_INTERACTING}
+_PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALISED}
+_PATH_NAMES = {v: k for k, v in _PATHS.items()}
+
+EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_transform_workspace",
+           "isopo_transform", "isopo_weighted_grad", "isopo_status_string", "isopo_version")
+
+
+class IsopoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [("X", ctypes.c_void_p), ("Delta", ctypes.c_void_p), ("dtype", ctypes.c_int),
+                ("n_tokens", ctypes.c_int64), ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
+                ("n_seq", ctypes.c_int32), ("seq_offsets_dev", ctypes.c_void_p),
+                ("seq_offsets_host", ctypes.c_void_p)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libisopo.so (built by `python -m paper_2512_23353_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is not built; run `python -m paper_2512_23353_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_float
+    lp = ctypes.POINTER(_Layer)
+    lib.isopo_layer_gram_plan.argtypes = [lp, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(sz),
+                                          ctypes.POINTER(sz)]
+    lib.isopo_layer_gram_plan.restype = ctypes.c_int
+    lib.isopo_gram_cost_model.argtypes = [lp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.isopo_gram_cost_model.restype = ctypes.c_int
+    lib.isopo_layer_gram.argtypes = [lp, ctypes.c_int, vp, vp, sz, ctypes.c_int, vp]
+    lib.isopo_layer_gram.restype = ctypes.c_int
+    lib.isopo_transform_workspace.argtypes = [i32, i32]
+    lib.isopo_transform_workspace.restype = sz
+    lib.isopo_transform.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.isopo_transform.restype = ctypes.c_int
+    lib.isopo_weighted_grad.argtypes = [lp, vp, vp, f32, vp, vp]
+    lib.isopo_weighted_grad.restype = ctypes.c_int
+    lib.isopo_status_string.argtypes = [ctypes.c_int]
+    lib.isopo_status_string.restype = ctypes.c_char_p
+    lib.isopo_version.argtypes = []
+    lib.isopo_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().isopo_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return load().isopo_version().decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise IsopoError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class Layer:
+    """One ragged layer problem.  Keeps the host offsets and the device copies
+    alive for as long as the C struct is in use."""
+
+    def __init__(self, X: Optional[torch.Tensor], Delta: Optional[torch.Tensor], seq_offsets,
+                 seq_offsets_dev: Optional[torch.Tensor] = None, d_in: Optional[int] = None,
+                 d_out: Optional[int] = None, dtype: Optional[int] = None, n_tokens: Optional[int] = None):
+        self.X, self.Delta = X, Delta
+        self.off_host = np.ascontiguousarray(np.asarray(seq_offsets, dtype=np.int32))
+        if X is not None:
+            if X.dtype != Delta.dtype or X.dim() != 2 or Delta.dim() != 2:
+                raise ValueError("X and Delta must be 2-D tensors of one dtype")
+            if not (X.is_contiguous() and Delta.is_contiguous()):
+                raise ValueError("X and Delta must be contiguous (row-major)")
+            if X.dtype not in (torch.float32, torch.bfloat16):
+                raise IsopoError(3, "Layer")
+            dtype = BF16 if X.dtype == torch.bfloat16 else F32
+            d_in, d_out, n_tokens = X.shape[1], Delta.shape[1], X.shape[0]
+            if Delta.shape[0] != n_tokens:
+                raise ValueError("X and Delta must have the same number of token rows")
+            if seq_offsets_dev is None and X.is_cuda:
+                seq_offsets_dev = torch.from_numpy(self.off_host).to(X.device)
+        self.off_dev = seq_offsets_dev
+        self.d_in, self.d_out, self.dtype = int(d_in), int(d_out), int(dtype)
+        self.n_seq = int(self.off_host.size - 1)
+        self.n_tokens = int(n_tokens)
+        self.c = _Layer(_ptr(X), _ptr(Delta), self.dtype, self.n_tokens, self.d_in, self.d_out, self.n_seq,
+                        _ptr(self.off_dev), self.off_host.ctypes.data)
+
+    @property
+    def device(self):
+        return self.X.device
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def gram_plan(layer: Layer, path="auto") -> Tuple[str, int, int]:
+    """(chosen path, ws_full bytes, ws_min bytes).  Host only."""
+    chosen, full, mn = ctypes.c_int(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().isopo_layer_gram_plan(layer.ref(), _PATHS[path], ctypes.byref(chosen), ctypes.byref(full),
+                                        ctypes.byref(mn)), "isopo_layer_gram_plan")
+    return _PATH_NAMES[chosen.value], int(full.value), int(mn.value)
+
+
+def gram_cost_model(layer: Layer) -> Tuple[float, float]:
+    tg, tm = ctypes.c_double(), ctypes.c_double()
+    _check(load().isopo_gram_cost_model(layer.ref(), ctypes.byref(tg), ctypes.byref(tm)), "isopo_gram_cost_model")
+    return tg.value, tm.value
+
+
+def alloc_workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def layer_gram(layer: Layer, path="auto", K: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, keep_stash: bool = False, stream=None):
+    """K [n_seq, n_seq] fp32.  Returns (K, workspace); with keep_stash the stash
+    lies at the start of the workspace."""
+    if K is None:
+        K = torch.empty((layer.n_seq, layer.n_seq), dtype=torch.float32, device=layer.device)
+    if workspace is None:
+        _, full, mn = gram_plan(layer, path)
+        workspace = alloc_workspace(full, layer.device)
+    _check(load().isopo_layer_gram(layer.ref(), _PATHS[path], K.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel(), int(keep_stash), _stream(stream)), "isopo_layer_gram")
+    return K, workspace
+
+
+def transform_workspace(n_seq: int, batch: int = 1) -> int:
+    return int(load().isopo_transform_workspace(n_seq, batch))
+
+
+def transform(K: torch.Tensor, A: torch.Tensor, variant="fisher", lam: float = 0.0, reg_mode: int = REG_ABSOLUTE,
+              c: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None,
+              workspace: Optional[torch.Tensor] = None, stream=None):
+    """c from K [batch?, m, m] and A [batch?, m].  Returns (c, info)."""
+    m = K.shape[-1]
+    batch = 1 if K.dim() == 2 else K.shape[0]
+    if K.dtype != torch.float32 or A.dtype != torch.float32 or not K.is_contiguous() or not A.is_contiguous():
+        raise ValueError("K and A must be contiguous fp32")
+    if c is None:
+        c = torch.empty_like(A)
+    if info is None:
+        info = torch.zeros(batch, dtype=torch.int32, device=K.device)
+    need = transform_workspace(m, batch)
+    if workspace is None and need:
+        workspace = alloc_workspace(need, K.device)
+    _check(load().isopo_transform(K.data_ptr(), A.data_ptr(), m, batch, _VARIANTS[variant], float(lam),
+                                  int(reg_mode), c.data_ptr(), info.data_ptr(), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream(stream)), "isopo_transform")
+    return c, info
+
+
+def weighted_grad(layer: Layer, c: torch.Tensor, stash: Optional[torch.Tensor] = None, beta: float = 0.0,
+                  dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """dW [d_out, d_in] fp32 = beta dW + sum_i c_i G_i (from the stash if given,
+    else by contracting X and Delta again)."""
+    if dW is None:
+        if beta != 0.0:
+            raise ValueError("beta != 0 needs an existing dW")
+        dW = torch.empty((layer.d_out, layer.d_in), dtype=torch.float32, device=layer.device)
+    _check(load().isopo_weighted_grad(layer.ref(), c.data_ptr(), _ptr(stash), float(beta), dW.data_ptr(),
+                                      _stream(stream)), "isopo_weighted_grad")
+    return dW
+
+
+def layer_step(layer: Layer, A: torch.Tensor, variant="interacting", lam: float = 0.0,
+               reg_mode: int = REG_ABSOLUTE, path="auto", beta: float = 0.0, dW: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, stream=None) -> dict:
+    """The three calls chained on one stream with no host synchronisation."""
+    chosen, full, _ = gram_plan(layer, path)
+    if workspace is None:
+        workspace = alloc_workspace(full, layer.device)
+    keep = chosen == "materialised" and workspace.numel() >= full
+    K, workspace = layer_gram(layer, path, workspace=workspace, keep_stash=keep, stream=stream)
+    c, info = transform(K, A, variant, lam, reg_mode, stream=stream)
+    dW = weighted_grad(layer, c, workspace if keep else None, beta, dW, stream=stream)
+    return {"K": K, "c": c, "info": info, "dW": dW, "path": chosen, "workspace": workspace}

@@ -1,0 +1,52 @@
+"""Comparison helpers shared by the GPU parity tests."""
+import numpy as np
+import torch
+
+from oracle import isopo_oracle as orc
+from paper_2512_23353_amd import workloads as wl
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # relative tolerances the benchmark definition states
+
+
+def rel_err(got, ref) -> float:
+    """Norm-wise relative error ||got - ref||_F / ||ref||_F."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
+
+
+def assert_K_close(K, K_ref, tol, what=""):
+    K = np.asarray(K, dtype=np.float64)
+    assert np.array_equal(K, K.T), f"{what}: K not bit-symmetric"
+    assert rel_err(K, K_ref) <= tol, f"{what}: K rel err {rel_err(K, K_ref):.3e} > {tol}"
+    d = np.sqrt(np.clip(np.diag(K_ref), 0, None))
+    guard = tol * np.outer(d, d)
+    bad = np.abs(K - K_ref) > guard + 1e-300
+    assert not bad.any(), f"{what}: |dK_ij| above tol*sqrt(K_ii K_jj) at {np.argwhere(bad)[:4].tolist()}"
+
+
+def assert_c_close(c, c_ref, tol, what=""):
+    c = np.asarray(c, dtype=np.float64)
+    assert rel_err(c, c_ref) <= tol, f"{what}: c rel err {rel_err(c, c_ref):.3e} > {tol}"
+    assert np.max(np.abs(c - c_ref)) <= tol * np.max(np.abs(c_ref)) + 1e-300, f"{what}: c element guard"
+
+
+def assert_dW_close(dW, dW_ref, tol, what=""):
+    dW = np.asarray(dW, dtype=np.float64)
+    assert rel_err(dW, dW_ref) <= tol, f"{what}: dW rel err {rel_err(dW, dW_ref):.3e} > {tol}"
+    rms = np.sqrt(np.mean(dW_ref ** 2))
+    assert np.max(np.abs(dW - dW_ref)) <= 8 * tol * rms + 1e-300, f"{what}: dW element guard"
+
+
+def oracle_step(prob, variant, lam, reg_mode=0, chunk_rows=None, dW_in=None, beta=0.0):
+    return orc.layer_step(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets, prob.A, variant, lam,
+                          reg_mode, dW_in=dW_in, beta=beta, chunk_rows=chunk_rows)
+
+
+def to_device(prob, device):
+    from paper_2512_23353_amd import isopo
+    X, D = prob.X.to(device), prob.Delta.to(device)
+    layer = isopo.Layer(X, D, prob.seq_offsets)
+    A = torch.from_numpy(prob.A).to(device)
+    return layer, A

@@ -1,0 +1,211 @@
+"""Parity of the HIP path (through the C ABI) with the CPU fp64 oracle.
+
+Every comparison is element by element on the same seeded input bytes.
+Tolerances are the benchmark definition's: 1e-4 relative for fp32 inputs, 2e-2
+relative for bf16 inputs with fp32 accumulation (norm-wise, with element
+guards; see helpers.py).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import isopo_oracle as orc
+from paper_2512_23353_amd import isopo
+from paper_2512_23353_amd import workloads as wl
+
+from helpers import TOL, assert_K_close, assert_c_close, assert_dW_close, oracle_step, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_step(prob, device, path, variant, lam, reg_mode=0, chunk_rows=None):
+    tol = TOL[prob.dtype]
+    layer, A = to_device(prob, device)
+    out = isopo.layer_step(layer, A, variant, lam, reg_mode, path)
+    torch.cuda.synchronize()
+    ref = oracle_step(prob, variant, lam, reg_mode, chunk_rows)
+    what = f"{prob.name}/{path}/{variant}"
+    assert out["path"] == path or path == "auto"
+    assert int(out["info"].item()) == ref["info"] == 0
+    assert_K_close(out["K"].cpu().numpy(), ref["K"], tol, what)
+    assert_c_close(out["c"].cpu().numpy(), ref["c"], tol, what)
+    assert_dW_close(out["dW"].cpu().numpy(), ref["dW"], tol, what)
+    # the same coefficients contracted again from X and Delta (no stash)
+    dW2 = isopo.weighted_grad(layer, out["c"])
+    assert_dW_close(dW2.cpu().numpy(), ref["dW"], tol, what + "/recompute")
+    return out, ref
+
+
+@pytest.mark.parametrize("path", ["materialised", "ghost"])
+@pytest.mark.parametrize("variant", ["fisher", "interacting"])
+@pytest.mark.parametrize("reg", [(1e-3, isopo.REG_ABSOLUTE), (1e-3, isopo.REG_REL_TRACE)])
+def test_config1_fp32(gpu_device, path, variant, reg):
+    w = wl.CONFIGS["config1"]
+    prob = wl.make_layer(w, w.projections[0])
+    _check_step(prob, gpu_device, path, variant, reg[0], reg[1])
+
+
+@pytest.mark.parametrize("path", ["materialised", "ghost"])
+def test_config1_correlated(gpu_device, path):
+    """Rollouts of one prompt correlate: off-diagonal K is a sizeable fraction
+    of the diagonal, so the interacting solve really mixes sequences."""
+    w = wl.CONFIGS["config1"]
+    prob = wl.make_layer(w, w.projections[0], rho=1.0)
+    out, ref = _check_step(prob, gpu_device, path, "interacting", 0.05, isopo.REG_REL_TRACE)
+    K = ref["K"]
+    offd = np.abs(K - np.diag(np.diag(K))).max() / np.diag(K).mean()
+    assert offd > 0.1
+
+
+EDGE_CASES = [
+    ("ragged", 256, 384, [100, 37, 1, 0, 250, 64]),
+    ("all_single_tokens", 64, 128, [1] * 40),
+    ("one_huge_many_tiny", 128, 256, [3, 1, 700, 2, 5, 1, 1, 9]),
+    ("one_sequence", 256, 128, [333]),
+    ("narrow_dims", 72, 200, [31, 32, 33, 65]),
+    ("empty_first_and_last", 128, 128, [0, 50, 0, 0, 70, 0]),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", EDGE_CASES, ids=[c[0] for c in EDGE_CASES])
+@pytest.mark.parametrize("path", ["materialised", "ghost"])
+def test_ragged_edge_cases(gpu_device, dtype, case, path):
+    _, d_in, d_out, lengths = case
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype=dtype, seed=11, sigma_delta=1e-2)
+    _check_step(prob, gpu_device, path, "interacting", 1e-2, isopo.REG_REL_TRACE)
+    _check_step(prob, gpu_device, path, "fisher", 1e-2, isopo.REG_REL_TRACE)
+
+
+def test_both_gram_paths_agree_and_are_symmetric(gpu_device):
+    prob = wl.custom_layer(512, 768, [300, 517, 33, 260, 128], dtype="bf16", seed=4, sigma_delta=1e-2, rho=0.7)
+    layer, _ = to_device(prob, gpu_device)
+    Km, _ = isopo.layer_gram(layer, "materialised")
+    Kg, _ = isopo.layer_gram(layer, "ghost")
+    Km2, _ = isopo.layer_gram(layer, "materialised")
+    torch.cuda.synchronize()
+    assert torch.equal(Km, Km.T) and torch.equal(Kg, Kg.T)
+    assert torch.equal(Km, Km2), "materialised K must be bit-reproducible"
+    assert rel_err(Km.cpu().numpy(), Kg.cpu().numpy()) < 1e-3
+
+
+def test_chunked_workspace_matches_whole(gpu_device):
+    """With only the minimum workspace the stash is formed and reduced in chunks
+    of output rows; K must not change beyond summation order."""
+    prob = wl.custom_layer(256, 1024, [200, 77, 300, 150], dtype="bf16", seed=5, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    _, full, mn = isopo.gram_plan(layer, "materialised")
+    assert mn < full
+    K_whole, _ = isopo.layer_gram(layer, "materialised")
+    ws = isopo.alloc_workspace(mn, gpu_device)
+    K_chunk, _ = isopo.layer_gram(layer, "materialised", workspace=ws)
+    torch.cuda.synchronize()
+    ref = orc.layer_ntk(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    assert_K_close(K_chunk.cpu().numpy(), ref, TOL["bf16"], "chunked")
+    assert rel_err(K_chunk.cpu().numpy(), K_whole.cpu().numpy()) < 1e-5
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.layer_gram(layer, "materialised", workspace=isopo.alloc_workspace(mn - 4096, gpu_device))
+    assert e.value.status == 4
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.layer_gram(layer, "materialised", workspace=ws, keep_stash=True)
+    assert e.value.status == 4
+
+
+def test_stash_holds_per_sequence_gradients(gpu_device):
+    prob = wl.custom_layer(128, 256, [90, 10, 45], dtype="f32", seed=6, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    _, ws = isopo.layer_gram(layer, "materialised", keep_stash=True)
+    torch.cuda.synchronize()
+    stash = ws[: 3 * 256 * 128 * 4].view(torch.float32).reshape(3, 256, 128).cpu().numpy()
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    assert rel_err(stash, G) < 1e-5
+
+
+@pytest.mark.parametrize("from_stash", [True, False])
+def test_weighted_grad_accumulates_with_beta(gpu_device, from_stash):
+    prob = wl.custom_layer(256, 256, [100, 64, 90], dtype="bf16", seed=7, sigma_delta=1e-2)
+    layer, A = to_device(prob, gpu_device)
+    _, ws = isopo.layer_gram(layer, "materialised", keep_stash=True)
+    dW0 = torch.randn(256, 256, device=gpu_device) * 1e-2
+    dW = dW0.clone()
+    isopo.weighted_grad(layer, A, ws if from_stash else None, beta=0.5, dW=dW)
+    torch.cuda.synchronize()
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    ref = orc.weighted_grad(G, prob.A, dW0.cpu().numpy(), 0.5)
+    assert_dW_close(dW.cpu().numpy(), ref, TOL["bf16"], "beta")
+
+
+def test_reinforce_baseline_is_weighted_grad_with_advantages(gpu_device):
+    prob = wl.custom_layer(384, 512, [257, 100, 511, 64], dtype="bf16", seed=8, sigma_delta=1e-2)
+    layer, A = to_device(prob, gpu_device)
+    dW = isopo.weighted_grad(layer, A)
+    torch.cuda.synchronize()
+    ref = oracle_step(prob, "fisher", 0.0)["dW_reinforce"]
+    assert_dW_close(dW.cpu().numpy(), ref, TOL["bf16"], "reinforce")
+
+
+def _random_gram(rng, m, rank_extra=8, scale=1.0):
+    J = rng.standard_normal((m, m + rank_extra)) * scale
+    J += 0.5 * scale * rng.standard_normal((1, m + rank_extra))    # common component -> dense K
+    return (J @ J.T).astype(np.float32)
+
+
+@pytest.mark.parametrize("m", [1, 2, 4, 16, 31, 32, 64, 128, 129, 256])
+@pytest.mark.parametrize("variant", ["fisher", "interacting"])
+def test_transform_sizes(gpu_device, m, variant):
+    rng = np.random.default_rng(100 + m)
+    batch = 3
+    K = np.stack([_random_gram(rng, m, scale=1.0 + b) for b in range(batch)])
+    A = rng.standard_normal((batch, m)).astype(np.float32)
+    for lam, mode in [(1e-2, isopo.REG_REL_TRACE), (0.5, isopo.REG_ABSOLUTE)]:
+        c, info = isopo.transform(torch.from_numpy(K).to(gpu_device), torch.from_numpy(A).to(gpu_device),
+                                  variant, lam, mode)
+        torch.cuda.synchronize()
+        assert info.cpu().tolist() == [0] * batch
+        for b in range(batch):
+            if variant == "fisher":
+                ref = orc.coeff_fisher(K[b], A[b], lam, mode)
+            else:
+                ref, oinfo = orc.coeff_interacting(K[b], A[b], lam, mode)
+                assert oinfo == 0
+            # K enters as given fp32 bits on both sides; the solve itself runs in fp64
+            assert_c_close(c[b].cpu().numpy(), ref, 1e-5, f"transform m={m} {variant}")
+
+
+def test_transform_reports_not_positive_definite(gpu_device):
+    K = np.array([[4.0, 2.0, 0.0], [2.0, 1.0, 0.0], [0.0, 0.0, 1.0]], dtype=np.float32)
+    Kb = np.stack([K, np.eye(3, dtype=np.float32), -np.eye(3, dtype=np.float32)])
+    A = np.ones((3, 3), dtype=np.float32)
+    c, info = isopo.transform(torch.from_numpy(Kb).to(gpu_device), torch.from_numpy(A).to(gpu_device),
+                              "interacting", 0.0)
+    torch.cuda.synchronize()
+    assert info.cpu().tolist() == [2, 0, 1]
+    assert [orc.coeff_interacting(Kb[b], A[b], 0.0)[1] for b in range(3)] == [2, 0, 1]
+    c = c.cpu().numpy()
+    assert np.all(np.isnan(c[0])) and np.all(np.isnan(c[2])) and np.allclose(c[1], 1.0)
+    # with a regulariser the singular problem is solvable and unique
+    c, info = isopo.transform(torch.from_numpy(K).to(gpu_device), torch.from_numpy(A[0]).to(gpu_device),
+                              "interacting", 0.1)
+    ref, _ = orc.coeff_interacting(K, A[0], 0.1)
+    assert info.item() == 0
+    assert_c_close(c.cpu().numpy(), ref, 1e-5, "regularised singular")
+    # fisher: an all-zero row with reg 0 gives c_i = 0
+    Kz = np.diag([1.0, 0.0, 2.0]).astype(np.float32)
+    c, info = isopo.transform(torch.from_numpy(Kz).to(gpu_device), torch.from_numpy(A[0]).to(gpu_device), "fisher", 0.0)
+    assert c.cpu().numpy()[1] == 0.0 and np.all(np.isfinite(c.cpu().numpy()))
+
+
+def test_bad_arguments_on_device_calls(gpu_device):
+    prob = wl.custom_layer(128, 128, [10, 20], dtype="bf16", seed=9)
+    layer, A = to_device(prob, gpu_device)
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.layer_gram(layer, "ghost", keep_stash=True)
+    assert e.value.status == 1
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.transform(torch.eye(4, device=gpu_device), torch.ones(4, device=gpu_device), "interacting", -1.0)
+    assert e.value.status == 1
+    K = torch.eye(200, device=gpu_device)
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.transform(K, torch.ones(200, device=gpu_device), "interacting", 0.1,
+                        workspace=isopo.alloc_workspace(1024, gpu_device))
+    assert e.value.status == 4

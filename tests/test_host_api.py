@@ -1,0 +1,102 @@
+"""Host-side checks that need no GPU: the library loads, exports what the
+header declares, validates arguments and plans the Gram path."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2512_23353_amd import isopo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _host_layer(lengths, d_in, d_out, dtype=isopo.BF16):
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    return isopo.Layer(None, None, off, d_in=d_in, d_out=d_out, dtype=dtype, n_tokens=int(off[-1]))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = isopo.load()
+    header = open(os.path.join(ROOT, "include", "isopo.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(isopo_[a-z_]+)\s*\(", header))
+    assert declared == set(isopo.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert isopo.version() == "0.1"
+    assert isopo.status_string(0) == "ok"
+    assert "offset" in isopo.status_string(2)
+
+
+def test_offsets_validation():
+    lay = _host_layer([3, 4], 64, 64)
+    assert isopo.gram_plan(lay)[0] in ("ghost", "materialised")
+    for bad in ([1, 3, 7], [0, 5, 3, 7], [0, 3, 6]):
+        lay = isopo.Layer(None, None, np.array(bad, dtype=np.int32), d_in=64, d_out=64, dtype=isopo.BF16, n_tokens=7)
+        with pytest.raises(isopo.IsopoError) as e:
+            isopo.gram_plan(lay)
+        assert e.value.status == 2
+    # zero-length sequences are legal
+    assert isopo.gram_plan(_host_layer([0, 5, 0], 64, 64))[0] in ("ghost", "materialised")
+
+
+def test_shape_and_dtype_validation():
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.gram_plan(_host_layer([4], 60, 64))          # d_in not a multiple of 8 for bf16
+    assert e.value.status == 3
+    assert isopo.gram_plan(_host_layer([4], 60, 64, isopo.F32))[0]   # fine for fp32 (multiple of 4)
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.gram_plan(_host_layer([4], 64, 64, dtype=7))
+    assert e.value.status == 3
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.gram_plan(_host_layer([1] * (isopo.MAX_SEQ + 1), 64, 64))
+    assert e.value.status == 3
+
+
+def test_null_device_pointers_rejected_before_any_launch():
+    lay = _host_layer([3, 4], 64, 64)
+    lib = isopo.load()
+    st = lib.isopo_layer_gram(lay.ref(), isopo.GRAM_AUTO, None, None, 0, 0, None)
+    assert st == 1
+    st = lib.isopo_weighted_grad(lay.ref(), None, None, 0.0, None, None)
+    assert st == 1
+    st = lib.isopo_transform(None, None, 4, 1, 0, 0.0, 0, None, None, None, 0, None)
+    assert st == 1
+    assert lib.isopo_layer_gram_plan(None, 0, None, None, None) == 1
+
+
+def test_plan_workspace_sizes():
+    lay = _host_layer([300, 200, 100], 512, 1024)
+    path, full, mn = isopo.gram_plan(lay, "materialised")
+    assert path == "materialised"
+    stash = 3 * 1024 * 512 * 2
+    assert full >= stash and mn < full and mn >= 3 * 256 * 512 * 2
+    path, full, mn = isopo.gram_plan(lay, "ghost")
+    assert path == "ghost" and full == mn and full >= 9 * 8 + 600 * 4
+    lay32 = _host_layer([300, 200, 100], 512, 1024, isopo.F32)
+    assert isopo.gram_plan(lay32, "materialised")[1] >= 2 * stash
+    assert isopo.transform_workspace(128) == 0
+    assert isopo.transform_workspace(256, 3) == 3 * (256 * 256 + 256) * 8
+
+
+def test_cost_model_prefers_ghost_only_for_few_tokens():
+    """Ghost costs ~N^2 (d_in + d_out), materialised ~2 N d_in d_out plus the
+    stash traffic: ghost must win for a handful of tokens on a wide layer and
+    lose for a long microbatch, and the modelled costs must order the same way
+    as the AUTO choice."""
+    small = _host_layer([16, 24, 8, 16], 4096, 14336)
+    big = _host_layer([2048] * 32, 4096, 14336)
+    assert isopo.gram_plan(small)[0] == "ghost"
+    assert isopo.gram_plan(big)[0] == "materialised"
+    for lay in (small, big):
+        tg, tm = isopo.gram_cost_model(lay)
+        assert tg > 0 and tm > 0
+        assert (isopo.gram_plan(lay)[0] == "ghost") == (tg < tm)
+    # monotone: adding tokens never makes ghost relatively cheaper
+    ratios = []
+    for t in (8, 64, 512, 4096):
+        tg, tm = isopo.gram_cost_model(_host_layer([t] * 8, 1536, 8960))
+        ratios.append(tg / tm)
+    assert all(a < b for a, b in zip(ratios, ratios[1:]))
