@@ -222,6 +222,16 @@ def weighted_grad(G, c, dW_in=None, beta: float = 0.0) -> np.ndarray:
     return dW
 
 
+def weighted_grad_abs(G, c) -> np.ndarray:
+    """sum_i |c_i| |G_i|, element-wise: the scale against which rounding of the
+    terms of dW = sum_i c_i G_i is measured when they cancel."""
+    c = np.abs(np.asarray(c, dtype=np.float64))
+    S = np.zeros(G.shape[1:], dtype=np.float64)
+    for i in range(G.shape[0]):
+        S += c[i] * np.abs(G[i])
+    return S
+
+
 def weighted_grad_tokens(X, Delta, seq_offsets, c, rows=None) -> np.ndarray:
     """The same contraction written over token rows:
     dW = Delta^T diag(c_tok) X with c_tok[t] = c_{seq(t)}."""
@@ -234,11 +244,13 @@ def weighted_grad_tokens(X, Delta, seq_offsets, c, rows=None) -> np.ndarray:
     return (Delta[:, r0:r1] * c_tok[:, None]).T @ X
 
 
-def weighted_grad_entry(X, Delta, seq_offsets, c, o: int, k: int) -> float:
-    """One element dW[o, k] = sum_t c_tok[t] Delta[t, o] X[t, k]."""
+def weighted_grad_entry(X, Delta, seq_offsets, c, o: int, k: int):
+    """One element dW[o, k] = sum_t c_tok[t] Delta[t, o] X[t, k], and the sum of
+    the absolute values of its terms."""
     off = check_offsets(seq_offsets, np.asarray(X).shape[0])
     c_tok = np.repeat(np.asarray(c, dtype=np.float64), np.diff(off))
-    return float(np.sum(c_tok * widen(np.asarray(Delta)[:, o]) * widen(np.asarray(X)[:, k])))
+    terms = c_tok * widen(np.asarray(Delta)[:, o]) * widen(np.asarray(X)[:, k])
+    return float(np.sum(terms)), float(np.sum(np.abs(terms)))
 
 
 def layer_step(X, Delta, seq_offsets, A, variant: str, lam: float,
@@ -266,15 +278,17 @@ def layer_step(X, Delta, seq_offsets, A, variant: str, lam: float,
         raise ValueError("variant must be 'fisher' or 'interacting'")
     dW = np.zeros((d_out, Xw.shape[1]), dtype=np.float64)
     dW_R = np.zeros_like(dW)
+    dW_abs = np.zeros_like(dW)
     if info == 0:
         for r0 in range(0, d_out, step):
             r1 = min(d_out, r0 + step)
             G = seq_logprob_grads(Xw, Dw, off, rows=(r0, r1))
             dW[r0:r1] = weighted_grad(G, c)
             dW_R[r0:r1] = weighted_grad(G, A)
+            dW_abs[r0:r1] = weighted_grad_abs(G, c)
         if dW_in is not None and beta != 0.0:
             dW += beta * np.asarray(dW_in, dtype=np.float64)
     else:
         dW[:] = np.nan
-    return {"K": K, "c": c, "info": info, "dW": dW, "dW_reinforce": dW_R,
+    return {"K": K, "c": c, "info": info, "dW": dW, "dW_reinforce": dW_R, "dW_abs": dW_abs,
             "reg_eff": effective_reg(K, lam, reg_mode)}

@@ -32,11 +32,20 @@ def assert_c_close(c, c_ref, tol, what=""):
     assert np.max(np.abs(c - c_ref)) <= tol * np.max(np.abs(c_ref)) + 1e-300, f"{what}: c element guard"
 
 
-def assert_dW_close(dW, dW_ref, tol, what=""):
+def assert_dW_close(dW, dW_ref, tol, what="", dW_abs=None):
+    """Norm-wise tolerance plus an element guard.  Rounding of the terms of
+    dW = sum_i c_i G_i (bf16 stash, bf16 pre-scaled Delta) is relative to the
+    terms, not to their possibly cancelling sum, and X has outlier channels 20x
+    the rest, so the guard is tol * (sum_i |c_i G_i| + its mean) where the
+    oracle provides that scale, else 8 tol rms(dW)."""
     dW = np.asarray(dW, dtype=np.float64)
     assert rel_err(dW, dW_ref) <= tol, f"{what}: dW rel err {rel_err(dW, dW_ref):.3e} > {tol}"
-    rms = np.sqrt(np.mean(dW_ref ** 2))
-    assert np.max(np.abs(dW - dW_ref)) <= 8 * tol * rms + 1e-300, f"{what}: dW element guard"
+    if dW_abs is not None:
+        guard = tol * (dW_abs + dW_abs.mean())
+    else:
+        guard = 8 * tol * np.sqrt(np.mean(dW_ref ** 2))
+    bad = np.abs(dW - dW_ref) > guard + 1e-300
+    assert not bad.any(), f"{what}: dW element guard at {np.argwhere(bad)[:4].tolist()}"
 
 
 def oracle_step(prob, variant, lam, reg_mode=0, chunk_rows=None, dW_in=None, beta=0.0):

@@ -260,7 +260,12 @@ def test_p12_weighted_grad_two_ways():
         for t in range(off[i], off[i + 1]):
             brute += c[i] * np.outer(D[t], X[t])
     np.testing.assert_allclose(dW, brute, rtol=1e-12, atol=1e-15)
-    assert orc.weighted_grad_entry(X, D, off, c, 2, 3) == pytest.approx(dW[2, 3], rel=1e-12)
+    val, mag = orc.weighted_grad_entry(X, D, off, c, 2, 3)
+    assert val == pytest.approx(dW[2, 3], rel=1e-12)
+    assert mag == pytest.approx(sum(abs(c[i] * D[t, 2] * X[t, 3]) for i in range(4) for t in range(off[i], off[i + 1])))
+    S = orc.weighted_grad_abs(G, c)
+    assert np.all(S >= np.abs(dW) - 1e-15)
+    np.testing.assert_allclose(orc.weighted_grad_abs(np.abs(G), np.abs(c)), orc.weighted_grad(np.abs(G), np.abs(c)))
     np.testing.assert_allclose(orc.weighted_grad_tokens(X, D, off, c, rows=(2, 5)), dW[2:5], rtol=1e-12, atol=1e-15)
     dW0 = rng.standard_normal((7, 6))
     np.testing.assert_allclose(orc.weighted_grad(G, c, dW0, 0.5), dW + 0.5 * dW0, rtol=1e-13)
