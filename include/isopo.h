@@ -109,6 +109,20 @@ isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, do
 isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, float* K,
                               void* workspace, size_t ws_bytes, int keep_stash, void* stream);
 
+/* The two halves of the MATERIALISED path on their own.
+ *
+ * isopo_seq_grads: stash[i] = G_i = Delta_i^T X_i for every sequence
+ * (`seq_grads.append(grad_out.T @ act_in)`), [n_seq, d_out, d_in] in the input
+ * dtype (fp32 accumulation, one rounding for bf16).
+ *
+ * isopo_stash_gram: K_ij = sum(G_i * G_j) from such a stash
+ * (`ntk[i, j] = torch.sum(seq_grads[i] * seq_grads[j])`), n_elem = d_out * d_in
+ * elements per sequence.  workspace >= isopo_stash_gram_workspace(n_seq). */
+isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream);
+size_t isopo_stash_gram_workspace(int32_t n_seq);
+isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_seq, int64_t n_elem, float* K,
+                              void* workspace, size_t ws_bytes, void* stream);
+
 /* Bytes of device workspace isopo_transform needs (0 for n_seq <= 128). */
 size_t isopo_transform_workspace(int32_t n_seq, int32_t batch);
 

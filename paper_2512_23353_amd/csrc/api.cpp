@@ -212,6 +212,39 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
   return launch_stash_gram_finish(partials, layer->n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
+isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream) {
+  isopo_status st = check_layer(layer, true);
+  if (st != ISOPO_OK) return st;
+  if (!stash || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
+  SeqGradArgs a;
+  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.c = nullptr;
+  a.out = stash; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq;
+  a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0;
+  a.out_seq_stride = (long long)layer->d_out * layer->d_in;
+  a.beta = 0.f; a.per_sequence = true; a.bf16 = layer->dtype == ISOPO_BF16;
+  return launch_seq_grad(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+size_t isopo_stash_gram_workspace(int32_t n_seq) {
+  if (n_seq <= 0) return 0;
+  return align_up((size_t)stash_gram_slots() * stash_gram_slot_floats(n_seq) * sizeof(float));
+}
+
+isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_seq, int64_t n_elem, float* K,
+                              void* workspace, size_t ws_bytes, void* stream) {
+  if (!stash || !K || !workspace || n_seq <= 0 || n_elem <= 0 || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
+  if (dtype != ISOPO_F32 && dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  if (n_seq > kMaterialisedMaxSeq || n_elem % (dtype == ISOPO_BF16 ? 8 : 4)) return ISOPO_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return ISOPO_ERR_INVALID_ARG;
+  if (ws_bytes < isopo_stash_gram_workspace(n_seq)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  StashGramArgs g;
+  g.stash = stash; g.seq_stride = n_elem; g.p0 = 0; g.p1 = n_elem; g.n_seq = n_seq;
+  g.bf16 = dtype == ISOPO_BF16; g.first = true; g.partials = static_cast<float*>(workspace);
+  if (launch_stash_gram(g, s) != hipSuccess) return ISOPO_ERR_HIP;
+  return launch_stash_gram_finish(g.partials, n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
 size_t isopo_transform_workspace(int32_t n_seq, int32_t batch) {
   if (n_seq <= kTransformLdsMax || batch <= 0) return 0;
   return (size_t)batch * ((size_t)n_seq * n_seq + n_seq) * sizeof(double);

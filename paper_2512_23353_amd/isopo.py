@@ -27,7 +27,8 @@ _VARIANTS = {"fisher": VARIANT_FISHER, "interacting": VARIANT_INTERACTING}
 _PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALISED}
 _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
-EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_transform_workspace",
+EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_seq_grads",
+           "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_status_string", "isopo_version")
 
 
@@ -65,6 +66,12 @@ def load() -> ctypes.CDLL:
     lib.isopo_gram_cost_model.restype = ctypes.c_int
     lib.isopo_layer_gram.argtypes = [lp, ctypes.c_int, vp, vp, sz, ctypes.c_int, vp]
     lib.isopo_layer_gram.restype = ctypes.c_int
+    lib.isopo_seq_grads.argtypes = [lp, vp, vp]
+    lib.isopo_seq_grads.restype = ctypes.c_int
+    lib.isopo_stash_gram_workspace.argtypes = [i32]
+    lib.isopo_stash_gram_workspace.restype = sz
+    lib.isopo_stash_gram.argtypes = [vp, ctypes.c_int, i32, ctypes.c_int64, vp, vp, sz, vp]
+    lib.isopo_stash_gram.restype = ctypes.c_int
     lib.isopo_transform_workspace.argtypes = [i32, i32]
     lib.isopo_transform_workspace.restype = sz
     lib.isopo_transform.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, ctypes.c_int, vp, vp, vp, sz, vp]
@@ -169,6 +176,33 @@ def layer_gram(layer: Layer, path="auto", K: Optional[torch.Tensor] = None,
     _check(load().isopo_layer_gram(layer.ref(), _PATHS[path], K.data_ptr(), workspace.data_ptr(),
                                    workspace.numel(), int(keep_stash), _stream(stream)), "isopo_layer_gram")
     return K, workspace
+
+
+def stash_nbytes(layer: Layer) -> int:
+    return layer.n_seq * layer.d_out * layer.d_in * (2 if layer.dtype == BF16 else 4)
+
+
+def seq_grads(layer: Layer, stash: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """The stash of per-sequence gradients [n_seq, d_out, d_in] in the input dtype."""
+    if stash is None:
+        stash = torch.empty((layer.n_seq, layer.d_out, layer.d_in), dtype=layer.X.dtype, device=layer.device)
+    _check(load().isopo_seq_grads(layer.ref(), stash.data_ptr(), _stream(stream)), "isopo_seq_grads")
+    return stash
+
+
+def stash_gram(stash: torch.Tensor, K: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+               stream=None) -> torch.Tensor:
+    """K from a stash [n_seq, d_out, d_in] (or any [n_seq, n_elem] view of it)."""
+    n_seq = stash.shape[0]
+    n_elem = stash.numel() // n_seq
+    if K is None:
+        K = torch.empty((n_seq, n_seq), dtype=torch.float32, device=stash.device)
+    if workspace is None:
+        workspace = alloc_workspace(load().isopo_stash_gram_workspace(n_seq), stash.device)
+    dtype = BF16 if stash.dtype == torch.bfloat16 else F32
+    _check(load().isopo_stash_gram(stash.data_ptr(), dtype, n_seq, n_elem, K.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel(), _stream(stream)), "isopo_stash_gram")
+    return K
 
 
 def transform_workspace(n_seq: int, batch: int = 1) -> int:
