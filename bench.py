@@ -90,7 +90,7 @@ def main() -> int:
 
     def reinforce_step():
         for l, dW in zip(layers, dWs):
-            isopo.weighted_grad(l, A, None, 0.0, dW, stream=stream)
+            isopo.weighted_grad(l, None, None, 0.0, dW, stream=stream)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -151,7 +151,7 @@ def main() -> int:
         "algorithmic_flops_per_step": total_flops,
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
-                      "what": "this library's own dW = Delta^T diag(A) X over the same 7 projections", **context},
+                      "what": "this library's own unweighted dW = Delta^T X over the same 7 projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
         "roofline": {"bound": "mfma", "kernel": "seq_grad_kernel (per-sequence gradients -> stash)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,

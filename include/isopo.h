@@ -138,11 +138,15 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
                              void* stream);
 
 /* dW [d_out, d_in] fp32 = beta * dW + sum_i c_i G_i.
- *   stash  NULL: contract X and Delta again, dW = Delta^T diag(c_tok) X (with
- *          c = A this is the plain REINFORCE gradient).  bf16 inputs: the
- *          scaled rows c_tok[t] * Delta[t,:] are rounded to bf16 before the
- *          MFMA, as a bf16 pre-scaling of Delta would.
- *          non-NULL: the stash isopo_layer_gram left (keep_stash), read once. */
+ *   stash  NULL: contract X and Delta again, dW = Delta^T diag(c_tok) X.
+ *          bf16 inputs: the scaled rows c_tok[t] * Delta[t,:] are rounded to
+ *          bf16 before the MFMA, as a bf16 pre-scaling of Delta would.
+ *          non-NULL: the stash isopo_layer_gram left (keep_stash), read once.
+ *   c      device [n_seq].  NULL (only with stash == NULL) means all ones:
+ *          dW = beta dW + Delta^T X with no scaling pass at all.  That is the
+ *          plain REINFORCE weight gradient when the advantages were folded into
+ *          the loss (so Delta already carries them), and it is the baseline the
+ *          layer step's overhead is measured against. */
 isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash,
                                  float beta, float* dW, void* stream);
 

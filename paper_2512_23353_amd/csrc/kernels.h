@@ -15,9 +15,9 @@ struct SeqGradArgs {
   const void* X;
   const void* Delta;
   const int32_t* off;        // device [n_seq+1]
-  const float* c;            // device [n_seq] (weighted mode only)
+  const float* c;            // device [n_seq]; nullptr = unweighted (all ones)
   void* out;                 // stash (input dtype) or dW (fp32)
-  int d_in, d_out, n_seq;
+  int d_in, d_out, n_seq, n_tokens;
   int row0, rows;            // output rows [row0, row0+rows) of d_out handled by this launch
   int out_row0;              // output row o is stored at row (o - out_row0)
   long long out_seq_stride;  // elements between consecutive sequences' outputs (per_sequence)
@@ -26,6 +26,8 @@ struct SeqGradArgs {
   bool bf16;
 };
 hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s);
+// bf16 only, c == nullptr only: the direct-to-LDS streaming kernel (launch_seq_grad routes to it).
+hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s);
 
 // K partials from the stash:  for p in [p0, p1):  acc[i][j] += S[i][p] * S[j][p].
 struct StashGramArgs {

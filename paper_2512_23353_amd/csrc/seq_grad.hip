@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void seq_grad_kernel(SeqGradParams p) {
       if (++seq >= seq_end) return false;
       t = p.off[seq];
       t_end = p.off[seq + 1];
-      if constexpr (WEIGHTED) scale = p.c[seq];
+      if constexpr (WEIGHTED) scale = p.c ? p.c[seq] : 1.f;
     }
     bt0 = t;
     bt1 = t_end;
@@ -274,6 +274,7 @@ hipError_t launch_cfg(const SeqGradArgs& a, hipStream_t s) {
 
 hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s) {
   typedef unsigned short bf;
+  if (a.bf16 && (a.per_sequence || a.c == nullptr)) return launch_seq_grad_stream(a, s);
   if (a.bf16) {
     const bool small = (a.rows <= 128 || a.d_in <= 128);
     if (a.per_sequence)

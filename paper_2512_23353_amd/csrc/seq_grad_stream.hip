@@ -1,0 +1,315 @@
+// Token-reduction contraction, bf16, streaming variant: the kernel behind the
+// per-sequence gradients G_i = Delta_i^T X_i (`grad_out.T @ act_in` of both hook
+// listings) and behind the unweighted dW = Delta^T X.
+//
+// Design (gfx950):
+//  * Operand tiles go from HBM/L2 straight into LDS with buffer_load ... lds
+//    (16 bytes per lane, no VGPR staging, no LDS-write instructions).  The
+//    buffer descriptor covers exactly the rows of the current token block, so
+//    rows past the end of a sequence are out of range and arrive as zeros:
+//    ragged tails cost no branches.
+//  * LDS holds a ring of NSTAGE token blocks ([token][feature], the HBM layout).
+//    NSTAGE-1 blocks are in flight while one is multiplied; one s_barrier per block.
+//  * MFMA fragments need 8 consecutive tokens of one feature per lane; they come
+//    from the LDS transpose read (ds_read_b64_tr_b16).  Rows are not padded:
+//    the 16-byte column index is XOR-swizzled with the token row
+//    (f(r) = 4*(r&3) ^ (r&2)), which makes both the linear DMA writes and the
+//    transpose reads bank-conflict free.
+//  * Fragments are double-buffered in registers and the reads of the next half
+//    block are interleaved one-to-one with the MFMAs of the current one.
+//  * Per-sequence mode: XCD x owns the x-th eighth of the output tiles of every
+//    sequence, so all eight L2s see every sequence (balanced under ragged
+//    lengths) and neighbouring workgroups share operand panels.  The bf16 tile is
+//    transposed through LDS in the epilogue so that every lane stores 16 bytes.
+#include "common.h"
+#include "kernels.h"
+
+namespace isopo {
+namespace {
+
+typedef unsigned short u16;
+typedef s16x4 __attribute__((address_space(3)))* lds_s16x4_ptr;
+typedef void __attribute__((address_space(3)))* lds_void_ptr;
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+struct StreamParams {
+  const u16* X;
+  const u16* Delta;
+  const int32_t* off;
+  void* out;
+  int d_in, d_out, n_seq, n_tokens;
+  int row0, row_end, out_row0;
+  long long out_seq_stride;
+  float beta;
+  int tiles_m, tiles_n;
+  unsigned n_blocks;
+};
+
+// Raw buffer descriptor over [base, base + bytes): loads beyond it return zero.
+__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
+  const unsigned long long a = (unsigned long long)base;
+  v4i r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+  r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
+
+// 16 bytes per lane from a buffer straight into LDS: lane l lands at lds_addr + 16*l.
+// Inline asm, so that the compiler's LDS-DMA tracking does not put a vmcnt(0) before
+// every later LDS read; the kernel orders them itself with s_waitcnt vmcnt(n) + s_barrier.
+__device__ __forceinline__ void load_lds16(v4i rsrc, unsigned lds_addr, unsigned voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               : : "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+}
+
+constexpr int BK = 32;
+
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
+__global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
+  constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
+  constexpr unsigned PA = BM * 2, PB = BN * 2;                 // LDS row pitch, bytes (no padding: swizzled)
+  constexpr unsigned A_BYTES = BK * PA, B_BYTES = BK * PB, STAGE = A_BYTES + B_BYTES;
+  constexpr int LA = A_BYTES / 1024 / 4, LB = B_BYTES / 1024 / 4;   // 1 KiB wave-loads per wave and tile
+  constexpr int RA = 1024 / PA, RB = 1024 / PB;                // tile rows per wave-load
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int item, tile;
+  if (PER_SEQ) {
+    // XCD x (= blockIdx % 8) owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int x = blockIdx.x & 7, e = blockIdx.x >> 3;
+    const int s0 = x * tiles / 8, cs = (x + 1) * tiles / 8 - s0;
+    if (cs == 0 || e >= p.n_seq * cs) return;
+    item = e / cs;
+    tile = s0 + e % cs;
+  } else {
+    item = 0;
+    tile = xcd_contiguous(blockIdx.x, p.n_blocks);
+  }
+  const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
+  const int m0 = p.row0 + tile_m * BM, n0 = tile_n * BN;
+  const int t0 = PER_SEQ ? p.off[item] : 0;
+  const int t1 = PER_SEQ ? p.off[item + 1] : p.n_tokens;
+  const int n_rows = t1 - t0;
+  const int n_tiles = (n_rows + BK - 1) / BK;
+  const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
+
+  unsigned offA[LA], offB[LB];
+#pragma unroll
+  for (int q = 0; q < LA; ++q) {
+    const int r = (wave * LA + q) * RA + lane / (64 / RA);
+    const int f = ((r & 3) << 2) ^ (r & 2);
+    const int g = (lane % (64 / RA)) ^ f;
+    offA[q] = (unsigned)r * rbA + (unsigned)(m0 * 2 + g * 16);
+  }
+#pragma unroll
+  for (int q = 0; q < LB; ++q) {
+    const int r = (wave * LB + q) * RB + lane / (64 / RB);
+    const int f = ((r & 3) << 2) ^ (r & 2);
+    const int g = (lane % (64 / RB)) ^ f;
+    offB[q] = (unsigned)r * rbB + (unsigned)(n0 * 2 + g * 16);
+  }
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const u16* baseA = p.Delta + (size_t)t0 * p.d_out;
+  const u16* baseB = p.X + (size_t)t0 * p.d_in;
+  auto issue_loads = [&](int it) {
+    int rows = n_rows - it * BK;
+    rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+    v4i ra = make_rsrc(baseA + (size_t)it * BK * p.d_out, (unsigned)rows * rbA);
+    v4i rb = make_rsrc(baseB + (size_t)it * BK * p.d_in, (unsigned)rows * rbB);
+    const unsigned stage = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+#pragma unroll
+    for (int q = 0; q < LA; ++q) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
+#pragma unroll
+    for (int q = 0; q < LB; ++q) load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + q) * 1024, offB[q]);
+  };
+
+  unsigned adA[FM], adB[FN];
+  {
+    const int l = lane & 15, g4 = lane >> 4;
+    const int kr = 8 * (g4 >> 1) + (l >> 2);
+    const int f = ((kr & 3) << 2) ^ (kr & 2);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int ca = wm * WM + i * 32 + 16 * (g4 & 1) + 4 * (l & 3);
+      adA[i] = (unsigned)kr * PA + (unsigned)(((ca >> 3) ^ f) << 4) + (unsigned)((ca & 7) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int cb = wn * WN + j * 32 + 16 * (g4 & 1) + 4 * (l & 3);
+      adB[j] = A_BYTES + (unsigned)kr * PB + (unsigned)(((cb >> 3) ^ f) << 4) + (unsigned)((cb & 7) * 2);
+    }
+  }
+  auto frA = [&](unsigned a) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PA));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto frB = [&](unsigned a) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PB));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+  constexpr int LPT = LA + LB;   // loads per wave and tile
+  constexpr int NRD = 2 * (FM + FN), NMF = FM * FN;
+
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s) issue_loads(s);
+
+  if (n_tiles > 0) {
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 2) * LPT) & 15) | ((((NSTAGE - 2) * LPT) >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa0[i] = frA(smem_base + adA[i]);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) fb0[j] = frB(smem_base + adB[j]);
+    for (int it = 0; it < n_tiles; ++it) {
+      const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa1[i] = frA(sb + adA[i] + 16 * PA);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb1[j] = frB(sb + adB[j] + 16 * PB);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+      }
+      __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 3) * LPT) & 15) | ((((NSTAGE - 3) * LPT) >> 4) << 14));
+      __builtin_amdgcn_s_barrier();
+      issue_loads(it + NSTAGE - 1);
+      const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa0[i] = frA(sn + adA[i]);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb0[j] = frB(sn + adB[j]);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+
+  if (PER_SEQ) {
+    __builtin_amdgcn_s_barrier();
+    constexpr unsigned PT = 80;
+    const unsigned W = smem_base + (unsigned)wave * 8192;
+    const int h = lane >> 5, nl = lane & 31;
+    const int l = lane & 15, gq = lane >> 4;
+    u16* outp = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int jp = 0; jp < FN / 2; ++jp) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const int j = jp * 2 + jj;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            v2u pk;
+            pk.x = (unsigned)f32_to_bf16_bits(acc[i][j][4 * g]) | ((unsigned)f32_to_bf16_bits(acc[i][j][4 * g + 1]) << 16);
+            pk.y = (unsigned)f32_to_bf16_bits(acc[i][j][4 * g + 2]) | ((unsigned)f32_to_bf16_bits(acc[i][j][4 * g + 3]) << 16);
+            const unsigned a = W + (unsigned)(jj * 32 + nl) * PT + (unsigned)(8 * g + 4 * h) * 2;
+            *(v2u __attribute__((address_space(3)))*)(a) = pk;
+          }
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int rb = s >> 1, pc = (s & 1) * 4 + gq;
+          const unsigned a = W + (unsigned)(8 * pc + (l >> 2)) * PT + (unsigned)(16 * rb + 4 * (l & 3)) * 2;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PT));
+          const int m = m0 + wm * WM + i * 32 + 16 * rb + l;
+          const int n = n0 + wn * WN + jp * 64 + 8 * pc;
+          if (m < p.row_end && n < p.d_in)
+            *(s16x8*)(outp + (size_t)(m - p.out_row0) * p.d_in + n) =
+                __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+      }
+    }
+  } else {
+    const int col = lane & 31;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + col;
+        if (n >= p.d_in) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (m >= p.row_end) continue;
+          float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
+          *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
+        }
+      }
+  }
+}
+
+
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
+hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
+  StreamParams p;
+  p.X = static_cast<const u16*>(a.X); p.Delta = static_cast<const u16*>(a.Delta); p.off = a.off; p.out = a.out;
+  p.d_in = a.d_in; p.d_out = a.d_out; p.n_seq = a.n_seq; p.n_tokens = a.n_tokens;
+  p.row0 = a.row0; p.row_end = a.row0 + a.rows; p.out_row0 = a.out_row0;
+  p.out_seq_stride = a.out_seq_stride; p.beta = a.beta;
+  p.tiles_m = (a.rows + BM - 1) / BM;
+  p.tiles_n = (a.d_in + BN - 1) / BN;
+  const long long tiles = (long long)p.tiles_m * p.tiles_n;
+  const long long blocks = PER_SEQ ? 8LL * a.n_seq * ((tiles + 7) / 8) : tiles;
+  if (blocks <= 0) return hipSuccess;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  p.n_blocks = (unsigned)blocks;
+  constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
+  constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
+  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// bf16, unscaled (per-sequence stash, or plain sum over all tokens).
+hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
+  const long long big_tiles = (long long)((a.rows + 255) / 256) * ((a.d_in + 255) / 256) * (a.per_sequence ? a.n_seq : 1);
+  const bool big = a.rows >= 256 && a.d_in >= 256 && big_tiles >= 256;
+  if (a.per_sequence)
+    return big ? launch_stream<256, 256, 4, 1, true>(a, s) : launch_stream<128, 128, 4, 2, true>(a, s);
+  return big ? launch_stream<256, 256, 4, 1, false>(a, s) : launch_stream<128, 128, 4, 2, false>(a, s);
+}
+
+}  // namespace isopo

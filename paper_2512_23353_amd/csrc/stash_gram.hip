@@ -10,18 +10,19 @@
 // fragments are the same registers: a wave loads one 16-byte piece per lane and
 // row block and issues mfma(a_i, a_j) for every block pair i <= j.
 //
-// Determinism: every wave owns one slot of a partial buffer, the p -> wave
-// assignment is a fixed formula, and the finishing kernel adds the slots in
-// index order; K is bit-reproducible and exactly symmetric.
+// Determinism: the p -> wave assignment is a fixed formula, the four waves of a
+// workgroup are added in wave order through LDS into the workgroup's slot of a
+// partial buffer, and the finishing kernel adds the slots in a fixed tree; K is
+// bit-reproducible and exactly symmetric.
 #include "common.h"
 #include "kernels.h"
 
 namespace isopo {
 namespace {
 
-constexpr int kGramBlocks = 512;            // workgroups of the streaming kernel
+constexpr int kGramBlocks = 1024;           // workgroups of the streaming kernel (4 per CU)
 constexpr int kGramWaves = 4;               // waves per workgroup
-constexpr int kGramSlots = kGramBlocks * kGramWaves;
+constexpr int kGramSlots = kGramBlocks;     // one partial slot per workgroup
 constexpr int kMaxRowBlocks = 4;            // 32-row blocks a single wave keeps pairs for (n_seq <= 128)
 
 __host__ __device__ constexpr int tri(int nb) { return nb * (nb + 1) / 2; }
@@ -37,17 +38,18 @@ struct GramParams {
   long long slot_floats;
 };
 
-// One wave handles "super steps" of 4 consecutive 32-byte-per-row pieces (128 B
-// of every row), so each row's cache line is consumed by one wave.
+// One wave handles "super steps" of kSuper consecutive 32-byte-per-row pieces, so
+// that each row is read in runs of kSuper*32 bytes and kSuper*NB loads are in flight.
 template <int NB, bool BF16>
 __global__ __launch_bounds__(256) void stash_gram_kernel(GramParams p) {
   constexpr int kElemPerVec = BF16 ? 8 : 4;           // per 16-byte lane load
   constexpr int kStepElems = 2 * kElemPerVec;         // per row and micro step (two lane halves)
-  constexpr int kSuper = 4;                           // micro steps per super step
+  constexpr int kSuper = NB == 1 ? 16 : (NB == 2 ? 8 : 4);
+  __shared__ float red[tri(NB) * 1024];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 31, half = lane >> 5;
-  const long long slot = (long long)blockIdx.x * kGramWaves + wave;
-  const long long n_slots = (long long)gridDim.x * kGramWaves;
+  const long long gw = (long long)blockIdx.x * kGramWaves + wave;
+  const long long n_waves = (long long)gridDim.x * kGramWaves;
 
   f32x16 acc[tri(NB)];
 #pragma unroll
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(256) void stash_gram_kernel(GramParams p) {
 
   const long long n_elems = p.p1 - p.p0;
   const long long n_super = (n_elems + kSuper * kStepElems - 1) / (kSuper * kStepElems);
-  for (long long u = slot; u < n_super; u += n_slots) {
+  for (long long u = gw; u < n_super; u += n_waves) {
     uint4 frag[NB][kSuper];
 #pragma unroll
     for (int q = 0; q < kSuper; ++q) {
@@ -99,30 +101,48 @@ __global__ __launch_bounds__(256) void stash_gram_kernel(GramParams p) {
     }
   }
 
-  // slot layout: [pair][v][lane]
-  float* out = p.partials + slot * p.slot_floats;
+  // waves 0..3 added in order; layout [pair][v][lane]
+  for (int w = 0; w < kGramWaves; ++w) {
+    if (wave == w) {
 #pragma unroll
-  for (int q = 0; q < tri(NB); ++q)
+      for (int q = 0; q < tri(NB); ++q)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      float* o = out + (q * 16 + v) * 64 + lane;
-      *o = (p.first ? 0.f : *o) + acc[q][v];
+        for (int v = 0; v < 16; ++v) {
+          float* o = red + (q * 16 + v) * 64 + lane;
+          *o = (w == 0 ? 0.f : *o) + acc[q][v];
+        }
     }
+    __syncthreads();
+  }
+  float* out = p.partials + (long long)blockIdx.x * p.slot_floats;
+  for (int e = threadIdx.x; e < tri(NB) * 1024; e += 256) out[e] = (p.first ? 0.f : out[e]) + red[e];
 }
 
-__global__ void stash_gram_finish_kernel(const float* __restrict__ partials, int n_slots, long long slot_floats,
-                                         int n_seq, int nb, float* __restrict__ K) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= n_seq * n_seq) return;
-  const int i = idx / n_seq, j = idx % n_seq;
-  if (i > j) return;
-  const int bi = i >> 5, bj = j >> 5, ri = i & 31, cj = j & 31;
-  const int v = 4 * (ri >> 3) + (ri & 3), lane = cj + 32 * ((ri >> 2) & 1);
-  const float* src = partials + ((long long)pair_index(bi, bj, nb) * 16 + v) * 64 + lane;
+// One 1024-thread block per 64 consecutive slot elements: wave w adds slots w, w+16, ... in order,
+// the 16 waves are added in wave order; only entries with i <= j are written, mirrored.
+__global__ __launch_bounds__(1024) void stash_gram_finish_kernel(const float* __restrict__ partials, int n_slots,
+                                                                 long long slot_floats, int n_seq, int nb,
+                                                                 float* __restrict__ K) {
+  __shared__ float red[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long e = (long long)blockIdx.x * 64 + lane;      // element of the slot layout [pair][v][lane]
   float s = 0.f;
-  for (int w = 0; w < n_slots; ++w) s += src[(long long)w * slot_floats];
-  K[(size_t)i * n_seq + j] = s;
-  K[(size_t)j * n_seq + i] = s;
+  for (int w = wave; w < n_slots; w += 16) s += partials[(long long)w * slot_floats + e];
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave != 0) return;
+  s = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) s += red[w][lane];
+  const int q = (int)(e >> 10), v = (int)(e >> 6) & 15;
+  int bi = 0, rem = q;
+  while (rem >= nb - bi) { rem -= nb - bi; ++bi; }
+  const int bj = bi + rem;
+  const int i = bi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), j = bj * 32 + (lane & 31);
+  if (i < n_seq && j < n_seq && i <= j) {
+    K[(size_t)i * n_seq + j] = s;
+    K[(size_t)j * n_seq + i] = s;
+  }
 }
 
 template <bool BF16>
@@ -200,9 +220,9 @@ hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s) {
 
 hipError_t launch_stash_gram_finish(const float* partials, int n_seq, float* K, hipStream_t s) {
   const int nb = (n_seq + 31) / 32;
-  const int n = n_seq * n_seq;
-  hipLaunchKernelGGL(stash_gram_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partials, kGramSlots,
-                     (long long)stash_gram_slot_floats(n_seq), n_seq, nb, K);
+  const long long slot_floats = (long long)stash_gram_slot_floats(n_seq);
+  hipLaunchKernelGGL(stash_gram_finish_kernel, dim3((unsigned)(slot_floats / 64)), dim3(1024), 0, s, partials,
+                     kGramSlots, slot_floats, n_seq, nb, K);
   return hipGetLastError();
 }
 

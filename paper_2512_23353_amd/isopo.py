@@ -230,7 +230,7 @@ def transform(K: torch.Tensor, A: torch.Tensor, variant="fisher", lam: float = 0
     return c, info
 
 
-def weighted_grad(layer: Layer, c: torch.Tensor, stash: Optional[torch.Tensor] = None, beta: float = 0.0,
+def weighted_grad(layer: Layer, c: Optional[torch.Tensor], stash: Optional[torch.Tensor] = None, beta: float = 0.0,
                   dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """dW [d_out, d_in] fp32 = beta dW + sum_i c_i G_i (from the stash if given,
     else by contracting X and Delta again)."""
@@ -238,7 +238,7 @@ def weighted_grad(layer: Layer, c: torch.Tensor, stash: Optional[torch.Tensor] =
         if beta != 0.0:
             raise ValueError("beta != 0 needs an existing dW")
         dW = torch.empty((layer.d_out, layer.d_in), dtype=torch.float32, device=layer.device)
-    _check(load().isopo_weighted_grad(layer.ref(), c.data_ptr(), _ptr(stash), float(beta), dW.data_ptr(),
+    _check(load().isopo_weighted_grad(layer.ref(), _ptr(c), _ptr(stash), float(beta), dW.data_ptr(),
                                       _stream(stream)), "isopo_weighted_grad")
     return dW
 
