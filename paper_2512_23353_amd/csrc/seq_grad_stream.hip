@@ -65,6 +65,23 @@ __device__ __forceinline__ void load_lds16(v4i rsrc, unsigned lds_addr, unsigned
                : : "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
 }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 -> one dword of two bf16 (round to nearest even), one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+
+// Accumulator element -> VGPR at the point of use.  Without this the register allocator copies the
+// whole 256-register tile out of the AGPRs before the epilogue and spills.
+__device__ __forceinline__ float acc_read(float a) {
+  float v;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
 constexpr int BK = 32;
 
 template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
@@ -218,7 +235,14 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 
   if (PER_SEQ) {
     __builtin_amdgcn_s_barrier();
+    // the last MFMAs have retired before the accumulators are read by hand (acc_read is opaque to the
+    // compiler's hazard tracking)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     constexpr unsigned PT = 80;
+    // a 256-register tile lives in AGPRs (one wave per SIMD); smaller tiles stay in VGPRs
+    auto rd = [](float a) {
+      if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
+    };
     const unsigned W = smem_base + (unsigned)wave * 8192;
     const int h = lane >> 5, nl = lane & 31;
     const int l = lane & 15, gq = lane >> 4;
@@ -233,8 +257,8 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             v2u pk;
-            pk.x = (unsigned)f32_to_bf16_bits(acc[i][j][4 * g]) | ((unsigned)f32_to_bf16_bits(acc[i][j][4 * g + 1]) << 16);
-            pk.y = (unsigned)f32_to_bf16_bits(acc[i][j][4 * g + 2]) | ((unsigned)f32_to_bf16_bits(acc[i][j][4 * g + 3]) << 16);
+            pk.x = pack_bf16(rd(acc[i][j][4 * g]), rd(acc[i][j][4 * g + 1]));
+            pk.y = pack_bf16(rd(acc[i][j][4 * g + 2]), rd(acc[i][j][4 * g + 3]));
             const unsigned a = W + (unsigned)(jj * 32 + nl) * PT + (unsigned)(8 * g + 4 * h) * 2;
             *(v2u __attribute__((address_space(3)))*)(a) = pk;
           }
