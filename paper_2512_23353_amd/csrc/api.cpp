@@ -209,7 +209,7 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
     g.n_seq = layer->n_seq; g.bf16 = bf16; g.first = (r0 == 0); g.partials = partials;
     if (launch_stash_gram(g, s) != hipSuccess) return ISOPO_ERR_HIP;
   }
-  return launch_stash_gram_finish(partials, layer->n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+  return launch_stash_gram_finish(partials, bf16, layer->n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
 isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream) {
@@ -242,7 +242,7 @@ isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_se
   g.stash = stash; g.seq_stride = n_elem; g.p0 = 0; g.p1 = n_elem; g.n_seq = n_seq;
   g.bf16 = dtype == ISOPO_BF16; g.first = true; g.partials = static_cast<float*>(workspace);
   if (launch_stash_gram(g, s) != hipSuccess) return ISOPO_ERR_HIP;
-  return launch_stash_gram_finish(g.partials, n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+  return launch_stash_gram_finish(g.partials, g.bf16, n_seq, K, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
 size_t isopo_transform_workspace(int32_t n_seq, int32_t batch) {

@@ -43,7 +43,10 @@ int stash_gram_slots();
 size_t stash_gram_slot_floats(int n_seq);
 hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s);
 // K[i][j] = K[j][i] = sum over slots (fixed order) of the (i<=j) entry.
-hipError_t launch_stash_gram_finish(const float* partials, int n_seq, float* K, hipStream_t s);
+hipError_t launch_stash_gram_finish(const float* partials, bool bf16, int n_seq, float* K, hipStream_t s);
+// bf16 stash: row-contiguous DMA into an LDS ring (launch_stash_gram routes to it); uses fewer slots.
+int stash_gram_stream_slots();
+hipError_t launch_stash_gram_stream(const StashGramArgs& a, hipStream_t s);
 
 // dW[p] = beta*dW[p] + sum_i c[i] * stash[i][p],  p in [0, n_elem).
 hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq_stride, long long n_elem,

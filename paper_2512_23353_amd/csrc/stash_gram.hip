@@ -203,9 +203,12 @@ size_t stash_gram_slot_floats(int n_seq) {
   return (size_t)tri(nb) * 1024;
 }
 
+static int slots_used(bool bf16) { return bf16 ? stash_gram_stream_slots() : kGramSlots; }
+
 hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s) {
   const int nb = (a.n_seq + 31) / 32;
   if (nb > kMaxRowBlocks) return hipErrorInvalidValue;
+  if (a.bf16) return launch_stash_gram_stream(a, s);
   GramParams p;
   p.stash = a.stash; p.seq_stride = a.seq_stride; p.p0 = a.p0; p.p1 = a.p1;
   p.n_seq = a.n_seq; p.first = a.first ? 1 : 0; p.partials = a.partials;
@@ -218,11 +221,11 @@ hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s) {
   }
 }
 
-hipError_t launch_stash_gram_finish(const float* partials, int n_seq, float* K, hipStream_t s) {
+hipError_t launch_stash_gram_finish(const float* partials, bool bf16, int n_seq, float* K, hipStream_t s) {
   const int nb = (n_seq + 31) / 32;
   const long long slot_floats = (long long)stash_gram_slot_floats(n_seq);
   hipLaunchKernelGGL(stash_gram_finish_kernel, dim3((unsigned)(slot_floats / 64)), dim3(1024), 0, s, partials,
-                     kGramSlots, slot_floats, n_seq, nb, K);
+                     slots_used(bf16), slot_floats, n_seq, nb, K);
   return hipGetLastError();
 }
 

@@ -1,0 +1,194 @@
+// Gram matrix of a bf16 stash, streaming variant (n_seq <= 128):
+//     K_ij = sum_p S[i][p] * S[j][p]        (interacting listing:
+//                                            ntk[i, j] = sum(seq_grads[i] * seq_grads[j]))
+// One pass over the stash, bound by HBM.  The stash rows are 10^7..10^8 elements
+// apart, so fragment-shaped loads (one row per lane) touch 32 cache lines per
+// instruction and use 32 bytes of each.  Here the loads are row-contiguous
+// instead: global_load_lds moves 16 bytes per lane straight into LDS, a wave
+// covering whole 1 KiB / 512 B / 256 B runs of a row, into a ring of 32 KiB
+// stages (all rows x KW elements).  Each wave then reads MFMA fragments for its
+// share of the stage's 16-element steps with ds_read_b128 (16-byte column index
+// XOR-swizzled with the row, so the row-per-lane reads do not pile on one bank)
+// and issues mfma(a_i, a_j) for every row-block pair i <= j; the A and B
+// fragments of K = S S^T are the same registers.
+//
+// Deterministic: fixed p -> workgroup -> wave assignment, waves added in order
+// through LDS into the workgroup's partial slot, slots added in a fixed tree by
+// the finishing kernel.
+#include "common.h"
+#include "kernels.h"
+
+namespace isopo {
+namespace {
+
+typedef unsigned short u16;
+typedef void __attribute__((address_space(3)))* lds_void_ptr;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef v4u __attribute__((address_space(3)))* lds_v4u_ptr;
+
+constexpr int kBlocks = 256;           // persistent workgroups, one per CU
+constexpr int kStageBytes = 32768;
+constexpr int kStages = 4;
+
+__host__ __device__ constexpr int tri(int nb) { return nb * (nb + 1) / 2; }
+__host__ __device__ constexpr int pair_index(int bi, int bj, int nb) { return bi * nb - bi * (bi - 1) / 2 + (bj - bi); }
+
+struct Params {
+  const u16* stash;
+  long long seq_stride, p0, p1;
+  int n_seq, first;
+  float* partials;
+  long long slot_floats;
+};
+
+// 16 bytes per lane, global -> LDS (lane l lands at lds_addr + 16*l).  Inline asm keeps the compiler's
+// LDS-DMA tracking from waiting on every outstanding load before each LDS read.
+__device__ __forceinline__ void load_lds16(const void* gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+}
+
+// NB   32-row blocks that carry sequences (pairs are formed among these)
+// NBL  row blocks of the LDS layout: 1, 2 or 4 (NBL >= NB); stage = 32*NBL rows x KW elements
+template <int NB, int NBL>
+__global__ __launch_bounds__(256) void stash_gram_stream_kernel(Params p) {
+  constexpr int ROWS = 32 * NBL;
+  constexpr int RB = kStageBytes / ROWS;           // bytes per row and stage: 1024, 512, 256
+  constexpr int KW = RB / 2;                        // elements per row and stage
+  constexpr int VPR = RB / 16;                      // 16-byte vectors per row: 64, 32, 16
+  constexpr int RPL = 1024 / RB;                    // rows per 1 KiB wave-load: 1, 2, 4
+  constexpr int LPW = kStageBytes / 1024 / 4;       // wave-loads per wave and stage: 8
+  constexpr int STEPS = KW / 16 / 4;                // 16-element steps per wave and stage: 8, 4, 2
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+
+  const long long n_elems = p.p1 - p.p0;
+  const long long n_super = (n_elems + KW - 1) / KW;
+  const long long my_first = blockIdx.x;
+  const long long my_count = my_first < n_super ? (n_super - my_first + gridDim.x - 1) / gridDim.x : 0;
+
+  // DMA addressing: wave-load q of this wave covers rows (wave*LPW + q)*RPL .. +RPL-1
+  const char* src[LPW];
+  int vec_off[LPW];
+#pragma unroll
+  for (int q = 0; q < LPW; ++q) {
+    const int row = (wave * LPW + q) * RPL + lane / VPR;
+    const int pos = lane % VPR;
+    const int g = pos ^ (row & (VPR - 1) & 31);                 // global vector this LDS slot holds
+    const int r = row < p.n_seq ? row : p.n_seq - 1;            // padded rows re-read a real row; their K entries are dropped
+    src[q] = reinterpret_cast<const char*>(p.stash + (size_t)r * p.seq_stride + p.p0);
+    vec_off[q] = g * 16;
+  }
+  auto issue = [&](long long k) {     // k-th super step of this workgroup -> ring stage k % kStages
+    const long long u = my_first + k * gridDim.x;
+    const long long e0 = u * KW;                                     // element offset of the stage within [p0, p1)
+    const unsigned stage = smem_base + (unsigned)(k % kStages) * kStageBytes;
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+      long long byte = e0 * 2 + vec_off[q];
+      const long long last = (n_elems - 8) * 2;
+      if (byte > last) byte = last;                               // tail: stays inside the row, zeroed at read time
+      if (k >= my_count) byte = 0;                                // look-ahead past the end: harmless re-read
+      load_lds16(src[q] + byte, stage + (unsigned)(wave_s * LPW + q) * 1024);
+    }
+  };
+
+  f32x16 acc[tri(NB)];
+#pragma unroll
+  for (int q = 0; q < tri(NB); ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+
+  // fragment addressing: lane (row = lane&31, half = lane>>5) of row block b, step s of this wave
+  const int frow = lane & 31, half = lane >> 5;
+
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s) issue(s);
+
+  for (long long k = 0; k < my_count; ++k) {
+    // this wave's part of stage k landed, then everyone's; the stage of step k-1 is free after the barrier
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (((kStages - 2) * LPW) & 15) | ((((kStages - 2) * LPW) >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    issue(k + kStages - 1);
+    const unsigned sb = smem_base + (unsigned)(k % kStages) * kStageBytes;
+    const long long u = my_first + k * gridDim.x;
+    const long long valid = n_elems - u * KW;                    // elements of this stage inside [p0, p1)
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      const int step = wave * STEPS + s;                         // 16-element step within the stage
+      const int vec = step * 2 + half;                           // 16-byte vector within the row
+      v4u frag[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const int row = b * 32 + frow;
+        const unsigned a = sb + (unsigned)row * RB + (unsigned)((vec ^ (row & (VPR - 1) & 31)) * 16);
+        frag[b] = *(lds_v4u_ptr)(a);
+        if (valid < KW && (long long)vec * 8 >= valid) frag[b] = v4u{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+        for (int bj = bi; bj < NB; ++bj)
+          acc[pair_index(bi, bj, NB)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, frag[bi]), __builtin_bit_cast(bf16x8, frag[bj]), acc[pair_index(bi, bj, NB)],
+              0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);      // drain the look-ahead loads before LDS is reused / released
+  __builtin_amdgcn_s_barrier();
+
+  // waves 0..3 added in order through LDS (reusing the ring); slot layout [pair][v][lane]
+  float* red = reinterpret_cast<float*>(smem);
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int q = 0; q < tri(NB); ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float* o = red + (q * 16 + v) * 64 + lane;
+          *o = (w == 0 ? 0.f : *o) + acc[q][v];
+        }
+    }
+    __syncthreads();
+  }
+  float* out = p.partials + (long long)blockIdx.x * p.slot_floats;
+  for (int e = threadIdx.x; e < tri(NB) * 1024; e += 256) out[e] = (p.first ? 0.f : out[e]) + red[e];
+}
+
+template <int NB, int NBL>
+hipError_t launch(const Params& p, hipStream_t s) {
+  constexpr size_t smem = (size_t)kStages * kStageBytes;
+  static_assert((size_t)tri(NB) * 4096 <= smem, "reduction scratch fits the ring");
+  auto kern = stash_gram_stream_kernel<NB, NBL>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(kBlocks), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int stash_gram_stream_slots() { return kBlocks; }
+
+hipError_t launch_stash_gram_stream(const StashGramArgs& a, hipStream_t s) {
+  const int nb = (a.n_seq + 31) / 32;
+  if (nb > 4 || !a.bf16 || a.n_seq < 1) return hipErrorInvalidValue;
+  Params p;
+  p.stash = static_cast<const u16*>(a.stash); p.seq_stride = a.seq_stride; p.p0 = a.p0; p.p1 = a.p1;
+  p.n_seq = a.n_seq; p.first = a.first ? 1 : 0; p.partials = a.partials;
+  p.slot_floats = (long long)stash_gram_slot_floats(a.n_seq);
+  switch (nb) {
+    case 1: return launch<1, 1>(p, s);
+    case 2: return launch<2, 2>(p, s);
+    case 3: return launch<3, 4>(p, s);
+    default: return launch<4, 4>(p, s);
+  }
+}
+
+}  // namespace isopo
