@@ -157,6 +157,7 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __r
 #pragma unroll
     for (int e = 0; e < kV; ++e) s[e] = 0.f;
     const char* src = static_cast<const char*>(stash) + vi * 16;
+#pragma unroll 8
     for (int i = 0; i < n_seq; ++i) {
       const float ci = c[i];
       const uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)i * seq_stride * (BF16 ? 2 : 4));
