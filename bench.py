@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--lam", type=float, default=1e-3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true", help="skip the torch.matmul context timing")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (untimed): the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the layer step has no cross-GPU part); use --gpus 1",
@@ -127,6 +130,14 @@ def main() -> int:
     total_flops = float(sum(sum(f.values()) for f in fl))
     reinforce_flops = float(sum(f["seq_grads"] for f in fl))
     achieved = seq_grad_flops_per_launch / avg_launch_s
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     context = {}
     if not args.no_context:

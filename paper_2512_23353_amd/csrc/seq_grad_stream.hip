@@ -109,7 +109,19 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     item = 0;
     tile = xcd_contiguous(blockIdx.x, p.n_blocks);
   }
-  const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
+  // Column-blocked tile order: ids run down 8-column strips of the tile grid, so the 32 workgroups an
+  // XCD runs at a time cover about 4 tile rows x 8 tile columns (12 operand panels) rather than
+  // 2 x 16 (18 panels): fewer L2 misses per flop.
+  int tile_m, tile_n;
+  {
+    constexpr int W = 8;
+    const int strip = tile / (p.tiles_m * W);
+    const int c0 = strip * W;
+    const int w = p.tiles_n - c0 < W ? p.tiles_n - c0 : W;     // the last strip may be narrower
+    const int in_strip = tile - strip * p.tiles_m * W;
+    tile_m = in_strip / w;
+    tile_n = c0 + in_strip % w;
+  }
   const int m0 = p.row0 + tile_m * BM, n0 = tile_n * BN;
   const int t0 = PER_SEQ ? p.off[item] : 0;
   const int t1 = PER_SEQ ? p.off[item + 1] : p.n_tokens;
