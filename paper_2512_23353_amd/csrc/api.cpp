@@ -14,7 +14,8 @@ using namespace isopo;
 
 constexpr size_t kAlign = 256;
 constexpr int kTileRows = 256;        // output rows per tile of the contraction kernel
-constexpr int kMaterialisedMaxSeq = 128;
+// the stash Gram kernels cover any bf16 batch; fp32 stashes up to 128 sequences
+bool materialised_ok(int n_seq, isopo_dtype t) { return n_seq <= 128 || t == ISOPO_BF16; }
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -73,7 +74,7 @@ size_t stash_bytes(const isopo_layer* l, int rows) {
 }
 
 size_t partial_bytes(const isopo_layer* l) {
-  return align_up((size_t)stash_gram_slots() * stash_gram_slot_floats(l->n_seq) * sizeof(float));
+  return align_up(stash_gram_partial_bytes(l->n_seq, l->dtype == ISOPO_BF16));
 }
 
 size_t ghost_bytes(const isopo_layer* l) {
@@ -82,7 +83,7 @@ size_t ghost_bytes(const isopo_layer* l) {
 
 isopo_gram_path resolve(const isopo_layer* l, isopo_gram_path req) {
   if (req != ISOPO_GRAM_AUTO) return req;
-  if (l->n_seq > kMaterialisedMaxSeq) return ISOPO_GRAM_GHOST;
+  if (!materialised_ok(l->n_seq, l->dtype)) return ISOPO_GRAM_GHOST;
   double tg, tm;
   cost_model(l, &tg, &tm);
   return tg < tm ? ISOPO_GRAM_GHOST : ISOPO_GRAM_MATERIALISED;
@@ -133,7 +134,7 @@ isopo_status isopo_layer_gram_plan(const isopo_layer* layer, isopo_gram_path req
   if (requested != ISOPO_GRAM_AUTO && requested != ISOPO_GRAM_GHOST && requested != ISOPO_GRAM_MATERIALISED)
     return ISOPO_ERR_INVALID_ARG;
   const isopo_gram_path path = resolve(layer, requested);
-  if (path == ISOPO_GRAM_MATERIALISED && layer->n_seq > kMaterialisedMaxSeq) return ISOPO_ERR_UNSUPPORTED;
+  if (path == ISOPO_GRAM_MATERIALISED && !materialised_ok(layer->n_seq, layer->dtype)) return ISOPO_ERR_UNSUPPORTED;
   if (chosen) *chosen = path;
   if (path == ISOPO_GRAM_GHOST) {
     if (ws_full) *ws_full = ghost_bytes(layer);
@@ -227,14 +228,15 @@ isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream
 
 size_t isopo_stash_gram_workspace(int32_t n_seq) {
   if (n_seq <= 0) return 0;
-  return align_up((size_t)stash_gram_slots() * stash_gram_slot_floats(n_seq) * sizeof(float));
+  return align_up(stash_gram_partial_bytes(n_seq, true));
 }
 
 isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_seq, int64_t n_elem, float* K,
                               void* workspace, size_t ws_bytes, void* stream) {
   if (!stash || !K || !workspace || n_seq <= 0 || n_elem <= 0 || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
   if (dtype != ISOPO_F32 && dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
-  if (n_seq > kMaterialisedMaxSeq || n_elem % (dtype == ISOPO_BF16 ? 8 : 4)) return ISOPO_ERR_UNSUPPORTED;
+  if (!materialised_ok(n_seq, dtype) || n_seq > ISOPO_MAX_SEQ || n_elem % (dtype == ISOPO_BF16 ? 8 : 4))
+    return ISOPO_ERR_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return ISOPO_ERR_INVALID_ARG;
   if (ws_bytes < isopo_stash_gram_workspace(n_seq)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);

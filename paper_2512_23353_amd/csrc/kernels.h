@@ -40,6 +40,13 @@ struct StashGramArgs {
   float* partials;           // [stash_gram_slots()][stash_gram_slot_floats(n_seq)]
 };
 int stash_gram_slots();
+// bytes of partial-sum scratch the Gram reduction needs (0 = shape not covered)
+size_t stash_gram_partial_bytes(int n_seq, bool bf16);
+// n_seq > 128 (bf16): 128x128 super-block pairs
+int stash_gram_large_slots(int n_seq);
+size_t stash_gram_large_slot_floats(int n_seq);
+hipError_t launch_stash_gram_large(const StashGramArgs& a, hipStream_t s);
+hipError_t launch_stash_gram_large_finish(const float* partials, int n_seq, float* K, hipStream_t s);
 size_t stash_gram_slot_floats(int n_seq);
 hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s);
 // K[i][j] = K[j][i] = sum over slots (fixed order) of the (i<=j) entry.

@@ -204,11 +204,17 @@ size_t stash_gram_slot_floats(int n_seq) {
   return (size_t)tri(nb) * 1024;
 }
 
+size_t stash_gram_partial_bytes(int n_seq, bool bf16) {
+  if (n_seq > 128)
+    return bf16 ? (size_t)stash_gram_large_slots(n_seq) * stash_gram_large_slot_floats(n_seq) * sizeof(float) : 0;
+  return (size_t)kGramSlots * stash_gram_slot_floats(n_seq) * sizeof(float);
+}
+
 static int slots_used(bool bf16) { return bf16 ? stash_gram_stream_slots() : kGramSlots; }
 
 hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s) {
   const int nb = (a.n_seq + 31) / 32;
-  if (nb > kMaxRowBlocks) return hipErrorInvalidValue;
+  if (nb > kMaxRowBlocks) return a.bf16 ? launch_stash_gram_large(a, s) : hipErrorInvalidValue;
   if (a.bf16) return launch_stash_gram_stream(a, s);
   GramParams p;
   p.stash = a.stash; p.seq_stride = a.seq_stride; p.p0 = a.p0; p.p1 = a.p1;
@@ -223,6 +229,7 @@ hipError_t launch_stash_gram(const StashGramArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_stash_gram_finish(const float* partials, bool bf16, int n_seq, float* K, hipStream_t s) {
+  if (n_seq > 128) return bf16 ? launch_stash_gram_large_finish(partials, n_seq, K, s) : hipErrorInvalidValue;
   const int nb = (n_seq + 31) / 32;
   const long long slot_floats = (long long)stash_gram_slot_floats(n_seq);
   hipLaunchKernelGGL(stash_gram_finish_kernel, dim3((unsigned)(slot_floats / 64)), dim3(1024), 0, s, partials,

@@ -172,9 +172,194 @@ hipError_t launch(const Params& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+
+// ---- more than 128 sequences --------------------------------------------------------------------
+// K is cut into 128x128 super blocks; one launch row (blockIdx.y) per super-block pair (I <= J).  A
+// workgroup streams the 128 (I == J) or 256 (I < J) rows of its pair through the same kind of LDS ring
+// and wave w forms the four 32x32 blocks (4I + w, 4J + 0..3).  Off-diagonal pairs read both row groups,
+// so the stash is read (number of super blocks + 1)/2 times on average; this path serves the large-batch
+// stress shape, where the contraction dominates anyway.  Partials: [gridDim.x][nbp*nbp blocks][16][64].
+struct LargeParams {
+  const u16* stash;
+  long long seq_stride, p0, p1;
+  int n_seq, first, nsb, nbp;       // super blocks, padded 32-row blocks per side (4 * nsb)
+  float* partials;
+  long long slot_floats;
+};
+
+template <bool DIAG>
+__global__ __launch_bounds__(256) void stash_gram_pair_kernel(LargeParams p) {
+  constexpr int ROWS = DIAG ? 128 : 256;
+  constexpr int RB = kStageBytes / ROWS;            // 256 or 128 bytes per row and stage
+  constexpr int KW = RB / 2;
+  constexpr int VPR = RB / 16;                       // 16 or 8
+  constexpr int RPL = 1024 / RB;                     // 4 or 8 rows per wave-load
+  constexpr int LPW = kStageBytes / 1024 / 4;        // 8
+  constexpr int STEPS = KW / 16;                     // every wave walks all steps of a stage
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+
+  // blockIdx.y enumerates the pairs of its kind: DIAG -> I = J = y; else the y-th pair with I < J
+  int I, J;
+  if (DIAG) {
+    I = J = blockIdx.y;
+  } else {
+    int rem = blockIdx.y;
+    I = 0;
+    while (rem >= p.nsb - 1 - I) { rem -= p.nsb - 1 - I; ++I; }
+    J = I + 1 + rem;
+  }
+
+  const long long n_elems = p.p1 - p.p0;
+  const long long n_super = (n_elems + KW - 1) / KW;
+  const long long my_first = blockIdx.x;
+  const long long my_count = my_first < n_super ? (n_super - my_first + gridDim.x - 1) / gridDim.x : 0;
+
+  const char* src[LPW];
+  int vec_off[LPW];
+#pragma unroll
+  for (int q = 0; q < LPW; ++q) {
+    const int row = (wave * LPW + q) * RPL + lane / VPR;               // row of the stage
+    const int pos = lane % VPR;
+    const int g = pos ^ (row & (VPR - 1));
+    int seq = (row < 128 ? I * 128 + row : J * 128 + (row - 128));
+    if (seq >= p.n_seq) seq = p.n_seq - 1;                             // padded rows: entries never written
+    src[q] = reinterpret_cast<const char*>(p.stash + (size_t)seq * p.seq_stride + p.p0);
+    vec_off[q] = g * 16;
+  }
+  auto issue = [&](long long k) {
+    const long long e0 = (my_first + k * gridDim.x) * KW;
+    const unsigned stage = smem_base + (unsigned)(k % kStages) * kStageBytes;
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+      long long byte = e0 * 2 + vec_off[q];
+      const long long last = (n_elems - 8) * 2;
+      if (byte > last) byte = last;
+      if (k >= my_count) byte = 0;
+      load_lds16(src[q] + byte, stage + (unsigned)(wave_s * LPW + q) * 1024);
+    }
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+  const int frow = lane & 31, half = lane >> 5;
+
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s) issue(s);
+  for (long long k = 0; k < my_count; ++k) {
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (((kStages - 2) * LPW) & 15) | ((((kStages - 2) * LPW) >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    issue(k + kStages - 1);
+    const unsigned sb = smem_base + (unsigned)(k % kStages) * kStageBytes;
+    const long long valid = n_elems - (my_first + k * gridDim.x) * KW;
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      const int vec = st * 2 + half;
+      const bool dead = valid < KW && (long long)vec * 8 >= valid;
+      const int ra = wave * 32 + frow;
+      v4u fa = *(lds_v4u_ptr)(sb + (unsigned)ra * RB + (unsigned)((vec ^ (ra & (VPR - 1))) * 16));
+      if (dead) fa = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int rb = (DIAG ? 0 : 128) + b * 32 + frow;
+        v4u fb = *(lds_v4u_ptr)(sb + (unsigned)rb * RB + (unsigned)((vec ^ (rb & (VPR - 1))) * 16));
+        if (dead) fb = v4u{0u, 0u, 0u, 0u};
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), __builtin_bit_cast(bf16x8, fb),
+                                                         acc[b], 0, 0, 0);
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+
+  float* out = p.partials + (long long)blockIdx.x * p.slot_floats;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int bi = 4 * I + wave, bj = 4 * J + b;
+    float* o = out + ((long long)(bi * p.nbp + bj) * 16) * 64 + lane;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[v * 64] = (p.first ? 0.f : o[v * 64]) + acc[b][v];
+  }
+}
+
+// grid: one 1024-thread block per (block bi <= bj, v); 16 waves add the slots, then wave order.
+__global__ __launch_bounds__(1024) void stash_gram_large_finish_kernel(const float* __restrict__ partials, int n_slots,
+                                                                       long long slot_floats, int n_seq, int nbp,
+                                                                       float* __restrict__ K) {
+  __shared__ float red[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int blk = blockIdx.x >> 4, v = blockIdx.x & 15;
+  const int bi = blk / nbp, bj = blk % nbp;
+  if (bi > bj || bi * 32 >= n_seq || bj * 32 >= n_seq) return;
+  const long long e = ((long long)blk * 16 + v) * 64 + lane;
+  float s = 0.f;
+  for (int w = wave; w < n_slots; w += 16) s += partials[(long long)w * slot_floats + e];
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave != 0) return;
+  s = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) s += red[w][lane];
+  const int i = bi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), j = bj * 32 + (lane & 31);
+  if (i < n_seq && j < n_seq && i <= j) {
+    K[(size_t)i * n_seq + j] = s;
+    K[(size_t)j * n_seq + i] = s;
+  }
+}
+
+template <bool DIAG>
+hipError_t launch_pair(const LargeParams& p, int gx, int n_pairs, hipStream_t s) {
+  if (n_pairs <= 0) return hipSuccess;
+  constexpr size_t smem = (size_t)kStages * kStageBytes;
+  auto kern = stash_gram_pair_kernel<DIAG>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(gx, n_pairs), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 int stash_gram_stream_slots() { return kBlocks; }
+
+// Large batches (n_seq > 128).
+int stash_gram_large_slots(int n_seq) {
+  const int nsb = (n_seq + 127) / 128;
+  const int pairs = nsb * (nsb + 1) / 2;
+  int gx = 512 / pairs;
+  return gx < 16 ? 16 : (gx > 128 ? 128 : gx);
+}
+size_t stash_gram_large_slot_floats(int n_seq) {
+  const int nbp = 4 * ((n_seq + 127) / 128);
+  return (size_t)nbp * nbp * 1024;
+}
+hipError_t launch_stash_gram_large(const StashGramArgs& a, hipStream_t s) {
+  if (!a.bf16 || a.n_seq <= 128) return hipErrorInvalidValue;
+  LargeParams p;
+  p.stash = static_cast<const u16*>(a.stash); p.seq_stride = a.seq_stride; p.p0 = a.p0; p.p1 = a.p1;
+  p.n_seq = a.n_seq; p.first = a.first ? 1 : 0; p.partials = a.partials;
+  p.nsb = (a.n_seq + 127) / 128; p.nbp = 4 * p.nsb;
+  p.slot_floats = (long long)stash_gram_large_slot_floats(a.n_seq);
+  const int gx = stash_gram_large_slots(a.n_seq);
+  hipError_t e = launch_pair<true>(p, gx, p.nsb, s);
+  if (e != hipSuccess) return e;
+  return launch_pair<false>(p, gx, p.nsb * (p.nsb - 1) / 2, s);
+}
+hipError_t launch_stash_gram_large_finish(const float* partials, int n_seq, float* K, hipStream_t s) {
+  const int nbp = 4 * ((n_seq + 127) / 128);
+  hipLaunchKernelGGL(stash_gram_large_finish_kernel, dim3((unsigned)(nbp * nbp * 16)), dim3(1024), 0, s, partials,
+                     stash_gram_large_slots(n_seq), (long long)stash_gram_large_slot_floats(n_seq), n_seq, nbp, K);
+  return hipGetLastError();
+}
 
 hipError_t launch_stash_gram_stream(const StashGramArgs& a, hipStream_t s) {
   const int nb = (a.n_seq + 31) / 32;

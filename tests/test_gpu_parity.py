@@ -209,3 +209,29 @@ def test_bad_arguments_on_device_calls(gpu_device):
         isopo.transform(K, torch.ones(200, device=gpu_device), "interacting", 0.1,
                         workspace=isopo.alloc_workspace(1024, gpu_device))
     assert e.value.status == 4
+
+
+@pytest.mark.parametrize("n_seq", [129, 200, 256, 300])
+def test_more_than_128_sequences(gpu_device, n_seq):
+    """Large batches take the super-block Gram kernel on the materialised path
+    (and the global-scratch Cholesky in the transform); both Gram paths and the
+    whole step are compared with the oracle."""
+    rng = np.random.default_rng(n_seq)
+    lengths = rng.integers(1, 40, size=n_seq)
+    lengths[5] = 0
+    prob = wl.custom_layer(136, 264, lengths, dtype="bf16", seed=n_seq, sigma_delta=1e-2, rho=0.3)
+    layer, A = to_device(prob, gpu_device)
+    ref = oracle_step(prob, "interacting", 1e-2, isopo.REG_REL_TRACE)
+    for path in ("materialised", "ghost"):
+        out = isopo.layer_step(layer, A, "interacting", 1e-2, isopo.REG_REL_TRACE, path)
+        torch.cuda.synchronize()
+        what = f"n_seq={n_seq}/{path}"
+        assert int(out["info"].item()) == 0
+        assert_K_close(out["K"].cpu().numpy(), ref["K"], TOL["bf16"], what)
+        assert_c_close(out["c"].cpu().numpy(), ref["c"], TOL["bf16"], what)
+        assert_dW_close(out["dW"].cpu().numpy(), ref["dW"], TOL["bf16"], what, ref["dW_abs"])
+    # chunked accumulation over output rows with the minimum workspace
+    _, full, mn = isopo.gram_plan(layer, "materialised")
+    K_chunk, _ = isopo.layer_gram(layer, "materialised", workspace=isopo.alloc_workspace(mn, gpu_device))
+    torch.cuda.synchronize()
+    assert_K_close(K_chunk.cpu().numpy(), ref["K"], TOL["bf16"], f"n_seq={n_seq}/chunked")
