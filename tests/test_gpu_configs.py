@@ -142,3 +142,20 @@ def test_config5_ghost_on_shortest_sequences(gpu_device, n_short):
     assert_K_close(Km.cpu().numpy(), K_ref, TOL["bf16"], "config5 materialised")
     c_ref, _ = orc.coeff_interacting(K_ref, prob.A, 1e-3, isopo.REG_REL_TRACE)
     assert_c_close(out["c"].cpu().numpy(), c_ref, TOL["bf16"], "config5 c")
+
+
+def test_config5_full_size_sampled(gpu_device):
+    """The stress layer at full size: 5120 -> 27648, B = 256 sequences with
+    clipped log-normal lengths (about 4e5 tokens, a 67 GiB bf16 stash).  AUTO
+    must choose the materialised path; K entries, the solve's residual and dW
+    elements are checked where the oracle can form them one by one."""
+    w = wl.CONFIGS["config5"]
+    lengths = wl.draw_lengths(w)
+    assert lengths.min() >= 128 and lengths.max() <= 16384
+    rng = np.random.default_rng(55)
+    prob = wl.make_layer(w, w.projections[0], lengths, device=gpu_device)
+    print(f"config5 gate N={prob.n_tokens}", flush=True)
+    layer, _ = to_device(prob, gpu_device)
+    assert isopo.gram_plan(layer)[0] == "materialised"
+    del layer
+    _sampled_checks(prob, gpu_device, rng, 3, full_k=False)
