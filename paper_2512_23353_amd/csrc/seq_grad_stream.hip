@@ -225,7 +225,6 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       }
       __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 3) * LPT) & 15) | ((((NSTAGE - 3) * LPT) >> 4) << 14));
       __builtin_amdgcn_s_barrier();
-      issue_loads(it + NSTAGE - 1);
       const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
 #pragma unroll
       for (int i = 0; i < FM; ++i) fa0[i] = frA(sn + adA[i]);
@@ -241,6 +240,9 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
       }
+      // the block NSTAGE-1 ahead goes to the stage freed at this iteration's barrier; issued behind the
+      // MFMAs so that the matrix pipe is not left idle while the DMA instructions go out
+      issue_loads(it + NSTAGE - 1);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);
