@@ -150,6 +150,16 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
 isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash,
                                  float beta, float* dW, void* stream);
 
+/* dst[t, :] = c[seq(t)] * src[t, :] for a token-major matrix [n_tokens, d] (X or Delta), rounded to
+ * the storage type; dst may not alias src.  Since Delta^T diag(c_tok) X = (diag(c_tok) Delta)^T X =
+ * Delta^T (diag(c_tok) X), scaling the narrower operand once and then calling isopo_weighted_grad with
+ * c = NULL gives the weighted update (`grad += advantages[i] * scale_i * seq_logprob_grad`) at the speed
+ * of the unweighted contraction.  For bf16 this is the same single rounding of the scaled rows that
+ * isopo_weighted_grad(c != NULL) applies to Delta. */
+isopo_status isopo_scale_rows(const void* src, isopo_dtype dtype, int64_t n_tokens, int32_t d,
+                              const int32_t* seq_offsets_dev, int32_t n_seq, const float* c, void* dst,
+                              void* stream);
+
 const char* isopo_status_string(isopo_status s);
 
 /* Library version, "major.minor". */

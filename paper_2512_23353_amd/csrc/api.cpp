@@ -271,6 +271,19 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
   return launch_transform(t, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
+isopo_status isopo_scale_rows(const void* src, isopo_dtype dtype, int64_t n_tokens, int32_t d,
+                              const int32_t* seq_offsets_dev, int32_t n_seq, const float* c, void* dst,
+                              void* stream) {
+  if (!src || !dst || !c || !seq_offsets_dev || src == dst || n_tokens < 0 || d <= 0 || n_seq <= 0)
+    return ISOPO_ERR_INVALID_ARG;
+  if (dtype != ISOPO_F32 && dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  if (d % (dtype == ISOPO_BF16 ? 8 : 4) || n_seq > ISOPO_MAX_SEQ || n_tokens >= (int64_t)1 << 31)
+    return ISOPO_ERR_UNSUPPORTED;
+  if (!aligned16(src) || !aligned16(dst)) return ISOPO_ERR_INVALID_ARG;
+  return launch_scale_rows(src, dtype == ISOPO_BF16, n_tokens, d, seq_offsets_dev, n_seq, c, dst,
+                           static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
 isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash, float beta, float* dW,
                                  void* stream) {
   isopo_status st = check_layer(layer, true);

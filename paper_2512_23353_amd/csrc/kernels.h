@@ -72,6 +72,10 @@ struct GhostArgs {
 };
 hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s);
 
+// dst[t][:] = c[seq(t)] * src[t][:] (rounded to the storage type).
+hipError_t launch_scale_rows(const void* src, bool bf16, long long n_tokens, int d, const int32_t* off, int n_seq,
+                             const float* c, void* dst, hipStream_t s);
+
 struct TransformArgs {
   const float* K;
   const float* A;

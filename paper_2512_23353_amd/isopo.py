@@ -29,7 +29,7 @@ _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
 EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
-           "isopo_transform", "isopo_weighted_grad", "isopo_status_string", "isopo_version")
+           "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows", "isopo_status_string", "isopo_version")
 
 
 class IsopoError(RuntimeError):
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_transform.restype = ctypes.c_int
     lib.isopo_weighted_grad.argtypes = [lp, vp, vp, f32, vp, vp]
     lib.isopo_weighted_grad.restype = ctypes.c_int
+    lib.isopo_scale_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int64, i32, vp, i32, vp, vp, vp]
+    lib.isopo_scale_rows.restype = ctypes.c_int
     lib.isopo_status_string.argtypes = [ctypes.c_int]
     lib.isopo_status_string.restype = ctypes.c_char_p
     lib.isopo_version.argtypes = []
@@ -241,6 +243,30 @@ def weighted_grad(layer: Layer, c: Optional[torch.Tensor], stash: Optional[torch
     _check(load().isopo_weighted_grad(layer.ref(), _ptr(c), _ptr(stash), float(beta), dW.data_ptr(),
                                       _stream(stream)), "isopo_weighted_grad")
     return dW
+
+
+def scale_rows(src: torch.Tensor, layer: Layer, c: torch.Tensor, dst: Optional[torch.Tensor] = None,
+               stream=None) -> torch.Tensor:
+    """dst[t, :] = c[seq(t)] * src[t, :] for src = X or Delta of `layer`."""
+    if dst is None:
+        dst = torch.empty_like(src)
+    dtype = BF16 if src.dtype == torch.bfloat16 else F32
+    _check(load().isopo_scale_rows(src.data_ptr(), dtype, src.shape[0], src.shape[1], _ptr(layer.off_dev),
+                                   layer.n_seq, c.data_ptr(), dst.data_ptr(), _stream(stream)), "isopo_scale_rows")
+    return dst
+
+
+def weighted_grad_prescaled(layer: Layer, c: torch.Tensor, scratch: Optional[torch.Tensor] = None, beta: float = 0.0,
+                            dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """dW = beta dW + Delta^T diag(c_tok) X: the narrower of X and Delta is scaled into `scratch`
+    (isopo_scale_rows), then the unweighted contraction runs on it."""
+    narrow_x = layer.d_in <= layer.d_out
+    src = layer.X if narrow_x else layer.Delta
+    if scratch is None:
+        scratch = torch.empty_like(src)
+    scaled = scale_rows(src, layer, c, scratch.view(src.dtype).reshape(-1)[: src.numel()].view(src.shape), stream)
+    lay2 = Layer(scaled if narrow_x else layer.X, layer.Delta if narrow_x else scaled, layer.off_host, layer.off_dev)
+    return weighted_grad(lay2, None, None, beta, dW, stream)
 
 
 def layer_step(layer: Layer, A: torch.Tensor, variant="interacting", lam: float = 0.0,

@@ -235,3 +235,27 @@ def test_more_than_128_sequences(gpu_device, n_seq):
     K_chunk, _ = isopo.layer_gram(layer, "materialised", workspace=isopo.alloc_workspace(mn, gpu_device))
     torch.cuda.synchronize()
     assert_K_close(K_chunk.cpu().numpy(), ref["K"], TOL["bf16"], f"n_seq={n_seq}/chunked")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dims", [(256, 640), (640, 256)])
+def test_prescaled_weighted_grad(gpu_device, dtype, dims):
+    """Scaling the narrower operand's rows by c_tok and contracting unweighted
+    equals the weighted contraction; the scaled rows themselves are the exact
+    product rounded once to the storage type."""
+    d_in, d_out = dims
+    prob = wl.custom_layer(d_in, d_out, [70, 0, 129, 33, 300], dtype=dtype, seed=21, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    rng = np.random.default_rng(5)
+    c = rng.standard_normal(prob.n_seq).astype(np.float32)
+    c_dev = torch.from_numpy(c).to(gpu_device)
+    dW = isopo.weighted_grad_prescaled(layer, c_dev)
+    scaled = isopo.scale_rows(layer.X, layer, c_dev)
+    torch.cuda.synchronize()
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    assert_dW_close(dW.cpu().numpy(), orc.weighted_grad(G, c), TOL[dtype], "prescaled", orc.weighted_grad_abs(G, c))
+    c_tok = np.repeat(c.astype(np.float64), np.diff(prob.seq_offsets))
+    exact = orc.widen(wl.to_oracle(prob.X)) * c_tok[:, None]
+    got = orc.widen(wl.to_oracle(scaled))
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -23
+    assert np.all(np.abs(got - exact) <= ulp * np.abs(exact) + 1e-300)
