@@ -20,7 +20,8 @@ Pins (tests/test_oracle_pins.py): autograd brute force, the ghost double sum,
 rank-one closed form, unit Fisher norm, the orthogonal-gradient reduction,
 solve residual and the eigendecomposition route, the MinSR property, the
 large-regulariser limit, equivariances, the one-sequence closed form, the
-token-by-token contraction, and duplicate sequences.  Every public function
+token-by-token contraction, duplicate sequences, and (token-sample Fisher
+estimate) the listing's own formula in torch plus a one-token closed form.  Every public function
 below is pinned by at least one of them; none is "parity unpinned".
 """
 from __future__ import annotations
@@ -170,6 +171,48 @@ def coeff_fisher(K, A, lam: float, reg_mode: int = REG_ABSOLUTE) -> np.ndarray:
     nz = den > 0
     c[nz] = A[nz] / np.sqrt(den[nz])
     return c
+
+
+def fisher_norm_sq_token_samples(X, Delta, seq_offsets, sample_idx) -> np.ndarray:
+    """The non-interacting listing's Fisher-norm estimate per sequence, squared
+    (eq. formal-F-norm):
+
+        ||v||_F^2 ~= sum_j (v . g^(j))^2 / sum_j ||g^(j)||^2
+
+    with v = G_i and g^(j) = grad_out[j] act_in[j]^T the un-reduced gradients at
+    the sampled token rows j (`a0 = act_in[samples]`, `g0 = grad_out[samples]`,
+    samples drawn from the whole microbatch).  Written with every G_i and every
+    rank-one g^(j) materialised; the listing's `sum((g0 @ G) * a0, dim=1)` and
+    `norm(g0) * norm(a0)` are eq. (one) and eq. (two) applied to the same sums.
+    """
+    Xw, Dw = widen(X), widen(Delta)
+    off = check_offsets(seq_offsets, Xw.shape[0])
+    idx = np.asarray(sample_idx, dtype=np.int64)
+    G = seq_logprob_grads(Xw, Dw, off)
+    num = np.zeros(G.shape[0])
+    den = 0.0
+    for j in idx:
+        gj = np.outer(Dw[j], Xw[j])                   # g^(j), [d_out, d_in]
+        den += np.sum(gj * gj)
+        for i in range(G.shape[0]):
+            num[i] += np.sum(G[i] * gj) ** 2
+    return num / den if den > 0 else np.zeros_like(num)
+
+
+def coeff_fisher_token_samples(X, Delta, seq_offsets, sample_idx, A, lam: float,
+                               reg_mode: int = REG_ABSOLUTE):
+    """c_i = A_i / sqrt(F_norm_i^2 + reg) with the token-sample estimate
+    (`rescaling()` of the non-interacting listing).  REL mode: reg = lam times
+    the batch mean of F_norm^2 (the listing's "trailing minibatch means", with
+    the current batch standing in).  Returns (c, F_norm^2)."""
+    A = np.asarray(A, dtype=np.float64)
+    f2 = fisher_norm_sq_token_samples(X, Delta, seq_offsets, sample_idx)
+    reg = float(lam) if reg_mode == REG_ABSOLUTE else float(lam) * float(np.mean(f2))
+    den = f2 + reg
+    c = np.zeros_like(A)
+    nz = den > 0
+    c[nz] = A[nz] / np.sqrt(den[nz])
+    return c, f2
 
 
 def coeff_interacting(K, A, lam: float, reg_mode: int = REG_ABSOLUTE):

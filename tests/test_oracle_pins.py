@@ -328,3 +328,39 @@ def test_widen_bf16_bits_exact():
         orc.check_offsets([0, 3, 2, 5], 5)
     with pytest.raises(ValueError):
         orc.check_offsets([1, 5], 5)
+
+
+def test_token_sample_fisher_estimate():
+    """The token-position-sample Fisher norm: the oracle (materialised rank-one
+    sample gradients) against the non-interacting listing's own expression in
+    torch, and against closed forms."""
+    rng = np.random.default_rng(20)
+    X, D, off = _rand_layer(rng, [5, 3, 6, 2], 7, 6)
+    idx = rng.permutation(16)[:9]
+    f2 = orc.fisher_norm_sq_token_samples(X, D, off, idx)
+    Xt, Dt = torch.from_numpy(X), torch.from_numpy(D)
+    a0, g0 = Xt[idx], Dt[idx]
+    for i in range(4):
+        G = Dt[off[i]:off[i + 1]].T @ Xt[off[i]:off[i + 1]]
+        F_norm = torch.norm(torch.sum((g0 @ G) * a0, dim=1)) / torch.norm(torch.norm(g0, dim=1) * torch.norm(a0, dim=1))
+        assert f2[i] == pytest.approx(float(F_norm) ** 2, rel=1e-12)
+    # one sample equal to the only token of a one-token sequence: v = g^(j), so
+    # ||v||_F^2 = (v.v)^2 / (v.v) = ||x||^2 ||delta||^2 (eq. (two))
+    X1, D1, off1 = _rand_layer(rng, [1, 4], 5, 4)
+    f2 = orc.fisher_norm_sq_token_samples(X1, D1, off1, [0])
+    assert f2[0] == pytest.approx(np.dot(X1[0], X1[0]) * np.dot(D1[0], D1[0]), rel=1e-12)
+    # scaling: Delta -> 2 Delta scales numerator by 2^4 and denominator by 2^2
+    f2a = orc.fisher_norm_sq_token_samples(X, D, off, idx)
+    f2b = orc.fisher_norm_sq_token_samples(X, 2 * D, off, idx)
+    np.testing.assert_allclose(f2b, 4 * f2a, rtol=1e-12)
+    # sample order and repetition-free permutation do not matter; coefficients follow the update formula
+    np.testing.assert_allclose(orc.fisher_norm_sq_token_samples(X, D, off, idx[::-1]), f2a, rtol=1e-12)
+    A = rng.standard_normal(4)
+    c, f2c = orc.coeff_fisher_token_samples(X, D, off, idx, A, 0.3)
+    np.testing.assert_allclose(c, A / np.sqrt(f2a + 0.3), rtol=1e-12)
+    c, _ = orc.coeff_fisher_token_samples(X, D, off, idx, A, 0.5, orc.REG_REL_TRACE)
+    np.testing.assert_allclose(c, A / np.sqrt(f2a + 0.5 * f2a.mean()), rtol=1e-12)
+    # an empty sequence has zero Fisher norm; with reg 0 its coefficient is 0
+    X2, D2, off2 = _rand_layer(rng, [3, 0, 4], 5, 4)
+    c, f2 = orc.coeff_fisher_token_samples(X2, D2, off2, [0, 5], np.ones(3), 0.0)
+    assert f2[1] == 0.0 and c[1] == 0.0
