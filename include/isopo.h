@@ -150,6 +150,26 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
 isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash,
                                  float beta, float* dW, void* stream);
 
+/* The non-interacting update's coefficients with the paper's own Fisher-norm estimate (eq.
+ * formal-F-norm; F_norm of the non-interacting listing): from n_samples sampled token rows j of the
+ * microbatch (a0 = act_in[samples], g0 = grad_out[samples]),
+ *     F_i^2 = sum_j (g0_j . G_i a0_j)^2 / sum_j (||g0_j|| ||a0_j||)^2,   c_i = A_i / sqrt(F_i^2 + reg).
+ * Evaluated in ghost form, G_i a0_j = sum_{t in i} delta_t (x_t . a0_j) (eq. (one)): no per-sequence
+ * gradient is formed, the cost is 2 N n_samples (d_in + d_out) flop, and c is known before any
+ * contraction, so the whole update is one weighted contraction (isopo_scale_rows + isopo_weighted_grad).
+ *   sample_idx_dev  device int32 [n_samples], token row indices in [0, n_tokens) (the caller draws
+ *                   them, e.g. randperm(N)[:n_samples]; an index outside the range is clamped
+ *                   into it); 1 <= n_samples <= ISOPO_MAX_SAMPLES
+ *   reg_mode        ABSOLUTE: reg = lambda.  REL_TRACE: reg = lambda * mean_i F_i^2 (the current
+ *                   batch's mean standing in for the listing's trailing minibatch means)
+ *   fisher_sq       optional device [n_seq]: F_i^2
+ * A zero denominator (empty sequence, reg = 0) gives c_i = 0. */
+#define ISOPO_MAX_SAMPLES 128
+size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_samples);
+isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,
+                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* c,
+                                  float* fisher_sq, void* workspace, size_t ws_bytes, void* stream);
+
 /* dst[t, :] = c[seq(t)] * src[t, :] for a token-major matrix [n_tokens, d] (X or Delta), rounded to
  * the storage type; dst may not alias src.  Since Delta^T diag(c_tok) X = (diag(c_tok) Delta)^T X =
  * Delta^T (diag(c_tok) X), scaling the narrower operand once and then calling isopo_weighted_grad with

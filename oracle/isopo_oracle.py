@@ -173,7 +173,7 @@ def coeff_fisher(K, A, lam: float, reg_mode: int = REG_ABSOLUTE) -> np.ndarray:
     return c
 
 
-def fisher_norm_sq_token_samples(X, Delta, seq_offsets, sample_idx) -> np.ndarray:
+def fisher_norm_sq_token_samples(X, Delta, seq_offsets, sample_idx, seqs=None) -> np.ndarray:
     """The non-interacting listing's Fisher-norm estimate per sequence, squared
     (eq. formal-F-norm):
 
@@ -181,22 +181,31 @@ def fisher_norm_sq_token_samples(X, Delta, seq_offsets, sample_idx) -> np.ndarra
 
     with v = G_i and g^(j) = grad_out[j] act_in[j]^T the un-reduced gradients at
     the sampled token rows j (`a0 = act_in[samples]`, `g0 = grad_out[samples]`,
-    samples drawn from the whole microbatch).  Written with every G_i and every
+    samples drawn from the whole microbatch).  Written with G_i and every
     rank-one g^(j) materialised; the listing's `sum((g0 @ G) * a0, dim=1)` and
     `norm(g0) * norm(a0)` are eq. (one) and eq. (two) applied to the same sums.
+
+    seqs: only these sequences are evaluated (the others' entries are NaN); rows
+    are widened one sequence at a time, so a large layer can be checked on a few
+    short sequences.
     """
-    Xw, Dw = widen(X), widen(Delta)
-    off = check_offsets(seq_offsets, Xw.shape[0])
+    off = check_offsets(seq_offsets, X.shape[0])
     idx = np.asarray(sample_idx, dtype=np.int64)
-    G = seq_logprob_grads(Xw, Dw, off)
-    num = np.zeros(G.shape[0])
+    m = off.size - 1
+    which = range(m) if seqs is None else [int(i) for i in seqs]
+    g0, a0 = widen(Delta[idx]), widen(X[idx])
     den = 0.0
-    for j in idx:
-        gj = np.outer(Dw[j], Xw[j])                   # g^(j), [d_out, d_in]
+    for j in range(idx.size):
+        gj = np.outer(g0[j], a0[j])                   # g^(j), [d_out, d_in]
         den += np.sum(gj * gj)
-        for i in range(G.shape[0]):
-            num[i] += np.sum(G[i] * gj) ** 2
-    return num / den if den > 0 else np.zeros_like(num)
+    num = np.full(m, np.nan)
+    for i in which:
+        s, e = off[i], off[i + 1]
+        G_i = widen(Delta[s:e]).T @ widen(X[s:e])     # zero for an empty sequence
+        num[i] = 0.0
+        for j in range(idx.size):
+            num[i] += np.sum(G_i * np.outer(g0[j], a0[j])) ** 2
+    return num / den if den > 0 else np.where(np.isnan(num), num, 0.0)
 
 
 def coeff_fisher_token_samples(X, Delta, seq_offsets, sample_idx, A, lam: float,

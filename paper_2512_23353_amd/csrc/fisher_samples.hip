@@ -1,0 +1,327 @@
+// Token-position-sample estimate of each sequence's Fisher norm, in ghost form.
+//
+// The non-interacting listing estimates ||G_i||_F from n_s sampled token rows j
+// (a0 = act_in[samples], g0 = grad_out[samples]; eq. formal-F-norm):
+//     F_i^2 = sum_j (G_i . g^(j))^2 / sum_j ||g^(j)||^2,   g^(j) = g0_j a0_j^T.
+// Since G_i = sum_{t in i} delta_t x_t^T is a sum of rank-one terms as well,
+//     G_i . g^(j) = sum_{t in i} (delta_t . g0_j)(x_t . a0_j)       (eq. (one), summed over t)
+//     ||g^(j)||^2 = ||g0_j||^2 ||a0_j||^2                            (eq. (two))
+// so the coefficients c_i = A_i / sqrt(F_i^2 + reg) need no per-sequence
+// gradient at all: two token-by-sample products P = Delta G0^T, Q = X A0^T
+// (2 N n_s (d_in + d_out) flop, a few per cent of the layer's contraction), their
+// element-wise product, and a segment sum over the tokens of each sequence.
+//
+// One workgroup takes 128 tokens (32 per wave).  Token rows and sample rows are
+// streamed global -> LDS (row-contiguous DMA, XOR-swizzled 16-byte columns) in a
+// four-stage ring; each wave multiplies its 32 tokens against all sample blocks
+// on the matrix cores.  Segment sums go to an fp64 accumulator with atomics
+// (order varies, but in fp64: the fp32 result moves by at most one rounding).
+#include "common.h"
+#include "kernels.h"
+
+namespace isopo {
+namespace {
+
+typedef void __attribute__((address_space(3)))* lds_void_ptr;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef v4u __attribute__((address_space(3)))* lds_v4u_ptr;
+
+constexpr int kStages = 4;
+constexpr int kRowBytes = 128;                 // bytes per row and stage
+constexpr int kVpr = kRowBytes / 16;           // 16-byte vectors per row: 8
+constexpr int kTok = 128;                      // tokens per workgroup
+constexpr int kMaxSampleBlocks = 4;            // n_samples <= 128
+
+__device__ __forceinline__ void load_lds16(const void* gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+}
+
+struct Params {
+  const void* X;
+  const void* Delta;
+  const int32_t* off;
+  const int32_t* idx;
+  int n_tokens, d_in, d_out, n_seq, n_samples;
+  int32_t* tok_seq;      // [n_tokens]
+  double* S64;           // [n_seq][32*NBS] segment sums s_ij
+  double* den;           // [n_samples] ||g0_j||^2 ||a0_j||^2
+};
+
+__global__ void tok_seq_kernel(const int32_t* __restrict__ off, int n_seq, int n_tokens, int32_t* __restrict__ tok_seq) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_tokens) return;
+  int lo = 0, hi = n_seq;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (off[mid] <= t) lo = mid; else hi = mid;
+  }
+  tok_seq[t] = lo;
+}
+
+__global__ void zero_f64_kernel(double* p, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0;
+}
+
+// den[j] = ||Delta[idx_j]||^2 * ||X[idx_j]||^2, one workgroup per sample, fixed reduction order.
+template <bool BF16>
+__global__ __launch_bounds__(256) void sample_norm_kernel(Params p) {
+  __shared__ double red[2][4];
+  const int j = blockIdx.x, row = min(max(p.idx[j], 0), p.n_tokens - 1);   // bad indices are clamped, never followed
+  double sx = 0.0, sd = 0.0;
+  for (int k = threadIdx.x; k < p.d_in; k += 256) {
+    const float v = BF16 ? bf16_bits_to_f32(static_cast<const unsigned short*>(p.X)[(size_t)row * p.d_in + k])
+                         : static_cast<const float*>(p.X)[(size_t)row * p.d_in + k];
+    sx += (double)v * v;
+  }
+  for (int k = threadIdx.x; k < p.d_out; k += 256) {
+    const float v = BF16 ? bf16_bits_to_f32(static_cast<const unsigned short*>(p.Delta)[(size_t)row * p.d_out + k])
+                         : static_cast<const float*>(p.Delta)[(size_t)row * p.d_out + k];
+    sd += (double)v * v;
+  }
+  sx = wave_sum(sx);
+  sd = wave_sum(sd);
+  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = sx; red[1][threadIdx.x >> 6] = sd; }
+  __syncthreads();
+  if (threadIdx.x == 0)
+    p.den[j] = (red[0][0] + red[0][1] + red[0][2] + red[0][3]) * (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+}
+
+// One token-by-sample product block per wave: acc[b] (32 tokens x 32 samples) += T S_b^T over d features.
+template <int NBS, bool BF16>
+__device__ __forceinline__ void product_pass(const void* M, int d, const int32_t* __restrict__ idx, int n_samples,
+                                             int n_tokens, int t0, unsigned smem_base, int lane, int wave,
+                                             f32x16 (&acc)[NBS]) {
+  constexpr int kEs = BF16 ? 2 : 4;
+  constexpr int kV = 16 / kEs;                          // elements per 16-byte vector
+  constexpr int KW = kRowBytes / kEs;                   // elements per row and stage
+  constexpr int ROWS = kTok + 32 * NBS;                 // token rows, then sample rows
+  constexpr int STAGE = ROWS * kRowBytes;
+  constexpr int LOADS = ROWS * kRowBytes / 1024;        // 1 KiB wave-loads per stage (8 rows each)
+  constexpr int LPW = (LOADS + 3) / 4;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int n_super = (d + KW - 1) / KW;
+
+  const char* src[LPW];
+  int vec_off[LPW];
+  bool active[LPW];
+#pragma unroll
+  for (int q = 0; q < LPW; ++q) {
+    const int load = wave * LPW + q;
+    active[q] = load < LOADS;
+    const int row = (active[q] ? load : 0) * 8 + lane / kVpr;
+    const int pos = lane % kVpr;
+    long long grow;
+    if (row < kTok) {
+      const int t = t0 + row;
+      grow = t < n_tokens ? t : n_tokens - 1;
+    } else {
+      const int j = row - kTok;
+      grow = min(max(idx[j < n_samples ? j : 0], 0), n_tokens - 1);
+    }
+    src[q] = static_cast<const char*>(M) + (size_t)grow * d * kEs;
+    vec_off[q] = (pos ^ (row & (kVpr - 1))) * 16;
+  }
+  auto issue = [&](int k) {
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+      long long byte = (long long)k * kRowBytes + vec_off[q];
+      const long long last = ((long long)d - kV) * kEs;
+      if (byte > last) byte = last;          // tail and look-ahead past the end: stays inside the row
+      const int load = wave_s * LPW + q;
+      if (load < LOADS) load_lds16(src[q] + byte, smem_base + (unsigned)(k % kStages) * STAGE + (unsigned)load * 1024);
+    }
+  };
+  // every wave issues the same number of loads per stage only if LOADS is a multiple of 4
+  static_assert(LOADS % 4 == 0, "wave-loads per stage divide evenly over the four waves");
+
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s) issue(s);
+  const int frow = lane & 31, half = lane >> 5;
+  for (int k = 0; k < n_super; ++k) {
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (((kStages - 2) * LPW) & 15) | ((((kStages - 2) * LPW) >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    issue(k + kStages - 1);
+    const unsigned sb = smem_base + (unsigned)(k % kStages) * STAGE;
+    const int valid = d - k * KW;
+#pragma unroll
+    for (int st = 0; st < kVpr / 2; ++st) {
+      const int vec = st * 2 + half;
+      const int ra = wave * 32 + frow;
+      v4u fa = *(lds_v4u_ptr)(sb + (unsigned)ra * kRowBytes + (unsigned)((vec ^ (ra & (kVpr - 1))) * 16));
+      if (valid < KW && vec * kV >= valid) fa = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int b = 0; b < NBS; ++b) {
+        const int rb = kTok + b * 32 + frow;
+        const v4u fb = *(lds_v4u_ptr)(sb + (unsigned)rb * kRowBytes + (unsigned)((vec ^ (rb & (kVpr - 1))) * 16));
+        if constexpr (BF16) {
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), __builtin_bit_cast(bf16x8, fb),
+                                                           acc[b], 0, 0, 0);
+        } else {
+          const f32x4 xa = __builtin_bit_cast(f32x4, fa), xb = __builtin_bit_cast(f32x4, fb);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[e], xb[e], acc[b], 0, 0, 0);
+        }
+      }
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+  __builtin_amdgcn_s_barrier();          // the ring is reused by the next pass
+}
+
+template <int NBS, bool BF16>
+__global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * kTok;
+
+  f32x16 P[NBS], Q[NBS];
+#pragma unroll
+  for (int b = 0; b < NBS; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { P[b][v] = 0.f; Q[b][v] = 0.f; }
+  product_pass<NBS, BF16>(p.Delta, p.d_out, p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, P);
+  product_pass<NBS, BF16>(p.X, p.d_in, p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, Q);
+
+  // lane holds sample column (lane & 31) of each block and token rows acc_row(v, lane) of the wave's 32 tokens
+  const int tw = t0 + wave * 32;
+  if (tw >= p.n_tokens) return;
+  const int t_last = min(tw + 31, p.n_tokens - 1);
+  const int r_first = p.tok_seq[tw], r_last = p.tok_seq[t_last];
+  const int ncol = 32 * NBS;
+#pragma unroll
+  for (int b = 0; b < NBS; ++b) {
+    const int j = b * 32 + (lane & 31);
+    if (r_first == r_last) {
+      double s = 0.0;
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (tw + acc_row(v, lane) < p.n_tokens) s += (double)P[b][v] * (double)Q[b][v];
+      s += __shfl_xor(s, 32, kWave);
+      if (lane < 32 && j < p.n_samples) atomicAdd(&p.S64[(size_t)r_first * ncol + j], s);
+    } else {
+      double run = 0.0;
+      int run_r = -1;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int t = tw + acc_row(v, lane);
+        if (t >= p.n_tokens) continue;
+        const int r = p.tok_seq[t];
+        if (r != run_r) {
+          if (run_r >= 0 && j < p.n_samples) atomicAdd(&p.S64[(size_t)run_r * ncol + j], run);
+          run_r = r;
+          run = 0.0;
+        }
+        run += (double)P[b][v] * (double)Q[b][v];
+      }
+      if (run_r >= 0 && j < p.n_samples) atomicAdd(&p.S64[(size_t)run_r * ncol + j], run);
+    }
+  }
+}
+
+// F_i^2 = sum_j s_ij^2 / sum_j den_j ;  c_i = A_i / sqrt(F_i^2 + reg).  One workgroup, fixed order.
+__global__ __launch_bounds__(256) void fisher_samples_finish_kernel(const double* __restrict__ S64,
+                                                                    const double* __restrict__ den, int n_seq,
+                                                                    int n_samples, int ncol, const float* __restrict__ A,
+                                                                    float lambda, int reg_mode, float* __restrict__ c,
+                                                                    float* __restrict__ f2_out, double* __restrict__ f2_tmp) {
+  __shared__ double sh[2];
+  if (threadIdx.x == 0) {
+    double d = 0.0;
+    for (int j = 0; j < n_samples; ++j) d += den[j];
+    sh[0] = d;
+  }
+  __syncthreads();
+  const double d = sh[0];
+  for (int i = threadIdx.x; i < n_seq; i += 256) {
+    double s = 0.0;
+    for (int j = 0; j < n_samples; ++j) {
+      const double x = S64[(size_t)i * ncol + j];
+      s += x * x;
+    }
+    f2_tmp[i] = d > 0.0 ? s / d : 0.0;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double m = 0.0;
+    for (int i = 0; i < n_seq; ++i) m += f2_tmp[i];
+    sh[1] = reg_mode == 1 ? (double)lambda * m / n_seq : (double)lambda;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_seq; i += 256) {
+    const double den_i = f2_tmp[i] + sh[1];
+    c[i] = den_i > 0.0 ? (float)((double)A[i] / sqrt(den_i)) : 0.f;
+    if (f2_out) f2_out[i] = (float)f2_tmp[i];
+  }
+}
+
+template <int NBS, bool BF16>
+hipError_t launch_main(const Params& p, hipStream_t s) {
+  constexpr size_t smem = (size_t)kStages * (kTok + 32 * NBS) * kRowBytes;
+  auto kern = fisher_samples_kernel<NBS, BF16>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((p.n_tokens + kTok - 1) / kTok), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+
+size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples) {
+  const int ncol = 32 * ((n_samples + 31) / 32);
+  return align256((size_t)n_tokens * 4) + align256((size_t)n_seq * ncol * 8) + align256((size_t)n_samples * 8) +
+         align256((size_t)n_seq * 8);
+}
+
+hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
+  const int nbs = (a.n_samples + 31) / 32;
+  if (nbs < 1 || nbs > kMaxSampleBlocks) return hipErrorInvalidValue;
+  const int ncol = 32 * nbs;
+  char* ws = static_cast<char*>(a.workspace);
+  Params p;
+  p.X = a.X; p.Delta = a.Delta; p.off = a.off; p.idx = a.sample_idx;
+  p.n_tokens = a.n_tokens; p.d_in = a.d_in; p.d_out = a.d_out; p.n_seq = a.n_seq; p.n_samples = a.n_samples;
+  p.tok_seq = reinterpret_cast<int32_t*>(ws);
+  ws += align256((size_t)a.n_tokens * 4);
+  p.S64 = reinterpret_cast<double*>(ws);
+  ws += align256((size_t)a.n_seq * ncol * 8);
+  p.den = reinterpret_cast<double*>(ws);
+  ws += align256((size_t)a.n_samples * 8);
+  double* f2_tmp = reinterpret_cast<double*>(ws);
+
+  const long long ns = (long long)a.n_seq * ncol;
+  hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, s, p.S64, ns);
+  if (a.n_tokens > 0) {
+    hipLaunchKernelGGL(tok_seq_kernel, dim3((a.n_tokens + 255) / 256), dim3(256), 0, s, a.off, a.n_seq, a.n_tokens,
+                       p.tok_seq);
+    if (a.bf16) hipLaunchKernelGGL((sample_norm_kernel<true>), dim3(a.n_samples), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((sample_norm_kernel<false>), dim3(a.n_samples), dim3(256), 0, s, p);
+    hipError_t e;
+    switch (nbs * 2 + (a.bf16 ? 1 : 0)) {
+      case 2: e = launch_main<1, false>(p, s); break;
+      case 3: e = launch_main<1, true>(p, s); break;
+      case 4: e = launch_main<2, false>(p, s); break;
+      case 5: e = launch_main<2, true>(p, s); break;
+      case 6: e = launch_main<3, false>(p, s); break;
+      case 7: e = launch_main<3, true>(p, s); break;
+      case 8: e = launch_main<4, false>(p, s); break;
+      default: e = launch_main<4, true>(p, s); break;
+    }
+    if (e != hipSuccess) return e;
+  } else {
+    hipLaunchKernelGGL(zero_f64_kernel, dim3((a.n_samples + 255) / 256), dim3(256), 0, s, p.den, (long long)a.n_samples);
+  }
+  hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(1), dim3(256), 0, s, p.S64, p.den, a.n_seq, a.n_samples, ncol,
+                     a.A, a.lambda, a.reg_mode, a.c, a.fisher_sq, f2_tmp);
+  return hipGetLastError();
+}
+
+}  // namespace isopo

@@ -76,6 +76,24 @@ hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s);
 hipError_t launch_scale_rows(const void* src, bool bf16, long long n_tokens, int d, const int32_t* off, int n_seq,
                              const float* c, void* dst, hipStream_t s);
 
+// Token-position-sample Fisher norms and the coefficients c_i = A_i / sqrt(F_i^2 + reg).
+struct FisherSamplesArgs {
+  const void* X;
+  const void* Delta;
+  const int32_t* off;
+  const int32_t* sample_idx;   // device [n_samples], token rows
+  int n_tokens, d_in, d_out, n_seq, n_samples;
+  bool bf16;
+  const float* A;
+  float lambda;
+  int reg_mode;
+  float* c;
+  float* fisher_sq;            // optional [n_seq]
+  void* workspace;
+};
+size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples);
+hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s);
+
 struct TransformArgs {
   const float* K;
   const float* A;

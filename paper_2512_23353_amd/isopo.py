@@ -29,7 +29,8 @@ _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
 EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
-           "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows", "isopo_status_string", "isopo_version")
+           "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
+           "isopo_fisher_samples_workspace", "isopo_fisher_samples", "isopo_status_string", "isopo_version")
 
 
 class IsopoError(RuntimeError):
@@ -80,6 +81,10 @@ def load() -> ctypes.CDLL:
     lib.isopo_weighted_grad.restype = ctypes.c_int
     lib.isopo_scale_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int64, i32, vp, i32, vp, vp, vp]
     lib.isopo_scale_rows.restype = ctypes.c_int
+    lib.isopo_fisher_samples_workspace.argtypes = [lp, i32]
+    lib.isopo_fisher_samples_workspace.restype = sz
+    lib.isopo_fisher_samples.argtypes = [lp, vp, i32, vp, f32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.isopo_fisher_samples.restype = ctypes.c_int
     lib.isopo_status_string.argtypes = [ctypes.c_int]
     lib.isopo_status_string.restype = ctypes.c_char_p
     lib.isopo_version.argtypes = []
@@ -243,6 +248,26 @@ def weighted_grad(layer: Layer, c: Optional[torch.Tensor], stash: Optional[torch
     _check(load().isopo_weighted_grad(layer.ref(), _ptr(c), _ptr(stash), float(beta), dW.data_ptr(),
                                       _stream(stream)), "isopo_weighted_grad")
     return dW
+
+
+def fisher_samples(layer: Layer, sample_idx: torch.Tensor, A: torch.Tensor, lam: float = 0.0,
+                   reg_mode: int = REG_ABSOLUTE, c: Optional[torch.Tensor] = None,
+                   fisher_sq: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Coefficients of the non-interacting update from the token-position-sample Fisher estimate.
+    sample_idx: int32 device tensor of token rows.  Returns (c, F^2)."""
+    n_s = int(sample_idx.numel())
+    if sample_idx.dtype != torch.int32 or not sample_idx.is_contiguous():
+        raise ValueError("sample_idx must be a contiguous int32 tensor")
+    if c is None:
+        c = torch.empty(layer.n_seq, dtype=torch.float32, device=layer.device)
+    if fisher_sq is None:
+        fisher_sq = torch.empty(layer.n_seq, dtype=torch.float32, device=layer.device)
+    if workspace is None:
+        workspace = alloc_workspace(load().isopo_fisher_samples_workspace(layer.ref(), n_s), layer.device)
+    _check(load().isopo_fisher_samples(layer.ref(), sample_idx.data_ptr(), n_s, A.data_ptr(), float(lam),
+                                       int(reg_mode), c.data_ptr(), fisher_sq.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel(), _stream(stream)), "isopo_fisher_samples")
+    return c, fisher_sq
 
 
 def scale_rows(src: torch.Tensor, layer: Layer, c: torch.Tensor, dst: Optional[torch.Tensor] = None,

@@ -1,0 +1,135 @@
+"""Parity of the token-position-sample Fisher coefficients (the non-interacting
+listing's F_norm estimate, evaluated in ghost form on the GPU) with the oracle,
+which forms every G_i and every rank-one g^(j) explicitly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import isopo_oracle as orc
+from paper_2512_23353_amd import isopo
+from paper_2512_23353_amd import workloads as wl
+
+from helpers import TOL, assert_c_close, assert_dW_close, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw_samples(rng, n_tokens, n_s, replace=False):
+    if replace or n_s > n_tokens:
+        return rng.integers(0, n_tokens, n_s).astype(np.int32)
+    return rng.permutation(n_tokens)[:n_s].astype(np.int32)
+
+
+def _check(prob, device, idx, lam, reg_mode, what):
+    tol = TOL[prob.dtype]
+    layer, A = to_device(prob, device)
+    c, f2 = isopo.fisher_samples(layer, torch.from_numpy(idx).to(device), A, lam, reg_mode)
+    torch.cuda.synchronize()
+    c_ref, f2_ref = orc.coeff_fisher_token_samples(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets,
+                                                   idx, prob.A, lam, reg_mode)
+    f2h = f2.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(f2h)) and np.all(f2h >= 0)
+    assert rel_err(f2h, f2_ref) <= tol, f"{what}: F^2 rel {rel_err(f2h, f2_ref)}"
+    assert np.all(np.abs(f2h - f2_ref) <= tol * (f2_ref + f2_ref.mean())), f"{what}: F^2 element guard"
+    assert_c_close(c.cpu().numpy(), c_ref, tol, what)
+    return layer, c, c_ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_s", [1, 8, 31, 32, 33, 64, 100, 128])
+def test_sample_counts(gpu_device, dtype, n_s):
+    """Every sample-block count (1..4 blocks of 32) with ragged last blocks, on a
+    microbatch spanning several 128-token workgroups and a ragged tail."""
+    rng = np.random.default_rng(100 + n_s)
+    lengths = [100, 37, 1, 0, 250, 64, 190]
+    prob = wl.custom_layer(256, 384, lengths, dtype=dtype, seed=5, sigma_delta=1e-2)
+    idx = _draw_samples(rng, prob.n_tokens, n_s)
+    _check(prob, gpu_device, idx, 1e-3, isopo.REG_REL_TRACE, f"{dtype}/n_s={n_s}")
+
+
+CASES = [
+    ("all_single_tokens", 64, 128, [1] * 40),
+    ("one_huge_many_tiny", 128, 256, [3, 1, 700, 2, 5, 1, 1, 9]),
+    ("one_sequence", 256, 128, [333]),
+    ("narrow_dims", 72, 200, [31, 32, 33, 65]),
+    ("empty_first_and_last", 128, 128, [0, 50, 0, 0, 70, 0]),
+    ("boundaries_inside_a_wave", 136, 88, [5, 7, 11, 13, 17, 19, 23, 29, 31, 2, 3]),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("reg", [(0.0, isopo.REG_ABSOLUTE), (1e-6, isopo.REG_ABSOLUTE), (1e-2, isopo.REG_REL_TRACE)])
+def test_ragged_edge_cases(gpu_device, dtype, case, reg):
+    name, d_in, d_out, lengths = case
+    rng = np.random.default_rng(7)
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype=dtype, seed=13, sigma_delta=1e-2)
+    idx = _draw_samples(rng, prob.n_tokens, 16)
+    _check(prob, gpu_device, idx, reg[0], reg[1], f"{name}/{dtype}")
+
+
+def test_repeated_and_clustered_samples(gpu_device):
+    """Samples drawn with replacement, and samples all taken from one sequence:
+    the estimate is defined for both."""
+    rng = np.random.default_rng(3)
+    prob = wl.custom_layer(192, 320, [60, 90, 30, 120], dtype="bf16", seed=17, sigma_delta=1e-2, rho=0.5)
+    _check(prob, gpu_device, _draw_samples(rng, prob.n_tokens, 48, replace=True), 1e-3, isopo.REG_REL_TRACE, "replace")
+    idx = (60 + rng.permutation(90)[:24]).astype(np.int32)
+    _check(prob, gpu_device, idx, 1e-3, isopo.REG_REL_TRACE, "clustered")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_whole_non_interacting_update(gpu_device, dtype):
+    """rescaling() followed by the weighted accumulation (non-interacting
+    listing): coefficients from the token samples, then one contraction with
+    pre-scaled rows, against the oracle's sum_i c_i G_i."""
+    rng = np.random.default_rng(23)
+    prob = wl.custom_layer(320, 256, [130, 70, 1, 200, 45], dtype=dtype, seed=29, sigma_delta=1e-2)
+    idx = _draw_samples(rng, prob.n_tokens, 32)
+    layer, c, c_ref = _check(prob, gpu_device, idx, 1e-3, isopo.REG_REL_TRACE, "update")
+    dW = isopo.weighted_grad_prescaled(layer, c)
+    torch.cuda.synchronize()
+    Xo, Do = wl.to_oracle(prob.X), wl.to_oracle(prob.Delta)
+    G = orc.seq_logprob_grads(Xo, Do, prob.seq_offsets)
+    ref = orc.weighted_grad(G, c_ref)
+    mag = orc.weighted_grad_abs(G, c_ref)
+    assert_dW_close(dW.cpu().numpy(), ref, TOL[dtype], "token-sample update", mag)
+
+
+def test_config3_full_size_sampled_sequences(gpu_device):
+    """The 7B-class gate projection at full size (3584 -> 18944, B = 32, lengths
+    in [512, 4096]) with the listing's default of 32 samples: F^2 of the three
+    shortest sequences against the oracle, and properties of the rest."""
+    w = wl.CONFIGS["config3"]
+    lengths = wl.draw_lengths(w)
+    proj = {p.name: p for p in w.projections}["gate"]
+    prob = wl.make_layer(w, proj, lengths, device=gpu_device)
+    rng = np.random.default_rng(303)
+    idx = _draw_samples(rng, prob.n_tokens, 32)
+    layer, A = to_device(prob, gpu_device)
+    c, f2 = isopo.fisher_samples(layer, torch.from_numpy(idx).to(gpu_device), A, 1e-3, isopo.REG_REL_TRACE)
+    torch.cuda.synchronize()
+    f2h = f2.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(f2h)) and np.all(f2h > 0)
+    ch = c.cpu().numpy().astype(np.float64)
+    assert np.allclose(ch, prob.A / np.sqrt(f2h + 1e-3 * f2h.mean()), rtol=1e-5, atol=0)
+    short = np.argsort(lengths)[:3]
+    Xo, Do = wl.to_oracle(prob.X), wl.to_oracle(prob.Delta)
+    ref = orc.fisher_norm_sq_token_samples(Xo, Do, prob.seq_offsets, idx, seqs=short)
+    for i in short:
+        print(f"config3 gate seq {i} len {lengths[i]}: F^2 {f2h[i]:.6e} vs {ref[i]:.6e}", flush=True)
+        assert abs(f2h[i] - ref[i]) <= TOL["bf16"] * ref[i]
+
+
+def test_bad_arguments(gpu_device):
+    prob = wl.custom_layer(64, 64, [10, 20], dtype="f32", seed=1)
+    layer, A = to_device(prob, gpu_device)
+    idx = torch.zeros(200, dtype=torch.int32, device=gpu_device)
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples(layer, idx[:0], A)
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples(layer, idx[:129], A)
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples(layer, idx[:8], A, lam=-1.0)
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples(layer, idx[:8], A, workspace=torch.empty(256, dtype=torch.uint8, device=gpu_device))
