@@ -20,8 +20,11 @@ Pins (tests/test_oracle_pins.py): autograd brute force, the ghost double sum,
 rank-one closed form, unit Fisher norm, the orthogonal-gradient reduction,
 solve residual and the eigendecomposition route, the MinSR property, the
 large-regulariser limit, equivariances, the one-sequence closed form, the
-token-by-token contraction, duplicate sequences, and (token-sample Fisher
-estimate) the listing's own formula in torch plus a one-token closed form.  Every public function
+token-by-token contraction, duplicate sequences, (token-sample Fisher
+estimate) the listing's own formula in torch plus a one-token closed form,
+(generalised re-scaling) a hand-worked fixture, the explicit-Fisher minimiser
+for r = -2 and unit norms for p = -1 / q = -1, and (eigh route) agreement with
+the Cholesky solve plus a hand-iterated EMA.  Every public function
 below is pinned by at least one of them; none is "parity unpinned".
 """
 from __future__ import annotations
@@ -222,6 +225,85 @@ def coeff_fisher_token_samples(X, Delta, seq_offsets, sample_idx, A, lam: float,
     nz = den > 0
     c[nz] = A[nz] / np.sqrt(den[nz])
     return c, f2
+
+
+RESCALE_EPS = 1e-8     # the additive constant of reg() in the generalised re-scaling listing
+
+
+def reg2_squared(val_sq, regularization: float = 0.0, expectation=None) -> np.ndarray:
+    """reg2(val)^2 of the generalised re-scaling listing, from val^2:
+    reg(val^2) = val^2 + regularization * E[val^2] + 1e-8  (reg2 is its square
+    root).  `expectation` is E[val^2]; None takes the batch mean of val_sq (the
+    listing suggests an EMA of trailing minibatch means; the caller carries it)."""
+    v = np.asarray(val_sq, dtype=np.float64)
+    e = float(np.mean(v)) if expectation is None else float(expectation)
+    return v + float(regularization) * e + RESCALE_EPS
+
+
+def rescaling_general(fisher_sq, grad_sq, p: float = -1.0, q: float = 0.0, r: float = 0.0,
+                      reg=(0.0, 0.0, 0.0), expectation=(None, None, None)) -> np.ndarray:
+    """Per-sequence scale factors of the generalised re-scaling (the alternative
+    re-scalings listing):
+
+        rel_F_norm = F_norm / ||G||
+        scaling = reg2(F_norm)^p * reg2(||G||)^q * reg2(rel_F_norm)^r
+
+    fisher_sq = F_norm^2 and grad_sq = ||G_i||^2 (= K_ii) per sequence.  reg and
+    expectation hold the regularisation factor and E[val^2] for the three
+    regularised quantities in the order (F_norm, ||G||, rel_F_norm).
+    p = -1: the KL-bounding re-scaling; r = -2: the closest-to-natural-gradient
+    one; q = -1, r = -2: the headline experiment's setting.
+
+    A sequence with G_i = 0 (empty, or all-zero rows) has no direction to scale:
+    rel_F_norm is taken as 0 there (the listing's 0/0), which leaves
+    reg2(rel)^r finite because of the 1e-8.
+    """
+    f2 = np.asarray(fisher_sq, dtype=np.float64)
+    g2 = np.asarray(grad_sq, dtype=np.float64)
+    rel2 = np.zeros_like(f2)
+    nz = g2 > 0
+    rel2[nz] = f2[nz] / g2[nz]
+    sF = np.sqrt(reg2_squared(f2, reg[0], expectation[0]))
+    sG = np.sqrt(reg2_squared(g2, reg[1], expectation[1]))
+    sR = np.sqrt(reg2_squared(rel2, reg[2], expectation[2]))
+    return sF ** float(p) * sG ** float(q) * sR ** float(r)
+
+
+def coeff_rescaled(fisher_sq, grad_sq, A, p=-1.0, q=0.0, r=0.0, reg=(0.0, 0.0, 0.0),
+                   expectation=(None, None, None)) -> np.ndarray:
+    """c_i = A_i * scaling_i: the coefficient with which G_i enters the layer's
+    update (`grad += advantages[seq_id] * rescaling(seq_logprob_grad, F_norm)`)."""
+    return np.asarray(A, dtype=np.float64) * rescaling_general(fisher_sq, grad_sq, p, q, r, reg, expectation)
+
+
+def ema_update(state, value: float, decay: float = 0.9):
+    """Trailing mean over minibatches with exponential decay (the interacting
+    experiment's E[mean(D)], decay 0.9).  state None: first minibatch, the mean
+    is the value itself.  Returns the new state (a float)."""
+    return float(value) if state is None else float(decay) * float(state) + (1.0 - float(decay)) * float(value)
+
+
+def ntk_eigh(K):
+    """D, U = eigh(K) of the interacting listing (ascending eigenvalues,
+    orthonormal columns)."""
+    return np.linalg.eigh(np.asarray(K, dtype=np.float64))
+
+
+def coeff_from_eigh(D, U, A, reg: float) -> np.ndarray:
+    """advantages_preconditioned = U ((1 / (D + regularization)) * (U^T A)) of
+    the interacting listing, for one decomposition and any number of
+    regularisers."""
+    A = np.asarray(A, dtype=np.float64)
+    return U @ ((1.0 / (D + float(reg))) * (U.T @ A))
+
+
+def coeff_interacting_ema(K, A, factor: float, ema_state, decay: float = 0.9):
+    """Interacting coefficients with the regulariser factor * E[mean(D)], the
+    expectation being the trailing mean over minibatches INCLUDING the current
+    one (so that the first minibatch is defined).  Returns (c, new_state)."""
+    D, U = ntk_eigh(K)
+    state = ema_update(ema_state, float(np.mean(D)), decay)
+    return coeff_from_eigh(D, U, A, float(factor) * state), state
 
 
 def coeff_interacting(K, A, lam: float, reg_mode: int = REG_ABSOLUTE):

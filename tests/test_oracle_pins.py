@@ -364,3 +364,98 @@ def test_token_sample_fisher_estimate():
     X2, D2, off2 = _rand_layer(rng, [3, 0, 4], 5, 4)
     c, f2 = orc.coeff_fisher_token_samples(X2, D2, off2, [0, 5], np.ones(3), 0.0)
     assert f2[1] == 0.0 and c[1] == 0.0
+
+
+def test_generalised_rescaling_fixture():
+    """Hand-worked values of the generalised re-scaling (alternative re-scalings
+    listing), including regularisation with batch-mean and caller-supplied
+    expectations."""
+    fx = json.load(open(os.path.join(GOLDEN, "hand_worked_rescaling.json")))
+    f2, g2 = fx["fisher_sq"], fx["grad_sq"]
+    for case in ("headline", "fisher_reg", "mixed"):
+        c = fx[case]
+        got = orc.rescaling_general(f2, g2, c["p"], c["q"], c["r"], tuple(c.get("reg", (0, 0, 0))),
+                                    tuple(c.get("expectation", (None, None, None))))
+        np.testing.assert_allclose(got, c["scaling"], rtol=c["rel_tol"], err_msg=case)
+
+
+def test_generalised_rescaling_properties():
+    """What the paper fixes about the (p, q, r) family: p = -1 is the
+    KL-bounding re-scaling (unit Fisher norm), q = -1 gives unit Euclidean norm,
+    r = -2 is the minimiser of ||lambda v - F^-1 g||_F over lambda for an
+    explicit Fisher matrix, and the exponents compose multiplicatively."""
+    rng = np.random.default_rng(31)
+    X, D, off = _rand_layer(rng, [5, 3, 6, 4, 7], 6, 5)
+    G = orc.seq_logprob_grads(X, D, off)
+    K = orc.ntk_from_seq_grads(G)
+    m = K.shape[0]
+    f2, g2 = orc.fisher_norm_sq(K), np.diag(K).copy()
+    # p = -1 reproduces the non-interacting coefficients with reg = 1e-8 (absolute)
+    A = rng.standard_normal(m)
+    np.testing.assert_allclose(orc.coeff_rescaled(f2, g2, A), orc.coeff_fisher(K, A, 1e-8), rtol=1e-12)
+    # ... and with a regularisation factor on E[F^2] given by the caller
+    np.testing.assert_allclose(orc.coeff_rescaled(f2, g2, A, reg=(0.3, 0, 0), expectation=(2.0, None, None)),
+                               orc.coeff_fisher(K, A, 0.6 + 1e-8), rtol=1e-12)
+    # q = -1: every scaled gradient has Euclidean norm 1
+    s = orc.rescaling_general(f2, g2, 0, -1, 0)
+    for i in range(m):
+        assert np.linalg.norm(s[i] * G[i]) == pytest.approx(1.0, rel=1e-7)
+    # r = -2 against an explicit Fisher matrix: F = (1/m) sum_j g_j g_j^T + small ridge (so F^-1 exists);
+    # the best scalar multiple of v = g_i approximating F^-1 (A v) in the F metric, found by
+    # fitting the quadratic objective at three points, is A ||v||^2 / (v.F v)
+    J = G.reshape(m, -1)
+    Fm = J.T @ J / m + 1e-3 * np.eye(J.shape[1])
+    Finv = np.linalg.inv(Fm)
+    for i in range(m):
+        v = J[i]
+        a = 1.7
+        target = Finv @ (a * v)
+        obj = lambda lam: (lam * v - target) @ Fm @ (lam * v - target)
+        y0, y1, y2 = obj(0.0), obj(1.0), obj(2.0)      # exact quadratic in lam
+        qa = (y2 - 2 * y1 + y0) / 2
+        qb = y1 - y0 - qa
+        lam_star = -qb / (2 * qa)
+        vFv = v @ Fm @ v
+        s_i = orc.rescaling_general([vFv], [v @ v], 0, 0, -2)[0]
+        assert a * s_i == pytest.approx(lam_star, rel=1e-6)
+    # exponents compose: scaling(p,q,r) = scaling(p,0,0) * scaling(0,q,0) * scaling(0,0,r); scaling(0,0,0) = 1
+    full = orc.rescaling_general(f2, g2, -0.5, 0.7, -1.3, (0.1, 0.2, 0.3))
+    parts = (orc.rescaling_general(f2, g2, -0.5, 0, 0, (0.1, 0.2, 0.3)) * orc.rescaling_general(f2, g2, 0, 0.7, 0, (0.1, 0.2, 0.3))
+             * orc.rescaling_general(f2, g2, 0, 0, -1.3, (0.1, 0.2, 0.3)))
+    np.testing.assert_allclose(full, parts, rtol=1e-12)
+    np.testing.assert_array_equal(orc.rescaling_general(f2, g2, 0, 0, 0), np.ones(m))
+    # homogeneity (no regularisation): G -> 3 G scales F by 9 (F is quadratic in g), ||G|| by 3, rel by 3
+    s1 = orc.rescaling_general(f2, g2, -1, -1, -2)
+    s3 = orc.rescaling_general(81 * f2, 9 * g2, -1, -1, -2)
+    np.testing.assert_allclose(s3, s1 * 9.0 ** -1 * 3.0 ** -1 * 3.0 ** -2, rtol=1e-6)
+    # a zero gradient: finite scaling, zero coefficient contribution c_i * G_i
+    s0 = orc.rescaling_general([0.0, 1.0], [0.0, 2.0], 0, -1, -2)
+    assert np.isfinite(s0).all()
+
+
+def test_eigh_route_and_ema():
+    """D, U = eigh(K) once, any number of regularisers: equals the Cholesky
+    solve for each; the trailing mean iterated by hand."""
+    rng = np.random.default_rng(41)
+    X, D_, off = _rand_layer(rng, [4, 6, 3, 5], 6, 5)
+    K = orc.layer_ntk(X, D_, off)
+    A = rng.standard_normal(4)
+    D, U = orc.ntk_eigh(K)
+    np.testing.assert_allclose(U @ np.diag(D) @ U.T, K, atol=1e-10 * np.trace(K))
+    np.testing.assert_allclose(U.T @ U, np.eye(4), atol=1e-12)
+    assert np.mean(D) == pytest.approx(np.trace(K) / 4, rel=1e-12)
+    for lam in (1e-4, 1e-3, 1e-2):
+        c_ref, info = orc.coeff_interacting(K, A, lam, orc.REG_REL_TRACE)
+        np.testing.assert_allclose(orc.coeff_from_eigh(D, U, A, lam * np.mean(D)), c_ref, rtol=1e-8)
+    # EMA with decay 0.9 over three minibatches, by hand: s1 = m1; s2 = 0.9 m1 + 0.1 m2; s3 = 0.9 s2 + 0.1 m3
+    state = None
+    means, states = [], []
+    for scale in (1.0, 4.0, 0.25):
+        c, state = orc.coeff_interacting_ema(scale * K, A, 1.0, state)
+        means.append(scale * np.trace(K) / 4)
+        states.append(state)
+        c_ref, _ = orc.coeff_interacting(scale * K, A, state, orc.REG_ABSOLUTE)
+        np.testing.assert_allclose(c, c_ref, rtol=1e-8)
+    assert states[0] == pytest.approx(means[0], rel=1e-12)
+    assert states[1] == pytest.approx(0.9 * means[0] + 0.1 * means[1], rel=1e-12)
+    assert states[2] == pytest.approx(0.81 * means[0] + 0.09 * means[1] + 0.1 * means[2], rel=1e-12)
