@@ -68,8 +68,11 @@ typedef enum {
 
 typedef enum {
   ISOPO_REG_ABSOLUTE = 0,           /* reg = lambda (the Tikhonov constant as printed) */
-  ISOPO_REG_REL_TRACE = 1           /* reg = lambda * tr(K)/m (relative to the mean eigenvalue,
+  ISOPO_REG_REL_TRACE = 1,          /* reg = lambda * tr(K)/m (relative to the mean eigenvalue,
                                        as the interacting experiment's regulariser is) */
+  ISOPO_REG_EMA_TRACE = 2           /* reg = lambda * trailing mean over minibatches of tr(K)/m
+                                       (interacting experiment: factor * E[mean(D)], decay 0.9);
+                                       isopo_transform_eigh only */
 } isopo_reg_mode;
 
 /* One ragged layer problem.  All pointers caller-owned. */
@@ -169,6 +172,64 @@ size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_sample
 isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,
                                   const float* A, float lambda, isopo_reg_mode reg_mode, float* c,
                                   float* fisher_sq, void* workspace, size_t ws_bytes, void* stream);
+
+/* Norms the re-scalings are built from, read off the Gram matrix: fisher_sq[i] = (1/m) sum_j K_ij^2
+ * (eq. F-norm-basic with the batch's reduced gradients as samples) and grad_sq[i] = K_ii = ||G_i||^2.
+ * Device pointers, either output may be NULL. */
+isopo_status isopo_gram_norms(const float* K, int32_t n_seq, float* fisher_sq, float* grad_sq, void* stream);
+
+/* Generalised re-scaling (alternative re-scalings listing):
+ *     rel_F_norm = F_norm / ||G||
+ *     c_i = A_i * reg2(F_norm_i)^p * reg2(||G_i||)^q * reg2(rel_F_norm_i)^r
+ *     reg2(val) = sqrt(val^2 + regularization * E[val^2] + 1e-8)
+ * p = -1 (q = r = 0): the KL-bounding re-scaling; r = -2: the multiple of G_i closest to the natural
+ * gradient in the Fisher metric; q = -1, r = -2: the headline experiment's setting.
+ *   fisher_sq      device [n_seq], F_norm^2 (from isopo_gram_norms or isopo_fisher_samples)
+ *   grad_sq        device, ||G_i||^2 at grad_sq[i * grad_sq_stride] (pass K with stride n_seq + 1 to
+ *                  read its diagonal in place)
+ *   reg[3]         host: regularisation factors for (F_norm, ||G||, rel_F_norm), each >= 0
+ *   expectation[3] host: E[val^2] for the same three, e.g. the caller's trailing mean over
+ *                  minibatches; a negative entry means "this batch's mean"
+ *   batch_means    optional device [3]: this batch's means of F^2, ||G||^2, rel^2, for the caller's
+ *                  trailing mean
+ * A sequence with ||G_i|| = 0 takes rel_F_norm = 0; its c_i is finite and multiplies a zero gradient. */
+typedef struct isopo_rescale_params {
+  float p, q, r;
+  float reg[3];
+  float expectation[3];
+} isopo_rescale_params;
+isopo_status isopo_rescale(const float* fisher_sq, const float* grad_sq, int64_t grad_sq_stride, int32_t n_seq,
+                           const float* A, const isopo_rescale_params* params, float* c, float* batch_means,
+                           void* stream);
+
+/* Eigendecomposition of the layer's Gram matrix (interacting listing: D, U = eigh(ntk)), so that a
+ * sweep over regularisers costs one decomposition.  Cyclic Jacobi in fp64 on one workgroup.
+ *   K     device fp32 [n_seq, n_seq], symmetric (the mean of K and K^T is decomposed)
+ *   D     device fp64 [n_seq], ascending
+ *   U     device fp64 [n_seq, n_seq] row-major, eigenvectors as columns: K = U diag(D) U^T
+ *   info  optional device int32: 0 converged, 1 not converged within the sweep limit
+ *   workspace  device, isopo_ntk_eigh_workspace(n_seq) bytes, 256-byte aligned (used when the work
+ *              matrices do not fit LDS) */
+size_t isopo_ntk_eigh_workspace(int32_t n_seq);
+isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, double* D, double* U, int32_t* info, void* workspace,
+                            size_t ws_bytes, void* stream);
+
+/* c_l = U ((U^T A) / (D + reg_l)) for l < n_lambda (interacting listing: preconditioner and
+ * advantages_preconditioned), all from one decomposition.
+ *   lambdas    host [n_lambda], 1 <= n_lambda <= ISOPO_MAX_LAMBDAS, each >= 0
+ *   reg_mode   ABSOLUTE: reg_l = lambda_l.  REL_TRACE: reg_l = lambda_l * mean(D).
+ *              EMA_TRACE: reg_l = lambda_l * E[mean(D)], the trailing mean over minibatches (this one
+ *              included) kept in ema_state and updated by this call:
+ *              E <- mean(D) on the first call, E <- decay E + (1 - decay) mean(D) after
+ *   ema_state  device float[2] {E, number of minibatches seen}; zero it before the first minibatch;
+ *              required for EMA_TRACE, ignored otherwise
+ *   c          device fp32 [n_lambda, n_seq]
+ *   info       optional device int32: number of (lambda, eigenvalue) pairs with D + reg <= 0; those
+ *              components are left out of c (0 for a positive definite K + reg I) */
+#define ISOPO_MAX_LAMBDAS 16
+isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_seq, const float* A,
+                                  const float* lambdas, int32_t n_lambda, isopo_reg_mode reg_mode, float* ema_state,
+                                  float ema_decay, float* c, int32_t* info, void* stream);
 
 /* dst[t, :] = c[seq(t)] * src[t, :] for a token-major matrix [n_tokens, d] (X or Delta), rounded to
  * the storage type; dst may not alias src.  Since Delta^T diag(c_tok) X = (diag(c_tok) Delta)^T X =

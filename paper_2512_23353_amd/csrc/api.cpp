@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 
+#include <cmath>
 #include "kernels.h"
 
 namespace {
@@ -294,6 +295,65 @@ isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sampl
   f.n_samples = n_samples; f.bf16 = layer->dtype == ISOPO_BF16; f.A = A; f.lambda = lambda;
   f.reg_mode = (int)reg_mode; f.c = c; f.fisher_sq = fisher_sq; f.workspace = workspace;
   return launch_fisher_samples(f, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_gram_norms(const float* K, int32_t n_seq, float* fisher_sq, float* grad_sq, void* stream) {
+  if (!K || n_seq <= 0 || (!fisher_sq && !grad_sq)) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  return launch_gram_norms(K, n_seq, fisher_sq, grad_sq, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_rescale(const float* fisher_sq, const float* grad_sq, int64_t grad_sq_stride, int32_t n_seq,
+                           const float* A, const isopo_rescale_params* params, float* c, float* batch_means,
+                           void* stream) {
+  if (!fisher_sq || !grad_sq || !A || !params || !c || n_seq <= 0 || grad_sq_stride < 1) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  RescaleArgs r;
+  r.fisher_sq = fisher_sq; r.grad_sq = grad_sq; r.grad_sq_stride = grad_sq_stride; r.n_seq = n_seq; r.A = A;
+  r.p = params->p; r.q = params->q; r.r = params->r;
+  if (!std::isfinite(r.p) || !std::isfinite(r.q) || !std::isfinite(r.r)) return ISOPO_ERR_INVALID_ARG;
+  for (int k = 0; k < 3; ++k) {
+    if (!(params->reg[k] >= 0.f) || std::isnan(params->expectation[k])) return ISOPO_ERR_INVALID_ARG;
+    r.reg[k] = params->reg[k];
+    r.expectation[k] = params->expectation[k];
+  }
+  r.c = c; r.batch_means = batch_means;
+  return launch_rescale(r, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+size_t isopo_ntk_eigh_workspace(int32_t n_seq) {
+  if (n_seq <= 0 || n_seq > ISOPO_MAX_SEQ) return 0;
+  return align_up(eigh_workspace(n_seq));
+}
+
+isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, double* D, double* U, int32_t* info, void* workspace,
+                            size_t ws_bytes, void* stream) {
+  if (!K || !D || !U || n_seq <= 0) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1))) return ISOPO_ERR_INVALID_ARG;
+  if (ws_bytes < isopo_ntk_eigh_workspace(n_seq)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  return launch_ntk_eigh(K, n_seq, D, U, info, workspace, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_seq, const float* A,
+                                  const float* lambdas, int32_t n_lambda, isopo_reg_mode reg_mode, float* ema_state,
+                                  float ema_decay, float* c, int32_t* info, void* stream) {
+  if (!D || !U || !A || !lambdas || !c || n_seq <= 0 || n_lambda < 1) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ || n_lambda > ISOPO_MAX_LAMBDAS) return ISOPO_ERR_UNSUPPORTED;
+  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE && reg_mode != ISOPO_REG_EMA_TRACE)
+    return ISOPO_ERR_INVALID_ARG;
+  if (reg_mode == ISOPO_REG_EMA_TRACE && (!ema_state || !(ema_decay >= 0.f && ema_decay < 1.f)))
+    return ISOPO_ERR_INVALID_ARG;
+  EighSolveArgs e;
+  e.D = D; e.U = U; e.n_seq = n_seq; e.A = A; e.n_lambda = n_lambda;
+  for (int l = 0; l < kEighMaxLambdas; ++l) {
+    e.lambdas[l] = l < n_lambda ? lambdas[l] : 0.f;
+    if (l < n_lambda && !(lambdas[l] >= 0.f)) return ISOPO_ERR_INVALID_ARG;
+  }
+  e.reg_mode = (int)reg_mode; e.ema_state = ema_state; e.ema_decay = ema_decay; e.c = c; e.info = info;
+  return launch_eigh_solve(e, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
 isopo_status isopo_scale_rows(const void* src, isopo_dtype dtype, int64_t n_tokens, int32_t d,

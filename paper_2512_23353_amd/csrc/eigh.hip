@@ -1,0 +1,214 @@
+// Eigendecomposition route of the interacting variant (interacting listing:
+// D, U = eigh(ntk); c = U ((1 / (D + regularization)) * (U^T A))).
+//
+// One decomposition serves any number of regularisers, so a sweep over lambda
+// costs one factorisation instead of one Cholesky per value.  K is m x m with
+// m the number of sequences (tens to a few hundred), so one workgroup runs a
+// cyclic two-sided Jacobi iteration in fp64: each round applies m/2 disjoint
+// plane rotations (round-robin pairing), first to the rows, then to the columns
+// of the work matrix and to the accumulated eigenvector matrix.  The matrices
+// live in LDS when they fit, else in a caller-provided global scratch that stays
+// in L2.  Eigenvalues come out ascending, eigenvectors as columns.
+#include "common.h"
+#include "kernels.h"
+
+namespace isopo {
+namespace {
+
+constexpr int kMaxPairs = kEighMaxSeq / 2;
+constexpr int kMaxSweeps = 40;
+constexpr double kOffTol = 1e-14;      // stop when ||off(A)||_F <= kOffTol * ||A||_F
+
+template <int THREADS>
+__device__ double block_sum(double x, double* red) {
+  x = wave_sum(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  double s = 0.0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) s += red[w];
+  return s;
+}
+
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void jacobi_eigh_kernel(const float* __restrict__ K, int m,
+                                                              double* __restrict__ D, double* __restrict__ U,
+                                                              int32_t* __restrict__ info, double* __restrict__ gws) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  __shared__ double rot_c[kMaxPairs], rot_s[kMaxPairs];
+  __shared__ short rot_p[kMaxPairs], rot_q[kMaxPairs];
+  __shared__ double red[THREADS / 64];
+  const int tid = threadIdx.x;
+  const int n = (m + 1) & ~1;            // even: an odd m gets one idle index
+  const int ld = n + 1;                  // odd pitch: column walks spread over the LDS banks
+  double* Aw = gws ? gws : reinterpret_cast<double*>(smem_raw);
+  double* V = Aw + (size_t)n * ld;
+  const int half = n / 2;
+
+  for (int e = tid; e < n * n; e += THREADS) {
+    const int i = e / n, j = e % n;
+    double v = 0.0;
+    if (i < m && j < m) v = 0.5 * ((double)K[(size_t)i * m + j] + (double)K[(size_t)j * m + i]);
+    Aw[(size_t)i * ld + j] = v;
+    V[(size_t)i * ld + j] = i == j ? 1.0 : 0.0;
+  }
+  __syncthreads();
+
+  int status = 1;                        // 1: not converged within kMaxSweeps
+  for (int sweep = 0; sweep <= kMaxSweeps; ++sweep) {
+    double off = 0.0, dia = 0.0;
+    for (int e = tid; e < n * n; e += THREADS) {
+      const int i = e / n, j = e % n;
+      const double v = Aw[(size_t)i * ld + j];
+      if (i == j) dia += v * v; else off += v * v;
+    }
+    off = block_sum<THREADS>(off, red);
+    dia = block_sum<THREADS>(dia, red);
+    if (off <= kOffTol * kOffTol * (off + dia)) { status = 0; break; }     // uniform: same sums in every thread
+    if (sweep == kMaxSweeps) break;
+    for (int round = 0; round < n - 1; ++round) {
+      if (tid < half) {
+        // round-robin pairing of n players: index n-1 stays, the others rotate
+        int p, q;
+        if (tid == 0) { p = n - 1; q = round; }
+        else { p = (round + tid) % (n - 1); q = (round - tid + (n - 1)) % (n - 1); }
+        double c = 1.0, s = 0.0;
+        if (p < m && q < m) {
+          const double apq = Aw[(size_t)p * ld + q];
+          if (apq != 0.0) {
+            const double tau = (Aw[(size_t)q * ld + q] - Aw[(size_t)p * ld + p]) / (2.0 * apq);
+            const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+            c = 1.0 / sqrt(1.0 + t * t);
+            s = t * c;
+          }
+        }
+        rot_c[tid] = c; rot_s[tid] = s; rot_p[tid] = (short)p; rot_q[tid] = (short)q;
+      }
+      __syncthreads();
+      for (int e = tid; e < half * n; e += THREADS) {            // rows p and q: A <- J^T A
+        const int pr = e / n, k = e % n;
+        const double c = rot_c[pr], s = rot_s[pr];
+        const int p = rot_p[pr], q = rot_q[pr];
+        const double ap = Aw[(size_t)p * ld + k], aq = Aw[(size_t)q * ld + k];
+        Aw[(size_t)p * ld + k] = c * ap - s * aq;
+        Aw[(size_t)q * ld + k] = s * ap + c * aq;
+      }
+      __syncthreads();
+      for (int e = tid; e < half * n; e += THREADS) {            // columns p and q: A <- A J, V <- V J
+        const int pr = e % half, k = e / half;
+        const double c = rot_c[pr], s = rot_s[pr];
+        const int p = rot_p[pr], q = rot_q[pr];
+        const double ap = Aw[(size_t)k * ld + p], aq = Aw[(size_t)k * ld + q];
+        Aw[(size_t)k * ld + p] = c * ap - s * aq;
+        Aw[(size_t)k * ld + q] = s * ap + c * aq;
+        const double vp = V[(size_t)k * ld + p], vq = V[(size_t)k * ld + q];
+        V[(size_t)k * ld + p] = c * vp - s * vq;
+        V[(size_t)k * ld + q] = s * vp + c * vq;
+      }
+      __syncthreads();
+    }
+  }
+
+  // ascending order by rank (ties broken by index), eigenvectors as columns of U
+  for (int i = tid; i < m; i += THREADS) {
+    const double di = Aw[(size_t)i * ld + i];
+    int rank = 0;
+    for (int j = 0; j < m; ++j) {
+      const double dj = Aw[(size_t)j * ld + j];
+      rank += (dj < di || (dj == di && j < i)) ? 1 : 0;
+    }
+    D[rank] = di;
+    for (int k = 0; k < m; ++k) U[(size_t)k * m + rank] = V[(size_t)k * ld + i];
+  }
+  if (info && tid == 0) *info = status;
+}
+
+constexpr int kSolveThreads = 256;
+
+// c[l] = U ((U^T A) / (D + reg_l)) for each regulariser of the sweep.
+__global__ __launch_bounds__(kSolveThreads) void eigh_solve_kernel(EighSolveArgs a) {
+  __shared__ double y[kEighMaxSeq];
+  __shared__ double red[kSolveThreads / 64];
+  __shared__ double sh_scale;
+  const int tid = threadIdx.x, m = a.n_seq;
+  double tr = 0.0;
+  for (int j = tid; j < m; j += kSolveThreads) {
+    double s = 0.0;
+    for (int i = 0; i < m; ++i) s += a.U[(size_t)i * m + j] * (double)a.A[i];
+    y[j] = s;
+    tr += a.D[j];
+  }
+  const double mean_d = block_sum<kSolveThreads>(tr, red) / (double)m;
+  if (tid == 0) {
+    double scale = 1.0;                                   // ABSOLUTE
+    if (a.reg_mode == 1) scale = mean_d;                  // this batch's mean eigenvalue
+    if (a.reg_mode == 2) {                                // trailing mean over minibatches, this one included
+      const double prev = (double)a.ema_state[0];
+      const bool first = a.ema_state[1] == 0.f;
+      scale = first ? mean_d : (double)a.ema_decay * prev + (1.0 - (double)a.ema_decay) * mean_d;
+      a.ema_state[0] = (float)scale;
+      a.ema_state[1] = a.ema_state[1] + 1.f;
+    }
+    sh_scale = scale;
+  }
+  __syncthreads();
+  const double scale = sh_scale;
+  int bad = 0;
+  for (int l = 0; l < a.n_lambda; ++l) {
+    const double reg = (double)a.lambdas[l] * scale;
+    for (int i = tid; i < m; i += kSolveThreads) {
+      double s = 0.0;
+      for (int j = 0; j < m; ++j) {
+        const double den = a.D[j] + reg;
+        if (den > 0.0) s += a.U[(size_t)i * m + j] * (y[j] / den);
+        else if (i == 0) ++bad;
+      }
+      a.c[(size_t)l * m + i] = (float)s;
+    }
+  }
+  if (a.info && tid == 0) *a.info = bad;
+}
+
+}  // namespace
+
+size_t eigh_workspace(int m) {
+  const int n = (m + 1) & ~1;
+  return 2 * (size_t)n * (n + 1) * sizeof(double);
+}
+
+hipError_t launch_ntk_eigh(const float* K, int m, double* D, double* U, int32_t* info, void* workspace,
+                           hipStream_t s) {
+  const size_t bytes = eigh_workspace(m);
+  const bool lds = bytes <= kEighLdsBytes;
+  if (m <= 64) {
+    auto kern = jacobi_eigh_kernel<256>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kEighLdsBytes);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(1), dim3(256), bytes, s, K, m, D, U, info, (double*)nullptr);
+  } else {
+    auto kern = jacobi_eigh_kernel<1024>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)kEighLdsBytes);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(1), dim3(1024), lds ? bytes : 0, s, K, m, D, U, info,
+                       lds ? (double*)nullptr : static_cast<double*>(workspace));
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(eigh_solve_kernel, dim3(1), dim3(kSolveThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace isopo

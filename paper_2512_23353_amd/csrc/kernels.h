@@ -107,4 +107,42 @@ struct TransformArgs {
 constexpr int kTransformLdsMax = 128;
 hipError_t launch_transform(const TransformArgs& a, hipStream_t s);
 
+// Generalised (p, q, r) re-scaling of the per-sequence coefficients.
+struct RescaleArgs {
+  const float* fisher_sq;      // [n_seq] F_norm^2
+  const float* grad_sq;        // ||G_i||^2 at grad_sq[i * grad_sq_stride]
+  long long grad_sq_stride;
+  int n_seq;
+  const float* A;
+  float p, q, r;
+  float reg[3];                // regularisation factors for (F_norm, ||G||, rel_F_norm)
+  float expectation[3];        // E[val^2] for each; negative: this batch's mean
+  float* c;
+  float* batch_means;          // optional [3]
+};
+hipError_t launch_rescale(const RescaleArgs& a, hipStream_t s);
+hipError_t launch_gram_norms(const float* K, int m, float* fisher_sq, float* grad_sq, hipStream_t s);
+
+// Eigendecomposition route of the interacting variant.
+constexpr int kEighMaxSeq = 1024;
+constexpr size_t kEighLdsBytes = 144 * 1024;     // work matrix + eigenvectors in LDS up to this size
+constexpr int kEighMaxLambdas = 16;
+struct EighSolveArgs {
+  const double* D;
+  const double* U;
+  int n_seq;
+  const float* A;
+  float lambdas[kEighMaxLambdas];
+  int n_lambda;
+  int reg_mode;                // 0 absolute, 1 times mean(D), 2 times the trailing mean of mean(D)
+  float* ema_state;            // [2]: trailing mean, number of minibatches seen
+  float ema_decay;
+  float* c;                    // [n_lambda][n_seq]
+  int32_t* info;
+};
+size_t eigh_workspace(int m);
+hipError_t launch_ntk_eigh(const float* K, int m, double* D, double* U, int32_t* info, void* workspace,
+                           hipStream_t s);
+hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s);
+
 }  // namespace isopo

@@ -20,7 +20,7 @@ OK = 0
 F32, BF16 = 0, 1
 GRAM_AUTO, GRAM_GHOST, GRAM_MATERIALISED = 0, 1, 2
 VARIANT_FISHER, VARIANT_INTERACTING = 0, 1
-REG_ABSOLUTE, REG_REL_TRACE = 0, 1
+REG_ABSOLUTE, REG_REL_TRACE, REG_EMA_TRACE = 0, 1, 2
 MAX_SEQ = 1024
 
 _VARIANTS = {"fisher": VARIANT_FISHER, "interacting": VARIANT_INTERACTING}
@@ -30,13 +30,20 @@ _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
-           "isopo_fisher_samples_workspace", "isopo_fisher_samples", "isopo_status_string", "isopo_version")
+           "isopo_fisher_samples_workspace", "isopo_fisher_samples",
+           "isopo_gram_norms", "isopo_rescale", "isopo_ntk_eigh_workspace", "isopo_ntk_eigh",
+           "isopo_transform_eigh", "isopo_status_string", "isopo_version")
 
 
 class IsopoError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class _RescaleParams(ctypes.Structure):
+    _fields_ = [("p", ctypes.c_float), ("q", ctypes.c_float), ("r", ctypes.c_float),
+                ("reg", ctypes.c_float * 3), ("expectation", ctypes.c_float * 3)]
 
 
 class _Layer(ctypes.Structure):
@@ -85,6 +92,17 @@ def load() -> ctypes.CDLL:
     lib.isopo_fisher_samples_workspace.restype = sz
     lib.isopo_fisher_samples.argtypes = [lp, vp, i32, vp, f32, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.isopo_fisher_samples.restype = ctypes.c_int
+    lib.isopo_gram_norms.argtypes = [vp, i32, vp, vp, vp]
+    lib.isopo_gram_norms.restype = ctypes.c_int
+    lib.isopo_rescale.argtypes = [vp, vp, ctypes.c_int64, i32, vp, ctypes.POINTER(_RescaleParams), vp, vp, vp]
+    lib.isopo_rescale.restype = ctypes.c_int
+    lib.isopo_ntk_eigh_workspace.argtypes = [i32]
+    lib.isopo_ntk_eigh_workspace.restype = sz
+    lib.isopo_ntk_eigh.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.isopo_ntk_eigh.restype = ctypes.c_int
+    lib.isopo_transform_eigh.argtypes = [vp, vp, i32, vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.c_int, vp, f32,
+                                         vp, vp, vp]
+    lib.isopo_transform_eigh.restype = ctypes.c_int
     lib.isopo_status_string.argtypes = [ctypes.c_int]
     lib.isopo_status_string.restype = ctypes.c_char_p
     lib.isopo_version.argtypes = []
@@ -268,6 +286,66 @@ def fisher_samples(layer: Layer, sample_idx: torch.Tensor, A: torch.Tensor, lam:
                                        int(reg_mode), c.data_ptr(), fisher_sq.data_ptr(), workspace.data_ptr(),
                                        workspace.numel(), _stream(stream)), "isopo_fisher_samples")
     return c, fisher_sq
+
+
+def gram_norms(K: torch.Tensor, stream=None):
+    """(F_norm^2, ||G||^2) per sequence from the Gram matrix: (1/m) sum_j K_ij^2 and K_ii."""
+    m = K.shape[-1]
+    f2 = torch.empty(m, dtype=torch.float32, device=K.device)
+    g2 = torch.empty(m, dtype=torch.float32, device=K.device)
+    _check(load().isopo_gram_norms(K.data_ptr(), m, f2.data_ptr(), g2.data_ptr(), _stream(stream)), "isopo_gram_norms")
+    return f2, g2
+
+
+def rescale(fisher_sq: torch.Tensor, grad_sq: torch.Tensor, A: torch.Tensor, p: float = -1.0, q: float = 0.0,
+            r: float = 0.0, reg=(0.0, 0.0, 0.0), expectation=(None, None, None), c: Optional[torch.Tensor] = None,
+            batch_means: Optional[torch.Tensor] = None, stream=None):
+    """c_i = A_i reg2(F_i)^p reg2(||G_i||)^q reg2(F_i/||G_i||)^r.  grad_sq may be a 1-d tensor or a
+    Gram matrix (its diagonal is read in place).  An expectation of None takes the batch mean."""
+    m = int(fisher_sq.numel())
+    if grad_sq.dim() == 2:
+        stride = grad_sq.shape[-1] + 1
+    else:
+        stride = 1
+    if not grad_sq.is_contiguous() or not fisher_sq.is_contiguous():
+        raise ValueError("fisher_sq and grad_sq must be contiguous")
+    prm = _RescaleParams(float(p), float(q), float(r), (ctypes.c_float * 3)(*[float(x) for x in reg]),
+                         (ctypes.c_float * 3)(*[-1.0 if x is None else float(x) for x in expectation]))
+    if c is None:
+        c = torch.empty(m, dtype=torch.float32, device=fisher_sq.device)
+    _check(load().isopo_rescale(fisher_sq.data_ptr(), grad_sq.data_ptr(), stride, m, A.data_ptr(), ctypes.byref(prm),
+                                c.data_ptr(), _ptr(batch_means), _stream(stream)), "isopo_rescale")
+    return c
+
+
+def ntk_eigh(K: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None):
+    """D (ascending), U (eigenvectors as columns), info from the Gram matrix; fp64 on the device."""
+    m = K.shape[-1]
+    D = torch.empty(m, dtype=torch.float64, device=K.device)
+    U = torch.empty((m, m), dtype=torch.float64, device=K.device)
+    info = torch.zeros(1, dtype=torch.int32, device=K.device)
+    if workspace is None:
+        workspace = alloc_workspace(load().isopo_ntk_eigh_workspace(m), K.device)
+    _check(load().isopo_ntk_eigh(K.data_ptr(), m, D.data_ptr(), U.data_ptr(), info.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel(), _stream(stream)), "isopo_ntk_eigh")
+    return D, U, info
+
+
+def transform_eigh(D: torch.Tensor, U: torch.Tensor, A: torch.Tensor, lambdas, reg_mode: int = REG_ABSOLUTE,
+                   ema_state: Optional[torch.Tensor] = None, ema_decay: float = 0.9,
+                   c: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None, stream=None):
+    """c [n_lambda, m] = U ((U^T A) / (D + reg_l)).  Returns (c, info)."""
+    m = int(D.numel())
+    lam = [float(x) for x in lambdas]
+    if c is None:
+        c = torch.empty((len(lam), m), dtype=torch.float32, device=D.device)
+    if info is None:
+        info = torch.zeros(1, dtype=torch.int32, device=D.device)
+    arr = (ctypes.c_float * max(len(lam), 1))(*lam)
+    _check(load().isopo_transform_eigh(D.data_ptr(), U.data_ptr(), m, A.data_ptr(), arr, len(lam), int(reg_mode),
+                                       _ptr(ema_state), float(ema_decay), c.data_ptr(), info.data_ptr(),
+                                       _stream(stream)), "isopo_transform_eigh")
+    return c, info
 
 
 def scale_rows(src: torch.Tensor, layer: Layer, c: torch.Tensor, dst: Optional[torch.Tensor] = None,
