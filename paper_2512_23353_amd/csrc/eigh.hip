@@ -34,16 +34,19 @@ __device__ double block_sum(double x, double* red) {
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void jacobi_eigh_kernel(const float* __restrict__ K, int m,
                                                               double* __restrict__ D, double* __restrict__ U,
-                                                              int32_t* __restrict__ info, double* __restrict__ gws) {
+                                                              int32_t* __restrict__ info, double* __restrict__ gA,
+                                                              double* __restrict__ gV) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   __shared__ double rot_c[kMaxPairs], rot_s[kMaxPairs];
   __shared__ short rot_p[kMaxPairs], rot_q[kMaxPairs];
   __shared__ double red[THREADS / 64];
+  __shared__ short rank_of[kEighMaxSeq];
   const int tid = threadIdx.x;
   const int n = (m + 1) & ~1;            // even: an odd m gets one idle index
   const int ld = n + 1;                  // odd pitch: column walks spread over the LDS banks
-  double* Aw = gws ? gws : reinterpret_cast<double*>(smem_raw);
-  double* V = Aw + (size_t)n * ld;
+  // work matrix and eigenvectors: each in LDS when the caller passes no global buffer for it
+  double* Aw = gA ? gA : reinterpret_cast<double*>(smem_raw);
+  double* V = gV ? gV : reinterpret_cast<double*>(smem_raw) + (gA ? 0 : (size_t)n * ld);
   const int half = n / 2;
 
   for (int e = tid; e < n * n; e += THREADS) {
@@ -86,22 +89,25 @@ __global__ __launch_bounds__(THREADS) void jacobi_eigh_kernel(const float* __res
         rot_c[tid] = c; rot_s[tid] = s; rot_p[tid] = (short)p; rot_q[tid] = (short)q;
       }
       __syncthreads();
-      for (int e = tid; e < half * n; e += THREADS) {            // rows p and q: A <- J^T A
-        const int pr = e / n, k = e % n;
-        const double c = rot_c[pr], s = rot_s[pr];
-        const int p = rot_p[pr], q = rot_q[pr];
-        const double ap = Aw[(size_t)p * ld + k], aq = Aw[(size_t)q * ld + k];
-        Aw[(size_t)p * ld + k] = c * ap - s * aq;
-        Aw[(size_t)q * ld + k] = s * ap + c * aq;
+      // A <- J^T A J, one 2x2 block per item: rows (p1, q1) of pair P, columns (p2, q2) of pair R.  The
+      // block's new value depends on the block alone, and blocks are disjoint, so read-modify-write in place.
+      for (int e = tid; e < half * half; e += THREADS) {
+        const int P = e / half, R = e % half;
+        const double c1 = rot_c[P], s1 = rot_s[P], c2 = rot_c[R], s2 = rot_s[R];
+        const int p1 = rot_p[P], q1 = rot_q[P], p2 = rot_p[R], q2 = rot_q[R];
+        const double a_pp = Aw[(size_t)p1 * ld + p2], a_pq = Aw[(size_t)p1 * ld + q2];
+        const double a_qp = Aw[(size_t)q1 * ld + p2], a_qq = Aw[(size_t)q1 * ld + q2];
+        const double r_pp = c1 * a_pp - s1 * a_qp, r_pq = c1 * a_pq - s1 * a_qq;     // rows: J_P^T B
+        const double r_qp = s1 * a_pp + c1 * a_qp, r_qq = s1 * a_pq + c1 * a_qq;
+        Aw[(size_t)p1 * ld + p2] = c2 * r_pp - s2 * r_pq;                             // columns: (.) J_R
+        Aw[(size_t)p1 * ld + q2] = s2 * r_pp + c2 * r_pq;
+        Aw[(size_t)q1 * ld + p2] = c2 * r_qp - s2 * r_qq;
+        Aw[(size_t)q1 * ld + q2] = s2 * r_qp + c2 * r_qq;
       }
-      __syncthreads();
-      for (int e = tid; e < half * n; e += THREADS) {            // columns p and q: A <- A J, V <- V J
-        const int pr = e % half, k = e / half;
-        const double c = rot_c[pr], s = rot_s[pr];
-        const int p = rot_p[pr], q = rot_q[pr];
-        const double ap = Aw[(size_t)k * ld + p], aq = Aw[(size_t)k * ld + q];
-        Aw[(size_t)k * ld + p] = c * ap - s * aq;
-        Aw[(size_t)k * ld + q] = s * ap + c * aq;
+      for (int e = tid; e < half * n; e += THREADS) {            // V <- V J, columns p and q of row k
+        const int R = e % half, k = e / half;
+        const double c = rot_c[R], s = rot_s[R];
+        const int p = rot_p[R], q = rot_q[R];
         const double vp = V[(size_t)k * ld + p], vq = V[(size_t)k * ld + q];
         V[(size_t)k * ld + p] = c * vp - s * vq;
         V[(size_t)k * ld + q] = s * vp + c * vq;
@@ -119,7 +125,12 @@ __global__ __launch_bounds__(THREADS) void jacobi_eigh_kernel(const float* __res
       rank += (dj < di || (dj == di && j < i)) ? 1 : 0;
     }
     D[rank] = di;
-    for (int k = 0; k < m; ++k) U[(size_t)k * m + rank] = V[(size_t)k * ld + i];
+    rank_of[i] = (short)rank;
+  }
+  __syncthreads();
+  for (int e = tid; e < m * m; e += THREADS) {
+    const int k = e / m, i = e % m;
+    U[(size_t)k * m + rank_of[i]] = V[(size_t)k * ld + i];
   }
   if (info && tid == 0) *info = status;
 }
@@ -177,33 +188,33 @@ size_t eigh_workspace(int m) {
   return 2 * (size_t)n * (n + 1) * sizeof(double);
 }
 
+template <int THREADS>
+hipError_t launch_jacobi(const float* K, int m, double* D, double* U, int32_t* info, size_t smem, double* gA,
+                         double* gV, hipStream_t s) {
+  auto kern = jacobi_eigh_kernel<THREADS>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kEighLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(1), dim3(THREADS), smem, s, K, m, D, U, info, gA, gV);
+  return hipGetLastError();
+}
+
 hipError_t launch_ntk_eigh(const float* K, int m, double* D, double* U, int32_t* info, void* workspace,
                            hipStream_t s) {
-  const size_t bytes = eigh_workspace(m);
-  const bool lds = bytes <= kEighLdsBytes;
-  if (m <= 64) {
-    auto kern = jacobi_eigh_kernel<256>;
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kEighLdsBytes);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(1), dim3(256), bytes, s, K, m, D, U, info, (double*)nullptr);
-  } else {
-    auto kern = jacobi_eigh_kernel<1024>;
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)kEighLdsBytes);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(1), dim3(1024), lds ? bytes : 0, s, K, m, D, U, info,
-                       lds ? (double*)nullptr : static_cast<double*>(workspace));
-  }
-  return hipGetLastError();
+  const int n = (m + 1) & ~1;
+  const size_t one = (size_t)n * (n + 1) * sizeof(double);
+  double* ws = static_cast<double*>(workspace);
+  size_t smem;
+  double *gA = nullptr, *gV = nullptr;
+  if (2 * one <= kEighLdsBytes) smem = 2 * one;                       // both in LDS
+  else if (one <= kEighLdsBytes) { smem = one; gV = ws; }             // work matrix in LDS, eigenvectors in L2
+  else { smem = 0; gA = ws; gV = ws + (size_t)n * (n + 1); }
+  return n <= 32 ? launch_jacobi<256>(K, m, D, U, info, smem, gA, gV, s)
+                 : launch_jacobi<1024>(K, m, D, U, info, smem, gA, gV, s);
 }
 
 hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s) {
