@@ -10,7 +10,11 @@ synthetic, seeded, and resident in HBM before the timed region starts.
 Prints ONE JSON line: tokens/s for the block step, TFLOP/s on algorithmic
 FLOPs, the dominant kernel's roofline (live HIP-event timing), the overhead
 over the plain REINFORCE contraction, and the CPU oracle timed on a bounded
-sample of the same workload.
+sample of the same workload.  "variants" holds the same block timed for the
+other routes to the coefficients (Fisher norms from K; Fisher norms from
+token-position samples followed by one weighted contraction), each with its
+overhead over REINFORCE.  --config config4 sweeps the 28-layer stack and adds
+the lambda sweep for both variants under "sweep".
 """
 from __future__ import annotations
 
@@ -53,6 +57,8 @@ def main() -> int:
     ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4"])
     ap.add_argument("--variant", default="interacting", choices=["fisher", "interacting"])
     ap.add_argument("--lam", type=float, default=1e-3)
+    ap.add_argument("--n-samples", type=int, default=32, help="token-position samples of the Fisher estimate")
+    ap.add_argument("--no-variants", action="store_true", help="time the headline route only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true", help="skip the torch.matmul context timing")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -72,9 +78,14 @@ def main() -> int:
     torch.cuda.set_device(dev)
     w = wl.CONFIGS[args.config]
     lengths = wl.draw_lengths(w)
-    block = wl.make_block(w, device=dev, lengths=lengths)
+    # a multi-layer stack is swept layer by layer; two distinct layers' inputs alternate (28 would not fit HBM)
+    n_layers = w.n_layers
+    blocks = [wl.make_block(w, device=dev, lengths=lengths, layer=l) for l in range(min(n_layers, 2))]
+    block = [p for b in blocks for p in b]
     n_tokens, n_seq = block[0].n_tokens, block[0].n_seq
     layers = [isopo.Layer(p.X, p.Delta, p.seq_offsets) for p in block]
+    sweeps = n_layers // len(blocks)          # passes over `layers` per step
+    assert sweeps * len(blocks) == n_layers
     A = torch.from_numpy(block[0].A).to(dev)
     plans = [isopo.gram_plan(l) for l in layers]
     ws = isopo.alloc_workspace(max(pl[1] for pl in plans), dev)
@@ -84,16 +95,37 @@ def main() -> int:
     dWs = [torch.zeros((l.d_out, l.d_in), dtype=torch.float32, device=dev) for l in layers]
     stream = torch.cuda.current_stream()
 
-    def step():
-        for l, pl, K, c, info, dW in zip(layers, plans, Ks, cs, infos, dWs):
-            keep = pl[0] == "materialised"
-            isopo.layer_gram(l, "auto", K=K, workspace=ws, keep_stash=keep, stream=stream)
-            isopo.transform(K, A, args.variant, args.lam, isopo.REG_REL_TRACE, c=c, info=info, stream=stream)
-            isopo.weighted_grad(l, c, ws if keep else None, 0.0, dW, stream=stream)
+    def make_step(variant, lam):
+        def step():
+            for _ in range(sweeps):
+                for l, pl, K, c, info, dW in zip(layers, plans, Ks, cs, infos, dWs):
+                    keep = pl[0] == "materialised"
+                    isopo.layer_gram(l, "auto", K=K, workspace=ws, keep_stash=keep, stream=stream)
+                    isopo.transform(K, A, variant, lam, isopo.REG_REL_TRACE, c=c, info=info, stream=stream)
+                    isopo.weighted_grad(l, c, ws if keep else None, 0.0, dW, stream=stream)
+        return step
+
+    step = make_step(args.variant, args.lam)
 
     def reinforce_step():
-        for l, dW in zip(layers, dWs):
-            isopo.weighted_grad(l, None, None, 0.0, dW, stream=stream)
+        for _ in range(sweeps):
+            for l, dW in zip(layers, dWs):
+                isopo.weighted_grad(l, None, None, 0.0, dW, stream=stream)
+
+    # Non-interacting update with the token-position-sample Fisher estimate: coefficients first, then ONE
+    # weighted contraction (rows of the narrower operand pre-scaled).  No stash, no Gram matrix.
+    g = torch.Generator(device="cpu").manual_seed(w.seed)
+    sample_idx = torch.randperm(n_tokens, generator=g)[: args.n_samples].to(torch.int32).to(dev)
+    fs_ws = isopo.alloc_workspace(max(isopo.load().isopo_fisher_samples_workspace(l.ref(), args.n_samples)
+                                      for l in layers), dev)
+    f2s = [torch.empty(n_seq, dtype=torch.float32, device=dev) for _ in layers]
+    scr = torch.empty(n_tokens * max(min(l.d_in, l.d_out) for l in layers), dtype=block[0].X.dtype, device=dev)
+
+    def token_sample_step():
+        for _ in range(sweeps):
+            for l, c, f2, dW in zip(layers, cs, f2s, dWs):
+                isopo.fisher_samples(l, sample_idx, A, args.lam, isopo.REG_REL_TRACE, c, f2, fs_ws, stream=stream)
+                isopo.weighted_grad_prescaled(l, c, scr, 0.0, dW, stream=stream)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -127,8 +159,30 @@ def main() -> int:
     avg_launch_s = float(np.mean(ms)) * 1e-3
     fl = [algorithmic_flops(n_tokens, l.d_in, l.d_out, n_seq) for l in layers]
     seq_grad_flops_per_launch = float(np.mean([f["seq_grads"] for f in fl]))
-    total_flops = float(sum(sum(f.values()) for f in fl))
-    reinforce_flops = float(sum(f["seq_grads"] for f in fl))
+    total_flops = float(sum(sum(f.values()) for f in fl)) * sweeps
+    reinforce_flops = float(sum(f["seq_grads"] for f in fl)) * sweeps
+
+    variants, sweep_report = {}, None
+    if not args.no_variants:
+        reps = max(2, args.steps // 3)
+        other = "fisher" if args.variant == "interacting" else "interacting"
+        t_other = timed(make_step(other, args.lam), reps, 1)
+        t_ts = timed(token_sample_step, reps, 1)
+        variants = {
+            f"{args.variant}_from_stash_gram": {"ms_per_step": t_step * 1e3, "overhead_over_reinforce": t_step / t_reinforce - 1.0},
+            f"{other}_from_stash_gram": {"ms_per_step": t_other * 1e3, "overhead_over_reinforce": t_other / t_reinforce - 1.0},
+            "fisher_from_token_samples": {"ms_per_step": t_ts * 1e3, "overhead_over_reinforce": t_ts / t_reinforce - 1.0,
+                                          "n_samples": args.n_samples,
+                                          "what": "isopo_fisher_samples -> isopo_scale_rows -> one unweighted contraction per projection"},
+        }
+        if n_layers > 1:
+            sweep_report = []
+            for variant in ("fisher", "interacting"):
+                for lam in (1e-4, 1e-3, 1e-2):
+                    t = timed(make_step(variant, lam), 2, 1)
+                    assert all(int(i.item()) == 0 for i in infos)
+                    sweep_report.append({"variant": variant, "lambda": lam, "ms_per_sweep": t * 1e3,
+                                         "overhead_over_reinforce": t / t_reinforce - 1.0})
     achieved = seq_grad_flops_per_launch / avg_launch_s
 
     if args.calibrate_copy:
@@ -142,9 +196,10 @@ def main() -> int:
     context = {}
     if not args.no_context:
         def torch_reinforce():
-            for p, dW in zip(block, dWs):
-                a_tok = torch.repeat_interleave(A, torch.from_numpy(np.diff(p.seq_offsets)).to(dev)).to(p.Delta.dtype)
-                torch.matmul((p.Delta * a_tok[:, None]).T, p.X, out=None)
+            for _ in range(sweeps):
+                for p, dW in zip(block, dWs):
+                    a_tok = torch.repeat_interleave(A, torch.from_numpy(np.diff(p.seq_offsets)).to(dev)).to(p.Delta.dtype)
+                    torch.matmul((p.Delta * a_tok[:, None]).T, p.X, out=None)
         context["torch_matmul_reinforce_ms"] = timed(torch_reinforce, 3, 1) * 1e3
 
     out = {
@@ -152,7 +207,7 @@ def main() -> int:
         "value": n_tokens / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: one transformer block, 7 projections "
+        "config": {"workload": f"{args.config}: {'one transformer block' if n_layers == 1 else f'{n_layers} transformer blocks swept layer by layer'}, 7 projections "
                                f"({', '.join(f'{p.name} {p.d_in}x{p.d_out}' for p in w.projections)}), "
                                f"B={n_seq} ragged sequences, N={n_tokens} tokens, bf16 inputs fp32 accumulation",
                    "variant": args.variant, "lambda": args.lam, "reg_mode": "rel_trace",
@@ -162,7 +217,7 @@ def main() -> int:
         "algorithmic_flops_per_step": total_flops,
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
-                      "what": "this library's own unweighted dW = Delta^T X over the same 7 projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
+                      "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
         "roofline": {"bound": "mfma", "kernel": "seq_grad_kernel (per-sequence gradients -> stash)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
@@ -170,23 +225,27 @@ def main() -> int:
                      "traffic": read_traffic(f"seq_grad_{args.config}")},
     }
 
+    if variants:
+        out["variants"] = variants
+    if sweep_report:
+        out["sweep"] = sweep_report
+
     if not args.no_cpu_baseline:
         from oracle import isopo_oracle as orc
         from threadpoolctl import threadpool_info
-        by_name = {p.name.split("/")[-1]: p for p in block}
+        by_name = {p.name.split("/")[-1]: p for p in blocks[0]}
         sample = by_name["k"]
         Xh, Dh = wl.to_oracle(sample.X), wl.to_oracle(sample.Delta)
         t0 = time.perf_counter()
         orc.layer_step(Xh, Dh, sample.seq_offsets, sample.A, args.variant, args.lam, orc.REG_REL_TRACE,
                        chunk_rows=512)
         t_cpu = time.perf_counter() - t0
-        share = sum(sum(f.values()) for f in fl) / sum(algorithmic_flops(n_tokens, sample.d_in, sample.d_out,
-                                                                         n_seq).values())
+        share = total_flops / sum(algorithmic_flops(n_tokens, sample.d_in, sample.d_out, n_seq).values())
         threads = max([ti.get("num_threads", 1) for ti in threadpool_info() if ti.get("user_api") == "blas"] or [1])
         out["cpu_baseline"] = {
             "value": n_tokens / (t_cpu * share), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"the block's k projection ({sample.d_in}x{sample.d_out}, all {n_seq} sequences, "
-                      f"{n_tokens} tokens) took {t_cpu:.1f} s; scaled to the 7-projection block by the "
+                      f"{n_tokens} tokens) took {t_cpu:.1f} s; scaled to the whole step by the "
                       f"algorithmic-FLOP ratio {share:.1f}"}
     print(json.dumps(out))
     return 0

@@ -47,26 +47,26 @@ struct Params {
   double* den;           // [n_samples] ||g0_j||^2 ||a0_j||^2
 };
 
-__global__ void tok_seq_kernel(const int32_t* __restrict__ off, int n_seq, int n_tokens, int32_t* __restrict__ tok_seq) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= n_tokens) return;
-  int lo = 0, hi = n_seq;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (off[mid] <= t) lo = mid; else hi = mid;
-  }
-  tok_seq[t] = lo;
-}
-
-__global__ void zero_f64_kernel(double* p, long long n) {
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0.0;
-}
-
-// den[j] = ||Delta[idx_j]||^2 * ||X[idx_j]||^2, one workgroup per sample, fixed reduction order.
+// One launch prepares everything the main kernel needs.  Blocks [0, n_samples): den[j] =
+// ||Delta[idx_j]||^2 * ||X[idx_j]||^2 (fixed reduction order).  The remaining blocks: the sequence of
+// every token (binary search in the offsets) and zeros in the segment-sum accumulator.
 template <bool BF16>
-__global__ __launch_bounds__(256) void sample_norm_kernel(Params p) {
+__global__ __launch_bounds__(256) void prep_kernel(Params p, long long n_acc) {
   __shared__ double red[2][4];
+  if ((int)blockIdx.x >= p.n_samples) {
+    const long long i = (long long)(blockIdx.x - p.n_samples) * 256 + threadIdx.x;
+    if (i < n_acc) p.S64[i] = 0.0;
+    if (i < p.n_tokens) {
+      const int t = (int)i;
+      int lo = 0, hi = p.n_seq;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (p.off[mid] <= t) lo = mid; else hi = mid;
+      }
+      p.tok_seq[t] = lo;
+    }
+    return;
+  }
   const int j = blockIdx.x, row = min(max(p.idx[j], 0), p.n_tokens - 1);   // bad indices are clamped, never followed
   double sx = 0.0, sd = 0.0;
   for (int k = threadIdx.x; k < p.d_in; k += 256) {
@@ -85,6 +85,11 @@ __global__ __launch_bounds__(256) void sample_norm_kernel(Params p) {
   __syncthreads();
   if (threadIdx.x == 0)
     p.den[j] = (red[0][0] + red[0][1] + red[0][2] + red[0][3]) * (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+}
+
+__global__ void zero_f64_kernel(double* p, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0;
 }
 
 // One token-by-sample product block per wave: acc[b] (32 tokens x 32 samples) += T S_b^T over d features.
@@ -220,37 +225,40 @@ __global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
   }
 }
 
+__device__ double block_sum256(double x, double* red) {
+  x = wave_sum(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
 // F_i^2 = sum_j s_ij^2 / sum_j den_j ;  c_i = A_i / sqrt(F_i^2 + reg).  One workgroup, fixed order.
 __global__ __launch_bounds__(256) void fisher_samples_finish_kernel(const double* __restrict__ S64,
                                                                     const double* __restrict__ den, int n_seq,
                                                                     int n_samples, int ncol, const float* __restrict__ A,
                                                                     float lambda, int reg_mode, float* __restrict__ c,
                                                                     float* __restrict__ f2_out, double* __restrict__ f2_tmp) {
-  __shared__ double sh[2];
-  if (threadIdx.x == 0) {
-    double d = 0.0;
-    for (int j = 0; j < n_samples; ++j) d += den[j];
-    sh[0] = d;
-  }
-  __syncthreads();
-  const double d = sh[0];
-  for (int i = threadIdx.x; i < n_seq; i += 256) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const double d = block_sum256(tid < n_samples ? den[tid] : 0.0, red);      // n_samples <= 128
+  // one wave per sequence: lanes stride over the samples
+  double part = 0.0;
+  for (int i = wave; i < n_seq; i += 4) {
     double s = 0.0;
-    for (int j = 0; j < n_samples; ++j) {
+    for (int j = lane; j < n_samples; j += 64) {
       const double x = S64[(size_t)i * ncol + j];
       s += x * x;
     }
-    f2_tmp[i] = d > 0.0 ? s / d : 0.0;
+    s = wave_sum(s);
+    const double f2 = d > 0.0 ? s / d : 0.0;
+    if (lane == 0) { f2_tmp[i] = f2; part += f2; }
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double m = 0.0;
-    for (int i = 0; i < n_seq; ++i) m += f2_tmp[i];
-    sh[1] = reg_mode == 1 ? (double)lambda * m / n_seq : (double)lambda;
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < n_seq; i += 256) {
-    const double den_i = f2_tmp[i] + sh[1];
+  const double mean = block_sum256(part, red) / n_seq;
+  const double reg = reg_mode == 1 ? (double)lambda * mean : (double)lambda;
+  __syncthreads();                                   // f2_tmp written by lane 0 of each wave, read by all below
+  for (int i = tid; i < n_seq; i += 256) {
+    const double den_i = f2_tmp[i] + reg;
     c[i] = den_i > 0.0 ? (float)((double)A[i] / sqrt(den_i)) : 0.f;
     if (f2_out) f2_out[i] = (float)f2_tmp[i];
   }
@@ -298,12 +306,11 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
   double* f2_tmp = reinterpret_cast<double*>(ws);
 
   const long long ns = (long long)a.n_seq * ncol;
-  hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, s, p.S64, ns);
   if (a.n_tokens > 0) {
-    hipLaunchKernelGGL(tok_seq_kernel, dim3((a.n_tokens + 255) / 256), dim3(256), 0, s, a.off, a.n_seq, a.n_tokens,
-                       p.tok_seq);
-    if (a.bf16) hipLaunchKernelGGL((sample_norm_kernel<true>), dim3(a.n_samples), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((sample_norm_kernel<false>), dim3(a.n_samples), dim3(256), 0, s, p);
+    const long long items = ns > a.n_tokens ? ns : (long long)a.n_tokens;
+    const dim3 grid((unsigned)(a.n_samples + (items + 255) / 256));
+    if (a.bf16) hipLaunchKernelGGL((prep_kernel<true>), grid, dim3(256), 0, s, p, ns);
+    else hipLaunchKernelGGL((prep_kernel<false>), grid, dim3(256), 0, s, p, ns);
     hipError_t e;
     switch (nbs * 2 + (a.bf16 ? 1 : 0)) {
       case 2: e = launch_main<1, false>(p, s); break;
@@ -317,6 +324,7 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
     }
     if (e != hipSuccess) return e;
   } else {
+    hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, s, p.S64, ns);
     hipLaunchKernelGGL(zero_f64_kernel, dim3((a.n_samples + 255) / 256), dim3(256), 0, s, p.den, (long long)a.n_samples);
   }
   hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(1), dim3(256), 0, s, p.S64, p.den, a.n_seq, a.n_samples, ncol,
