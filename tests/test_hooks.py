@@ -1,0 +1,113 @@
+"""The autograd hook harness (both listings are written as a full backward hook
+of a linear module, run on objective = sum(log_prob) without advantages).
+
+CPU tests check the plumbing against autograd brute force with the oracle as
+the layer step; the GPU test runs the HIP library behind the same hooks and
+compares with the oracle on the captured matrices."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import isopo_oracle as orc
+from paper_2512_23353_amd.hooks import IsopoHooks
+
+from toy_block import ToyBlock, make_batch
+
+LENGTHS = [5, 9, 1, 7]
+
+
+def _oracle_step(X, Delta, off, A, cfg):
+    out = orc.layer_step(X.double().numpy(), Delta.double().numpy(), off, A.double().numpy(), cfg["variant"],
+                         cfg["lam"], orc.REG_REL_TRACE if cfg["relative_reg"] else orc.REG_ABSOLUTE)
+    return torch.from_numpy(out["dW"])
+
+
+def test_hooks_capture_what_the_listings_assume():
+    """Packed ragged input: the captured (act_in, grad_out) of every linear
+    layer reproduce, sequence by sequence, the autograd gradient of that
+    sequence's log-probability alone; apply() installs the oracle's update."""
+    torch.manual_seed(0)
+    model = ToyBlock(dtype=torch.float64)
+    tokens, targets, off, A = make_batch(LENGTHS)
+    At = torch.from_numpy(A)
+    hooks = IsopoHooks(model, off, At, "interacting", 1e-2, layer_step=_oracle_step)
+    logp = model(tokens, targets, off)
+    logp.sum().backward()
+    hooks.apply()
+    hooks.remove()
+    linears = {n: m for n, m in model.named_modules() if isinstance(m, torch.nn.Linear)}
+    assert set(hooks.captured) == set(linears.values()) and len(linears) == 8
+    for name, mod in linears.items():
+        X, Delta, off_c = hooks.captured[mod]
+        assert X.shape == (sum(LENGTHS), mod.in_features) and Delta.shape == (sum(LENGTHS), mod.out_features)
+        G = orc.seq_logprob_grads(X.numpy(), Delta.numpy(), off_c)
+        for i in range(len(LENGTHS)):
+            model.zero_grad()
+            lp = model(tokens, targets, off)
+            lp[off[i]:off[i + 1]].sum().backward()
+            np.testing.assert_allclose(G[i], mod.weight.grad.numpy(), atol=1e-10, err_msg=f"{name} seq {i}")
+        ref = orc.layer_step(X.numpy(), Delta.numpy(), off_c, A, "interacting", 1e-2, orc.REG_REL_TRACE)["dW"]
+        np.testing.assert_allclose(hooks.grads[mod].numpy(), ref, rtol=1e-12)
+    # the hooks are gone: a further backward leaves hooks.grads alone
+    before = {m: g.clone() for m, g in hooks.grads.items()}
+    model(tokens, targets, off).sum().backward()
+    assert all(torch.equal(before[m], hooks.grads[m]) for m in before)
+
+
+def test_hooks_padded_batch_layout_and_accumulation():
+    """[B, T, d] inputs imply uniform offsets; a second microbatch accumulates."""
+    torch.manual_seed(1)
+    lin = torch.nn.Linear(8, 12, bias=False, dtype=torch.float64)
+    A = torch.tensor([1.0, -1.0, 0.5])
+    hooks = IsopoHooks(lin, None, A, "fisher", 1e-2, layer_step=_oracle_step)
+    total = 0
+    for _ in range(2):
+        x = torch.randn(3, 6, 8, dtype=torch.float64)
+        y = lin(x)
+        (y ** 2).sum().backward()
+        X, Delta, off = hooks.captured[lin]
+        assert list(off) == [0, 6, 12, 18]
+        total = total + orc.layer_step(X.numpy(), Delta.numpy(), off, A.numpy(), "fisher", 1e-2, orc.REG_REL_TRACE)["dW"]
+    hooks.apply()
+    np.testing.assert_allclose(lin.weight.grad.numpy(), total, rtol=1e-12)
+    with pytest.raises(ValueError):
+        IsopoHooks(lin, None, A, "no such variant")
+    packed = IsopoHooks(torch.nn.Linear(8, 4, bias=False), None, A, layer_step=_oracle_step)
+    with pytest.raises(ValueError):
+        packed.modules[0](torch.randn(5, 8, requires_grad=True)).sum().backward()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", ["interacting", "fisher", "fisher_token_samples", "rescaled"])
+def test_hooks_run_the_hip_library(gpu_device, variant):
+    """The same harness on the GPU with the HIP library as the layer step, fp32:
+    every hooked layer's update against the oracle on the captured matrices."""
+    from paper_2512_23353_amd import isopo
+    from helpers import TOL, assert_dW_close
+    torch.manual_seed(2)
+    model = ToyBlock(dtype=torch.float32).to(gpu_device)
+    lengths = [40, 9, 1, 70, 33, 17]
+    tokens, targets, off, A = make_batch(lengths, device=gpu_device)
+    At = torch.from_numpy(A.astype(np.float32)).to(gpu_device)
+    hooks = IsopoHooks(model, off, At, variant, 1e-2, n_samples=16, seed=5)
+    model(tokens, targets, off).sum().backward()
+    hooks.apply()
+    hooks.remove()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cpu").manual_seed(5)       # the sample draws, in hook call order
+    order = list(hooks.captured)                              # dict keeps backward (call) order
+    assert len(order) == 8
+    for mod in order:
+        X, Delta, off_c = (t.cpu().numpy() if torch.is_tensor(t) else t for t in hooks.captured[mod])
+        Af = A.astype(np.float32).astype(np.float64)
+        G = orc.seq_logprob_grads(X, Delta, off_c)
+        K = orc.ntk_from_seq_grads(G)
+        if variant in ("interacting", "fisher"):
+            c = orc.layer_step(X, Delta, off_c, Af, variant, 1e-2, orc.REG_REL_TRACE)["c"]
+        elif variant == "fisher_token_samples":
+            idx = torch.randperm(X.shape[0], generator=gen)[:16].numpy()
+            c, _ = orc.coeff_fisher_token_samples(X, Delta, off_c, idx, Af, 1e-2, orc.REG_REL_TRACE)
+        else:
+            c = orc.coeff_rescaled(orc.fisher_norm_sq(K), np.diag(K), Af, 0.0, -1.0, -2.0)
+        ref, mag = orc.weighted_grad(G, c), orc.weighted_grad_abs(G, c)
+        assert_dW_close(mod.weight.grad.cpu().numpy(), ref, TOL["f32"], f"{variant}", mag)
