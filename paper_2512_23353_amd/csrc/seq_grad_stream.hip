@@ -21,6 +21,10 @@
 //    sequence, so all eight L2s see every sequence (balanced under ragged
 //    lengths) and neighbouring workgroups share operand panels.  The bf16 tile is
 //    transposed through LDS in the epilogue so that every lane stores 16 bytes.
+//  * Sum-over-all-tokens mode with few output tiles (narrow projections, long
+//    microbatches): the token range is split into chunks, a workgroup takes one
+//    (tile, chunk) with the same XCD mapping, and the fp32 partial tiles are added
+//    to dW with hardware float atomics after a pass that applies beta.
 #include "common.h"
 #include "kernels.h"
 
@@ -44,6 +48,7 @@ struct StreamParams {
   float beta;
   int tiles_m, tiles_n;
   unsigned n_blocks;
+  int n_chunks, chunk_tokens;      // sum-over-all-tokens mode: token chunks (1: no split)
 };
 
 // Raw buffer descriptor over [base, base + bytes): loads beyond it return zero.
@@ -97,12 +102,13 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
   const int wm = wave >> 1, wn = wave & 1;
 
   int item, tile;
-  if (PER_SEQ) {
-    // XCD x (= blockIdx % 8) owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence
+  const bool split = !PER_SEQ && p.n_chunks > 1;
+  if (PER_SEQ || split) {
+    // XCD x (= blockIdx % 8) owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence (or token chunk)
     const int tiles = p.tiles_m * p.tiles_n;
     const int x = blockIdx.x & 7, e = blockIdx.x >> 3;
     const int s0 = x * tiles / 8, cs = (x + 1) * tiles / 8 - s0;
-    if (cs == 0 || e >= p.n_seq * cs) return;
+    if (cs == 0 || e >= (PER_SEQ ? p.n_seq : p.n_chunks) * cs) return;
     item = e / cs;
     tile = s0 + e % cs;
   } else {
@@ -123,8 +129,8 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     tile_n = c0 + in_strip % w;
   }
   const int m0 = p.row0 + tile_m * BM, n0 = tile_n * BN;
-  const int t0 = PER_SEQ ? p.off[item] : 0;
-  const int t1 = PER_SEQ ? p.off[item + 1] : p.n_tokens;
+  const int t0 = PER_SEQ ? p.off[item] : item * p.chunk_tokens;
+  const int t1 = PER_SEQ ? p.off[item + 1] : min(p.n_tokens, t0 + p.chunk_tokens);
   const int n_rows = t1 - t0;
   const int n_tiles = (n_rows + BK - 1) / BK;
   const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
@@ -304,12 +310,25 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
           if (m >= p.row_end) continue;
           float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
-          *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
+          if (split) atomicAdd(o, acc[i][j][v]);        // beta already applied by the pass before
+          else *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
         }
       }
   }
 }
 
+
+// o[i] = beta * o[i] (0 for beta = 0, whatever o held), ahead of the atomic accumulation.
+__global__ __launch_bounds__(256) void apply_beta_kernel(float* __restrict__ o, long long n, float beta) {
+  const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i + 3 < n) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (beta != 0.f) v = *(f32x4*)(o + i) * beta;
+    *(f32x4*)(o + i) = v;
+  } else {
+    for (long long k = i; k < n; ++k) o[k] = beta != 0.f ? beta * o[k] : 0.f;
+  }
+}
 
 template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
 hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
@@ -321,7 +340,30 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
   p.tiles_m = (a.rows + BM - 1) / BM;
   p.tiles_n = (a.d_in + BN - 1) / BN;
   const long long tiles = (long long)p.tiles_m * p.tiles_n;
-  const long long blocks = PER_SEQ ? 8LL * a.n_seq * ((tiles + 7) / 8) : tiles;
+  p.n_chunks = 1;
+  p.chunk_tokens = a.n_tokens;
+  if (!PER_SEQ) {
+    // Fewest chunks (of at least 4096 tokens) that fill the resident workgroup slots evenly: the
+    // smallest count whose last round of workgroups is at least 85 % full, else the fullest.
+    const long long slots = 256LL * OCC;
+    const long long most = a.n_tokens / 4096 > 1 ? a.n_tokens / 4096 : 1;
+    long long want = 1;
+    if (tiles < 4 * slots) {
+      double best = 0.0;
+      for (long long w = 1; w <= most && w <= 64; ++w) {
+        const long long wg = tiles * w, rounds = (wg + slots - 1) / slots;
+        const double fill = (double)wg / (double)(rounds * slots);
+        if (fill > best + 1e-9) { best = fill; want = w; }
+        if (fill >= 0.85) break;
+      }
+    }
+    if (want > 1) {
+      p.chunk_tokens = (int)(((a.n_tokens + want - 1) / want + BK - 1) / BK * BK);
+      p.n_chunks = (a.n_tokens + p.chunk_tokens - 1) / p.chunk_tokens;
+    }
+  }
+  const bool mapped = PER_SEQ || p.n_chunks > 1;
+  const long long blocks = mapped ? 8LL * (PER_SEQ ? a.n_seq : p.n_chunks) * ((tiles + 7) / 8) : tiles;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   p.n_blocks = (unsigned)blocks;
@@ -335,6 +377,12 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
+  if (!PER_SEQ && p.n_chunks > 1) {
+    // the band of output rows this launch owns is contiguous in dW
+    float* band = static_cast<float*>(a.out) + (size_t)(a.row0 - a.out_row0) * a.d_in;
+    const long long n = (long long)a.rows * a.d_in;
+    hipLaunchKernelGGL(apply_beta_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, band, n, a.beta);
+  }
   hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(256), smem, s, p);
   return hipGetLastError();
 }
@@ -343,10 +391,14 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
 
 // bf16, unscaled (per-sequence stash, or plain sum over all tokens).
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
-  const long long big_tiles = (long long)((a.rows + 255) / 256) * ((a.d_in + 255) / 256) * (a.per_sequence ? a.n_seq : 1);
-  const bool big = a.rows >= 256 && a.d_in >= 256 && big_tiles >= 256;
-  if (a.per_sequence)
+  const long long big_tiles = (long long)((a.rows + 255) / 256) * ((a.d_in + 255) / 256);
+  if (a.per_sequence) {
+    const bool big = a.rows >= 256 && a.d_in >= 256 && big_tiles * a.n_seq >= 256;
     return big ? launch_stream<256, 256, 4, 1, true>(a, s) : launch_stream<128, 128, 4, 2, true>(a, s);
+  }
+  // sum over all tokens: the token split supplies the parallelism, so the larger tile whenever it fits
+  // (few tiles and few tokens: the smaller tile)
+  const bool big = a.rows >= 256 && a.d_in >= 256 && big_tiles * (a.n_tokens / 1024 > 1 ? a.n_tokens / 1024 : 1) >= 256;
   return big ? launch_stream<256, 256, 4, 1, false>(a, s) : launch_stream<128, 128, 4, 2, false>(a, s);
 }
 

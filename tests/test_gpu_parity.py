@@ -259,3 +259,27 @@ def test_prescaled_weighted_grad(gpu_device, dtype, dims):
     got = orc.widen(wl.to_oracle(scaled))
     ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -23
     assert np.all(np.abs(got - exact) <= ulp * np.abs(exact) + 1e-300)
+
+
+@pytest.mark.parametrize("dims", [(256, 384), (512, 256), (200, 136)])
+@pytest.mark.parametrize("beta", [0.0, 0.75])
+def test_unweighted_contraction_with_token_split(gpu_device, dims, beta):
+    """Few output tiles and many tokens: the sum over all tokens is split into
+    token chunks whose partial tiles are accumulated atomically.  Both tile
+    sizes, a ragged last chunk, beta = 0 over a NaN-filled dW (must not be read)
+    and beta != 0."""
+    d_in, d_out = dims
+    lengths = [3000, 1400, 1, 4200, 333, 4100]      # 13034 tokens: three chunks of at least 4096, the last ragged
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=31, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    rng = np.random.default_rng(6)
+    dW0 = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    dW = torch.from_numpy(dW0).to(gpu_device) if beta != 0.0 else torch.full((d_out, d_in), float("nan"),
+                                                                           device=gpu_device)
+    isopo.weighted_grad(layer, None, None, beta, dW)
+    torch.cuda.synchronize()
+    Xo, Do = wl.to_oracle(prob.X), wl.to_oracle(prob.Delta)
+    ones = np.ones(prob.n_seq)
+    ref = orc.weighted_grad_tokens(Xo, Do, prob.seq_offsets, ones) + beta * dW0.astype(np.float64)
+    mag = orc.weighted_grad_tokens(np.abs(orc.widen(Xo)), np.abs(orc.widen(Do)), prob.seq_offsets, ones) + np.abs(beta * dW0)
+    assert_dW_close(dW.cpu().numpy(), ref, TOL["bf16"], f"token split {dims} beta={beta}", mag)
