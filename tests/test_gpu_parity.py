@@ -283,3 +283,63 @@ def test_unweighted_contraction_with_token_split(gpu_device, dims, beta):
     ref = orc.weighted_grad_tokens(Xo, Do, prob.seq_offsets, ones) + beta * dW0.astype(np.float64)
     mag = orc.weighted_grad_tokens(np.abs(orc.widen(Xo)), np.abs(orc.widen(Do)), prob.seq_offsets, ones) + np.abs(beta * dW0)
     assert_dW_close(dW.cpu().numpy(), ref, TOL["bf16"], f"token split {dims} beta={beta}", mag)
+
+
+def test_hip_graph_replays_match_eager(gpu_device):
+    """The whole layer step (both Gram routes' kernels, the solve, the stash
+    sum, the token-sample route) captured in a HIP graph: the library allocates
+    nothing, synchronises nowhere and records no memset nodes, so every replay
+    must reproduce the eager result for the buffers' current contents."""
+    prob = wl.custom_layer(256, 384, [100, 37, 0, 250, 64, 300], dtype="bf16", seed=41, sigma_delta=1e-2)
+    layer, A = to_device(prob, gpu_device)
+    m = prob.n_seq
+    _, full, _ = isopo.gram_plan(layer, "materialised")
+    ws = isopo.alloc_workspace(full, gpu_device)
+    gws = isopo.alloc_workspace(isopo.gram_plan(layer, "ghost")[1], gpu_device)
+    K = torch.empty((m, m), dtype=torch.float32, device=gpu_device)
+    Kg = torch.empty_like(K)
+    c = torch.empty(m, dtype=torch.float32, device=gpu_device)
+    cf = torch.empty_like(c)
+    f2 = torch.empty_like(c)
+    info = torch.zeros(1, dtype=torch.int32, device=gpu_device)
+    dW = torch.empty((prob.d_out, prob.d_in), dtype=torch.float32, device=gpu_device)
+    dWf = torch.empty_like(dW)
+    idx = torch.arange(0, 16 * 40, 40, dtype=torch.int32, device=gpu_device)
+    fws = isopo.alloc_workspace(isopo.load().isopo_fisher_samples_workspace(layer.ref(), 16), gpu_device)
+    scratch = torch.empty_like(layer.X)
+
+    def run():
+        isopo.layer_gram(layer, "materialised", K=K, workspace=ws, keep_stash=True)
+        isopo.layer_gram(layer, "ghost", K=Kg, workspace=gws)
+        isopo.transform(K, A, "interacting", 1e-2, isopo.REG_REL_TRACE, c=c, info=info)
+        isopo.weighted_grad(layer, c, ws, 0.0, dW)
+        isopo.fisher_samples(layer, idx, A, 1e-2, isopo.REG_REL_TRACE, cf, f2, fws)
+        isopo.weighted_grad_prescaled(layer, cf, scratch, 0.0, dWf)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (K, Kg, c, dW, cf, dWf)]
+
+    run()                                   # warm-up outside the capture (kernel attributes are set once)
+    eager = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    A0 = A.clone()
+    for rep in range(3):
+        A.copy_(A0 * (1.0 + rep))           # the graph reads the buffers' current contents
+        for t in (K, Kg, c, dW, cf, dWf):
+            t.fill_(float("nan"))
+        graph.replay()
+        got = snapshot()
+        run()                               # eager work between replays, same inputs
+        want = snapshot()
+        for name, g, w in zip(("K", "K ghost", "c", "dW", "c samples", "dW samples"), got, want):
+            if name == "K ghost":           # fp64 atomics: order varies, one fp32 rounding at most
+                assert torch.allclose(g, w, rtol=1e-6, atol=0), f"replay {rep}: {name}"
+            elif name == "dW samples":      # may use the token split's fp32 atomics
+                assert torch.allclose(g, w, rtol=1e-4, atol=1e-6 * float(w.abs().max())), f"replay {rep}: {name}"
+            else:
+                assert torch.equal(g, w), f"replay {rep}: {name}"
+    assert torch.equal(eager[0], K)         # K does not depend on A
+    A.copy_(A0)
