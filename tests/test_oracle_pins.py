@@ -159,6 +159,11 @@ def test_p6_orthogonal_reduction():
     ci, _ = orc.coeff_interacting(K, A, lam)
     np.testing.assert_allclose(ci, A / (np.diag(K) + lam), rtol=1e-12)
     np.testing.assert_allclose(orc.coeff_fisher(K, A, lam), A / np.sqrt(np.diag(K) ** 2 / m + lam), rtol=1e-12)
+    # for reg > 0 the interacting coefficients match the r = -2 re-scaling ("Alternative sequence
+    # re-scalings"): rel_F_norm^2 = (k_i^2/m)/k_i = k_i/m, so A_i/(k_i/m + reg) = m A_i/(k_i + m reg), i.e.
+    # interacting(lam) = (1/m) alt(reg = lam/m); the listing's 1e-8 moves it by under 1e-8 relative here
+    alt = orc.coeff_rescaled(orc.fisher_norm_sq(K), np.diag(K), A, 0, 0, -2, reg=(0, 0, lam / m), expectation=(None, None, 1.0))
+    np.testing.assert_allclose(alt / m, ci, rtol=1e-7)
 
 
 def test_p7_solve_residual_and_eigh_route():
