@@ -149,7 +149,10 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
  *          dW = beta dW + Delta^T X with no scaling pass at all.  That is the
  *          plain REINFORCE weight gradient when the advantages were folded into
  *          the loss (so Delta already carries them), and it is the baseline the
- *          layer step's overhead is measured against. */
+ *          layer step's overhead is measured against.
+ * Reproducibility: from the stash the sum runs in a fixed order (bit-identical from run to run).
+ * From X and Delta with few output tiles and many tokens the token range is split and the partial
+ * tiles are added with fp32 atomics, so dW can then differ between runs by fp32 rounding. */
 isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash,
                                  float beta, float* dW, void* stream);
 

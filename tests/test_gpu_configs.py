@@ -159,3 +159,15 @@ def test_config5_full_size_sampled(gpu_device):
     assert isopo.gram_plan(layer)[0] == "materialised"
     del layer
     _sampled_checks(prob, gpu_device, rng, 3, full_k=False)
+    # the token-sample Fisher coefficients at the same size (256 sequences, 64 samples): the two
+    # shortest sequences against the oracle, finiteness and positivity for the rest
+    layer, A = to_device(prob, gpu_device)
+    idx = rng.permutation(prob.n_tokens)[:64].astype(np.int32)
+    c, f2 = isopo.fisher_samples(layer, torch.from_numpy(idx).to(gpu_device), A, 1e-3, isopo.REG_REL_TRACE)
+    torch.cuda.synchronize()
+    f2h = f2.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(f2h)) and np.all(f2h > 0) and np.all(np.isfinite(c.cpu().numpy()))
+    short = np.argsort(lengths)[:2]
+    ref = orc.fisher_norm_sq_token_samples(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets, idx, seqs=short)
+    for i in short:
+        assert abs(f2h[i] - ref[i]) <= TOL["bf16"] * ref[i], f"config5 F^2[{i}] {f2h[i]} vs {ref[i]}"
