@@ -1,4 +1,4 @@
-// Gram matrix of a bf16 stash, streaming variant (n_seq <= 128):
+// Gram matrix of a bf16 stash, streaming variants (n_seq <= 128 first; larger batches further down):
 //     K_ij = sum_p S[i][p] * S[j][p]        (interacting listing:
 //                                            ntk[i, j] = sum(seq_grads[i] * seq_grads[j]))
 // One pass over the stash, bound by HBM.  The stash rows are 10^7..10^8 elements
@@ -286,6 +286,124 @@ __global__ __launch_bounds__(256) void stash_gram_pair_kernel(LargeParams p) {
   }
 }
 
+// ---- 129..256 sequences in one pass ---------------------------------------------------------------
+// A 128-element slice of all 256 rows is two 32 KiB half-stages (rows 0..127 and 128..255, 256 bytes
+// per row: shorter runs per row stream noticeably slower from HBM).  LDS holds a ring of five
+// half-stages: two are multiplied while three are in flight.  The 36 upper-triangle 32x32 blocks of the
+// 8x8 block grid are dealt to the four waves by block row: wave w takes rows w and 7-w, nine blocks
+// each, and reads the row-block fragments it needs per 16-element step.  Every wave walks every step.
+// The stash is read exactly once; partials have the large path's layout.
+constexpr int kWideHalves = 5;
+
+template <int W>
+__device__ __forceinline__ void wide_body(const LargeParams& p, unsigned smem_base, int lane, int wave_s,
+                                          const char* const (&src)[2][8], const int (&vec_off)[8],
+                                          long long n_elems, long long my_first, long long my_count) {
+  constexpr int RB = 256, KW = 128, VPR = 16, LPW = 8, STEPS = 8;
+  constexpr int R0 = W, R1 = 7 - W;                  // this wave's two block rows
+  auto issue = [&](long long j) {                    // half-stage j = 2 * slice + half
+    const long long e0 = (my_first + (j >> 1)) * KW;
+    const unsigned stage = smem_base + (unsigned)(j % kWideHalves) * kStageBytes;
+    const int h = (int)(j & 1);
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+      long long byte = e0 * 2 + vec_off[q];
+      const long long last = (n_elems - 8) * 2;
+      if (byte > last) byte = last;
+      if ((j >> 1) >= my_count) byte = 0;
+      load_lds16((h ? src[1][q] : src[0][q]) + byte, stage + (unsigned)(wave_s * LPW + q) * 1024);
+    }
+  };
+  f32x16 acc[9];
+#pragma unroll
+  for (int b = 0; b < 9; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+  const int frow = lane & 31, half = lane >> 5;
+
+  issue(0); issue(1); issue(2);
+  for (long long k = 0; k < my_count; ++k) {
+    // half-stages 2k and 2k+1 landed (only 2k+2 may still be out), then everyone's; the two half-stages of
+    // slice k-1 are free after the barrier and take 2k+3 and 2k+4
+    __builtin_amdgcn_s_waitcnt(0x0f70 | LPW);
+    __builtin_amdgcn_s_barrier();
+    issue(2 * k + 3);
+    issue(2 * k + 4);
+    const unsigned sb0 = smem_base + (unsigned)((2 * k) % kWideHalves) * kStageBytes;
+    const unsigned sb1 = smem_base + (unsigned)((2 * k + 1) % kWideHalves) * kStageBytes;
+    const long long valid = n_elems - (my_first + k) * KW;
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      const int vec = st * 2 + half;
+      const bool dead = valid < KW && (long long)vec * 8 >= valid;
+      v4u frag[8];
+#pragma unroll
+      for (int b = R0; b < 8; ++b) {                 // row blocks below R0 pair with no block of this wave
+        const int row = (b & 3) * 32 + frow;
+        frag[b] = *(lds_v4u_ptr)((b < 4 ? sb0 : sb1) + (unsigned)row * RB + (unsigned)((vec ^ (row & (VPR - 1))) * 16));
+        if (dead) frag[b] = v4u{0u, 0u, 0u, 0u};
+      }
+      int q = 0;
+#pragma unroll
+      for (int bj = R0; bj < 8; ++bj, ++q)
+        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[R0]),
+                                                         __builtin_bit_cast(bf16x8, frag[bj]), acc[q], 0, 0, 0);
+#pragma unroll
+      for (int bj = R1; bj < 8; ++bj, ++q)
+        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[R1]),
+                                                         __builtin_bit_cast(bf16x8, frag[bj]), acc[q], 0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+
+  float* out = p.partials + (long long)blockIdx.x * p.slot_floats;
+  int q = 0;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int bi = pass == 0 ? R0 : R1;
+#pragma unroll
+    for (int bj = bi; bj < 8; ++bj, ++q) {
+      float* o = out + ((long long)(bi * 8 + bj) * 16) * 64 + lane;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[v * 64] = (p.first ? 0.f : o[v * 64]) + acc[q][v];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void stash_gram_wide_kernel(LargeParams p) {
+  constexpr int KW = 128, VPR = 16, RPL = 4, LPW = 8;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const long long n_elems = p.p1 - p.p0;
+  const long long n_super = (n_elems + KW - 1) / KW;
+  // a contiguous run of slices per workgroup: each of its 256 row streams walks consecutive cache lines
+  const long long my_first = n_super * blockIdx.x / gridDim.x;
+  const long long my_count = n_super * (blockIdx.x + 1) / gridDim.x - my_first;
+  const char* src[2][LPW];
+  int vec_off[LPW];
+#pragma unroll
+  for (int q = 0; q < LPW; ++q) {
+    const int row = (wave * LPW + q) * RPL + lane / VPR;                // row within a half-stage, 0..127
+    const int pos = lane % VPR;
+    vec_off[q] = (pos ^ (row & (VPR - 1))) * 16;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int r = h * 128 + row;
+      const int seq = r < p.n_seq ? r : p.n_seq - 1;                    // padded rows: entries never written
+      src[h][q] = reinterpret_cast<const char*>(p.stash + (size_t)seq * p.seq_stride + p.p0);
+    }
+  }
+  // every wave runs the same loop (same barriers), specialised on its block rows
+  switch (wave_s) {
+    case 0: wide_body<0>(p, smem_base, lane, wave_s, src, vec_off, n_elems, my_first, my_count); break;
+    case 1: wide_body<1>(p, smem_base, lane, wave_s, src, vec_off, n_elems, my_first, my_count); break;
+    case 2: wide_body<2>(p, smem_base, lane, wave_s, src, vec_off, n_elems, my_first, my_count); break;
+    default: wide_body<3>(p, smem_base, lane, wave_s, src, vec_off, n_elems, my_first, my_count); break;
+  }
+}
+
 // grid: one 1024-thread block per (block bi <= bj, v); 16 waves add the slots, then wave order.
 __global__ __launch_bounds__(1024) void stash_gram_large_finish_kernel(const float* __restrict__ partials, int n_slots,
                                                                        long long slot_floats, int n_seq, int nbp,
@@ -333,6 +451,7 @@ int stash_gram_stream_slots() { return kBlocks; }
 
 // Large batches (n_seq > 128).
 int stash_gram_large_slots(int n_seq) {
+  if (n_seq <= 256) return kBlocks;          // one-pass kernel: one persistent workgroup per CU
   const int nsb = (n_seq + 127) / 128;
   const int pairs = nsb * (nsb + 1) / 2;
   int gx = 512 / pairs;
@@ -350,6 +469,18 @@ hipError_t launch_stash_gram_large(const StashGramArgs& a, hipStream_t s) {
   p.nsb = (a.n_seq + 127) / 128; p.nbp = 4 * p.nsb;
   p.slot_floats = (long long)stash_gram_large_slot_floats(a.n_seq);
   const int gx = stash_gram_large_slots(a.n_seq);
+  if (a.n_seq <= 256) {
+    constexpr size_t smem = (size_t)kWideHalves * kStageBytes;          // 160 KiB: the whole LDS of a CU
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(stash_gram_wide_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(stash_gram_wide_kernel, dim3(gx), dim3(256), smem, s, p);
+    return hipGetLastError();
+  }
   hipError_t e = launch_pair<true>(p, gx, p.nsb, s);
   if (e != hipSuccess) return e;
   return launch_pair<false>(p, gx, p.nsb * (p.nsb - 1) / 2, s);
