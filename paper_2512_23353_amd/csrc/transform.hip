@@ -18,8 +18,7 @@
 namespace isopo {
 namespace {
 
-constexpr int kThreads = 256;
-
+template <int kThreads>
 __device__ double block_sum(double x, double* red /* [kThreads/64] */) {
   x = wave_sum(x);
   __syncthreads();
@@ -31,6 +30,7 @@ __device__ double block_sum(double x, double* red /* [kThreads/64] */) {
   return s;
 }
 
+template <int kThreads>
 __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __restrict__ Kb, const float* __restrict__ Ab,
                                                              int m, int variant, int reg_mode, float lambda,
                                                              float* __restrict__ cb, int32_t* __restrict__ info,
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
   if (reg_mode == 1) {
     double tr = 0.0;
     for (int i = tid; i < m; i += kThreads) tr += (double)K[(size_t)i * m + i];
-    reg = (double)lambda * block_sum(tr, red) / (double)m;
+    reg = (double)lambda * block_sum<kThreads>(tr, red) / (double)m;
   }
 
   if (variant == 0) {
@@ -73,21 +73,40 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
   for (int i = tid; i < m; i += kThreads) y[i] = (double)A[i];
   __syncthreads();
 
-  for (int k = 0; k < m; ++k) {
-    const double d = M[(size_t)k * m + k];
-    if (!(d > 0.0)) {                       // uniform: every thread reads the same value
-      for (int i = tid; i < m; i += kThreads) c[i] = __builtin_nanf("");
-      if (info && tid == 0) info[prob] = k + 1;
-      return;
+  // Right-looking Cholesky in panels of kPanel columns: the panel is factored column by column (updates
+  // confined to the panel), then the trailing matrix takes one rank-kPanel update, so the large matrix is
+  // swept m/kPanel times instead of m times.
+  constexpr int kPanel = 8;
+  for (int k0 = 0; k0 < m; k0 += kPanel) {
+    const int nb = m - k0 < kPanel ? m - k0 : kPanel;
+    for (int kk = 0; kk < nb; ++kk) {
+      const int k = k0 + kk;
+      const double d = M[(size_t)k * m + k];
+      if (!(d > 0.0)) {                       // uniform: every thread reads the same value
+        for (int i = tid; i < m; i += kThreads) c[i] = __builtin_nanf("");
+        if (info && tid == 0) info[prob] = k + 1;
+        return;
+      }
+      const double inv = 1.0 / sqrt(d);
+      __syncthreads();                        // everyone has read the pivot
+      for (int r = k + tid; r < m; r += kThreads) M[(size_t)r * m + k] *= inv;   // column k of L (M[k][k] -> sqrt(d))
+      __syncthreads();
+      const int ncol = k0 + nb - 1 - k;       // panel columns right of k
+      const int nrow = m - k - 1;
+      for (int e = tid; e < nrow * ncol; e += kThreads) {
+        const int r = k + 1 + e / ncol, q = k + 1 + e % ncol;
+        if (q <= r) M[(size_t)r * m + q] -= M[(size_t)r * m + k] * M[(size_t)q * m + k];
+      }
+      __syncthreads();
     }
-    const double inv = 1.0 / sqrt(d);
-    __syncthreads();                        // everyone has read the pivot
-    for (int r = k + tid; r < m; r += kThreads) M[(size_t)r * m + k] *= inv;   // column k of L (M[k][k] -> sqrt(d))
-    __syncthreads();
-    const int rem = m - k - 1;              // trailing lower triangle, rows/cols k+1..m-1
+    const int t0 = k0 + nb, rem = m - t0;     // trailing lower triangle, rows/cols t0..m-1
     for (int e = tid; e < rem * rem; e += kThreads) {
-      const int r = k + 1 + e / rem, q = k + 1 + e % rem;
-      if (q <= r) M[(size_t)r * m + q] -= M[(size_t)r * m + k] * M[(size_t)q * m + k];
+      const int r = t0 + e / rem, q = t0 + e % rem;
+      if (q <= r) {
+        double s = 0.0;
+        for (int kk = 0; kk < nb; ++kk) s += M[(size_t)r * m + k0 + kk] * M[(size_t)q * m + k0 + kk];
+        M[(size_t)r * m + q] -= s;
+      }
     }
     __syncthreads();
   }
@@ -113,21 +132,31 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
 
 }  // namespace
 
+template <int THREADS>
+hipError_t launch_transform_t(const TransformArgs& a, size_t smem, double* gws, hipStream_t s) {
+  auto kern = transform_kernel<THREADS>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    const int max_smem = (int)(((size_t)kTransformLdsMax * kTransformLdsMax + kTransformLdsMax) * sizeof(double));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       max_smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(a.batch), dim3(THREADS), smem, s, a.K, a.A, a.n_seq, a.variant, a.reg_mode, a.lambda,
+                     a.c, a.info, gws);
+  return hipGetLastError();
+}
+
 hipError_t launch_transform(const TransformArgs& a, hipStream_t s) {
   const bool lds = a.n_seq <= kTransformLdsMax;
   size_t smem = 0;
   if (a.variant == 1 && lds) smem = ((size_t)a.n_seq * a.n_seq + a.n_seq) * sizeof(double);
-  static bool attr_set = false;
-  if (!attr_set) {
-    const int max_smem = (int)(((size_t)kTransformLdsMax * kTransformLdsMax + kTransformLdsMax) * sizeof(double));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(transform_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, max_smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(transform_kernel, dim3(a.batch), dim3(kThreads), smem, s, a.K, a.A, a.n_seq, a.variant,
-                     a.reg_mode, a.lambda, a.c, a.info, (a.variant == 1 && !lds) ? a.workspace : nullptr);
-  return hipGetLastError();
+  double* gws = (a.variant == 1 && !lds) ? a.workspace : nullptr;
+  // the trailing update of column k has (m-k)^2/2 independent elements: more threads for larger problems
+  if (a.n_seq <= 48) return launch_transform_t<256>(a, smem, gws, s);
+  if (a.n_seq <= 96) return launch_transform_t<512>(a, smem, gws, s);
+  return launch_transform_t<1024>(a, smem, gws, s);
 }
 
 }  // namespace isopo
