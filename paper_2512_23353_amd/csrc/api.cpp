@@ -43,31 +43,33 @@ isopo_status check_layer(const isopo_layer* l, bool need_dev) {
   return ISOPO_OK;
 }
 
-// Rates of this library's own kernels on one MI355X, used only to rank the two
-// Gram paths.  The materialised path runs the tiled MFMA contraction once and
-// then streams the stash (one write, one read); the ghost path is two
-// token-by-token Gram matrices whose fragments come straight from cache.
-constexpr double kRateContraction = 6.0e14;   // flop/s, per-sequence gradient kernel
-constexpr double kRateGhost = 1.2e14;         // flop/s, ghost kernel
-constexpr double kRateStash = 3.0e12;         // B/s, stash write / read
+// Rates of this library's own kernels, measured on one MI355X, used only to rank the two Gram paths.
+// Materialised: the tiled MFMA contraction writes the stash while it computes (whichever of the two takes
+// longer bounds that launch), then the Gram pass reads the stash once.  Ghost: two token-by-token Gram
+// matrices over d_in + d_out features; a workgroup walks all features of its 64x64 token-tile pair
+// serially, which sets a floor however few tokens there are.
+constexpr double kRateContraction = 1.0e15;   // flop/s, per-sequence gradient kernel
+constexpr double kRateGhost = 9.5e13;         // token-pair-features/s, ghost kernel
+constexpr double kGhostPerFeature = 1.65e-8;  // s per feature of the serial walk
+constexpr double kRateStash = 3.7e12;         // B/s, stash write / read
 constexpr double kLaunch = 6.0e-6;            // s per kernel launch in the chain
 
 void cost_model(const isopo_layer* l, double* t_ghost, double* t_mat) {
-  const double n = (double)l->n_tokens, di = l->d_in, d_o = l->d_out, b = l->n_seq;
+  const double di = l->d_in, d_o = l->d_out, b = l->n_seq;
   const double D = di * d_o;
-  // ghost: N^2/2 token pairs (symmetry), 2 flops per multiply-add, over d_in + d_out features;
-  // the kernel works on 64-token tiles, so a short batch still pays whole tiles
+  // ghost: the kernel works on 64-token tiles, so a short batch still pays whole tiles
   const double nt = (double)((l->n_tokens + 63) / 64) * 64.0;
-  *t_ghost = nt * nt * (di + d_o) / kRateGhost + 4 * kLaunch;
+  const double walk = kGhostPerFeature * (di + d_o), pairs = nt * nt * (di + d_o) / kRateGhost;
+  *t_ghost = (walk > pairs ? walk : pairs) + 4 * kLaunch;
   // materialised: every tile is padded to whole 32-token blocks per sequence
   double n_pad = 0;
   for (int i = 0; i < l->n_seq; ++i) {
     const int len = l->seq_offsets_host[i + 1] - l->seq_offsets_host[i];
     n_pad += (double)((len + 31) / 32) * 32.0;
   }
-  (void)n;
-  const double es = (double)elem_size(l->dtype);
-  *t_mat = 2.0 * n_pad * D / kRateContraction + 2.0 * b * D * es / kRateStash + 3 * kLaunch;
+  const double pass = b * D * (double)elem_size(l->dtype) / kRateStash;      // one pass over the stash
+  const double contract = 2.0 * n_pad * D / kRateContraction;
+  *t_mat = (contract > pass ? contract : pass) + pass + 3 * kLaunch;
 }
 
 size_t stash_bytes(const isopo_layer* l, int rows) {
