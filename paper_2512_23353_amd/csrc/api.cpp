@@ -46,19 +46,19 @@ isopo_status check_layer(const isopo_layer* l, bool need_dev) {
 // Rates of this library's own kernels, measured on one MI355X, used only to rank the two Gram paths.
 // Materialised: the tiled MFMA contraction writes the stash while it computes (whichever of the two takes
 // longer bounds that launch), then the Gram pass reads the stash once.  Ghost: two token-by-token Gram
-// matrices over d_in + d_out features; a workgroup walks all features of its 64x64 token-tile pair
+// matrices over d_in + d_out features; a workgroup walks all features of its 128x128 token-tile pair
 // serially, which sets a floor however few tokens there are.
 constexpr double kRateContraction = 1.0e15;   // flop/s, per-sequence gradient kernel
-constexpr double kRateGhost = 9.5e13;         // token-pair-features/s, ghost kernel
-constexpr double kGhostPerFeature = 1.65e-8;  // s per feature of the serial walk
+constexpr double kRateGhost = 5.5e14;         // token-pair-features/s, ghost kernel
+constexpr double kGhostPerFeature = 9.0e-9;   // s per feature of the serial walk
 constexpr double kRateStash = 3.7e12;         // B/s, stash write / read
 constexpr double kLaunch = 6.0e-6;            // s per kernel launch in the chain
 
 void cost_model(const isopo_layer* l, double* t_ghost, double* t_mat) {
   const double di = l->d_in, d_o = l->d_out, b = l->n_seq;
   const double D = di * d_o;
-  // ghost: the kernel works on 64-token tiles, so a short batch still pays whole tiles
-  const double nt = (double)((l->n_tokens + 63) / 64) * 64.0;
+  // ghost: the kernel works on 128-token tiles, so a short batch still pays whole tiles
+  const double nt = (double)((l->n_tokens + 127) / 128) * 128.0;
   const double walk = kGhostPerFeature * (di + d_o), pairs = nt * nt * (di + d_o) / kRateGhost;
   *t_ghost = (walk > pairs ? walk : pairs) + 4 * kLaunch;
   // materialised: every tile is padded to whole 32-token blocks per sequence

@@ -128,16 +128,13 @@ def test_config4_one_layer_sampled(gpu_device):
 @pytest.mark.parametrize("n_short", [4, 8, 16])
 def test_config5_ghost_on_shortest_sequences(gpu_device, n_short):
     """Sub-microbatches of the stress layer's shortest sequences: few tokens on
-    a 5120 -> 27648 layer is where the ghost form is the cheaper one (AUTO picks
-    it for 4 and 8 sequences; 16 sit at the measured crossover, where either
-    choice is within a few per cent, so the ghost path is forced there)."""
+    a 5120 -> 27648 layer is where the ghost form is the cheaper one."""
     w = wl.CONFIGS["config5"]
     lengths = np.sort(wl.draw_lengths(w))[:n_short]
     prob = wl.make_layer(w, w.projections[0], lengths, device=gpu_device)
     layer, A = to_device(prob, gpu_device)
-    if n_short <= 8:
-        assert isopo.gram_plan(layer)[0] == "ghost"
-    out = isopo.layer_step(layer, A, "interacting", 1e-3, isopo.REG_REL_TRACE, "auto" if n_short <= 8 else "ghost")
+    assert isopo.gram_plan(layer)[0] == "ghost"
+    out = isopo.layer_step(layer, A, "interacting", 1e-3, isopo.REG_REL_TRACE, "auto")
     Km, _ = isopo.layer_gram(layer, "materialised")
     torch.cuda.synchronize()
     K_ref = orc.layer_ntk(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets, chunk_rows=2048)
