@@ -125,7 +125,7 @@ __device__ __forceinline__ void product_pass(const void* M, int d, const int32_t
       grow = min(max(idx[j < n_samples ? j : 0], 0), n_tokens - 1);
     }
     src[q] = static_cast<const char*>(M) + (size_t)grow * d * kEs;
-    vec_off[q] = (pos ^ (row & (kVpr - 1))) * 16;
+    vec_off[q] = (pos ^ ((row >> 1) & (kVpr - 1))) * 16;
   }
   auto issue = [&](int k) {
 #pragma unroll
@@ -153,12 +153,12 @@ __device__ __forceinline__ void product_pass(const void* M, int d, const int32_t
     for (int st = 0; st < kVpr / 2; ++st) {
       const int vec = st * 2 + half;
       const int ra = wave * 32 + frow;
-      v4u fa = *(lds_v4u_ptr)(sb + (unsigned)ra * kRowBytes + (unsigned)((vec ^ (ra & (kVpr - 1))) * 16));
+      v4u fa = *(lds_v4u_ptr)(sb + (unsigned)ra * kRowBytes + (unsigned)((vec ^ ((ra >> 1) & (kVpr - 1))) * 16));
       if (valid < KW && vec * kV >= valid) fa = v4u{0u, 0u, 0u, 0u};
 #pragma unroll
       for (int b = 0; b < NBS; ++b) {
         const int rb = kTok + b * 32 + frow;
-        const v4u fb = *(lds_v4u_ptr)(sb + (unsigned)rb * kRowBytes + (unsigned)((vec ^ (rb & (kVpr - 1))) * 16));
+        const v4u fb = *(lds_v4u_ptr)(sb + (unsigned)rb * kRowBytes + (unsigned)((vec ^ ((rb >> 1) & (kVpr - 1))) * 16));
         if constexpr (BF16) {
           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), __builtin_bit_cast(bf16x8, fb),
                                                            acc[b], 0, 0, 0);
