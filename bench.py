@@ -251,6 +251,11 @@ def main() -> int:
                                f"B={n_seq} ragged sequences, N={n_tokens} tokens, bf16 inputs fp32 accumulation",
                    "variant": args.variant, "lambda": args.lam, "reg_mode": "rel_trace",
                    "gram_paths": sorted(set(pl[0] for pl in plans)), "seed": w.seed},
+        "device": {"name": torch.cuda.get_device_properties(dev).name,
+                   "compute_units": torch.cuda.get_device_properties(dev).multi_processor_count,
+                   "hbm_gib": round(torch.cuda.get_device_properties(dev).total_memory / 2 ** 30, 1),
+                   "peaks_used": {"bf16_mfma_tflops": PEAK_BF16_MFMA / 1e12, "hbm_tb_s": PEAK_HBM / 1e12},
+                   "clocks": "as found (not pinned); under this load the part runs near 1.8 GHz, see profiles/"},
         "tflops": total_flops / t_step / 1e12,
         "pct_bf16_mfma_peak": 100.0 * total_flops / t_step / PEAK_BF16_MFMA,
         "algorithmic_flops_per_step": total_flops,
