@@ -192,13 +192,10 @@ template <int THREADS>
 hipError_t launch_jacobi(const float* K, int m, double* D, double* U, int32_t* info, size_t smem, double* gA,
                          double* gV, hipStream_t s) {
   auto kern = jacobi_eigh_kernel<THREADS>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kEighLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (static initialisation is thread-safe); a failure is returned by every call
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kEighLdsBytes);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(1), dim3(THREADS), smem, s, K, m, D, U, info, gA, gV);
   return hipGetLastError();
 }

@@ -268,13 +268,10 @@ template <int NBS, bool BF16>
 hipError_t launch_main(const Params& p, hipStream_t s) {
   constexpr size_t smem = (size_t)kStages * (kTok + 32 * NBS) * kRowBytes;
   auto kern = fisher_samples_kernel<NBS, BF16>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (static initialisation is thread-safe); a failure is returned by every call
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3((p.n_tokens + kTok - 1) / kTok), dim3(256), smem, s, p);
   return hipGetLastError();
 }

@@ -290,13 +290,10 @@ hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s) {
     if (a.bf16) {
       const int nt = (a.n_tokens + kGT - 1) / kGT;
       constexpr size_t smem = (size_t)kGStages * kGStageBytes;
-      static bool attr_set = false;
-      if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_gram_tiled_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-      }
+      // once per process (static initialisation is thread-safe); a failure is returned by every call
+      static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_gram_tiled_kernel),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (attr != hipSuccess) return attr;
       hipLaunchKernelGGL(ghost_gram_tiled_kernel, dim3((unsigned)((long long)nt * (nt + 1) / 2)), dim3(256), smem, s,
                          static_cast<const unsigned short*>(a.X), static_cast<const unsigned short*>(a.Delta), a.tok_seq,
                          a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, a.K64);

@@ -259,13 +259,10 @@ hipError_t launch_cfg(const SeqGradArgs& a, hipStream_t s) {
   p.n_blocks = (unsigned)blocks;
   constexpr size_t smem = 2ull * BK * ((BM + PAD) + (BN + PAD)) * sizeof(T);
   auto kern = seq_grad_kernel<T, BM, BN, BK, PAD, WEIGHTED>;
-  static bool attr_set = false;   // per instantiation; benign if raced (idempotent call)
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process and instantiation (static initialisation is thread-safe); a failure is returned by every call
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(256), smem, s, p);
   return hipGetLastError();
 }

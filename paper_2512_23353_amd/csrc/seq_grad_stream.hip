@@ -370,13 +370,10 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
   constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
   constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
   auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (static initialisation is thread-safe); a failure is returned by every call
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return attr;
   if (!PER_SEQ && p.n_chunks > 1) {
     // the band of output rows this launch owns is contiguous in dW
     float* band = static_cast<float*>(a.out) + (size_t)(a.row0 - a.out_row0) * a.d_in;

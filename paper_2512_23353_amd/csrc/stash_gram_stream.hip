@@ -161,13 +161,10 @@ hipError_t launch(const Params& p, hipStream_t s) {
   constexpr size_t smem = (size_t)kStages * kStageBytes;
   static_assert((size_t)tri(NB) * 4096 <= smem, "reduction scratch fits the ring");
   auto kern = stash_gram_stream_kernel<NB, NBL>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (static initialisation is thread-safe); a failure is returned by every call
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(kBlocks), dim3(256), smem, s, p);
   return hipGetLastError();
 }
@@ -434,13 +431,10 @@ hipError_t launch_pair(const LargeParams& p, int gx, int n_pairs, hipStream_t s)
   if (n_pairs <= 0) return hipSuccess;
   constexpr size_t smem = (size_t)kStages * kStageBytes;
   auto kern = stash_gram_pair_kernel<DIAG>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process (static initialisation is thread-safe); a failure is returned by every call
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(gx, n_pairs), dim3(256), smem, s, p);
   return hipGetLastError();
 }
@@ -471,13 +465,10 @@ hipError_t launch_stash_gram_large(const StashGramArgs& a, hipStream_t s) {
   const int gx = stash_gram_large_slots(a.n_seq);
   if (a.n_seq <= 256) {
     constexpr size_t smem = (size_t)kWideHalves * kStageBytes;          // 160 KiB: the whole LDS of a CU
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(stash_gram_wide_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    // once per process (static initialisation is thread-safe); a failure is returned by every call
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(stash_gram_wide_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(stash_gram_wide_kernel, dim3(gx), dim3(256), smem, s, p);
     return hipGetLastError();
   }

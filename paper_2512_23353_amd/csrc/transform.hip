@@ -135,14 +135,11 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
 template <int THREADS>
 hipError_t launch_transform_t(const TransformArgs& a, size_t smem, double* gws, hipStream_t s) {
   auto kern = transform_kernel<THREADS>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    const int max_smem = (int)(((size_t)kTransformLdsMax * kTransformLdsMax + kTransformLdsMax) * sizeof(double));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       max_smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per process and instantiation (static initialisation is thread-safe); a failure is returned by every call
+  constexpr int max_smem = (int)(((size_t)kTransformLdsMax * kTransformLdsMax + kTransformLdsMax) * sizeof(double));
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, max_smem);
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(a.batch), dim3(THREADS), smem, s, a.K, a.A, a.n_seq, a.variant, a.reg_mode, a.lambda,
                      a.c, a.info, gws);
   return hipGetLastError();
