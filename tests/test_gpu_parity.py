@@ -150,7 +150,7 @@ def _random_gram(rng, m, rank_extra=8, scale=1.0):
     return (J @ J.T).astype(np.float32)
 
 
-@pytest.mark.parametrize("m", [1, 2, 4, 16, 31, 32, 64, 128, 129, 256])
+@pytest.mark.parametrize("m", [1, 2, 4, 7, 8, 9, 16, 31, 32, 48, 49, 64, 96, 97, 128, 129, 200, 256])
 @pytest.mark.parametrize("variant", ["fisher", "interacting"])
 def test_transform_sizes(gpu_device, m, variant):
     rng = np.random.default_rng(100 + m)

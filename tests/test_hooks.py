@@ -78,14 +78,16 @@ def test_hooks_padded_batch_layout_and_accumulation():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("variant", ["interacting", "fisher", "fisher_token_samples", "rescaled"])
-def test_hooks_run_the_hip_library(gpu_device, variant):
-    """The same harness on the GPU with the HIP library as the layer step, fp32:
-    every hooked layer's update against the oracle on the captured matrices."""
-    from paper_2512_23353_amd import isopo
+@pytest.mark.parametrize("variant,dtype", [("interacting", "f32"), ("fisher", "f32"), ("fisher_token_samples", "f32"),
+                                           ("rescaled", "f32"), ("interacting", "bf16"), ("fisher_token_samples", "bf16")])
+def test_hooks_run_the_hip_library(gpu_device, variant, dtype):
+    """The same harness on the GPU with the HIP library as the layer step, fp32
+    and bf16 models: every hooked layer's update against the oracle on the
+    captured matrices."""
+    from paper_2512_23353_amd import isopo, workloads as wl
     from helpers import TOL, assert_dW_close
     torch.manual_seed(2)
-    model = ToyBlock(dtype=torch.float32).to(gpu_device)
+    model = ToyBlock(dtype=torch.float32 if dtype == "f32" else torch.bfloat16).to(gpu_device)
     lengths = [40, 9, 1, 70, 33, 17]
     tokens, targets, off, A = make_batch(lengths, device=gpu_device)
     At = torch.from_numpy(A.astype(np.float32)).to(gpu_device)
@@ -98,7 +100,7 @@ def test_hooks_run_the_hip_library(gpu_device, variant):
     order = list(hooks.captured)                              # dict keeps backward (call) order
     assert len(order) == 8
     for mod in order:
-        X, Delta, off_c = (t.cpu().numpy() if torch.is_tensor(t) else t for t in hooks.captured[mod])
+        X, Delta, off_c = (wl.to_oracle(t) if torch.is_tensor(t) else t for t in hooks.captured[mod])
         Af = A.astype(np.float32).astype(np.float64)
         G = orc.seq_logprob_grads(X, Delta, off_c)
         K = orc.ntk_from_seq_grads(G)
@@ -110,4 +112,4 @@ def test_hooks_run_the_hip_library(gpu_device, variant):
         else:
             c = orc.coeff_rescaled(orc.fisher_norm_sq(K), np.diag(K), Af, 0.0, -1.0, -2.0)
         ref, mag = orc.weighted_grad(G, c), orc.weighted_grad_abs(G, c)
-        assert_dW_close(mod.weight.grad.cpu().numpy(), ref, TOL["f32"], f"{variant}", mag)
+        assert_dW_close(mod.weight.grad.float().cpu().numpy(), ref, TOL[dtype], f"{variant}/{dtype}", mag)
