@@ -187,7 +187,7 @@ def main() -> int:
             f"{other}_from_stash_gram": {"ms_per_step": t_other * 1e3, "overhead_over_reinforce": t_other / t_reinforce - 1.0},
             "fisher_from_token_samples": {"ms_per_step": t_ts * 1e3, "overhead_over_reinforce": t_ts / t_reinforce - 1.0,
                                           "n_samples": args.n_samples,
-                                          "what": "isopo_fisher_samples -> isopo_scale_rows -> one unweighted contraction per projection"},
+                                          "what": "isopo_fisher_samples -> isopo_weighted_grad_prescaled (rows of the narrower operand scaled, then one unweighted contraction) per projection"},
         }
         if n_layers > 1:
             # The sweep with K and the stash formed once per layer: six transforms (both variants x three

@@ -244,6 +244,16 @@ isopo_status isopo_scale_rows(const void* src, isopo_dtype dtype, int64_t n_toke
                               const int32_t* seq_offsets_dev, int32_t n_seq, const float* c, void* dst,
                               void* stream);
 
+/* The weighted update from X and Delta (no stash) in two launches: isopo_scale_rows on the narrower of
+ * X and Delta into `scratch`, then the unweighted contraction on the scaled copy:
+ *     dW = beta dW + Delta^T diag(c_tok) X      (`grad += advantages[i] * scale_i * seq_logprob_grad`).
+ * For callers that have no stash (coefficients from isopo_fisher_samples, or a workspace too small to
+ * keep one).  scratch: device, 16-byte aligned, isopo_weighted_grad_scratch(layer) bytes
+ * (n_tokens * min(d_in, d_out) elements of the input dtype). */
+size_t isopo_weighted_grad_scratch(const isopo_layer* layer);
+isopo_status isopo_weighted_grad_prescaled(const isopo_layer* layer, const float* c, float beta, float* dW,
+                                           void* scratch, size_t scratch_bytes, void* stream);
+
 const char* isopo_status_string(isopo_status s);
 
 /* Library version, "major.minor". */

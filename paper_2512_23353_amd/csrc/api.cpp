@@ -392,4 +392,27 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
   return launch_seq_grad(a, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
+size_t isopo_weighted_grad_scratch(const isopo_layer* layer) {
+  if (check_layer(layer, false) != ISOPO_OK) return 0;
+  const int d = layer->d_in <= layer->d_out ? layer->d_in : layer->d_out;
+  return (size_t)layer->n_tokens * (size_t)d * elem_size(layer->dtype);
+}
+
+isopo_status isopo_weighted_grad_prescaled(const isopo_layer* layer, const float* c, float beta, float* dW,
+                                           void* scratch, size_t scratch_bytes, void* stream) {
+  isopo_status st = check_layer(layer, true);
+  if (st != ISOPO_OK) return st;
+  if (!c || !dW || !aligned16(dW)) return ISOPO_ERR_INVALID_ARG;
+  if (layer->n_tokens == 0) return isopo_weighted_grad(layer, nullptr, nullptr, beta, dW, stream);
+  if (!scratch || !aligned16(scratch)) return ISOPO_ERR_INVALID_ARG;
+  if (scratch_bytes < isopo_weighted_grad_scratch(layer)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  const bool narrow_x = layer->d_in <= layer->d_out;
+  st = isopo_scale_rows(narrow_x ? layer->X : layer->Delta, layer->dtype, layer->n_tokens,
+                        narrow_x ? layer->d_in : layer->d_out, layer->seq_offsets_dev, layer->n_seq, c, scratch, stream);
+  if (st != ISOPO_OK) return st;
+  isopo_layer scaled = *layer;
+  if (narrow_x) scaled.X = scratch; else scaled.Delta = scratch;
+  return isopo_weighted_grad(&scaled, nullptr, nullptr, beta, dW, stream);
+}
+
 }  // extern "C"

@@ -31,6 +31,7 @@ EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
+           "isopo_weighted_grad_scratch", "isopo_weighted_grad_prescaled",
            "isopo_gram_norms", "isopo_rescale", "isopo_ntk_eigh_workspace", "isopo_ntk_eigh",
            "isopo_transform_eigh", "isopo_status_string", "isopo_version")
 
@@ -92,6 +93,10 @@ def load() -> ctypes.CDLL:
     lib.isopo_fisher_samples_workspace.restype = sz
     lib.isopo_fisher_samples.argtypes = [lp, vp, i32, vp, f32, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.isopo_fisher_samples.restype = ctypes.c_int
+    lib.isopo_weighted_grad_scratch.argtypes = [lp]
+    lib.isopo_weighted_grad_scratch.restype = sz
+    lib.isopo_weighted_grad_prescaled.argtypes = [lp, vp, f32, vp, vp, sz, vp]
+    lib.isopo_weighted_grad_prescaled.restype = ctypes.c_int
     lib.isopo_gram_norms.argtypes = [vp, i32, vp, vp, vp]
     lib.isopo_gram_norms.restype = ctypes.c_int
     lib.isopo_rescale.argtypes = [vp, vp, ctypes.c_int64, i32, vp, ctypes.POINTER(_RescaleParams), vp, vp, vp]
@@ -361,15 +366,19 @@ def scale_rows(src: torch.Tensor, layer: Layer, c: torch.Tensor, dst: Optional[t
 
 def weighted_grad_prescaled(layer: Layer, c: torch.Tensor, scratch: Optional[torch.Tensor] = None, beta: float = 0.0,
                             dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """dW = beta dW + Delta^T diag(c_tok) X: the narrower of X and Delta is scaled into `scratch`
-    (isopo_scale_rows), then the unweighted contraction runs on it."""
-    narrow_x = layer.d_in <= layer.d_out
-    src = layer.X if narrow_x else layer.Delta
+    """dW = beta dW + Delta^T diag(c_tok) X without a stash: the narrower of X and Delta is scaled
+    into `scratch`, then the unweighted contraction runs on it (one ABI call)."""
+    need = int(load().isopo_weighted_grad_scratch(layer.ref()))
     if scratch is None:
-        scratch = torch.empty_like(src)
-    scaled = scale_rows(src, layer, c, scratch.view(src.dtype).reshape(-1)[: src.numel()].view(src.shape), stream)
-    lay2 = Layer(scaled if narrow_x else layer.X, layer.Delta if narrow_x else scaled, layer.off_host, layer.off_dev)
-    return weighted_grad(lay2, None, None, beta, dW, stream)
+        scratch = alloc_workspace(need, layer.device)
+    if dW is None:
+        if beta != 0.0:
+            raise ValueError("beta != 0 needs an existing dW")
+        dW = torch.empty((layer.d_out, layer.d_in), dtype=torch.float32, device=layer.device)
+    _check(load().isopo_weighted_grad_prescaled(layer.ref(), c.data_ptr(), float(beta), dW.data_ptr(),
+                                                scratch.data_ptr(), scratch.numel() * scratch.element_size(),
+                                                _stream(stream)), "isopo_weighted_grad_prescaled")
+    return dW
 
 
 def layer_step(layer: Layer, A: torch.Tensor, variant="interacting", lam: float = 0.0,
