@@ -1,0 +1,72 @@
+"""Seeded random shapes through every route of the HIP path against the oracle:
+dimensions that are not multiples of any tile size, sequences of length 0 and
+1 mixed with long ones, both dtypes, both Gram paths, both transforms, the
+stash-free update and the token-sample coefficients."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import isopo_oracle as orc
+from paper_2512_23353_amd import isopo
+from paper_2512_23353_amd import workloads as wl
+
+from helpers import TOL, assert_K_close, assert_c_close, assert_dW_close, oracle_step, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw_case(seed):
+    rng = np.random.default_rng(seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    unit = 8 if dtype == "bf16" else 4
+    d_in = int(rng.integers(1, 80)) * unit
+    d_out = int(rng.integers(1, 80)) * unit
+    n_seq = int(rng.integers(1, 12))
+    kinds = rng.integers(0, 4, n_seq)
+    lengths = [int({0: 0, 1: 1, 2: rng.integers(2, 40), 3: rng.integers(40, 400)}[k]) for k in kinds]
+    if sum(lengths) == 0:
+        lengths[0] = int(rng.integers(1, 50))
+    return dtype, d_in, d_out, lengths
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape(gpu_device, seed):
+    dtype, d_in, d_out, lengths = _draw_case(seed)
+    print(f"seed {seed}: {dtype} d_in={d_in} d_out={d_out} lengths={lengths}", flush=True)
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype=dtype, seed=1000 + seed, sigma_delta=1e-2, rho=0.3 * (seed % 3))
+    tol = TOL[dtype]
+    layer, A = to_device(prob, gpu_device)
+    ref = oracle_step(prob, "interacting", 1e-2, isopo.REG_REL_TRACE)
+    ref_f = oracle_step(prob, "fisher", 1e-2, isopo.REG_REL_TRACE)
+    for path in ("materialised", "ghost"):
+        out = isopo.layer_step(layer, A, "interacting", 1e-2, isopo.REG_REL_TRACE, path)
+        torch.cuda.synchronize()
+        what = f"seed {seed}/{path}"
+        assert int(out["info"].item()) == 0
+        Kh = out["K"].cpu().numpy()
+        assert np.array_equal(Kh, Kh.T)
+        assert_K_close(Kh, ref["K"], tol, what)
+        assert_c_close(out["c"].cpu().numpy(), ref["c"], tol, what)
+        assert_dW_close(out["dW"].cpu().numpy(), ref["dW"], tol, what, ref["dW_abs"])
+        cf, _ = isopo.transform(out["K"], A, "fisher", 1e-2, isopo.REG_REL_TRACE)
+        assert_c_close(cf.cpu().numpy(), ref_f["c"], tol, what + "/fisher")
+    # the stash-free routes with the oracle's own coefficients
+    c_dev = torch.from_numpy(ref["c"].astype(np.float32)).to(gpu_device)
+    c32 = c_dev.cpu().numpy().astype(np.float64)
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    want, mag = orc.weighted_grad(G, c32), orc.weighted_grad_abs(G, c32)
+    for name, dW in (("weighted", isopo.weighted_grad(layer, c_dev)), ("prescaled", isopo.weighted_grad_prescaled(layer, c_dev))):
+        assert_dW_close(dW.cpu().numpy(), want, tol, f"seed {seed}/{name}", mag)
+    plain = isopo.weighted_grad(layer, None)
+    ones = np.ones(prob.n_seq)
+    assert_dW_close(plain.cpu().numpy(), orc.weighted_grad(G, ones), tol, f"seed {seed}/plain", orc.weighted_grad_abs(G, ones))
+    # token-sample coefficients
+    rng = np.random.default_rng(seed)
+    n_s = int(rng.integers(1, min(prob.n_tokens, 128) + 1))
+    idx = rng.permutation(prob.n_tokens)[:n_s].astype(np.int32)
+    c_ts, f2 = isopo.fisher_samples(layer, torch.from_numpy(idx).to(gpu_device), A, 1e-2, isopo.REG_REL_TRACE)
+    torch.cuda.synchronize()
+    c_ref, f2_ref = orc.coeff_fisher_token_samples(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets,
+                                                   idx, prob.A, 1e-2, isopo.REG_REL_TRACE)
+    assert rel_err(f2.cpu().numpy(), f2_ref) <= tol, f"seed {seed}: F^2"
+    assert_c_close(c_ts.cpu().numpy(), c_ref, tol, f"seed {seed}/token samples")
