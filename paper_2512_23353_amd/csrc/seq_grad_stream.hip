@@ -16,7 +16,9 @@
 //    (f(r) = 4*(r&3) ^ (r&2)), which makes both the linear DMA writes and the
 //    transpose reads bank-conflict free.
 //  * Fragments are double-buffered in registers and the reads of the next half
-//    block are interleaved one-to-one with the MFMAs of the current one.
+//    block are interleaved one-to-one with the MFMAs of the current one; the
+//    eight DMA instructions of the block NSTAGE-1 ahead go out between the MFMAs
+//    of the second half block, so the matrix pipe never waits on their issue.
 //  * Per-sequence mode: XCD x owns the x-th eighth of the output tiles of every
 //    sequence, so all eight L2s see every sequence (balanced under ragged
 //    lengths) and neighbouring workgroups share operand panels.  The bf16 tile is
@@ -232,23 +234,32 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 3) * LPT) & 15) | ((((NSTAGE - 3) * LPT) >> 4) << 14));
       __builtin_amdgcn_s_barrier();
       const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
+      // second half block: its 16 MFMAs carry the fragment reads of the next block's first half and the
+      // DMA instructions of the block NSTAGE-1 ahead
+      {
+        const int nb = it + NSTAGE - 1;
+        int rows = n_rows - nb * BK;
+        rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+        const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
+        const v4i rb = make_rsrc(baseB + (size_t)nb * BK * p.d_in, (unsigned)rows * rbB);
+        const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
 #pragma unroll
-      for (int i = 0; i < FM; ++i) fa0[i] = frA(sn + adA[i]);
+        for (int i = 0; i < FM; ++i) {
 #pragma unroll
-      for (int j = 0; j < FN; ++j) fb0[j] = frB(sn + adB[j]);
+          for (int j = 0; j < FN; ++j) {
+            const int idx = i * FN + j;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+            if (idx < FM) fa0[idx] = frA(sn + adA[idx]);
+            else if (idx < FM + FN) fb0[idx - FM] = frB(sn + adB[idx - FM]);
+            // the LPT DMA instructions spread evenly over the NMF MFMAs
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-      for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+            for (int q = idx * LPT / NMF; q < (idx + 1) * LPT / NMF; ++q) {
+              if (q < LA) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
+              else load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + (q - LA)) * 1024, offB[q - LA]);
+            }
+          }
+        }
       }
-      // the block NSTAGE-1 ahead goes to the stage freed at this iteration's barrier; issued behind the
-      // MFMAs so that the matrix pipe is not left idle while the DMA instructions go out
-      issue_loads(it + NSTAGE - 1);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);
