@@ -47,44 +47,19 @@ struct Params {
   double* den;           // [n_samples] ||g0_j||^2 ||a0_j||^2
 };
 
-// One launch prepares everything the main kernel needs.  Blocks [0, n_samples): den[j] =
-// ||Delta[idx_j]||^2 * ||X[idx_j]||^2 (fixed reduction order).  The remaining blocks: the sequence of
-// every token (binary search in the offsets) and zeros in the segment-sum accumulator.
-template <bool BF16>
+// The sequence of every token (binary search in the offsets) and zeros in the segment-sum accumulator.
 __global__ __launch_bounds__(256) void prep_kernel(Params p, long long n_acc) {
-  __shared__ double red[2][4];
-  if ((int)blockIdx.x >= p.n_samples) {
-    const long long i = (long long)(blockIdx.x - p.n_samples) * 256 + threadIdx.x;
-    if (i < n_acc) p.S64[i] = 0.0;
-    if (i < p.n_tokens) {
-      const int t = (int)i;
-      int lo = 0, hi = p.n_seq;
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (p.off[mid] <= t) lo = mid; else hi = mid;
-      }
-      p.tok_seq[t] = lo;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n_acc) p.S64[i] = 0.0;
+  if (i < p.n_tokens) {
+    const int t = (int)i;
+    int lo = 0, hi = p.n_seq;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.off[mid] <= t) lo = mid; else hi = mid;
     }
-    return;
+    p.tok_seq[t] = lo;
   }
-  const int j = blockIdx.x, row = min(max(p.idx[j], 0), p.n_tokens - 1);   // bad indices are clamped, never followed
-  double sx = 0.0, sd = 0.0;
-  for (int k = threadIdx.x; k < p.d_in; k += 256) {
-    const float v = BF16 ? bf16_bits_to_f32(static_cast<const unsigned short*>(p.X)[(size_t)row * p.d_in + k])
-                         : static_cast<const float*>(p.X)[(size_t)row * p.d_in + k];
-    sx += (double)v * v;
-  }
-  for (int k = threadIdx.x; k < p.d_out; k += 256) {
-    const float v = BF16 ? bf16_bits_to_f32(static_cast<const unsigned short*>(p.Delta)[(size_t)row * p.d_out + k])
-                         : static_cast<const float*>(p.Delta)[(size_t)row * p.d_out + k];
-    sd += (double)v * v;
-  }
-  sx = wave_sum(sx);
-  sd = wave_sum(sd);
-  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = sx; red[1][threadIdx.x >> 6] = sd; }
-  __syncthreads();
-  if (threadIdx.x == 0)
-    p.den[j] = (red[0][0] + red[0][1] + red[0][2] + red[0][3]) * (red[1][0] + red[1][1] + red[1][2] + red[1][3]);
 }
 
 __global__ void zero_f64_kernel(double* p, long long n) {
@@ -198,6 +173,14 @@ __global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
 #pragma unroll
   for (int b = 0; b < NBS; ++b) {
     const int j = b * 32 + (lane & 31);
+    // ||g^(j)||^2 = ||g0_j||^2 ||a0_j||^2 (eq. (two)) is the product's own entry at the sampled row:
+    // P[idx_j][j] = g0_j . g0_j and Q[idx_j][j] = a0_j . a0_j; exactly one lane of the grid holds it
+    if (j < p.n_samples) {
+      const int tj = min(max(p.idx[j], 0), p.n_tokens - 1);
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (tw + acc_row(v, lane) == tj) p.den[j] = (double)P[b][v] * (double)Q[b][v];
+    }
     if (r_first == r_last) {
       double s = 0.0;
 #pragma unroll
@@ -305,9 +288,7 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
   const long long ns = (long long)a.n_seq * ncol;
   if (a.n_tokens > 0) {
     const long long items = ns > a.n_tokens ? ns : (long long)a.n_tokens;
-    const dim3 grid((unsigned)(a.n_samples + (items + 255) / 256));
-    if (a.bf16) hipLaunchKernelGGL((prep_kernel<true>), grid, dim3(256), 0, s, p, ns);
-    else hipLaunchKernelGGL((prep_kernel<false>), grid, dim3(256), 0, s, p, ns);
+    hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, p, ns);
     hipError_t e;
     switch (nbs * 2 + (a.bf16 ? 1 : 0)) {
       case 2: e = launch_main<1, false>(p, s); break;
