@@ -72,7 +72,8 @@ typedef enum {
                                        as the interacting experiment's regulariser is) */
   ISOPO_REG_EMA_TRACE = 2           /* reg = lambda * trailing mean over minibatches of tr(K)/m
                                        (interacting experiment: factor * E[mean(D)], decay 0.9);
-                                       isopo_transform_eigh only */
+                                       isopo_transform_eigh and isopo_fisher_samples (there: of the
+                                       batch mean of F^2) */
 } isopo_reg_mode;
 
 /* One ragged layer problem.  All pointers caller-owned. */
@@ -166,15 +167,20 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
  *   sample_idx_dev  device int32 [n_samples], token row indices in [0, n_tokens) (the caller draws
  *                   them, e.g. randperm(N)[:n_samples]; an index outside the range is clamped
  *                   into it); 1 <= n_samples <= ISOPO_MAX_SAMPLES
- *   reg_mode        ABSOLUTE: reg = lambda.  REL_TRACE: reg = lambda * mean_i F_i^2 (the current
- *                   batch's mean standing in for the listing's trailing minibatch means)
+ *   reg_mode        ABSOLUTE: reg = lambda.  REL_TRACE: reg = lambda * mean_i F_i^2 of this batch.
+ *                   EMA_TRACE: reg = lambda * E[mean_i F_i^2], the listing's "trailing minibatch
+ *                   means": E <- the batch mean on the first call, E <- decay E + (1 - decay) mean
+ *                   after, this batch included
+ *   ema_state       device float[2] {E, number of minibatches seen}; zero it before the first
+ *                   minibatch; required for EMA_TRACE, ignored otherwise
  *   fisher_sq       optional device [n_seq]: F_i^2
  * A zero denominator (empty sequence, reg = 0) gives c_i = 0. */
 #define ISOPO_MAX_SAMPLES 128
 size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_samples);
 isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,
-                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* c,
-                                  float* fisher_sq, void* workspace, size_t ws_bytes, void* stream);
+                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* ema_state,
+                                  float ema_decay, float* c, float* fisher_sq, void* workspace, size_t ws_bytes,
+                                  void* stream);
 
 /* Norms the re-scalings are built from, read off the Gram matrix: fisher_sq[i] = (1/m) sum_j K_ij^2
  * (eq. F-norm-basic with the batch's reduced gradients as samples) and grad_sq[i] = K_ii = ||G_i||^2.

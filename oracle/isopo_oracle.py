@@ -227,6 +227,20 @@ def coeff_fisher_token_samples(X, Delta, seq_offsets, sample_idx, A, lam: float,
     return c, f2
 
 
+def coeff_fisher_token_samples_ema(X, Delta, seq_offsets, sample_idx, A, factor: float, ema_state, decay: float = 0.9):
+    """The same coefficients with the regulariser the listing suggests: factor
+    times the trailing mean over minibatches (this one included) of the batch
+    mean of F_norm^2.  Returns (c, F_norm^2, new_state)."""
+    A = np.asarray(A, dtype=np.float64)
+    f2 = fisher_norm_sq_token_samples(X, Delta, seq_offsets, sample_idx)
+    state = ema_update(ema_state, float(np.mean(f2)), decay)
+    den = f2 + float(factor) * state
+    c = np.zeros_like(A)
+    nz = den > 0
+    c[nz] = A[nz] / np.sqrt(den[nz])
+    return c, f2, state
+
+
 RESCALE_EPS = 1e-8     # the additive constant of reg() in the generalised re-scaling listing
 
 

@@ -280,14 +280,18 @@ size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_sample
 }
 
 isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,
-                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* c,
-                                  float* fisher_sq, void* workspace, size_t ws_bytes, void* stream) {
+                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* ema_state,
+                                  float ema_decay, float* c, float* fisher_sq, void* workspace, size_t ws_bytes,
+                                  void* stream) {
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
   if (!sample_idx_dev || !A || !c || !workspace || !(lambda >= 0.f)) return ISOPO_ERR_INVALID_ARG;
   if (n_samples < 1) return ISOPO_ERR_INVALID_ARG;
   if (n_samples > ISOPO_MAX_SAMPLES) return ISOPO_ERR_UNSUPPORTED;
-  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE) return ISOPO_ERR_INVALID_ARG;
+  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE && reg_mode != ISOPO_REG_EMA_TRACE)
+    return ISOPO_ERR_INVALID_ARG;
+  if (reg_mode == ISOPO_REG_EMA_TRACE && (!ema_state || !(ema_decay >= 0.f && ema_decay < 1.f)))
+    return ISOPO_ERR_INVALID_ARG;
   if (layer->n_tokens == 0) return ISOPO_ERR_INVALID_ARG;     // nothing to sample from
   if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return ISOPO_ERR_INVALID_ARG;
   if (ws_bytes < isopo_fisher_samples_workspace(layer, n_samples)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
@@ -295,7 +299,8 @@ isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sampl
   f.X = layer->X; f.Delta = layer->Delta; f.off = layer->seq_offsets_dev; f.sample_idx = sample_idx_dev;
   f.n_tokens = (int)layer->n_tokens; f.d_in = layer->d_in; f.d_out = layer->d_out; f.n_seq = layer->n_seq;
   f.n_samples = n_samples; f.bf16 = layer->dtype == ISOPO_BF16; f.A = A; f.lambda = lambda;
-  f.reg_mode = (int)reg_mode; f.c = c; f.fisher_sq = fisher_sq; f.workspace = workspace;
+  f.reg_mode = (int)reg_mode; f.ema_state = ema_state; f.ema_decay = ema_decay; f.c = c; f.fisher_sq = fisher_sq;
+  f.workspace = workspace;
   return launch_fisher_samples(f, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 

@@ -220,7 +220,8 @@ __device__ double block_sum256(double x, double* red) {
 __global__ __launch_bounds__(256) void fisher_samples_finish_kernel(const double* __restrict__ S64,
                                                                     const double* __restrict__ den, int n_seq,
                                                                     int n_samples, int ncol, const float* __restrict__ A,
-                                                                    float lambda, int reg_mode, float* __restrict__ c,
+                                                                    float lambda, int reg_mode, float* __restrict__ ema_state,
+                                                                    float ema_decay, float* __restrict__ c,
                                                                     float* __restrict__ f2_out, double* __restrict__ f2_tmp) {
   __shared__ double red[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -238,7 +239,20 @@ __global__ __launch_bounds__(256) void fisher_samples_finish_kernel(const double
     if (lane == 0) { f2_tmp[i] = f2; part += f2; }
   }
   const double mean = block_sum256(part, red) / n_seq;
-  const double reg = reg_mode == 1 ? (double)lambda * mean : (double)lambda;
+  __shared__ double sh_scale;
+  if (tid == 0) {
+    double scale = 1.0;                                  // absolute
+    if (reg_mode == 1) scale = mean;                     // this batch's mean F^2
+    if (reg_mode == 2) {                                 // trailing mean over minibatches, this one included
+      const bool first = ema_state[1] == 0.f;
+      scale = first ? mean : (double)ema_decay * (double)ema_state[0] + (1.0 - (double)ema_decay) * mean;
+      ema_state[0] = (float)scale;
+      ema_state[1] = ema_state[1] + 1.f;
+    }
+    sh_scale = scale;
+  }
+  __syncthreads();
+  const double reg = (double)lambda * sh_scale;
   __syncthreads();                                   // f2_tmp written by lane 0 of each wave, read by all below
   for (int i = tid; i < n_seq; i += 256) {
     const double den_i = f2_tmp[i] + reg;
@@ -306,7 +320,7 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(zero_f64_kernel, dim3((a.n_samples + 255) / 256), dim3(256), 0, s, p.den, (long long)a.n_samples);
   }
   hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(1), dim3(256), 0, s, p.S64, p.den, a.n_seq, a.n_samples, ncol,
-                     a.A, a.lambda, a.reg_mode, a.c, a.fisher_sq, f2_tmp);
+                     a.A, a.lambda, a.reg_mode, a.ema_state, a.ema_decay, a.c, a.fisher_sq, f2_tmp);
   return hipGetLastError();
 }
 

@@ -86,7 +86,9 @@ struct FisherSamplesArgs {
   bool bf16;
   const float* A;
   float lambda;
-  int reg_mode;
+  int reg_mode;                // 0 absolute, 1 times this batch's mean F^2, 2 times its trailing mean
+  float* ema_state;            // [2]: trailing mean, number of minibatches seen (reg_mode 2)
+  float ema_decay;
   float* c;
   float* fisher_sq;            // optional [n_seq]
   void* workspace;

@@ -91,7 +91,7 @@ def load() -> ctypes.CDLL:
     lib.isopo_scale_rows.restype = ctypes.c_int
     lib.isopo_fisher_samples_workspace.argtypes = [lp, i32]
     lib.isopo_fisher_samples_workspace.restype = sz
-    lib.isopo_fisher_samples.argtypes = [lp, vp, i32, vp, f32, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.isopo_fisher_samples.argtypes = [lp, vp, i32, vp, f32, ctypes.c_int, vp, f32, vp, vp, vp, sz, vp]
     lib.isopo_fisher_samples.restype = ctypes.c_int
     lib.isopo_weighted_grad_scratch.argtypes = [lp]
     lib.isopo_weighted_grad_scratch.restype = sz
@@ -275,7 +275,8 @@ def weighted_grad(layer: Layer, c: Optional[torch.Tensor], stash: Optional[torch
 
 def fisher_samples(layer: Layer, sample_idx: torch.Tensor, A: torch.Tensor, lam: float = 0.0,
                    reg_mode: int = REG_ABSOLUTE, c: Optional[torch.Tensor] = None,
-                   fisher_sq: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+                   fisher_sq: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
+                   ema_state: Optional[torch.Tensor] = None, ema_decay: float = 0.9):
     """Coefficients of the non-interacting update from the token-position-sample Fisher estimate.
     sample_idx: int32 device tensor of token rows.  Returns (c, F^2)."""
     n_s = int(sample_idx.numel())
@@ -288,7 +289,8 @@ def fisher_samples(layer: Layer, sample_idx: torch.Tensor, A: torch.Tensor, lam:
     if workspace is None:
         workspace = alloc_workspace(load().isopo_fisher_samples_workspace(layer.ref(), n_s), layer.device)
     _check(load().isopo_fisher_samples(layer.ref(), sample_idx.data_ptr(), n_s, A.data_ptr(), float(lam),
-                                       int(reg_mode), c.data_ptr(), fisher_sq.data_ptr(), workspace.data_ptr(),
+                                       int(reg_mode), _ptr(ema_state), float(ema_decay), c.data_ptr(),
+                                       fisher_sq.data_ptr(), workspace.data_ptr(),
                                        workspace.numel(), _stream(stream)), "isopo_fisher_samples")
     return c, fisher_sq
 

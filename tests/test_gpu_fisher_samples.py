@@ -121,6 +121,28 @@ def test_config3_full_size_sampled_sequences(gpu_device):
         assert abs(f2h[i] - ref[i]) <= TOL["bf16"] * ref[i]
 
 
+def test_trailing_mean_regulariser(gpu_device):
+    """reg = factor * E[mean F^2] with the trailing mean kept on the device over
+    three minibatches of different scale."""
+    rng = np.random.default_rng(71)
+    ema = torch.zeros(2, dtype=torch.float32, device=gpu_device)
+    state = None
+    for k, scale in enumerate((1e-2, 3e-2, 5e-3)):
+        prob = wl.custom_layer(192, 256, [60, 90, 30, 120, 11], dtype="bf16", seed=80 + k, sigma_delta=scale)
+        idx = _draw_samples(rng, prob.n_tokens, 24)
+        layer, A = to_device(prob, gpu_device)
+        c, f2 = isopo.fisher_samples(layer, torch.from_numpy(idx).to(gpu_device), A, 0.7, isopo.REG_EMA_TRACE,
+                                     ema_state=ema, ema_decay=0.9)
+        torch.cuda.synchronize()
+        c_ref, f2_ref, state = orc.coeff_fisher_token_samples_ema(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta),
+                                                                  prob.seq_offsets, idx, prob.A, 0.7, state, 0.9)
+        assert ema[0].item() == pytest.approx(state, rel=TOL["bf16"])
+        assert ema[1].item() == k + 1
+        assert_c_close(c.cpu().numpy(), c_ref, TOL["bf16"], f"minibatch {k}")
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples(layer, torch.from_numpy(idx).to(gpu_device), A, 0.7, isopo.REG_EMA_TRACE)   # no state
+
+
 def test_bad_arguments(gpu_device):
     prob = wl.custom_layer(64, 64, [10, 20], dtype="f32", seed=1)
     layer, A = to_device(prob, gpu_device)

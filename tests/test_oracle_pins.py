@@ -365,6 +365,16 @@ def test_token_sample_fisher_estimate():
     np.testing.assert_allclose(c, A / np.sqrt(f2a + 0.3), rtol=1e-12)
     c, _ = orc.coeff_fisher_token_samples(X, D, off, idx, A, 0.5, orc.REG_REL_TRACE)
     np.testing.assert_allclose(c, A / np.sqrt(f2a + 0.5 * f2a.mean()), rtol=1e-12)
+    # trailing-mean regulariser over three minibatches of different scale, iterated by hand
+    state, means = None, []
+    for scale in (1.0, 3.0, 0.5):
+        c, f2s, state = orc.coeff_fisher_token_samples_ema(X, scale * D, off, idx, A, 0.7, state, 0.9)
+        means.append(float(np.mean(f2s)))
+        np.testing.assert_allclose(f2s, scale ** 2 * f2a, rtol=1e-12)
+        want = means[0] if len(means) == 1 else (0.9 * means[0] + 0.1 * means[1] if len(means) == 2
+                                                 else 0.81 * means[0] + 0.09 * means[1] + 0.1 * means[2])
+        assert state == pytest.approx(want, rel=1e-12)
+        np.testing.assert_allclose(c, A / np.sqrt(f2s + 0.7 * want), rtol=1e-12)
     # an empty sequence has zero Fisher norm; with reg 0 its coefficient is 0
     X2, D2, off2 = _rand_layer(rng, [3, 0, 4], 5, 4)
     c, f2 = orc.coeff_fisher_token_samples(X2, D2, off2, [0, 5], np.ones(3), 0.0)
