@@ -84,7 +84,8 @@ def main() -> int:
     blocks = [wl.make_block(w, device=dev, lengths=lengths, layer=l) for l in range(min(n_layers, 2))]
     block = [p for b in blocks for p in b]
     n_tokens, n_seq = block[0].n_tokens, block[0].n_seq
-    layers = [isopo.Layer(p.X, p.Delta, p.seq_offsets) for p in block]
+    layers = [isopo.Layer(p.X, p.Delta, p.seq_offsets) for p in block[:1]]
+    layers += [isopo.Layer(p.X, p.Delta, p.seq_offsets, seq_offsets_dev=layers[0].off_dev) for p in block[1:]]
     sweeps = n_layers // len(blocks)          # passes over `layers` per step
     assert sweeps * len(blocks) == n_layers
     A = torch.from_numpy(block[0].A).to(dev)
@@ -130,16 +131,28 @@ def main() -> int:
     # weighted contraction (rows of the narrower operand pre-scaled).  No stash, no Gram matrix.
     g = torch.Generator(device="cpu").manual_seed(w.seed)
     sample_idx = torch.randperm(n_tokens, generator=g)[: args.n_samples].to(torch.int32).to(dev)
-    fs_ws = isopo.alloc_workspace(max(isopo.load().isopo_fisher_samples_workspace(l.ref(), args.n_samples)
-                                      for l in layers), dev)
-    f2s = [torch.empty(n_seq, dtype=torch.float32, device=dev) for _ in layers]
+    # projections that share their input (q/k/v, gate/up) form one group: X is streamed once per group
+    groups = []
+    for i, l in enumerate(layers):
+        same_block = groups and groups[-1][0] // npj == i // npj
+        if same_block and len(groups[-1]) < 4 and layers[groups[-1][0]].X.data_ptr() == l.X.data_ptr():
+            groups[-1].append(i)
+        else:
+            groups.append([i])
+    fs_ws = isopo.alloc_workspace(max(isopo.load().isopo_fisher_samples_group_workspace(layers[g[0]].ref(), len(g),
+                                                                                        args.n_samples)
+                                      for g in groups), dev)
+    f2b = [torch.empty((npj, n_seq), dtype=torch.float32, device=dev) for _ in blocks]
     scr = torch.empty(n_tokens * max(min(l.d_in, l.d_out) for l in layers), dtype=block[0].X.dtype, device=dev)
 
     def token_sample_step():
         for _ in range(sweeps):
-            for l, c, f2, dW in zip(layers, cs, f2s, dWs):
-                isopo.fisher_samples(l, sample_idx, A, args.lam, isopo.REG_REL_TRACE, c, f2, fs_ws, stream=stream)
-                isopo.weighted_grad_prescaled(l, c, scr, 0.0, dW, stream=stream)
+            for g in groups:
+                b, j0 = g[0] // npj, g[0] % npj
+                isopo.fisher_samples_group([layers[i] for i in g], sample_idx, A, args.lam, isopo.REG_REL_TRACE,
+                                           cb[b][j0:j0 + len(g)], f2b[b][j0:j0 + len(g)], fs_ws, stream=stream)
+                for i in g:
+                    isopo.weighted_grad_prescaled(layers[i], cs[i], scr, 0.0, dWs[i], stream=stream)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -187,7 +200,7 @@ def main() -> int:
             f"{other}_from_stash_gram": {"ms_per_step": t_other * 1e3, "overhead_over_reinforce": t_other / t_reinforce - 1.0},
             "fisher_from_token_samples": {"ms_per_step": t_ts * 1e3, "overhead_over_reinforce": t_ts / t_reinforce - 1.0,
                                           "n_samples": args.n_samples,
-                                          "what": "isopo_fisher_samples -> isopo_weighted_grad_prescaled (rows of the narrower operand scaled, then one unweighted contraction) per projection"},
+                                          "what": "isopo_fisher_samples_group per set of projections sharing an input, then isopo_weighted_grad_prescaled (rows of the narrower operand scaled, one unweighted contraction) per projection"},
         }
         if n_layers > 1:
             # The sweep with K and the stash formed once per layer: six transforms (both variants x three

@@ -182,6 +182,19 @@ isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sampl
                                   float ema_decay, float* c, float* fisher_sq, void* workspace, size_t ws_bytes,
                                   void* stream);
 
+/* The same for up to ISOPO_MAX_GROUP layers that share their input (q/k/v, gate/up of a transformer
+ * block): every layers[l] must have the same X pointer, dtype, n_tokens, d_in, n_seq and offsets; only
+ * Delta and d_out differ.  X is streamed once for the group (its token-by-sample product is common),
+ * each Delta once.  One set of samples and one advantage vector serve the group.
+ *   c, fisher_sq   device [n_layers, n_seq]
+ *   ema_state      device float[n_layers][2] (EMA_TRACE), one trailing mean per layer */
+#define ISOPO_MAX_GROUP 4
+size_t isopo_fisher_samples_group_workspace(const isopo_layer* layer, int32_t n_layers, int32_t n_samples);
+isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_t n_layers,
+                                        const int32_t* sample_idx_dev, int32_t n_samples, const float* A, float lambda,
+                                        isopo_reg_mode reg_mode, float* ema_state, float ema_decay, float* c,
+                                        float* fisher_sq, void* workspace, size_t ws_bytes, void* stream);
+
 /* Norms the re-scalings are built from, read off the Gram matrix: fisher_sq[i] = (1/m) sum_j K_ij^2
  * (eq. F-norm-basic with the batch's reduced gradients as samples) and grad_sq[i] = K_ii = ||G_i||^2.
  * Device pointers, either output may be NULL. */

@@ -274,17 +274,37 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
   return launch_transform(t, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
-size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_samples) {
-  if (!layer || n_samples < 1 || n_samples > ISOPO_MAX_SAMPLES || layer->n_seq <= 0 || layer->n_tokens < 0) return 0;
-  return fisher_samples_workspace((int)layer->n_tokens, layer->n_seq, n_samples);
+static_assert(kFisherMaxGroup == ISOPO_MAX_GROUP, "group size of the kernel and of the header");
+
+size_t isopo_fisher_samples_group_workspace(const isopo_layer* layer, int32_t n_layers, int32_t n_samples) {
+  if (!layer || n_samples < 1 || n_samples > ISOPO_MAX_SAMPLES || layer->n_seq <= 0 || layer->n_tokens < 0 ||
+      n_layers < 1 || n_layers > ISOPO_MAX_GROUP)
+    return 0;
+  return fisher_samples_workspace((int)layer->n_tokens, layer->n_seq, n_samples, n_layers);
 }
 
-isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,
-                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* ema_state,
-                                  float ema_decay, float* c, float* fisher_sq, void* workspace, size_t ws_bytes,
-                                  void* stream) {
-  isopo_status st = check_layer(layer, true);
-  if (st != ISOPO_OK) return st;
+size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_samples) {
+  return isopo_fisher_samples_group_workspace(layer, 1, n_samples);
+}
+
+isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_t n_layers,
+                                        const int32_t* sample_idx_dev, int32_t n_samples, const float* A, float lambda,
+                                        isopo_reg_mode reg_mode, float* ema_state, float ema_decay, float* c,
+                                        float* fisher_sq, void* workspace, size_t ws_bytes, void* stream) {
+  if (!layers || n_layers < 1) return ISOPO_ERR_INVALID_ARG;
+  if (n_layers > ISOPO_MAX_GROUP) return ISOPO_ERR_UNSUPPORTED;
+  for (int l = 0; l < n_layers; ++l) {
+    isopo_status st = check_layer(layers[l], true);
+    if (st != ISOPO_OK) return st;
+  }
+  const isopo_layer* first = layers[0];
+  for (int l = 1; l < n_layers; ++l) {          // one input, one ragged layout for the whole group
+    const isopo_layer* o = layers[l];
+    if (o->X != first->X || o->dtype != first->dtype || o->n_tokens != first->n_tokens || o->d_in != first->d_in ||
+        o->n_seq != first->n_seq || o->seq_offsets_dev != first->seq_offsets_dev ||
+        std::memcmp(o->seq_offsets_host, first->seq_offsets_host, sizeof(int32_t) * (size_t)(first->n_seq + 1)) != 0)
+      return ISOPO_ERR_INVALID_ARG;
+  }
   if (!sample_idx_dev || !A || !c || !workspace || !(lambda >= 0.f)) return ISOPO_ERR_INVALID_ARG;
   if (n_samples < 1) return ISOPO_ERR_INVALID_ARG;
   if (n_samples > ISOPO_MAX_SAMPLES) return ISOPO_ERR_UNSUPPORTED;
@@ -292,16 +312,29 @@ isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sampl
     return ISOPO_ERR_INVALID_ARG;
   if (reg_mode == ISOPO_REG_EMA_TRACE && (!ema_state || !(ema_decay >= 0.f && ema_decay < 1.f)))
     return ISOPO_ERR_INVALID_ARG;
-  if (layer->n_tokens == 0) return ISOPO_ERR_INVALID_ARG;     // nothing to sample from
+  if (first->n_tokens == 0) return ISOPO_ERR_INVALID_ARG;     // nothing to sample from
   if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return ISOPO_ERR_INVALID_ARG;
-  if (ws_bytes < isopo_fisher_samples_workspace(layer, n_samples)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < isopo_fisher_samples_group_workspace(first, n_layers, n_samples)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
   FisherSamplesArgs f;
-  f.X = layer->X; f.Delta = layer->Delta; f.off = layer->seq_offsets_dev; f.sample_idx = sample_idx_dev;
-  f.n_tokens = (int)layer->n_tokens; f.d_in = layer->d_in; f.d_out = layer->d_out; f.n_seq = layer->n_seq;
-  f.n_samples = n_samples; f.bf16 = layer->dtype == ISOPO_BF16; f.A = A; f.lambda = lambda;
+  f.X = first->X; f.off = first->seq_offsets_dev; f.sample_idx = sample_idx_dev; f.n_layers = n_layers;
+  for (int l = 0; l < kFisherMaxGroup; ++l) {
+    f.Delta[l] = l < n_layers ? layers[l]->Delta : nullptr;
+    f.d_out[l] = l < n_layers ? layers[l]->d_out : 0;
+  }
+  f.n_tokens = (int)first->n_tokens; f.d_in = first->d_in; f.n_seq = first->n_seq;
+  f.n_samples = n_samples; f.bf16 = first->dtype == ISOPO_BF16; f.A = A; f.lambda = lambda;
   f.reg_mode = (int)reg_mode; f.ema_state = ema_state; f.ema_decay = ema_decay; f.c = c; f.fisher_sq = fisher_sq;
   f.workspace = workspace;
   return launch_fisher_samples(f, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,
+                                  const float* A, float lambda, isopo_reg_mode reg_mode, float* ema_state,
+                                  float ema_decay, float* c, float* fisher_sq, void* workspace, size_t ws_bytes,
+                                  void* stream) {
+  if (!layer) return ISOPO_ERR_INVALID_ARG;
+  return isopo_fisher_samples_group(&layer, 1, sample_idx_dev, n_samples, A, lambda, reg_mode, ema_state, ema_decay, c,
+                                    fisher_sq, workspace, ws_bytes, stream);
 }
 
 isopo_status isopo_gram_norms(const float* K, int32_t n_seq, float* fisher_sq, float* grad_sq, void* stream) {

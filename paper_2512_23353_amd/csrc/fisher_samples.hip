@@ -38,13 +38,15 @@ __device__ __forceinline__ void load_lds16(const void* gptr, unsigned lds_addr) 
 
 struct Params {
   const void* X;
-  const void* Delta;
+  const void* Delta[kFisherMaxGroup];
+  int d_out[kFisherMaxGroup];
+  int n_layers;
   const int32_t* off;
   const int32_t* idx;
-  int n_tokens, d_in, d_out, n_seq, n_samples;
+  int n_tokens, d_in, n_seq, n_samples;
   int32_t* tok_seq;      // [n_tokens]
-  double* S64;           // [n_seq][32*NBS] segment sums s_ij
-  double* den;           // [n_samples] ||g0_j||^2 ||a0_j||^2
+  double* S64;           // [n_layers][n_seq][32*NBS] segment sums s_ij
+  double* den;           // [n_layers][n_samples] ||g0_j||^2 ||a0_j||^2
 };
 
 // The sequence of every token (binary search in the offsets) and zeros in the segment-sum accumulator.
@@ -156,54 +158,65 @@ __global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int t0 = blockIdx.x * kTok;
 
-  f32x16 P[NBS], Q[NBS];
+  // Q = X A0^T once for the group, then per layer P = Delta G0^T, H = P o Q and the segment sums
+  f32x16 Q[NBS];
 #pragma unroll
   for (int b = 0; b < NBS; ++b)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { P[b][v] = 0.f; Q[b][v] = 0.f; }
-  product_pass<NBS, BF16>(p.Delta, p.d_out, p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, P);
+    for (int v = 0; v < 16; ++v) Q[b][v] = 0.f;
   product_pass<NBS, BF16>(p.X, p.d_in, p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, Q);
 
   // lane holds sample column (lane & 31) of each block and token rows acc_row(v, lane) of the wave's 32 tokens
   const int tw = t0 + wave * 32;
-  if (tw >= p.n_tokens) return;
+  const bool live = tw < p.n_tokens;                  // wave-uniform; idle waves still join every pass's barriers
   const int t_last = min(tw + 31, p.n_tokens - 1);
-  const int r_first = p.tok_seq[tw], r_last = p.tok_seq[t_last];
+  const int r_first = live ? p.tok_seq[tw] : 0, r_last = live ? p.tok_seq[t_last] : 0;
   const int ncol = 32 * NBS;
+  for (int l = 0; l < p.n_layers; ++l) {
+    f32x16 P[NBS];
 #pragma unroll
-  for (int b = 0; b < NBS; ++b) {
-    const int j = b * 32 + (lane & 31);
-    // ||g^(j)||^2 = ||g0_j||^2 ||a0_j||^2 (eq. (two)) is the product's own entry at the sampled row:
-    // P[idx_j][j] = g0_j . g0_j and Q[idx_j][j] = a0_j . a0_j; exactly one lane of the grid holds it
-    if (j < p.n_samples) {
-      const int tj = min(max(p.idx[j], 0), p.n_tokens - 1);
+    for (int b = 0; b < NBS; ++b)
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if (tw + acc_row(v, lane) == tj) p.den[j] = (double)P[b][v] * (double)Q[b][v];
-    }
-    if (r_first == r_last) {
-      double s = 0.0;
+      for (int v = 0; v < 16; ++v) P[b][v] = 0.f;
+    product_pass<NBS, BF16>(p.Delta[l], p.d_out[l], p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, P);
+    if (!live) continue;
+    double* S64 = p.S64 + (size_t)l * p.n_seq * ncol;
+    double* den = p.den + (size_t)l * p.n_samples;
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if (tw + acc_row(v, lane) < p.n_tokens) s += (double)P[b][v] * (double)Q[b][v];
-      s += __shfl_xor(s, 32, kWave);
-      if (lane < 32 && j < p.n_samples) atomicAdd(&p.S64[(size_t)r_first * ncol + j], s);
-    } else {
-      double run = 0.0;
-      int run_r = -1;
+    for (int b = 0; b < NBS; ++b) {
+      const int j = b * 32 + (lane & 31);
+      // ||g^(j)||^2 = ||g0_j||^2 ||a0_j||^2 (eq. (two)) is the product's own entry at the sampled row:
+      // P[idx_j][j] = g0_j . g0_j and Q[idx_j][j] = a0_j . a0_j; exactly one lane of the grid holds it
+      if (j < p.n_samples) {
+        const int tj = min(max(p.idx[j], 0), p.n_tokens - 1);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int t = tw + acc_row(v, lane);
-        if (t >= p.n_tokens) continue;
-        const int r = p.tok_seq[t];
-        if (r != run_r) {
-          if (run_r >= 0 && j < p.n_samples) atomicAdd(&p.S64[(size_t)run_r * ncol + j], run);
-          run_r = r;
-          run = 0.0;
-        }
-        run += (double)P[b][v] * (double)Q[b][v];
+        for (int v = 0; v < 16; ++v)
+          if (tw + acc_row(v, lane) == tj) den[j] = (double)P[b][v] * (double)Q[b][v];
       }
-      if (run_r >= 0 && j < p.n_samples) atomicAdd(&p.S64[(size_t)run_r * ncol + j], run);
+      if (r_first == r_last) {
+        double s = 0.0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (tw + acc_row(v, lane) < p.n_tokens) s += (double)P[b][v] * (double)Q[b][v];
+        s += __shfl_xor(s, 32, kWave);
+        if (lane < 32 && j < p.n_samples) atomicAdd(&S64[(size_t)r_first * ncol + j], s);
+      } else {
+        double run = 0.0;
+        int run_r = -1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int t = tw + acc_row(v, lane);
+          if (t >= p.n_tokens) continue;
+          const int r = p.tok_seq[t];
+          if (r != run_r) {
+            if (run_r >= 0 && j < p.n_samples) atomicAdd(&S64[(size_t)run_r * ncol + j], run);
+            run_r = r;
+            run = 0.0;
+          }
+          run += (double)P[b][v] * (double)Q[b][v];
+        }
+        if (run_r >= 0 && j < p.n_samples) atomicAdd(&S64[(size_t)run_r * ncol + j], run);
+      }
     }
   }
 }
@@ -225,6 +238,13 @@ __global__ __launch_bounds__(256) void fisher_samples_finish_kernel(const double
                                                                     float* __restrict__ f2_out, double* __restrict__ f2_tmp) {
   __shared__ double red[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int layer = blockIdx.x;                    // one workgroup per layer of the group
+  S64 += (size_t)layer * n_seq * ncol;
+  den += (size_t)layer * n_samples;
+  f2_tmp += (size_t)layer * n_seq;
+  c += (size_t)layer * n_seq;
+  if (f2_out) f2_out += (size_t)layer * n_seq;
+  if (ema_state) ema_state += 2 * layer;
   const double d = block_sum256(tid < n_samples ? den[tid] : 0.0, red);      // n_samples <= 128
   // one wave per sequence: lanes stride over the samples
   double part = 0.0;
@@ -277,29 +297,33 @@ size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
 
-size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples) {
+size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples, int n_layers) {
   const int ncol = 32 * ((n_samples + 31) / 32);
-  return align256((size_t)n_tokens * 4) + align256((size_t)n_seq * ncol * 8) + align256((size_t)n_samples * 8) +
-         align256((size_t)n_seq * 8);
+  return align256((size_t)n_tokens * 4) + align256((size_t)n_layers * n_seq * ncol * 8) +
+         align256((size_t)n_layers * n_samples * 8) + align256((size_t)n_layers * n_seq * 8);
 }
 
 hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
   const int nbs = (a.n_samples + 31) / 32;
-  if (nbs < 1 || nbs > kMaxSampleBlocks) return hipErrorInvalidValue;
+  if (nbs < 1 || nbs > kMaxSampleBlocks || a.n_layers < 1 || a.n_layers > kFisherMaxGroup) return hipErrorInvalidValue;
   const int ncol = 32 * nbs;
   char* ws = static_cast<char*>(a.workspace);
   Params p;
-  p.X = a.X; p.Delta = a.Delta; p.off = a.off; p.idx = a.sample_idx;
-  p.n_tokens = a.n_tokens; p.d_in = a.d_in; p.d_out = a.d_out; p.n_seq = a.n_seq; p.n_samples = a.n_samples;
+  p.X = a.X; p.off = a.off; p.idx = a.sample_idx; p.n_layers = a.n_layers;
+  for (int l = 0; l < kFisherMaxGroup; ++l) {
+    p.Delta[l] = l < a.n_layers ? a.Delta[l] : nullptr;
+    p.d_out[l] = l < a.n_layers ? a.d_out[l] : 0;
+  }
+  p.n_tokens = a.n_tokens; p.d_in = a.d_in; p.n_seq = a.n_seq; p.n_samples = a.n_samples;
   p.tok_seq = reinterpret_cast<int32_t*>(ws);
   ws += align256((size_t)a.n_tokens * 4);
   p.S64 = reinterpret_cast<double*>(ws);
-  ws += align256((size_t)a.n_seq * ncol * 8);
+  ws += align256((size_t)a.n_layers * a.n_seq * ncol * 8);
   p.den = reinterpret_cast<double*>(ws);
-  ws += align256((size_t)a.n_samples * 8);
+  ws += align256((size_t)a.n_layers * a.n_samples * 8);
   double* f2_tmp = reinterpret_cast<double*>(ws);
 
-  const long long ns = (long long)a.n_seq * ncol;
+  const long long ns = (long long)a.n_layers * a.n_seq * ncol;
   if (a.n_tokens > 0) {
     const long long items = ns > a.n_tokens ? ns : (long long)a.n_tokens;
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, p, ns);
@@ -317,10 +341,11 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
   } else {
     hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, s, p.S64, ns);
-    hipLaunchKernelGGL(zero_f64_kernel, dim3((a.n_samples + 255) / 256), dim3(256), 0, s, p.den, (long long)a.n_samples);
+    const long long nd = (long long)a.n_layers * a.n_samples;
+    hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, p.den, nd);
   }
-  hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(1), dim3(256), 0, s, p.S64, p.den, a.n_seq, a.n_samples, ncol,
-                     a.A, a.lambda, a.reg_mode, a.ema_state, a.ema_decay, a.c, a.fisher_sq, f2_tmp);
+  hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(a.n_layers), dim3(256), 0, s, p.S64, p.den, a.n_seq,
+                     a.n_samples, ncol, a.A, a.lambda, a.reg_mode, a.ema_state, a.ema_decay, a.c, a.fisher_sq, f2_tmp);
   return hipGetLastError();
 }
 

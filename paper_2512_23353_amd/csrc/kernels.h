@@ -76,24 +76,28 @@ hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s);
 hipError_t launch_scale_rows(const void* src, bool bf16, long long n_tokens, int d, const int32_t* off, int n_seq,
                              const float* c, void* dst, hipStream_t s);
 
-// Token-position-sample Fisher norms and the coefficients c_i = A_i / sqrt(F_i^2 + reg).
+// Token-position-sample Fisher norms and the coefficients c_i = A_i / sqrt(F_i^2 + reg), for a group of
+// layers that share their input X (q/k/v, gate/up): X is streamed once for the whole group.
+constexpr int kFisherMaxGroup = 4;
 struct FisherSamplesArgs {
   const void* X;
-  const void* Delta;
+  const void* Delta[kFisherMaxGroup];
+  int d_out[kFisherMaxGroup];
+  int n_layers;
   const int32_t* off;
   const int32_t* sample_idx;   // device [n_samples], token rows
-  int n_tokens, d_in, d_out, n_seq, n_samples;
+  int n_tokens, d_in, n_seq, n_samples;
   bool bf16;
   const float* A;
   float lambda;
   int reg_mode;                // 0 absolute, 1 times this batch's mean F^2, 2 times its trailing mean
-  float* ema_state;            // [2]: trailing mean, number of minibatches seen (reg_mode 2)
+  float* ema_state;            // [n_layers][2]: trailing mean, number of minibatches seen (reg_mode 2)
   float ema_decay;
-  float* c;
-  float* fisher_sq;            // optional [n_seq]
+  float* c;                    // [n_layers][n_seq]
+  float* fisher_sq;            // optional [n_layers][n_seq]
   void* workspace;
 };
-size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples);
+size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples, int n_layers);
 hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s);
 
 struct TransformArgs {

@@ -31,6 +31,7 @@ EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
+           "isopo_fisher_samples_group_workspace", "isopo_fisher_samples_group",
            "isopo_weighted_grad_scratch", "isopo_weighted_grad_prescaled",
            "isopo_gram_norms", "isopo_rescale", "isopo_ntk_eigh_workspace", "isopo_ntk_eigh",
            "isopo_transform_eigh", "isopo_status_string", "isopo_version")
@@ -93,6 +94,11 @@ def load() -> ctypes.CDLL:
     lib.isopo_fisher_samples_workspace.restype = sz
     lib.isopo_fisher_samples.argtypes = [lp, vp, i32, vp, f32, ctypes.c_int, vp, f32, vp, vp, vp, sz, vp]
     lib.isopo_fisher_samples.restype = ctypes.c_int
+    lib.isopo_fisher_samples_group_workspace.argtypes = [lp, i32, i32]
+    lib.isopo_fisher_samples_group_workspace.restype = sz
+    lib.isopo_fisher_samples_group.argtypes = [ctypes.POINTER(lp), i32, vp, i32, vp, f32, ctypes.c_int, vp, f32, vp, vp,
+                                               vp, sz, vp]
+    lib.isopo_fisher_samples_group.restype = ctypes.c_int
     lib.isopo_weighted_grad_scratch.argtypes = [lp]
     lib.isopo_weighted_grad_scratch.restype = sz
     lib.isopo_weighted_grad_prescaled.argtypes = [lp, vp, f32, vp, vp, sz, vp]
@@ -353,6 +359,31 @@ def transform_eigh(D: torch.Tensor, U: torch.Tensor, A: torch.Tensor, lambdas, r
                                        _ptr(ema_state), float(ema_decay), c.data_ptr(), info.data_ptr(),
                                        _stream(stream)), "isopo_transform_eigh")
     return c, info
+
+
+def fisher_samples_group(layers, sample_idx: torch.Tensor, A: torch.Tensor, lam: float = 0.0,
+                         reg_mode: int = REG_ABSOLUTE, c: Optional[torch.Tensor] = None,
+                         fisher_sq: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
+                         ema_state: Optional[torch.Tensor] = None, ema_decay: float = 0.9):
+    """fisher_samples for layers that share X (same tensor, same offsets): X is read once.
+    Returns (c [n_layers, n_seq], F^2 [n_layers, n_seq])."""
+    n = len(layers)
+    first = layers[0]
+    n_s = int(sample_idx.numel())
+    if sample_idx.dtype != torch.int32 or not sample_idx.is_contiguous():
+        raise ValueError("sample_idx must be a contiguous int32 tensor")
+    if c is None:
+        c = torch.empty((n, first.n_seq), dtype=torch.float32, device=first.device)
+    if fisher_sq is None:
+        fisher_sq = torch.empty((n, first.n_seq), dtype=torch.float32, device=first.device)
+    if workspace is None:
+        workspace = alloc_workspace(load().isopo_fisher_samples_group_workspace(first.ref(), n, n_s), first.device)
+    arr = (ctypes.POINTER(_Layer) * n)(*[ctypes.pointer(l.c) for l in layers])
+    _check(load().isopo_fisher_samples_group(arr, n, sample_idx.data_ptr(), n_s, A.data_ptr(), float(lam), int(reg_mode),
+                                             _ptr(ema_state), float(ema_decay), c.data_ptr(), fisher_sq.data_ptr(),
+                                             workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "isopo_fisher_samples_group")
+    return c, fisher_sq
 
 
 def scale_rows(src: torch.Tensor, layer: Layer, c: torch.Tensor, dst: Optional[torch.Tensor] = None,

@@ -121,6 +121,40 @@ def test_config3_full_size_sampled_sequences(gpu_device):
         assert abs(f2h[i] - ref[i]) <= TOL["bf16"] * ref[i]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_group_sharing_the_input(gpu_device, dtype):
+    """q/k/v-like layers on one input: the group call (X streamed once) against
+    the oracle layer by layer and against the single-layer calls."""
+    rng = np.random.default_rng(91)
+    lengths = [130, 70, 1, 0, 200, 45]
+    base = wl.custom_layer(256, 320, lengths, dtype=dtype, seed=60, sigma_delta=1e-2)
+    d_outs = [320, 64, 136, 512]
+    X = base.X.to(gpu_device)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = torch.Generator().manual_seed(61)
+    Deltas = [(torch.randn(base.n_tokens, d, generator=g) * 1e-2).to(tdt).to(gpu_device) for d in d_outs]
+    first = isopo.Layer(X, Deltas[0], base.seq_offsets)
+    layers = [first] + [isopo.Layer(X, D, base.seq_offsets, seq_offsets_dev=first.off_dev) for D in Deltas[1:]]
+    A = torch.from_numpy(base.A).to(gpu_device)
+    idx = _draw_samples(rng, base.n_tokens, 40)
+    idx_d = torch.from_numpy(idx).to(gpu_device)
+    for n in (1, 2, 4):
+        c, f2 = isopo.fisher_samples_group(layers[:n], idx_d, A, 1e-3, isopo.REG_REL_TRACE)
+        torch.cuda.synchronize()
+        for l in range(n):
+            c_ref, f2_ref = orc.coeff_fisher_token_samples(wl.to_oracle(X), wl.to_oracle(Deltas[l]), base.seq_offsets,
+                                                           idx, base.A, 1e-3, isopo.REG_REL_TRACE)
+            assert rel_err(f2[l].cpu().numpy(), f2_ref) <= TOL[dtype], f"group of {n}, layer {l}"
+            assert_c_close(c[l].cpu().numpy(), c_ref, TOL[dtype], f"group of {n}, layer {l}")
+            c1, f1 = isopo.fisher_samples(layers[l], idx_d, A, 1e-3, isopo.REG_REL_TRACE)
+            assert torch.allclose(f1, f2[l], rtol=1e-5, atol=0)
+    other = isopo.Layer(X.clone(), Deltas[1], base.seq_offsets, seq_offsets_dev=first.off_dev)
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples_group([first, other], idx_d, A)           # not the same input
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples_group(layers + [layers[0]], idx_d, A)      # more than ISOPO_MAX_GROUP
+
+
 def test_trailing_mean_regulariser(gpu_device):
     """reg = factor * E[mean F^2] with the trailing mean kept on the device over
     three minibatches of different scale."""
