@@ -217,19 +217,34 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     for (int j = 0; j < FN; ++j) fb0[j] = frB(smem_base + adB[j]);
     for (int it = 0; it < n_tiles; ++it) {
       const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+      if constexpr (PER_SEQ) {
+        // written out MFMA by MFMA: each of the first FM + FN MFMAs is followed by one fragment's reads
 #pragma unroll
-      for (int i = 0; i < FM; ++i) fa1[i] = frA(sb + adA[i] + 16 * PA);
+        for (int i = 0; i < FM; ++i) {
 #pragma unroll
-      for (int j = 0; j < FN; ++j) fb1[j] = frB(sb + adB[j] + 16 * PB);
+          for (int j = 0; j < FN; ++j) {
+            const int idx = i * FN + j;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+            if (idx < FM) fa1[idx] = frA(sb + adA[idx] + 16 * PA);
+            else if (idx < FM + FN) fb1[idx - FM] = frB(sb + adB[idx - FM] + 16 * PB);
+          }
+        }
+      } else {
+        // sum-over-all-tokens mode: the scheduler places the reads, one per MFMA
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+        for (int i = 0; i < FM; ++i) fa1[i] = frA(sb + adA[i] + 16 * PA);
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < FN; ++j) fb1[j] = frB(sb + adB[j] + 16 * PB);
 #pragma unroll
-      for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+        }
       }
       __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 3) * LPT) & 15) | ((((NSTAGE - 3) * LPT) >> 4) << 14));
       __builtin_amdgcn_s_barrier();
