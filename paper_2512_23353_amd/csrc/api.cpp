@@ -201,7 +201,7 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
   for (int r0 = 0; r0 < layer->d_out; r0 += (int)chunk_rows) {
     const int rows = (layer->d_out - r0) < (int)chunk_rows ? (layer->d_out - r0) : (int)chunk_rows;
     SeqGradArgs a;
-    a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.c = nullptr;
+    a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.off_host = layer->seq_offsets_host; a.c = nullptr;
     a.out = ws; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
     a.row0 = r0; a.rows = rows; a.out_row0 = whole ? 0 : r0; a.out_seq_stride = seq_stride;
     a.beta = 0.f; a.per_sequence = true; a.bf16 = bf16;
@@ -221,7 +221,7 @@ isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream
   if (st != ISOPO_OK) return st;
   if (!stash || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
   SeqGradArgs a;
-  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.c = nullptr;
+  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.off_host = layer->seq_offsets_host; a.c = nullptr;
   a.out = stash; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
   a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0;
   a.out_seq_stride = (long long)layer->d_out * layer->d_in;
@@ -423,7 +423,7 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
                                                                                                       : ISOPO_ERR_HIP;
   }
   SeqGradArgs a;
-  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.c = c; a.out = dW;
+  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.off_host = layer->seq_offsets_host; a.c = c; a.out = dW;
   a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
   a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0; a.out_seq_stride = 0;
   a.beta = beta; a.per_sequence = false; a.bf16 = bf16;

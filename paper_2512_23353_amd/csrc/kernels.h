@@ -15,6 +15,7 @@ struct SeqGradArgs {
   const void* X;
   const void* Delta;
   const int32_t* off;        // device [n_seq+1]
+  const int32_t* off_host = nullptr;   // the same values on the host, if the caller has them (work balancing)
   const float* c;            // device [n_seq]; nullptr = unweighted (all ones)
   void* out;                 // stash (input dtype) or dW (fp32)
   int d_in, d_out, n_seq, n_tokens;

@@ -21,12 +21,18 @@
 //    of the second half block, so the matrix pipe never waits on their issue.
 //  * Per-sequence mode: XCD x owns the x-th eighth of the output tiles of every
 //    sequence, so all eight L2s see every sequence (balanced under ragged
-//    lengths) and neighbouring workgroups share operand panels.  The bf16 tile is
-//    transposed through LDS in the epilogue so that every lane stores 16 bytes.
+//    lengths) and neighbouring workgroups share operand panels.  When the tile
+//    count is no multiple of eight that would leave XCDs unevenly loaded (or
+//    idle); the host then cuts the sequence-major list of (sequence, tile) pairs
+//    into eight contiguous ranges of equal work (tokens plus a fixed charge per
+//    workgroup) and each XCD walks one.  The bf16 tile is transposed through LDS
+//    in the epilogue so that every lane stores 16 bytes.
 //  * Sum-over-all-tokens mode with few output tiles (narrow projections, long
 //    microbatches): the token range is split into chunks, a workgroup takes one
-//    (tile, chunk) with the same XCD mapping, and the fp32 partial tiles are added
-//    to dW with hardware float atomics after a pass that applies beta.
+//    (chunk, tile) pair from its XCD's range of the same kind of list, and the
+//    fp32 partial tiles are added to dW with hardware float atomics after a pass
+//    that applies beta.  This mode keeps one more token block in flight: a block's
+//    stage is free once the barrier after its last fragment read is passed.
 #include "common.h"
 #include "kernels.h"
 
@@ -51,6 +57,7 @@ struct StreamParams {
   int tiles_m, tiles_n;
   unsigned n_blocks;
   int n_chunks, chunk_tokens;      // sum-over-all-tokens mode: token chunks (1: no split)
+  int xcd_start[9];                // XCD x takes (item, tile) pairs [xcd_start[x], xcd_start[x+1]), item-major
 };
 
 // Raw buffer descriptor over [base, base + bytes): loads beyond it return zero.
@@ -106,13 +113,22 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
   int item, tile;
   const bool split = !PER_SEQ && p.n_chunks > 1;
   if (PER_SEQ || split) {
-    // XCD x (= blockIdx % 8) owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence (or token chunk)
     const int tiles = p.tiles_m * p.tiles_n;
     const int x = blockIdx.x & 7, e = blockIdx.x >> 3;
-    const int s0 = x * tiles / 8, cs = (x + 1) * tiles / 8 - s0;
-    if (cs == 0 || e >= (PER_SEQ ? p.n_seq : p.n_chunks) * cs) return;
-    item = e / cs;
-    tile = s0 + e % cs;
+    if (p.xcd_start[8] > 0) {
+      // XCD x (= blockIdx % 8) walks a contiguous range of the item-major (item, tile) list; the host cut
+      // the list into eight ranges of equal work
+      const int id = p.xcd_start[x] + e;
+      if (id >= p.xcd_start[x + 1]) return;
+      item = id / tiles;
+      tile = id - item * tiles;
+    } else {
+      // XCD x owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence (or token chunk)
+      const int s0 = x * tiles / 8, cs = (x + 1) * tiles / 8 - s0;
+      if (cs == 0 || e >= (PER_SEQ ? p.n_seq : p.n_chunks) * cs) return;
+      item = e / cs;
+      tile = s0 + e % cs;
+    }
   } else {
     item = 0;
     tile = xcd_contiguous(blockIdx.x, p.n_blocks);
@@ -203,13 +219,18 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
   constexpr int LPT = LA + LB;   // loads per wave and tile
+  // Token blocks in flight ahead of the one being multiplied.  The stage a block leaves is free as soon
+  // as the barrier after its second half's fragment reads has been passed, so the ring can carry NSTAGE
+  // blocks ahead; the per-sequence mode, whose stash stores compete with the operand fetches, runs
+  // better one block shallower.
+  constexpr int AHEAD = PER_SEQ ? NSTAGE - 1 : NSTAGE;
   constexpr int NRD = 2 * (FM + FN), NMF = FM * FN;
 
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) issue_loads(s);
+  for (int s = 0; s < AHEAD; ++s) issue_loads(s);
 
   if (n_tiles > 0) {
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 2) * LPT) & 15) | ((((NSTAGE - 2) * LPT) >> 4) << 14));
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 1) * LPT) & 15) | ((((AHEAD - 1) * LPT) >> 4) << 14));
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < FM; ++i) fa0[i] = frA(smem_base + adA[i]);
@@ -246,13 +267,15 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
         }
       }
-      __builtin_amdgcn_s_waitcnt(0x0f70 | (((NSTAGE - 3) * LPT) & 15) | ((((NSTAGE - 3) * LPT) >> 4) << 14));
+      // block it+1 has landed (this wave's part; the barrier makes it everyone's) and this wave's fragment
+      // reads of block it are complete: its stage may be overwritten after the barrier
+      __builtin_amdgcn_s_waitcnt((AHEAD == NSTAGE ? 0x0070 : 0x0f70) | (((AHEAD - 2) * LPT) & 15) | ((((AHEAD - 2) * LPT) >> 4) << 14));
       __builtin_amdgcn_s_barrier();
       const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
       // second half block: its 16 MFMAs carry the fragment reads of the next block's first half and the
-      // DMA instructions of the block NSTAGE-1 ahead
+      // DMA instructions of the block AHEAD ahead
       {
-        const int nb = it + NSTAGE - 1;
+        const int nb = it + AHEAD;
         int rows = n_rows - nb * BK;
         rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
         const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
@@ -369,19 +392,23 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
   p.n_chunks = 1;
   p.chunk_tokens = a.n_tokens;
   if (!PER_SEQ) {
-    // Fewest chunks (of at least 4096 tokens) that fill the resident workgroup slots evenly: the
-    // smallest count whose last round of workgroups is at least 85 % full, else the fullest.
-    const long long slots = 256LL * OCC;
-    const long long most = a.n_tokens / 4096 > 1 ? a.n_tokens / 4096 : 1;
+    // Number of token chunks: the count with the smallest modelled time
+    //   rounds(w) * ceil(N / w) * t_token  +  (w > 1) * w * outputs * t_atomic,
+    // rounds(w) = passes an XCD's 32 CUs make over its eighth of the tiles * w workgroups.  t_token is a
+    // workgroup's time per token row, t_atomic the chip's time per fp32 atomic add (about 0.8 TB/s), both
+    // measured; without the second term more chunks always look better, and the adds then cost more than
+    // the idle CUs did.
+    const long long slots = 32LL * OCC;                              // per XCD
+    const double t_token = 2.0e-8 * (double)(BM * BN) / 65536.0 * OCC, t_atomic = 5.0e-12;
+    const double outputs = (double)a.rows * a.d_in;
+    const long long most = a.n_tokens / 512 > 1 ? a.n_tokens / 512 : 1;
     long long want = 1;
-    if (tiles < 4 * slots) {
-      double best = 0.0;
-      for (long long w = 1; w <= most && w <= 64; ++w) {
-        const long long wg = tiles * w, rounds = (wg + slots - 1) / slots;
-        const double fill = (double)wg / (double)(rounds * slots);
-        if (fill > best + 1e-9) { best = fill; want = w; }
-        if (fill >= 0.85) break;
-      }
+    double best = 0.0;
+    for (long long w = 1; w <= most && w <= 64; ++w) {
+      const long long rounds = ((tiles * w + 7) / 8 + slots - 1) / slots;
+      const double t = (double)rounds * (double)((a.n_tokens + w - 1) / w) * t_token + (w > 1 ? w * outputs * t_atomic : 0.0);
+      if (w == 1) best = 0.9 * t;                                    // a split has to win by a margin
+      else if (t < best) { best = t; want = w; }
     }
     if (want > 1) {
       p.chunk_tokens = (int)(((a.n_tokens + want - 1) / want + BK - 1) / BK * BK);
@@ -389,7 +416,35 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
     }
   }
   const bool mapped = PER_SEQ || p.n_chunks > 1;
-  const long long blocks = mapped ? 8LL * (PER_SEQ ? a.n_seq : p.n_chunks) * ((tiles + 7) / 8) : tiles;
+  long long blocks = mapped ? 8LL * (PER_SEQ ? a.n_seq : p.n_chunks) * ((tiles + 7) / 8) : tiles;
+  for (int x = 0; x <= 8; ++x) p.xcd_start[x] = 0;
+  const int n_items = PER_SEQ ? a.n_seq : p.n_chunks;
+  if (mapped && (!PER_SEQ || tiles % 8 != 0) && tiles * n_items <= 0x7fffffffLL) {
+    // Work of item i: its tokens plus a fixed charge for the workgroup's prologue and epilogue.
+    const long long fixed = PER_SEQ ? 192 : 64;
+    auto weight = [&](int i) -> long long {
+      if (PER_SEQ) return (a.off_host ? (long long)(a.off_host[i + 1] - a.off_host[i]) : 1024) + fixed;
+      const long long t0 = (long long)i * p.chunk_tokens;
+      const long long t1 = t0 + p.chunk_tokens < a.n_tokens ? t0 + p.chunk_tokens : a.n_tokens;
+      return (t1 - t0) + fixed;
+    };
+    long long total = 0;
+    for (int i = 0; i < n_items; ++i) total += weight(i) * tiles;
+    // pair (i, t) starts at work cum_i + t*w_i; XCD x's range opens at the first pair starting at or
+    // beyond x/8 of the total
+    long long cum = 0;
+    int i = 0, most = 0;
+    for (int x = 1; x < 8; ++x) {
+      const long long target = (x * total + 7) / 8;
+      while (i < n_items && cum + tiles * weight(i) <= target) cum += tiles * weight(i++);
+      if (i == n_items) { p.xcd_start[x] = (int)(tiles * n_items); continue; }
+      const long long w = weight(i);
+      p.xcd_start[x] = (int)(i * tiles + (target - cum + w - 1) / w);
+    }
+    p.xcd_start[8] = (int)(tiles * n_items);
+    for (int k = 0; k < 8; ++k) most = p.xcd_start[k + 1] - p.xcd_start[k] > most ? p.xcd_start[k + 1] - p.xcd_start[k] : most;
+    blocks = 8LL * most;
+  }
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   p.n_blocks = (unsigned)blocks;

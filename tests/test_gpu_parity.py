@@ -269,7 +269,7 @@ def test_unweighted_contraction_with_token_split(gpu_device, dims, beta):
     sizes, a ragged last chunk, beta = 0 over a NaN-filled dW (must not be read)
     and beta != 0."""
     d_in, d_out = dims
-    lengths = [3000, 1400, 1, 4200, 333, 4100]      # 13034 tokens: three chunks of at least 4096, the last ragged
+    lengths = [3000, 1400, 1, 4200, 333, 4100]      # 13034 tokens on 2 to 6 output tiles: a dozen or more chunks, the last ragged
     prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=31, sigma_delta=1e-2)
     layer, _ = to_device(prob, gpu_device)
     rng = np.random.default_rng(6)
