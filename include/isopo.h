@@ -101,6 +101,26 @@ isopo_status isopo_layer_gram_plan(const isopo_layer* layer, isopo_gram_path req
  * choice is the smaller.  Pure host function; exposed for tests. */
 isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, double* t_materialised);
 
+/* How the bf16 contraction behind isopo_seq_grads (per_sequence != 0; `grad_out.T @ act_in` per sequence,
+ * both hook listings) or the unweighted isopo_weighted_grad (per_sequence == 0) would be launched for
+ * this layer.  Pure host function; needs seq_offsets_host; exposed for tests of the launch logic.
+ *   tile               square output tile edge, 256 or 128
+ *   workgroups_per_cu  resident workgroups per compute unit for that tile (1 or 2)
+ *   tiles              output tiles of one item (item: a sequence, or a token chunk)
+ *   n_chunks, chunk_tokens   token split of the unweighted mode (1, n_tokens: none); partial tiles of a
+ *                      split are added to dW with fp32 atomics
+ *   xcd_start[9]       the item-major list of (item, tile) pairs is cut into 8 contiguous ranges of equal
+ *                      work, XCD x walks [xcd_start[x], xcd_start[x+1]).  All zero: no list - per-sequence
+ *                      mode with tiles % 8 == 0 gives XCD x the x-th eighth of every sequence's tiles,
+ *                      the unsplit unweighted mode has one item
+ *   workgroups         grid size (some workgroups may find their XCD's range exhausted and exit) */
+typedef struct {
+  int32_t tile, workgroups_per_cu, tiles, n_chunks, chunk_tokens;
+  int32_t xcd_start[9];
+  int64_t workgroups;
+} isopo_contraction_plan_info;
+isopo_status isopo_contraction_plan(const isopo_layer* layer, int per_sequence, isopo_contraction_plan_info* plan);
+
 /* K [n_seq, n_seq] fp32, both triangles written, bit-symmetric.
  *   workspace/ws_bytes  device scratch, >= ws_min of the plan.
  *   keep_stash          non-zero: leave the per-sequence gradients in the

@@ -130,6 +130,23 @@ isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, do
   return ISOPO_OK;
 }
 
+isopo_status isopo_contraction_plan(const isopo_layer* layer, int per_sequence, isopo_contraction_plan_info* plan) {
+  isopo_status st = check_layer(layer, false);
+  if (st != ISOPO_OK) return st;
+  if (!plan) return ISOPO_ERR_INVALID_ARG;
+  if (layer->dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  const ContractionPlan pl = plan_contraction(layer->d_out, layer->d_in, (int)layer->n_tokens, layer->n_seq,
+                                              layer->seq_offsets_host, per_sequence != 0);
+  plan->tile = pl.tile;
+  plan->workgroups_per_cu = pl.occupancy;
+  plan->tiles = pl.tiles_m * pl.tiles_n;
+  plan->n_chunks = pl.n_chunks;
+  plan->chunk_tokens = pl.chunk_tokens;
+  for (int x = 0; x <= 8; ++x) plan->xcd_start[x] = pl.xcd_start[x];
+  plan->workgroups = pl.blocks;
+  return ISOPO_OK;
+}
+
 isopo_status isopo_layer_gram_plan(const isopo_layer* layer, isopo_gram_path requested, isopo_gram_path* chosen,
                                    size_t* ws_full, size_t* ws_min) {
   isopo_status st = check_layer(layer, false);

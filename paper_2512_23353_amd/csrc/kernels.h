@@ -26,6 +26,19 @@ struct SeqGradArgs {
   bool per_sequence;
   bool bf16;
 };
+// Launch plan of the streaming bf16 contraction (host arithmetic only).
+struct ContractionPlan {
+  int tile;                    // 256 (one workgroup per CU) or 128 (two)
+  int occupancy;
+  int tiles_m, tiles_n;
+  int n_chunks, chunk_tokens;  // sum-over-all-tokens mode: token chunks (1: no split)
+  int xcd_start[9];            // XCD x walks (item, tile) pairs [xcd_start[x], xcd_start[x+1]) of the item-major
+                               // list (items: sequences or chunks); all zero: the x-th eighth of every item's
+                               // tiles (per-sequence mode), or no items at all (unsplit)
+  long long blocks;            // workgroups to launch
+};
+ContractionPlan plan_contraction(int rows, int d_in, int n_tokens, int n_seq, const int32_t* off_host,
+                                 bool per_sequence);
 hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s);
 // bf16 only, c == nullptr only: the direct-to-LDS streaming kernel (launch_seq_grad routes to it).
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s);

@@ -380,74 +380,20 @@ __global__ __launch_bounds__(256) void apply_beta_kernel(float* __restrict__ o, 
 }
 
 template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
-hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
+hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStream_t s) {
   StreamParams p;
   p.X = static_cast<const u16*>(a.X); p.Delta = static_cast<const u16*>(a.Delta); p.off = a.off; p.out = a.out;
   p.d_in = a.d_in; p.d_out = a.d_out; p.n_seq = a.n_seq; p.n_tokens = a.n_tokens;
   p.row0 = a.row0; p.row_end = a.row0 + a.rows; p.out_row0 = a.out_row0;
   p.out_seq_stride = a.out_seq_stride; p.beta = a.beta;
-  p.tiles_m = (a.rows + BM - 1) / BM;
-  p.tiles_n = (a.d_in + BN - 1) / BN;
-  const long long tiles = (long long)p.tiles_m * p.tiles_n;
-  p.n_chunks = 1;
-  p.chunk_tokens = a.n_tokens;
-  if (!PER_SEQ) {
-    // Number of token chunks: the count with the smallest modelled time
-    //   rounds(w) * ceil(N / w) * t_token  +  (w > 1) * w * outputs * t_atomic,
-    // rounds(w) = passes an XCD's 32 CUs make over its eighth of the tiles * w workgroups.  t_token is a
-    // workgroup's time per token row, t_atomic the chip's time per fp32 atomic add (about 0.8 TB/s), both
-    // measured; without the second term more chunks always look better, and the adds then cost more than
-    // the idle CUs did.
-    const long long slots = 32LL * OCC;                              // per XCD
-    const double t_token = 2.0e-8 * (double)(BM * BN) / 65536.0 * OCC, t_atomic = 5.0e-12;
-    const double outputs = (double)a.rows * a.d_in;
-    const long long most = a.n_tokens / 512 > 1 ? a.n_tokens / 512 : 1;
-    long long want = 1;
-    double best = 0.0;
-    for (long long w = 1; w <= most && w <= 64; ++w) {
-      const long long rounds = ((tiles * w + 7) / 8 + slots - 1) / slots;
-      const double t = (double)rounds * (double)((a.n_tokens + w - 1) / w) * t_token + (w > 1 ? w * outputs * t_atomic : 0.0);
-      if (w == 1) best = 0.9 * t;                                    // a split has to win by a margin
-      else if (t < best) { best = t; want = w; }
-    }
-    if (want > 1) {
-      p.chunk_tokens = (int)(((a.n_tokens + want - 1) / want + BK - 1) / BK * BK);
-      p.n_chunks = (a.n_tokens + p.chunk_tokens - 1) / p.chunk_tokens;
-    }
-  }
-  const bool mapped = PER_SEQ || p.n_chunks > 1;
-  long long blocks = mapped ? 8LL * (PER_SEQ ? a.n_seq : p.n_chunks) * ((tiles + 7) / 8) : tiles;
-  for (int x = 0; x <= 8; ++x) p.xcd_start[x] = 0;
-  const int n_items = PER_SEQ ? a.n_seq : p.n_chunks;
-  if (mapped && (!PER_SEQ || tiles % 8 != 0) && tiles * n_items <= 0x7fffffffLL) {
-    // Work of item i: its tokens plus a fixed charge for the workgroup's prologue and epilogue.
-    const long long fixed = PER_SEQ ? 192 : 64;
-    auto weight = [&](int i) -> long long {
-      if (PER_SEQ) return (a.off_host ? (long long)(a.off_host[i + 1] - a.off_host[i]) : 1024) + fixed;
-      const long long t0 = (long long)i * p.chunk_tokens;
-      const long long t1 = t0 + p.chunk_tokens < a.n_tokens ? t0 + p.chunk_tokens : a.n_tokens;
-      return (t1 - t0) + fixed;
-    };
-    long long total = 0;
-    for (int i = 0; i < n_items; ++i) total += weight(i) * tiles;
-    // pair (i, t) starts at work cum_i + t*w_i; XCD x's range opens at the first pair starting at or
-    // beyond x/8 of the total
-    long long cum = 0;
-    int i = 0, most = 0;
-    for (int x = 1; x < 8; ++x) {
-      const long long target = (x * total + 7) / 8;
-      while (i < n_items && cum + tiles * weight(i) <= target) cum += tiles * weight(i++);
-      if (i == n_items) { p.xcd_start[x] = (int)(tiles * n_items); continue; }
-      const long long w = weight(i);
-      p.xcd_start[x] = (int)(i * tiles + (target - cum + w - 1) / w);
-    }
-    p.xcd_start[8] = (int)(tiles * n_items);
-    for (int k = 0; k < 8; ++k) most = p.xcd_start[k + 1] - p.xcd_start[k] > most ? p.xcd_start[k + 1] - p.xcd_start[k] : most;
-    blocks = 8LL * most;
-  }
-  if (blocks <= 0) return hipSuccess;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  p.n_blocks = (unsigned)blocks;
+  p.tiles_m = pl.tiles_m;
+  p.tiles_n = pl.tiles_n;
+  p.n_chunks = pl.n_chunks;
+  p.chunk_tokens = pl.chunk_tokens;
+  for (int x = 0; x <= 8; ++x) p.xcd_start[x] = pl.xcd_start[x];
+  if (pl.blocks <= 0) return hipSuccess;
+  if (pl.blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  p.n_blocks = (unsigned)pl.blocks;
   constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
   constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
   auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ>;
@@ -469,15 +415,10 @@ hipError_t launch_stream(const SeqGradArgs& a, hipStream_t s) {
 
 // bf16, unscaled (per-sequence stash, or plain sum over all tokens).
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
-  const long long big_tiles = (long long)((a.rows + 255) / 256) * ((a.d_in + 255) / 256);
-  if (a.per_sequence) {
-    const bool big = a.rows >= 256 && a.d_in >= 256 && big_tiles * a.n_seq >= 256;
-    return big ? launch_stream<256, 256, 4, 1, true>(a, s) : launch_stream<128, 128, 4, 2, true>(a, s);
-  }
-  // sum over all tokens: the token split supplies the parallelism, so the larger tile whenever it fits
-  // (few tiles and few tokens: the smaller tile)
-  const bool big = a.rows >= 256 && a.d_in >= 256 && big_tiles * (a.n_tokens / 1024 > 1 ? a.n_tokens / 1024 : 1) >= 256;
-  return big ? launch_stream<256, 256, 4, 1, false>(a, s) : launch_stream<128, 128, 4, 2, false>(a, s);
+  const ContractionPlan pl = plan_contraction(a.rows, a.d_in, a.n_tokens, a.n_seq, a.off_host, a.per_sequence);
+  if (a.per_sequence)
+    return pl.tile == 256 ? launch_stream<256, 256, 4, 1, true>(a, pl, s) : launch_stream<128, 128, 4, 2, true>(a, pl, s);
+  return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false>(a, pl, s) : launch_stream<128, 128, 4, 2, false>(a, pl, s);
 }
 
 }  // namespace isopo

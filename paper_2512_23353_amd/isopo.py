@@ -27,7 +27,7 @@ _VARIANTS = {"fisher": VARIANT_FISHER, "interacting": VARIANT_INTERACTING}
 _PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALISED}
 _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
-EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_layer_gram", "isopo_seq_grads",
+EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_plan", "isopo_layer_gram", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_layer_gram_plan.restype = ctypes.c_int
     lib.isopo_gram_cost_model.argtypes = [lp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.isopo_gram_cost_model.restype = ctypes.c_int
+    lib.isopo_contraction_plan.argtypes = [lp, ctypes.c_int, vp]
+    lib.isopo_contraction_plan.restype = ctypes.c_int
     lib.isopo_layer_gram.argtypes = [lp, ctypes.c_int, vp, vp, sz, ctypes.c_int, vp]
     lib.isopo_layer_gram.restype = ctypes.c_int
     lib.isopo_seq_grads.argtypes = [lp, vp, vp]
@@ -194,6 +196,23 @@ def gram_cost_model(layer: Layer) -> Tuple[float, float]:
     tg, tm = ctypes.c_double(), ctypes.c_double()
     _check(load().isopo_gram_cost_model(layer.ref(), ctypes.byref(tg), ctypes.byref(tm)), "isopo_gram_cost_model")
     return tg.value, tm.value
+
+
+class ContractionPlanInfo(ctypes.Structure):
+    _fields_ = [("tile", ctypes.c_int32), ("workgroups_per_cu", ctypes.c_int32), ("tiles", ctypes.c_int32),
+                ("n_chunks", ctypes.c_int32), ("chunk_tokens", ctypes.c_int32), ("xcd_start", ctypes.c_int32 * 9),
+                ("workgroups", ctypes.c_int64)]
+
+
+def contraction_plan(layer_ref, per_sequence: bool) -> dict:
+    """Launch plan of the bf16 contraction (host arithmetic only).  `layer_ref`: an isopo_layer struct
+    (Layer.ref(), or one built on the host with null device pointers)."""
+    info = ContractionPlanInfo()
+    _check(load().isopo_contraction_plan(layer_ref, int(bool(per_sequence)), ctypes.byref(info)),
+           "isopo_contraction_plan")
+    return {"tile": info.tile, "workgroups_per_cu": info.workgroups_per_cu, "tiles": info.tiles,
+            "n_chunks": info.n_chunks, "chunk_tokens": info.chunk_tokens, "xcd_start": list(info.xcd_start),
+            "workgroups": info.workgroups}
 
 
 def alloc_workspace(nbytes: int, device) -> torch.Tensor:

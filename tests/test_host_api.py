@@ -107,3 +107,70 @@ def test_cost_model_prefers_ghost_only_for_few_tokens():
     first_mat = choices.index("materialised")
     assert all(c == "materialised" for c in choices[first_mat:])
     assert all(a <= b for a, b in zip(ghost_costs, ghost_costs[1:]))
+
+
+def test_contraction_plan_ranges_partition_the_work():
+    """Launch plan of the per-sequence contraction.  Tile counts that are a
+    multiple of eight keep the tile-eighths mapping (no range list); otherwise
+    the eight XCD ranges must tile [0, n_seq * tiles) exactly, in order, and
+    carry equal work up to one pair."""
+    # config-3 shapes: 256, 64, 896 tiles -> eighths
+    for d_in, d_out in ((4096, 4096), (4096, 1024), (4096, 14336)):
+        plan = isopo.contraction_plan(_host_layer([2048] * 32, d_in, d_out).ref(), True)
+        assert plan["tile"] == 256 and plan["tiles"] % 8 == 0
+        assert plan["xcd_start"] == [0] * 9
+        assert plan["workgroups"] == 32 * plan["tiles"]
+    rng = np.random.default_rng(5)
+    cases = [([2048] * 64, 1536, 1536), ([2048] * 64, 1536, 256), ([2048] * 64, 1536, 8960),
+             (list(rng.integers(256, 1025, 16)), 1536, 1536), (list(rng.integers(1, 3000, 37)), 1536, 8960),
+             ([0, 5, 0, 700, 0], 1536, 256), ([100, 0, 5000], 1536, 256)]
+    checked = 0
+    for lengths, d_in, d_out in cases:
+        plan = isopo.contraction_plan(_host_layer(lengths, d_in, d_out).ref(), True)
+        tiles, st = plan["tiles"], plan["xcd_start"]
+        if tiles % 8 == 0:                      # few sequences on a narrow layer: 128-wide tiles, 24 of them
+            assert plan["tile"] == 128 and st == [0] * 9
+            continue
+        checked += 1
+        assert st[0] == 0 and st[8] == len(lengths) * tiles
+        assert all(a <= b for a, b in zip(st, st[1:]))
+        assert plan["workgroups"] == 8 * max(b - a for a, b in zip(st, st[1:]))
+        # equal work: tokens + 192 per pair, no XCD more than one pair's work above the mean
+        w = np.asarray(lengths) + 192
+        work = [int(np.sum(w[np.arange(st[x], st[x + 1]) // tiles])) for x in range(8)]
+        assert sum(work) == int(np.sum(w)) * tiles
+        assert max(work) <= sum(work) / 8 + int(w.max()), (lengths[:4], d_in, d_out, work)
+    assert checked >= 5
+
+
+def test_contraction_plan_token_split():
+    """Unweighted mode.  Enough tiles: no split.  Few tiles and many tokens: a
+    split whose (chunk, tile) pairs fit the 32 CUs of an XCD in whole rounds,
+    chunks a multiple of the 32-token block, covering all tokens; a split is
+    never chosen when its atomic adds would cost more than the idle CUs."""
+    # 4096x4096 on 70k tokens: 256 tiles fill the chip
+    plan = isopo.contraction_plan(_host_layer([70107], 4096, 4096).ref(), False)
+    assert (plan["n_chunks"], plan["chunk_tokens"], plan["xcd_start"]) == (1, 70107, [0] * 9)
+    assert plan["workgroups"] == plan["tiles"] == 256
+    # config-4 q: 36 tiles, 131072 tokens -> 7 chunks = 252 pairs, 31 or 32 per XCD
+    plan = isopo.contraction_plan(_host_layer([2048] * 64, 1536, 1536).ref(), False)
+    assert plan["tile"] == 256 and plan["tiles"] == 36 and plan["n_chunks"] == 7
+    assert plan["chunk_tokens"] % 32 == 0 and plan["chunk_tokens"] * 7 >= 131072 > plan["chunk_tokens"] * 6
+    st = plan["xcd_start"]
+    assert st[0] == 0 and st[8] == 252 and all(31 <= b - a <= 32 for a, b in zip(st, st[1:]))
+    assert plan["workgroups"] == 256
+    # 210 tiles on 10k tokens: splitting would add 13.8M atomic adds per chunk for little gain
+    plan = isopo.contraction_plan(_host_layer([10365], 1536, 8960).ref(), False)
+    assert plan["n_chunks"] == 1
+    # narrow layer, short microbatch: the small tile, and some split
+    plan = isopo.contraction_plan(_host_layer([3000, 1400, 1, 4200, 333, 4100], 256, 384).ref(), False)
+    assert plan["tile"] == 128 and plan["workgroups_per_cu"] == 2 and plan["n_chunks"] > 1
+    assert plan["chunk_tokens"] % 32 == 0 and plan["chunk_tokens"] * plan["n_chunks"] >= 13034
+    assert plan["xcd_start"][8] == plan["n_chunks"] * plan["tiles"]
+    # nothing to do
+    plan = isopo.contraction_plan(_host_layer([0, 0], 256, 256).ref(), False)
+    assert plan["n_chunks"] == 1
+    # fp32 inputs do not use this kernel
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.contraction_plan(_host_layer([64], 64, 64, dtype=isopo.F32).ref(), True)
+    assert e.value.status == 3
