@@ -36,6 +36,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace isopo {
 namespace {
 
@@ -226,6 +228,21 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
   constexpr int AHEAD = PER_SEQ ? NSTAGE - 1 : NSTAGE;
   constexpr int NRD = 2 * (FM + FN), NMF = FM * FN;
 
+  // Per-sequence mode, 256x256 tile: the two waves of the lower tile half read their fragments behind
+  // MFMAs 8..15 of a half block instead of 0..7, in the order the next half block first uses them
+  // (B0, A0, B1, B2, B3, A1, A2, A3), so the LDS serves two waves' reads at a time, not four.
+  // frag_of: the fragment read behind MFMA idx (-1: none).
+  auto frag_of = [](int idx, bool late, bool& is_a) -> int {
+    const int k = idx - (late ? NMF - FM - FN : 0);
+    if (k < 0 || k >= FM + FN) return -1;
+    if (!late) { is_a = k < FM; return is_a ? k : k - FM; }
+    if (k == 0) { is_a = false; return 0; }
+    if (k == 1) { is_a = true; return 0; }
+    if (k <= FN) { is_a = false; return k - 1; }
+    is_a = true; return k - FN;
+  };
+  const bool late_wave = PER_SEQ && NMF >= 2 * (FM + FN) && (wave_s & 2);
+
 #pragma unroll
   for (int s = 0; s < AHEAD; ++s) issue_loads(s);
 
@@ -236,18 +253,25 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     for (int i = 0; i < FM; ++i) fa0[i] = frA(smem_base + adA[i]);
 #pragma unroll
     for (int j = 0; j < FN; ++j) fb0[j] = frB(smem_base + adB[j]);
-    for (int it = 0; it < n_tiles; ++it) {
+    // one token block; LATE: this wave's fragment-read slots (compile-time, so that both bodies stay
+    // straight-line code)
+    auto token_block = [&](int it, auto late_c) {
+      constexpr bool LATE = decltype(late_c)::value;
       const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
       if constexpr (PER_SEQ) {
-        // written out MFMA by MFMA: each of the first FM + FN MFMAs is followed by one fragment's reads
+        // written out MFMA by MFMA: one fragment's reads behind each MFMA of this wave's read slots
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
 #pragma unroll
           for (int j = 0; j < FN; ++j) {
             const int idx = i * FN + j;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
-            if (idx < FM) fa1[idx] = frA(sb + adA[idx] + 16 * PA);
-            else if (idx < FM + FN) fb1[idx - FM] = frB(sb + adB[idx - FM] + 16 * PB);
+            bool is_a = false;
+            const int f = frag_of(idx, LATE, is_a);
+            if (f >= 0) {
+              if (is_a) fa1[f] = frA(sb + adA[f] + 16 * PA);
+              else fb1[f] = frB(sb + adB[f] + 16 * PB);
+            }
           }
         }
       } else {
@@ -287,8 +311,12 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           for (int j = 0; j < FN; ++j) {
             const int idx = i * FN + j;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-            if (idx < FM) fa0[idx] = frA(sn + adA[idx]);
-            else if (idx < FM + FN) fb0[idx - FM] = frB(sn + adB[idx - FM]);
+            bool is_a = false;
+            const int f = frag_of(idx, LATE, is_a);
+            if (f >= 0) {
+              if (is_a) fa0[f] = frA(sn + adA[f]);
+              else fb0[f] = frB(sn + adB[f]);
+            }
             // the LPT DMA instructions spread evenly over the NMF MFMAs
 #pragma unroll
             for (int q = idx * LPT / NMF; q < (idx + 1) * LPT / NMF; ++q) {
@@ -298,6 +326,11 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           }
         }
       }
+    };
+    if (late_wave) {
+      for (int it = 0; it < n_tiles; ++it) token_block(it, std::true_type{});
+    } else {
+      for (int it = 0; it < n_tiles; ++it) token_block(it, std::false_type{});
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);
