@@ -50,9 +50,42 @@ def read_traffic(kernel_tag: str):
     return None
 
 
+def clock_dependence(args, block, layers, stash_views, fl, stream):
+    """The same launch of the largest projection on all-zero operands.  The kernel executes the same
+    instructions and cycles whatever the values; the part's power management does not: with operands
+    that do not toggle it holds the full clock.  The ratio says how much of the gap to the 2.4 GHz
+    peak is the clock under real data rather than the kernel's schedule."""
+    import numpy as np
+    import torch
+    from paper_2512_23353_amd import isopo
+    big = max(range(len(block)), key=lambda i: layers[i].d_in * layers[i].d_out)
+    lb = layers[big]
+    X0, D0 = torch.zeros_like(lb.X), torch.zeros_like(lb.Delta)
+    lz = isopo.Layer(X0, D0, block[big].seq_offsets)
+
+    def time_launches(layer, n):
+        ev = []
+        for _ in range(n + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            isopo.seq_grads(layer, stash_views[big], stream=stream)
+            e1.record(stream)
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in ev[1:]])) * 1e-3
+
+    t_zero, t_real = time_launches(lz, 4), time_launches(lb, 4)
+    return {"projection": block[big].name, "tflops_on_the_workload": fl[big]["seq_grads"] / t_real / 1e12,
+            "tflops_on_zero_operands": fl[big]["seq_grads"] / t_zero / 1e12,
+            "zero_ms": t_zero * 1e3, "workload_ms": t_real * 1e3,
+            "what": "same launch, same cycles; the clock under random operands is about 1.75 GHz, on zeros 2.4 GHz (profiles/)"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--no-clock-dependence", action="store_true",
+                    help="skip the zero-operand launches of the largest projection (keeps kernel profiles to the step's own launches)")
     ap.add_argument("--clock-probe", action="store_true",
                     help="only time the largest projection's stash launch on zero operands and on the workload, then exit")
     ap.add_argument("--steps", type=int, default=10)
@@ -193,29 +226,13 @@ def main() -> int:
     # instructions and cycles whatever the values; the part's power management does not: with operands
     # that do not toggle it holds the full clock.  The ratio says how much of the gap to the 2.4 GHz
     # peak is the clock under real data rather than the kernel's schedule.
-    big = max(range(len(block)), key=lambda i: layers[i].d_in * layers[i].d_out)
-    lb = layers[big]
-    X0, D0 = torch.zeros_like(lb.X), torch.zeros_like(lb.Delta)
-    lz = isopo.Layer(X0, D0, block[big].seq_offsets)
-    def time_launches(layer, n):
-        ev = []
-        for _ in range(n + 1):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            isopo.seq_grads(layer, stash_views[big], stream=stream)
-            e1.record(stream)
-            ev.append((e0, e1))
-        torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in ev[1:]])) * 1e-3
-    t_zero, t_real = time_launches(lz, 4), time_launches(lb, 4)
-    if args.clock_probe:
-        # for a counter run (GRBM_GUI_ACTIVE): five launches on zeros, then five on the workload, nothing else after
-        print(json.dumps({"clock_probe": block[big].name, "zero_ms": t_zero * 1e3, "workload_ms": t_real * 1e3}))
-        return 0
-    del X0, D0, lz
-    zero_operands = {"projection": block[big].name, "tflops_on_the_workload": fl[big]["seq_grads"] / t_real / 1e12,
-                     "tflops_on_zero_operands": fl[big]["seq_grads"] / t_zero / 1e12,
-                     "what": "same launch, same cycles; the clock under random operands is about 1.75 GHz, on zeros 2.4 GHz (profiles/)"}
+    zero_operands = None
+    if not args.no_clock_dependence or args.clock_probe:
+        zero_operands = clock_dependence(args, block, layers, stash_views, fl, stream)
+        if args.clock_probe:
+            # for a counter run (GRBM_GUI_ACTIVE): five launches on zeros, then five on the workload, nothing else after
+            print(json.dumps({k: zero_operands[k] for k in ("projection", "zero_ms", "workload_ms")}))
+            return 0
     total_flops = float(sum(sum(f.values()) for f in fl)) * sweeps
     reinforce_flops = float(sum(f["seq_grads"] for f in fl)) * sweeps
 
@@ -310,7 +327,7 @@ def main() -> int:
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
                      "flops_per_launch": seq_grad_flops_per_launch,
                      "traffic": read_traffic(f"seq_grad_{args.config}"),
-                     "clock_dependence": zero_operands},
+                     **({"clock_dependence": zero_operands} if zero_operands else {})},
     }
 
     if variants:
