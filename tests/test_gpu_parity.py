@@ -121,6 +121,34 @@ def test_stash_holds_per_sequence_gradients(gpu_device):
     assert rel_err(stash, G) < 1e-5
 
 
+@pytest.mark.parametrize("dims,n_seq", [((768, 512), 48), ((1536, 256), 44), ((768, 512), 3)])
+def test_per_sequence_gradients_with_xcd_work_ranges(gpu_device, dims, n_seq):
+    """Tile counts that are no multiple of eight (6 tiles of 256x256, or 24/12 of
+    128x128 with few sequences): the launcher hands each XCD a contiguous range
+    of (sequence, tile) pairs balanced by tokens.  Ragged lengths with empty
+    sequences; every per-sequence gradient in the stash and K are checked, so a
+    pair that no XCD took, or two took, cannot pass."""
+    d_in, d_out = dims
+    rng = np.random.default_rng(77)
+    lengths = [int(x) for x in rng.integers(0, 160, n_seq)]
+    lengths[1] = 0
+    lengths[-1] = 0
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=12, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    plan = isopo.contraction_plan(layer.ref(), True)
+    assert plan["tiles"] % 8 != 0 or n_seq == 3
+    K, ws = isopo.layer_gram(layer, "materialised", keep_stash=True)
+    torch.cuda.synchronize()
+    stash = ws[: n_seq * d_out * d_in * 2].view(torch.bfloat16).reshape(n_seq, d_out, d_in).float().cpu().numpy()
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    for i in range(n_seq):
+        if lengths[i] == 0:
+            assert not stash[i].any()
+        else:
+            assert rel_err(stash[i], G[i]) < 4e-3, i        # one bf16 rounding of an fp32 sum
+    assert_K_close(K.cpu().numpy(), orc.ntk_from_seq_grads(G), TOL["bf16"], f"xcd ranges {dims} B={n_seq}")
+
+
 @pytest.mark.parametrize("from_stash", [True, False])
 def test_weighted_grad_accumulates_with_beta(gpu_device, from_stash):
     prob = wl.custom_layer(256, 256, [100, 64, 90], dtype="bf16", seed=7, sigma_delta=1e-2)
