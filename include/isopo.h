@@ -244,32 +244,34 @@ isopo_status isopo_rescale(const float* fisher_sq, const float* grad_sq, int64_t
                            const float* A, const isopo_rescale_params* params, float* c, float* batch_means,
                            void* stream);
 
-/* Eigendecomposition of the layer's Gram matrix (interacting listing: D, U = eigh(ntk)), so that a
- * sweep over regularisers costs one decomposition.  Cyclic Jacobi in fp64 on one workgroup.
- *   K     device fp32 [n_seq, n_seq], symmetric (the mean of K and K^T is decomposed)
- *   D     device fp64 [n_seq], ascending
- *   U     device fp64 [n_seq, n_seq] row-major, eigenvectors as columns: K = U diag(D) U^T
- *   info  optional device int32: 0 converged, 1 not converged within the sweep limit
- *   workspace  device, isopo_ntk_eigh_workspace(n_seq) bytes, 256-byte aligned (used when the work
- *              matrices do not fit LDS) */
-size_t isopo_ntk_eigh_workspace(int32_t n_seq);
-isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, double* D, double* U, int32_t* info, void* workspace,
-                            size_t ws_bytes, void* stream);
+/* Eigendecomposition of the layers' Gram matrices (interacting listing: D, U = eigh(ntk)), so that a
+ * sweep over regularisers costs one decomposition.  `batch` independent problems laid out back to back
+ * (the projections of a block), one workgroup each, cyclic Jacobi in fp64.
+ *   K     device fp32 [batch, n_seq, n_seq], symmetric (the mean of K and K^T is decomposed)
+ *   D     device fp64 [batch, n_seq], ascending
+ *   U     device fp64 [batch, n_seq, n_seq] row-major, eigenvectors as columns: K = U diag(D) U^T
+ *   info  optional device int32 [batch]: 0 converged, 1 not converged within the sweep limit
+ *   workspace  device, isopo_ntk_eigh_workspace(n_seq, batch) bytes, 256-byte aligned (used when the
+ *              work matrices do not fit LDS) */
+size_t isopo_ntk_eigh_workspace(int32_t n_seq, int32_t batch);
+isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, int32_t batch, double* D, double* U, int32_t* info,
+                            void* workspace, size_t ws_bytes, void* stream);
 
 /* c_l = U ((U^T A) / (D + reg_l)) for l < n_lambda (interacting listing: preconditioner and
- * advantages_preconditioned), all from one decomposition.
+ * advantages_preconditioned), all from one decomposition, for each of `batch` problems
+ * (D [batch, n_seq], U [batch, n_seq, n_seq], A [batch, n_seq]).
  *   lambdas    host [n_lambda], 1 <= n_lambda <= ISOPO_MAX_LAMBDAS, each >= 0
  *   reg_mode   ABSOLUTE: reg_l = lambda_l.  REL_TRACE: reg_l = lambda_l * mean(D).
  *              EMA_TRACE: reg_l = lambda_l * E[mean(D)], the trailing mean over minibatches (this one
  *              included) kept in ema_state and updated by this call:
  *              E <- mean(D) on the first call, E <- decay E + (1 - decay) mean(D) after
- *   ema_state  device float[2] {E, number of minibatches seen}; zero it before the first minibatch;
- *              required for EMA_TRACE, ignored otherwise
- *   c          device fp32 [n_lambda, n_seq]
- *   info       optional device int32: number of (lambda, eigenvalue) pairs with D + reg <= 0; those
- *              components are left out of c (0 for a positive definite K + reg I) */
+ *   ema_state  device float [batch, 2] {E, number of minibatches seen} per problem; zero it before the
+ *              first minibatch; required for EMA_TRACE, ignored otherwise
+ *   c          device fp32 [batch, n_lambda, n_seq]
+ *   info       optional device int32 [batch]: number of (lambda, eigenvalue) pairs with D + reg <= 0;
+ *              those components are left out of c (0 for a positive definite K + reg I) */
 #define ISOPO_MAX_LAMBDAS 16
-isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_seq, const float* A,
+isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_seq, int32_t batch, const float* A,
                                   const float* lambdas, int32_t n_lambda, isopo_reg_mode reg_mode, float* ema_state,
                                   float ema_decay, float* c, int32_t* info, void* stream);
 

@@ -379,32 +379,32 @@ isopo_status isopo_rescale(const float* fisher_sq, const float* grad_sq, int64_t
   return launch_rescale(r, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
-size_t isopo_ntk_eigh_workspace(int32_t n_seq) {
-  if (n_seq <= 0 || n_seq > ISOPO_MAX_SEQ) return 0;
-  return align_up(eigh_workspace(n_seq));
+size_t isopo_ntk_eigh_workspace(int32_t n_seq, int32_t batch) {
+  if (n_seq <= 0 || n_seq > ISOPO_MAX_SEQ || batch <= 0) return 0;
+  return align_up((size_t)batch * eigh_workspace(n_seq));
 }
 
-isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, double* D, double* U, int32_t* info, void* workspace,
-                            size_t ws_bytes, void* stream) {
-  if (!K || !D || !U || n_seq <= 0) return ISOPO_ERR_INVALID_ARG;
+isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, int32_t batch, double* D, double* U, int32_t* info,
+                            void* workspace, size_t ws_bytes, void* stream) {
+  if (!K || !D || !U || n_seq <= 0 || batch <= 0) return ISOPO_ERR_INVALID_ARG;
   if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1))) return ISOPO_ERR_INVALID_ARG;
-  if (ws_bytes < isopo_ntk_eigh_workspace(n_seq)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
-  return launch_ntk_eigh(K, n_seq, D, U, info, workspace, static_cast<hipStream_t>(stream)) == hipSuccess
+  if (ws_bytes < isopo_ntk_eigh_workspace(n_seq, batch)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  return launch_ntk_eigh(K, n_seq, batch, D, U, info, workspace, static_cast<hipStream_t>(stream)) == hipSuccess
              ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
-isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_seq, const float* A,
+isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_seq, int32_t batch, const float* A,
                                   const float* lambdas, int32_t n_lambda, isopo_reg_mode reg_mode, float* ema_state,
                                   float ema_decay, float* c, int32_t* info, void* stream) {
-  if (!D || !U || !A || !lambdas || !c || n_seq <= 0 || n_lambda < 1) return ISOPO_ERR_INVALID_ARG;
+  if (!D || !U || !A || !lambdas || !c || n_seq <= 0 || batch <= 0 || n_lambda < 1) return ISOPO_ERR_INVALID_ARG;
   if (n_seq > ISOPO_MAX_SEQ || n_lambda > ISOPO_MAX_LAMBDAS) return ISOPO_ERR_UNSUPPORTED;
   if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE && reg_mode != ISOPO_REG_EMA_TRACE)
     return ISOPO_ERR_INVALID_ARG;
   if (reg_mode == ISOPO_REG_EMA_TRACE && (!ema_state || !(ema_decay >= 0.f && ema_decay < 1.f)))
     return ISOPO_ERR_INVALID_ARG;
   EighSolveArgs e;
-  e.D = D; e.U = U; e.n_seq = n_seq; e.A = A; e.n_lambda = n_lambda;
+  e.D = D; e.U = U; e.n_seq = n_seq; e.batch = batch; e.A = A; e.n_lambda = n_lambda;
   for (int l = 0; l < kEighMaxLambdas; ++l) {
     e.lambdas[l] = l < n_lambda ? lambdas[l] : 0.f;
     if (l < n_lambda && !(lambdas[l] >= 0.f)) return ISOPO_ERR_INVALID_ARG;

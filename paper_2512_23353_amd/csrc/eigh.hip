@@ -3,8 +3,9 @@
 //
 // One decomposition serves any number of regularisers, so a sweep over lambda
 // costs one factorisation instead of one Cholesky per value.  K is m x m with
-// m the number of sequences (tens to a few hundred), so one workgroup runs a
-// cyclic two-sided Jacobi iteration in fp64: each round applies m/2 disjoint
+// m the number of sequences (tens to a few hundred), so one workgroup per problem
+// (a block's projections go in one launch) runs a cyclic two-sided Jacobi iteration
+// in fp64: each round applies m/2 disjoint
 // plane rotations (round-robin pairing), first to the rows, then to the columns
 // of the work matrix and to the accumulated eigenvector matrix.  The matrices
 // live in LDS when they fit, else in a caller-provided global scratch that stays
@@ -32,16 +33,23 @@ __device__ double block_sum(double x, double* red) {
 }
 
 template <int THREADS>
-__global__ __launch_bounds__(THREADS) void jacobi_eigh_kernel(const float* __restrict__ K, int m,
-                                                              double* __restrict__ D, double* __restrict__ U,
-                                                              int32_t* __restrict__ info, double* __restrict__ gA,
-                                                              double* __restrict__ gV) {
+__global__ __launch_bounds__(THREADS) void jacobi_eigh_kernel(const float* __restrict__ Kb, int m,
+                                                              double* __restrict__ Db, double* __restrict__ Ub,
+                                                              int32_t* __restrict__ infob, double* __restrict__ gAb,
+                                                              double* __restrict__ gVb, size_t ws_stride) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   __shared__ double rot_c[kMaxPairs], rot_s[kMaxPairs];
   __shared__ short rot_p[kMaxPairs], rot_q[kMaxPairs];
   __shared__ double red[THREADS / 64];
   __shared__ short rank_of[kEighMaxSeq];
   const int tid = threadIdx.x;
+  const size_t prob = blockIdx.x;        // one problem per workgroup
+  const float* K = Kb + prob * m * m;
+  double* D = Db + prob * m;
+  double* U = Ub + prob * m * m;
+  int32_t* info = infob ? infob + prob : nullptr;
+  double* gA = gAb ? gAb + prob * ws_stride : nullptr;
+  double* gV = gVb ? gVb + prob * ws_stride : nullptr;
   const int n = (m + 1) & ~1;            // even: an odd m gets one idle index
   const int ld = n + 1;                  // odd pitch: column walks spread over the LDS banks
   // work matrix and eigenvectors: each in LDS when the caller passes no global buffer for it
@@ -143,6 +151,10 @@ __global__ __launch_bounds__(kSolveThreads) void eigh_solve_kernel(EighSolveArgs
   __shared__ double red[kSolveThreads / 64];
   __shared__ double sh_scale;
   const int tid = threadIdx.x, m = a.n_seq;
+  const size_t prob = blockIdx.x;        // one problem per workgroup
+  a.D += prob * m; a.U += prob * m * m; a.A += prob * m; a.c += prob * a.n_lambda * m;
+  if (a.ema_state) a.ema_state += prob * 2;
+  if (a.info) a.info += prob;
   double tr = 0.0;
   for (int j = tid; j < m; j += kSolveThreads) {
     double s = 0.0;
@@ -189,18 +201,18 @@ size_t eigh_workspace(int m) {
 }
 
 template <int THREADS>
-hipError_t launch_jacobi(const float* K, int m, double* D, double* U, int32_t* info, size_t smem, double* gA,
-                         double* gV, hipStream_t s) {
+hipError_t launch_jacobi(const float* K, int m, int batch, double* D, double* U, int32_t* info, size_t smem,
+                         double* gA, double* gV, size_t ws_stride, hipStream_t s) {
   auto kern = jacobi_eigh_kernel<THREADS>;
   // once per process (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kEighLdsBytes);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL(kern, dim3(1), dim3(THREADS), smem, s, K, m, D, U, info, gA, gV);
+  hipLaunchKernelGGL(kern, dim3(batch), dim3(THREADS), smem, s, K, m, D, U, info, gA, gV, ws_stride);
   return hipGetLastError();
 }
 
-hipError_t launch_ntk_eigh(const float* K, int m, double* D, double* U, int32_t* info, void* workspace,
+hipError_t launch_ntk_eigh(const float* K, int m, int batch, double* D, double* U, int32_t* info, void* workspace,
                            hipStream_t s) {
   const int n = (m + 1) & ~1;
   const size_t one = (size_t)n * (n + 1) * sizeof(double);
@@ -210,12 +222,13 @@ hipError_t launch_ntk_eigh(const float* K, int m, double* D, double* U, int32_t*
   if (2 * one <= kEighLdsBytes) smem = 2 * one;                       // both in LDS
   else if (one <= kEighLdsBytes) { smem = one; gV = ws; }             // work matrix in LDS, eigenvectors in L2
   else { smem = 0; gA = ws; gV = ws + (size_t)n * (n + 1); }
-  return n <= 32 ? launch_jacobi<256>(K, m, D, U, info, smem, gA, gV, s)
-                 : launch_jacobi<1024>(K, m, D, U, info, smem, gA, gV, s);
+  const size_t ws_stride = eigh_workspace(m) / sizeof(double);      // doubles per problem
+  return n <= 32 ? launch_jacobi<256>(K, m, batch, D, U, info, smem, gA, gV, ws_stride, s)
+                 : launch_jacobi<1024>(K, m, batch, D, U, info, smem, gA, gV, ws_stride, s);
 }
 
 hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(eigh_solve_kernel, dim3(1), dim3(kSolveThreads), 0, s, a);
+  hipLaunchKernelGGL(eigh_solve_kernel, dim3(a.batch), dim3(kSolveThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -148,20 +148,20 @@ constexpr int kEighMaxSeq = 1024;
 constexpr size_t kEighLdsBytes = 144 * 1024;     // work matrix + eigenvectors in LDS up to this size
 constexpr int kEighMaxLambdas = 16;
 struct EighSolveArgs {
-  const double* D;
-  const double* U;
-  int n_seq;
-  const float* A;
+  const double* D;             // [batch][n_seq]
+  const double* U;             // [batch][n_seq][n_seq]
+  int n_seq, batch;
+  const float* A;              // [batch][n_seq]
   float lambdas[kEighMaxLambdas];
   int n_lambda;
   int reg_mode;                // 0 absolute, 1 times mean(D), 2 times the trailing mean of mean(D)
-  float* ema_state;            // [2]: trailing mean, number of minibatches seen
+  float* ema_state;            // [batch][2]: trailing mean, number of minibatches seen
   float ema_decay;
-  float* c;                    // [n_lambda][n_seq]
-  int32_t* info;
+  float* c;                    // [batch][n_lambda][n_seq]
+  int32_t* info;               // [batch]
 };
-size_t eigh_workspace(int m);
-hipError_t launch_ntk_eigh(const float* K, int m, double* D, double* U, int32_t* info, void* workspace,
+size_t eigh_workspace(int m);           // bytes per problem
+hipError_t launch_ntk_eigh(const float* K, int m, int batch, double* D, double* U, int32_t* info, void* workspace,
                            hipStream_t s);
 hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s);
 

@@ -109,11 +109,11 @@ def load() -> ctypes.CDLL:
     lib.isopo_gram_norms.restype = ctypes.c_int
     lib.isopo_rescale.argtypes = [vp, vp, ctypes.c_int64, i32, vp, ctypes.POINTER(_RescaleParams), vp, vp, vp]
     lib.isopo_rescale.restype = ctypes.c_int
-    lib.isopo_ntk_eigh_workspace.argtypes = [i32]
+    lib.isopo_ntk_eigh_workspace.argtypes = [i32, i32]
     lib.isopo_ntk_eigh_workspace.restype = sz
-    lib.isopo_ntk_eigh.argtypes = [vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.isopo_ntk_eigh.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.isopo_ntk_eigh.restype = ctypes.c_int
-    lib.isopo_transform_eigh.argtypes = [vp, vp, i32, vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.c_int, vp, f32,
+    lib.isopo_transform_eigh.argtypes = [vp, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.c_int, vp, f32,
                                          vp, vp, vp]
     lib.isopo_transform_eigh.restype = ctypes.c_int
     lib.isopo_status_string.argtypes = [ctypes.c_int]
@@ -351,32 +351,42 @@ def rescale(fisher_sq: torch.Tensor, grad_sq: torch.Tensor, A: torch.Tensor, p: 
 
 
 def ntk_eigh(K: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None):
-    """D (ascending), U (eigenvectors as columns), info from the Gram matrix; fp64 on the device."""
+    """D (ascending), U (eigenvectors as columns), info from the Gram matrix; fp64 on the device.
+    K [m, m] or a batch [b, m, m] (one launch); outputs carry the same leading dimension."""
+    if not K.is_contiguous():
+        raise ValueError("K must be contiguous")
     m = K.shape[-1]
-    D = torch.empty(m, dtype=torch.float64, device=K.device)
-    U = torch.empty((m, m), dtype=torch.float64, device=K.device)
-    info = torch.zeros(1, dtype=torch.int32, device=K.device)
+    batch = K.shape[0] if K.dim() == 3 else 1
+    lead = (batch,) if K.dim() == 3 else ()
+    D = torch.empty(lead + (m,), dtype=torch.float64, device=K.device)
+    U = torch.empty(lead + (m, m), dtype=torch.float64, device=K.device)
+    info = torch.zeros(batch, dtype=torch.int32, device=K.device)
     if workspace is None:
-        workspace = alloc_workspace(load().isopo_ntk_eigh_workspace(m), K.device)
-    _check(load().isopo_ntk_eigh(K.data_ptr(), m, D.data_ptr(), U.data_ptr(), info.data_ptr(), workspace.data_ptr(),
-                                 workspace.numel(), _stream(stream)), "isopo_ntk_eigh")
+        workspace = alloc_workspace(load().isopo_ntk_eigh_workspace(m, batch), K.device)
+    _check(load().isopo_ntk_eigh(K.data_ptr(), m, batch, D.data_ptr(), U.data_ptr(), info.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), _stream(stream)), "isopo_ntk_eigh")
     return D, U, info
 
 
 def transform_eigh(D: torch.Tensor, U: torch.Tensor, A: torch.Tensor, lambdas, reg_mode: int = REG_ABSOLUTE,
                    ema_state: Optional[torch.Tensor] = None, ema_decay: float = 0.9,
                    c: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None, stream=None):
-    """c [n_lambda, m] = U ((U^T A) / (D + reg_l)).  Returns (c, info)."""
-    m = int(D.numel())
+    """c [n_lambda, m] = U ((U^T A) / (D + reg_l)); with a batch (D [b, m], U [b, m, m], A [b, m],
+    ema_state [b, 2]) c is [b, n_lambda, m].  Returns (c, info)."""
+    m = int(D.shape[-1])
+    batch = D.shape[0] if D.dim() == 2 else 1
+    lead = (batch,) if D.dim() == 2 else ()
+    if A.numel() != batch * m:
+        raise ValueError("A must hold one advantage per sequence and problem")
     lam = [float(x) for x in lambdas]
     if c is None:
-        c = torch.empty((len(lam), m), dtype=torch.float32, device=D.device)
+        c = torch.empty(lead + (len(lam), m), dtype=torch.float32, device=D.device)
     if info is None:
-        info = torch.zeros(1, dtype=torch.int32, device=D.device)
+        info = torch.zeros(batch, dtype=torch.int32, device=D.device)
     arr = (ctypes.c_float * max(len(lam), 1))(*lam)
-    _check(load().isopo_transform_eigh(D.data_ptr(), U.data_ptr(), m, A.data_ptr(), arr, len(lam), int(reg_mode),
-                                       _ptr(ema_state), float(ema_decay), c.data_ptr(), info.data_ptr(),
-                                       _stream(stream)), "isopo_transform_eigh")
+    _check(load().isopo_transform_eigh(D.data_ptr(), U.data_ptr(), m, batch, A.data_ptr(), arr, len(lam),
+                                       int(reg_mode), _ptr(ema_state), float(ema_decay), c.data_ptr(),
+                                       info.data_ptr(), _stream(stream)), "isopo_transform_eigh")
     return c, info
 
 

@@ -102,6 +102,37 @@ def test_eigh_sizes(gpu_device, m):
         assert rel_err(c_chol[l].cpu().numpy(), c_ref) <= 1e-5
 
 
+@pytest.mark.parametrize("m,batch", [(5, 3), (64, 7), (96, 4), (200, 2)])
+def test_eigh_batch_of_problems(gpu_device, m, batch):
+    """The projections of a block in one launch (one workgroup per problem), in
+    every storage regime: each problem's D, U and its lambda sweep must equal
+    what a launch of its own gives (bit for bit: the same arithmetic), the
+    trailing-mean state is kept per problem, and the coefficients match the
+    oracle's eigendecomposition route."""
+    rng = np.random.default_rng(2000 + m)
+    Ks = np.stack([_random_gram(rng, m, scale=10.0 ** b) for b in range(batch)])
+    A = rng.standard_normal((batch, m)).astype(np.float32)
+    Kd, Ad = torch.from_numpy(Ks).to(gpu_device), torch.from_numpy(A).to(gpu_device)
+    D, U, info = isopo.ntk_eigh(Kd)
+    lambdas = [1e-3, 1e-1]
+    ema = torch.zeros((batch, 2), dtype=torch.float32, device=gpu_device)
+    c, sinfo = isopo.transform_eigh(D, U, Ad, lambdas, isopo.REG_EMA_TRACE, ema_state=ema, ema_decay=0.9)
+    torch.cuda.synchronize()
+    assert D.shape == (batch, m) and U.shape == (batch, m, m) and c.shape == (batch, 2, m)
+    assert not info.any() and not sinfo.any()
+    for b in range(batch):
+        D1, U1, _ = isopo.ntk_eigh(Kd[b])
+        e1 = torch.zeros(2, dtype=torch.float32, device=gpu_device)
+        c1, _ = isopo.transform_eigh(D1, U1, Ad[b], lambdas, isopo.REG_EMA_TRACE, ema_state=e1, ema_decay=0.9)
+        torch.cuda.synchronize()
+        assert torch.equal(D[b], D1) and torch.equal(U[b], U1) and torch.equal(c[b], c1)
+        assert torch.equal(ema[b], e1) and ema[b, 1].item() == 1.0
+        K64 = Ks[b].astype(np.float64)
+        for l, lam in enumerate(lambdas):
+            c_ref = orc.coeff_interacting_eigh(K64, A[b], lam, orc.REG_REL_TRACE)      # first minibatch: E = mean(D)
+            assert rel_err(c[b, l].cpu().numpy(), c_ref) <= 1e-5, f"problem {b} lambda={lam}"
+
+
 def test_eigh_on_a_layer_and_lambda_sweep(gpu_device):
     """Config-2-shaped projection: K from the layer, one decomposition, the
     lambda sweep of the 28-layer configuration, against the oracle's
