@@ -72,8 +72,8 @@ typedef enum {
                                        as the interacting experiment's regulariser is) */
   ISOPO_REG_EMA_TRACE = 2           /* reg = lambda * trailing mean over minibatches of tr(K)/m
                                        (interacting experiment: factor * E[mean(D)], decay 0.9);
-                                       isopo_transform_eigh and isopo_fisher_samples (there: of the
-                                       batch mean of F^2) */
+                                       isopo_transform_ema, isopo_transform_eigh and
+                                       isopo_fisher_samples (there: of the batch mean of F^2) */
 } isopo_reg_mode;
 
 /* One ragged layer problem.  All pointers caller-owned. */
@@ -160,6 +160,18 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
                              isopo_variant variant, float lambda, isopo_reg_mode reg_mode,
                              float* c, int32_t* info_dev, void* workspace, size_t ws_bytes,
                              void* stream);
+
+/* isopo_transform with the interacting experiment's regulariser, reg = factor * E[mean(D)]: the
+ * trailing mean over minibatches (this one included) of the Gram matrix's mean eigenvalue, which is
+ * tr(K)/n_seq, so the fast factorisation route serves it too.
+ *   ema_state  device float [batch, 2] per problem {E, number of minibatches seen}; zero it before the
+ *              first minibatch.  Updated by the call: E <- tr(K)/n_seq on the first minibatch,
+ *              E <- decay E + (1 - decay) tr(K)/n_seq after (decay 0.9 in the experiment)
+ *   factor     >= 0 (1.0 in the experiment);  0 <= ema_decay < 1
+ * Everything else as isopo_transform. */
+isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, int32_t batch,
+                                 isopo_variant variant, float factor, float* ema_state, float ema_decay,
+                                 float* c, int32_t* info_dev, void* workspace, size_t ws_bytes, void* stream);
 
 /* dW [d_out, d_in] fp32 = beta * dW + sum_i c_i G_i.
  *   stash  NULL: contract X and Delta again, dW = Delta^T diag(c_tok) X.

@@ -291,6 +291,25 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
   return launch_transform(t, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
+isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, int32_t batch, isopo_variant variant,
+                                 float factor, float* ema_state, float ema_decay, float* c, int32_t* info_dev,
+                                 void* workspace, size_t ws_bytes, void* stream) {
+  if (!K || !A || !c || !ema_state || n_seq <= 0 || batch <= 0) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  if (variant != ISOPO_VARIANT_FISHER && variant != ISOPO_VARIANT_INTERACTING) return ISOPO_ERR_INVALID_ARG;
+  if (!(factor >= 0.f) || !(ema_decay >= 0.f && ema_decay < 1.f)) return ISOPO_ERR_INVALID_ARG;
+  if (variant == ISOPO_VARIANT_INTERACTING) {
+    const size_t need = isopo_transform_workspace(n_seq, batch);
+    if (need && (!workspace || ws_bytes < need)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+    if (need && (reinterpret_cast<uintptr_t>(workspace) & 15u)) return ISOPO_ERR_INVALID_ARG;
+  }
+  TransformArgs t;
+  t.K = K; t.A = A; t.n_seq = n_seq; t.batch = batch; t.variant = (int)variant; t.reg_mode = (int)ISOPO_REG_EMA_TRACE;
+  t.lambda = factor; t.c = c; t.info = info_dev; t.workspace = static_cast<double*>(workspace);
+  t.ema_state = ema_state; t.ema_decay = ema_decay;
+  return launch_transform(t, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
 static_assert(kFisherMaxGroup == ISOPO_MAX_GROUP, "group size of the kernel and of the header");
 
 size_t isopo_fisher_samples_group_workspace(const isopo_layer* layer, int32_t n_layers, int32_t n_samples) {

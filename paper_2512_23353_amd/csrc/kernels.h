@@ -123,6 +123,8 @@ struct TransformArgs {
   float* c;
   int32_t* info;
   double* workspace;         // [batch][n_seq*n_seq] when n_seq > kTransformLdsMax, else unused
+  float* ema_state = nullptr;  // reg_mode 2: [batch][2] trailing mean of tr(K)/m, number of minibatches seen
+  float ema_decay = 0.f;
 };
 constexpr int kTransformLdsMax = 128;
 hipError_t launch_transform(const TransformArgs& a, hipStream_t s);

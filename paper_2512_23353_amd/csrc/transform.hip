@@ -6,7 +6,10 @@
 //                included)
 //   INTERACTING  c = (K + reg I)^-1 A          (v = J^T (K + cI)^-1 A)
 //
-// reg = lambda, or lambda * tr(K)/m.  The m x m problem is tiny next to the
+// reg = lambda, or lambda * tr(K)/m, or lambda * the trailing mean over minibatches
+// of tr(K)/m (the interacting experiment's regulariser, factor * E[mean(D)]: the
+// mean eigenvalue is the trace over m, so no decomposition is needed for it).
+// The m x m problem is tiny next to the
 // contractions around it, so one workgroup per problem works in fp64: a
 // right-looking Cholesky factorisation in LDS (m <= 128) or in a caller-provided
 // global scratch (larger m), then two triangular solves.  The result is the
@@ -34,7 +37,8 @@ template <int kThreads>
 __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __restrict__ Kb, const float* __restrict__ Ab,
                                                              int m, int variant, int reg_mode, float lambda,
                                                              float* __restrict__ cb, int32_t* __restrict__ info,
-                                                             double* __restrict__ gws) {
+                                                             double* __restrict__ gws, float* __restrict__ ema_state,
+                                                             float ema_decay) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ double red[kThreads / 64];
   const int prob = blockIdx.x, tid = threadIdx.x;
@@ -43,10 +47,21 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
   float* c = cb + (size_t)prob * m;
 
   double reg = (double)lambda;
-  if (reg_mode == 1) {
+  if (reg_mode != 0) {
     double tr = 0.0;
     for (int i = tid; i < m; i += kThreads) tr += (double)K[(size_t)i * m + i];
-    reg = (double)lambda * block_sum<kThreads>(tr, red) / (double)m;
+    double scale = block_sum<kThreads>(tr, red) / (double)m;          // this batch's mean eigenvalue
+    if (reg_mode == 2) {
+      // trailing mean over minibatches, this one included; every thread forms the same value from the
+      // state as it was, then one thread stores the new state
+      float* st = ema_state + (size_t)prob * 2;
+      const double prev = (double)st[0];
+      const bool first = st[1] == 0.f;
+      scale = first ? scale : (double)ema_decay * prev + (1.0 - (double)ema_decay) * scale;
+      __syncthreads();                                                  // everyone has read the old state
+      if (tid == 0) { st[0] = (float)scale; st[1] = st[1] + 1.f; }
+    }
+    reg = (double)lambda * scale;
   }
 
   if (variant == 0) {
@@ -141,7 +156,7 @@ hipError_t launch_transform_t(const TransformArgs& a, size_t smem, double* gws, 
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, max_smem);
   if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL(kern, dim3(a.batch), dim3(THREADS), smem, s, a.K, a.A, a.n_seq, a.variant, a.reg_mode, a.lambda,
-                     a.c, a.info, gws);
+                     a.c, a.info, gws, a.ema_state, a.ema_decay);
   return hipGetLastError();
 }
 

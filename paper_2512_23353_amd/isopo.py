@@ -27,7 +27,8 @@ _VARIANTS = {"fisher": VARIANT_FISHER, "interacting": VARIANT_INTERACTING}
 _PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALISED}
 _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
-EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_plan", "isopo_layer_gram", "isopo_seq_grads",
+EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_plan", "isopo_layer_gram",
+           "isopo_transform_ema", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
@@ -88,6 +89,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_transform_workspace.restype = sz
     lib.isopo_transform.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.isopo_transform.restype = ctypes.c_int
+    lib.isopo_transform_ema.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, vp, f32, vp, vp, vp, sz, vp]
+    lib.isopo_transform_ema.restype = ctypes.c_int
     lib.isopo_weighted_grad.argtypes = [lp, vp, vp, f32, vp, vp]
     lib.isopo_weighted_grad.restype = ctypes.c_int
     lib.isopo_scale_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int64, i32, vp, i32, vp, vp, vp]
@@ -282,6 +285,31 @@ def transform(K: torch.Tensor, A: torch.Tensor, variant="fisher", lam: float = 0
     _check(load().isopo_transform(K.data_ptr(), A.data_ptr(), m, batch, _VARIANTS[variant], float(lam),
                                   int(reg_mode), c.data_ptr(), info.data_ptr(), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _stream(stream)), "isopo_transform")
+    return c, info
+
+
+def transform_ema(K: torch.Tensor, A: torch.Tensor, variant, factor: float, ema_state: torch.Tensor,
+                  ema_decay: float = 0.9, c: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None):
+    """transform() with reg = factor * trailing mean over minibatches of tr(K)/m; ema_state [batch?, 2]
+    fp32 on the device is read and updated.  Returns (c, info)."""
+    m = K.shape[-1]
+    batch = 1 if K.dim() == 2 else K.shape[0]
+    if K.dtype != torch.float32 or A.dtype != torch.float32 or not K.is_contiguous() or not A.is_contiguous():
+        raise ValueError("K and A must be contiguous fp32")
+    if ema_state.dtype != torch.float32 or ema_state.numel() != 2 * batch or not ema_state.is_contiguous():
+        raise ValueError("ema_state must be contiguous fp32 [batch, 2]")
+    if c is None:
+        c = torch.empty_like(A)
+    if info is None:
+        info = torch.zeros(batch, dtype=torch.int32, device=K.device)
+    need = transform_workspace(m, batch)
+    if workspace is None and need:
+        workspace = alloc_workspace(need, K.device)
+    _check(load().isopo_transform_ema(K.data_ptr(), A.data_ptr(), m, batch, _VARIANTS[variant], float(factor),
+                                      ema_state.data_ptr(), float(ema_decay), c.data_ptr(), info.data_ptr(),
+                                      _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                      _stream(stream)), "isopo_transform_ema")
     return c, info
 
 

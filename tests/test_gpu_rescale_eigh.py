@@ -174,6 +174,39 @@ def test_trailing_mean_regulariser(gpu_device):
     assert ema[1].item() == 3.0
 
 
+@pytest.mark.parametrize("m", [24, 160])
+def test_trailing_mean_regulariser_on_the_factorisation_route(gpu_device, m):
+    """isopo_transform_ema: the same regulariser without a decomposition (the mean
+    eigenvalue is tr(K)/m), for a batch of two problems with states of their
+    own, both variants, over three minibatches; LDS and global-scratch sizes."""
+    rng = np.random.default_rng(19 + m)
+    K0 = np.stack([_random_gram(rng, m), _random_gram(rng, m, scale=50.0)])
+    A = rng.standard_normal((2, m)).astype(np.float32)
+    Ad = torch.from_numpy(A).to(gpu_device)
+    for variant in ("interacting", "fisher"):
+        ema = torch.zeros((2, 2), dtype=torch.float32, device=gpu_device)
+        states = [None, None]
+        for scale in (1.0, 4.0, 0.25):
+            K = (scale * K0).astype(np.float32)
+            c, info = isopo.transform_ema(torch.from_numpy(K).to(gpu_device), Ad, variant, 0.5, ema, 0.9)
+            torch.cuda.synchronize()
+            assert not info.any()
+            for b in range(2):
+                K64 = K[b].astype(np.float64)
+                if variant == "interacting":
+                    c_ref, states[b] = orc.coeff_interacting_ema(K64, A[b], 0.5, states[b], 0.9)
+                else:
+                    states[b] = orc.ema_update(states[b], float(np.trace(K64)) / m, 0.9)
+                    c_ref = orc.coeff_fisher(K64, A[b], 0.5 * states[b], orc.REG_ABSOLUTE)
+                assert ema[b, 0].item() == pytest.approx(states[b], rel=1e-6)
+                assert rel_err(c[b].cpu().numpy(), c_ref) <= 1e-5, (variant, scale, b)
+        assert ema[:, 1].tolist() == [3.0, 3.0]
+    with pytest.raises(isopo.IsopoError):
+        isopo.transform_ema(torch.from_numpy(K0).to(gpu_device), Ad, "interacting", 0.5, ema, 1.0)     # decay < 1
+    with pytest.raises(isopo.IsopoError):
+        isopo.transform_ema(torch.from_numpy(K0).to(gpu_device), Ad, "interacting", -1.0, ema, 0.9)
+
+
 def test_eigh_semidefinite_and_bad_arguments(gpu_device):
     """Duplicate sequences make K singular: with reg = 0 the null components are
     reported and left out; with reg > 0 the result matches the oracle."""
