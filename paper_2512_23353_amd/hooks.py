@@ -27,7 +27,7 @@ import numpy as np
 import torch
 from torch import nn
 
-VARIANTS = ("interacting", "fisher", "fisher_token_samples", "rescaled")
+VARIANTS = ("interacting", "interacting_ema", "fisher", "fisher_token_samples", "rescaled")
 
 
 def _hip_layer_step(X, Delta, seq_offsets, A, cfg) -> torch.Tensor:
@@ -39,6 +39,12 @@ def _hip_layer_step(X, Delta, seq_offsets, A, cfg) -> torch.Tensor:
     variant = cfg["variant"]
     if variant in ("interacting", "fisher"):
         return isopo.layer_step(layer, A, variant, cfg["lam"], reg_mode, "auto")["dW"]
+    if variant == "interacting_ema":
+        # the interacting experiment's regulariser: lam * trailing mean over steps of the layer's mean eigenvalue,
+        # the state living on the device with the hooks object (one per module)
+        K, ws = isopo.layer_gram(layer, "materialised", keep_stash=True)
+        c, _ = isopo.transform_ema(K, A, "interacting", cfg["lam"], cfg["ema_state"], cfg["ema_decay"])
+        return isopo.weighted_grad(layer, c, ws)
     if variant == "fisher_token_samples":
         n_s = min(cfg["n_samples"], layer.n_tokens)
         idx = torch.randperm(layer.n_tokens, generator=cfg["generator"], device="cpu")[:n_s]
@@ -64,14 +70,18 @@ class IsopoHooks:
     def __init__(self, model: nn.Module, seq_offsets, advantages: torch.Tensor, variant: str = "interacting",
                  lam: float = 1e-3, relative_reg: bool = True, n_samples: int = 32, pqr=(0.0, -1.0, -2.0),
                  reg3=(0.0, 0.0, 0.0), modules: Optional[Iterable[nn.Linear]] = None, seed: int = 0,
-                 layer_step: Optional[Callable] = None):
+                 layer_step: Optional[Callable] = None, ema_decay: float = 0.9,
+                 ema_states: Optional[Dict[nn.Linear, torch.Tensor]] = None):
         if variant not in VARIANTS:
             raise ValueError(f"variant must be one of {VARIANTS}")
         self.seq_offsets = None if seq_offsets is None else np.ascontiguousarray(np.asarray(seq_offsets, dtype=np.int32))
         self.A = advantages
         self.cfg = {"variant": variant, "lam": float(lam), "relative_reg": bool(relative_reg),
                     "n_samples": int(n_samples), "pqr": tuple(pqr), "reg3": tuple(reg3),
-                    "generator": torch.Generator(device="cpu").manual_seed(seed)}
+                    "generator": torch.Generator(device="cpu").manual_seed(seed), "ema_decay": float(ema_decay)}
+        # variant "interacting_ema": per-module {trailing mean, steps seen} on the device; pass the dict of a
+        # previous step's hooks object (its .ema_states) to carry the means over training steps
+        self.ema_states: Dict[nn.Linear, torch.Tensor] = ema_states if ema_states is not None else {}
         self.layer_step = layer_step or _hip_layer_step
         self.grads: Dict[nn.Linear, torch.Tensor] = {}
         self.captured: Dict[nn.Linear, tuple] = {}
@@ -102,6 +112,10 @@ class IsopoHooks:
         if int(off[-1]) != X.shape[0]:
             raise ValueError(f"seq_offsets cover {int(off[-1])} tokens, the layer saw {X.shape[0]}")
         self.captured[mod] = (X, Delta, off)
+        if self.cfg["variant"] == "interacting_ema":
+            if mod not in self.ema_states:
+                self.ema_states[mod] = torch.zeros(2, dtype=torch.float32, device=X.device)
+            self.cfg["ema_state"] = self.ema_states[mod]
         dW = self.layer_step(X, Delta, off, self.A, self.cfg)
         if mod in self.grads:
             self.grads[mod] += dW           # a second microbatch accumulates, as `mod.grad += grad` does

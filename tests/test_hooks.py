@@ -79,7 +79,8 @@ def test_hooks_padded_batch_layout_and_accumulation():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("variant,dtype", [("interacting", "f32"), ("fisher", "f32"), ("fisher_token_samples", "f32"),
-                                           ("rescaled", "f32"), ("interacting", "bf16"), ("fisher_token_samples", "bf16")])
+                                           ("rescaled", "f32"), ("interacting", "bf16"), ("fisher_token_samples", "bf16"),
+                                           ("interacting_ema", "f32")])
 def test_hooks_run_the_hip_library(gpu_device, variant, dtype):
     """The same harness on the GPU with the HIP library as the layer step, fp32
     and bf16 models: every hooked layer's update against the oracle on the
@@ -106,6 +107,10 @@ def test_hooks_run_the_hip_library(gpu_device, variant, dtype):
         K = orc.ntk_from_seq_grads(G)
         if variant in ("interacting", "fisher"):
             c = orc.layer_step(X, Delta, off_c, Af, variant, 1e-2, orc.REG_REL_TRACE)["c"]
+        elif variant == "interacting_ema":
+            c, state = orc.coeff_interacting_ema(K, Af, 1e-2, None, 0.9)        # first step: E = this batch's mean
+            assert hooks.ema_states[mod][0].item() == pytest.approx(state, rel=1e-5)
+            assert hooks.ema_states[mod][1].item() == 1.0
         elif variant == "fisher_token_samples":
             idx = torch.randperm(X.shape[0], generator=gen)[:16].numpy()
             c, _ = orc.coeff_fisher_token_samples(X, Delta, off_c, idx, Af, 1e-2, orc.REG_REL_TRACE)
