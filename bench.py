@@ -90,7 +90,7 @@ def main() -> int:
                     help="only time the largest projection's stash launch on zero operands and on the workload, then exit")
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4"])
+    ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4", "config5"])
     ap.add_argument("--variant", default="interacting", choices=["fisher", "interacting"])
     ap.add_argument("--lam", type=float, default=1e-3)
     ap.add_argument("--n-samples", type=int, default=32, help="token-position samples of the Fisher estimate")
@@ -306,7 +306,7 @@ def main() -> int:
         "value": n_tokens / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: {'one transformer block' if n_layers == 1 else f'{n_layers} transformer blocks swept layer by layer'}, 7 projections "
+        "config": {"workload": f"{args.config}: {('one transformer block' if len(w.projections) > 1 else 'one layer') if n_layers == 1 else f'{n_layers} transformer blocks swept layer by layer'}, {len(w.projections)} projection{'s' if len(w.projections) > 1 else ''} "
                                f"({', '.join(f'{p.name} {p.d_in}x{p.d_out}' for p in w.projections)}), "
                                f"B={n_seq} ragged sequences, N={n_tokens} tokens, bf16 inputs fp32 accumulation",
                    "variant": args.variant, "lambda": args.lam, "reg_mode": "rel_trace",
@@ -322,7 +322,7 @@ def main() -> int:
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
                       "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
-        "roofline": {"bound": "mfma", "kernel": "seq_grad_kernel (per-sequence gradients -> stash)",
+        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true> (per-sequence gradients -> stash)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
                      "flops_per_launch": seq_grad_flops_per_launch,
