@@ -174,3 +174,15 @@ def test_contraction_plan_token_split():
     with pytest.raises(isopo.IsopoError) as e:
         isopo.contraction_plan(_host_layer([64], 64, 64, dtype=isopo.F32).ref(), True)
     assert e.value.status == 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The layer step has no cross-GPU part: bench.py --gpus N > 1 exits with a
+    message instead of printing a number (and touches no GPU on the way)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+    assert not r.stdout.strip().startswith("{")
