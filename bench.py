@@ -75,7 +75,41 @@ def clock_dependence(args, block, layers, stash_views, fl, stream):
         return float(np.mean([a.elapsed_time(b) for a, b in ev[1:]])) * 1e-3
 
     t_zero, t_real = time_launches(lz, 4), time_launches(lb, 4)
-    return {"projection": block[big].name, "tflops_on_the_workload": fl[big]["seq_grads"] / t_real / 1e12,
+    power = None
+    if args.clock_probe:
+        # what the board reports while each case runs for a few seconds: socket power and the XCDs' clocks
+        import re
+        import subprocess
+        import threading
+
+        def smi():
+            try:
+                out = subprocess.run(["amd-smi", "metric", "-p", "-c"], capture_output=True, text=True, timeout=20).stdout
+            except (OSError, subprocess.SubprocessError):
+                return None
+            pw = re.search(r"SOCKET_POWER:\s*(\d+)", out)
+            clk = [int(x) for x in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)", out)]
+            return {"socket_power_w": int(pw.group(1)) if pw else None, "xcd_clocks_mhz": clk[:8]}
+
+        def sustained(layer, seconds=4.0):
+            stop = time.time() + seconds
+            samples = []
+
+            def poll():
+                time.sleep(1.5)
+                while time.time() < stop - 0.3:
+                    samples.append(smi())
+                    time.sleep(0.7)
+            th = threading.Thread(target=poll)
+            th.start()
+            while time.time() < stop:
+                for _ in range(20):
+                    isopo.seq_grads(layer, stash_views[big], stream=stream)
+                torch.cuda.synchronize()
+            th.join()
+            return [x for x in samples if x]
+        power = {"zero_operands": sustained(lz), "workload": sustained(lb)}
+    return {"projection": block[big].name, **({"board": power} if power else {}), "tflops_on_the_workload": fl[big]["seq_grads"] / t_real / 1e12,
             "tflops_on_zero_operands": fl[big]["seq_grads"] / t_zero / 1e12,
             "zero_ms": t_zero * 1e3, "workload_ms": t_real * 1e3,
             "what": "same launch, same cycles; the clock under random operands is about 1.75 GHz, on zeros 2.4 GHz (profiles/)"}
@@ -231,7 +265,7 @@ def main() -> int:
         zero_operands = clock_dependence(args, block, layers, stash_views, fl, stream)
         if args.clock_probe:
             # for a counter run (GRBM_GUI_ACTIVE): five launches on zeros, then five on the workload, nothing else after
-            print(json.dumps({k: zero_operands[k] for k in ("projection", "zero_ms", "workload_ms")}))
+            print(json.dumps({k: zero_operands[k] for k in ("projection", "zero_ms", "workload_ms", "board") if k in zero_operands}))
             return 0
     total_flops = float(sum(sum(f.values()) for f in fl)) * sweeps
     reinforce_flops = float(sum(f["seq_grads"] for f in fl)) * sweeps
