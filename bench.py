@@ -50,7 +50,7 @@ def read_traffic(kernel_tag: str):
     return None
 
 
-def clock_dependence(args, block, layers, stash_views, fl, stream):
+def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
     """The same launch of the largest projection on all-zero operands.  The kernel executes the same
     instructions and cycles whatever the values; the part's power management does not: with operands
     that do not toggle it holds the full clock.  The ratio says how much of the gap to the 2.4 GHz
@@ -68,7 +68,7 @@ def clock_dependence(args, block, layers, stash_views, fl, stream):
         for _ in range(n + 1):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            isopo.seq_grads(layer, stash_views[big], stream=stream)
+            isopo.seq_grads(layer, stash_views[big], stream=stream, max_workgroups=256, queue=wg_queue)
             e1.record(stream)
             ev.append((e0, e1))
         torch.cuda.synchronize()
@@ -104,7 +104,7 @@ def clock_dependence(args, block, layers, stash_views, fl, stream):
             th.start()
             while time.time() < stop:
                 for _ in range(20):
-                    isopo.seq_grads(layer, stash_views[big], stream=stream)
+                    isopo.seq_grads(layer, stash_views[big], stream=stream, max_workgroups=256, queue=wg_queue)
                 torch.cuda.synchronize()
             th.join()
             return [x for x in samples if x]
@@ -242,12 +242,14 @@ def main() -> int:
     stash_views = [ws[: isopo.stash_nbytes(l)].view(torch.bfloat16 if l.dtype == isopo.BF16 else torch.float32)
                    .view(l.n_seq, l.d_out, l.d_in) for l in layers]
     reps = max(3, args.steps // 2)
+    wg_queue = torch.zeros(8, dtype=torch.int32, device=dev)
     durs = []
     for _ in range(reps):
         for l, sv in zip(layers, stash_views):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            isopo.seq_grads(l, sv, stream=stream)
+            # the launch isopo_layer_gram makes: one persistent workgroup per compute unit
+            isopo.seq_grads(l, sv, stream=stream, max_workgroups=256, queue=wg_queue)
             e1.record(stream)
             durs.append((e0, e1))
     torch.cuda.synchronize()
@@ -262,7 +264,7 @@ def main() -> int:
     # peak is the clock under real data rather than the kernel's schedule.
     zero_operands = None
     if not args.no_clock_dependence or args.clock_probe:
-        zero_operands = clock_dependence(args, block, layers, stash_views, fl, stream)
+        zero_operands = clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue)
         if args.clock_probe:
             # for a counter run (GRBM_GUI_ACTIVE): five launches on zeros, then five on the workload, nothing else after
             print(json.dumps({k: zero_operands[k] for k in ("projection", "zero_ms", "workload_ms", "board") if k in zero_operands}))
@@ -356,7 +358,7 @@ def main() -> int:
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
                       "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
-        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true> (per-sequence gradients -> stash)",
+        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true> (per-sequence gradients -> stash, persistent launch)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
                      "flops_per_launch": seq_grad_flops_per_launch,

@@ -143,6 +143,19 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
  * (`ntk[i, j] = torch.sum(seq_grads[i] * seq_grads[j])`), n_elem = d_out * d_in
  * elements per sequence.  workspace >= isopo_stash_gram_workspace(n_seq). */
 isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream);
+
+/* isopo_seq_grads on a budget of compute units, for callers that overlap this layer's contraction with
+ * bandwidth-bound work queued on another stream (the Gram pass and the stash-weighted sum of the layer
+ * before): at most max_workgroups workgroups are resident at a time, each on a compute unit of its own,
+ * and the other units stay free.  The result is the same stash, bit for bit.
+ *   max_workgroups  0: no limit (isopo_seq_grads).  Otherwise 8..256, rounded down to a multiple of 8
+ *                   (the workgroups are dealt evenly to the 8 accelerator dies).  Honoured for bf16
+ *                   layers large enough for the 256x256 tile with more tiles than the budget; smaller
+ *                   problems and fp32 inputs run as isopo_seq_grads does.
+ *   queue_dev       device uint32[8], 4-byte aligned, caller-owned scratch; zeroed and used by the call
+ *                   (work counters); must not be shared by launches that may run concurrently */
+isopo_status isopo_seq_grads_limited(const isopo_layer* layer, void* stash, int32_t max_workgroups,
+                                     uint32_t* queue_dev, void* stream);
 size_t isopo_stash_gram_workspace(int32_t n_seq);
 isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_seq, int64_t n_elem, float* K,
                               void* workspace, size_t ws_bytes, void* stream);

@@ -19,6 +19,7 @@ constexpr int kTileRows = 256;        // output rows per tile of the contraction
 bool materialised_ok(int n_seq, isopo_dtype t) { return n_seq <= 128 || t == ISOPO_BF16; }
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+constexpr int kComputeUnits = 256;        // MI355X
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 size_t elem_size(isopo_dtype t) { return t == ISOPO_BF16 ? 2 : 4; }
 
@@ -76,9 +77,11 @@ size_t stash_bytes(const isopo_layer* l, int rows) {
   return (size_t)l->n_seq * (size_t)rows * (size_t)l->d_in * elem_size(l->dtype);
 }
 
-size_t partial_bytes(const isopo_layer* l) {
+// Gram partial sums, then one aligned block holding the contraction's eight work counters.
+size_t gram_partial_bytes(const isopo_layer* l) {
   return align_up(stash_gram_partial_bytes(l->n_seq, l->dtype == ISOPO_BF16));
 }
+size_t partial_bytes(const isopo_layer* l) { return gram_partial_bytes(l) + kAlign; }
 
 size_t ghost_bytes(const isopo_layer* l) {
   return align_up((size_t)l->n_seq * l->n_seq * sizeof(double)) + align_up((size_t)l->n_tokens * sizeof(int32_t));
@@ -222,6 +225,9 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
     a.out = ws; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
     a.row0 = r0; a.rows = rows; a.out_row0 = whole ? 0 : r0; a.out_seq_stride = seq_stride;
     a.beta = 0.f; a.per_sequence = true; a.bf16 = bf16;
+    // one persistent workgroup per compute unit, fed from counters behind the Gram partials
+    a.max_workgroups = kComputeUnits;
+    a.queue = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(partials) + gram_partial_bytes(layer));
     if (launch_seq_grad(a, s) != hipSuccess) return ISOPO_ERR_HIP;
     StashGramArgs g;
     g.stash = ws; g.seq_stride = seq_stride;
@@ -234,10 +240,19 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
 }
 
 isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream) {
+  return isopo_seq_grads_limited(layer, stash, 0, nullptr, stream);
+}
+
+isopo_status isopo_seq_grads_limited(const isopo_layer* layer, void* stash, int32_t max_workgroups,
+                                     uint32_t* queue_dev, void* stream) {
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
   if (!stash || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
+  if (max_workgroups != 0 && (max_workgroups < 8 || max_workgroups > 256 || !queue_dev ||
+                              (reinterpret_cast<uintptr_t>(queue_dev) & 3u)))
+    return ISOPO_ERR_INVALID_ARG;
   SeqGradArgs a;
+  a.max_workgroups = max_workgroups; a.queue = queue_dev;
   a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.off_host = layer->seq_offsets_host; a.c = nullptr;
   a.out = stash; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
   a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0;

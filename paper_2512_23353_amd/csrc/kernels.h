@@ -25,6 +25,10 @@ struct SeqGradArgs {
   float beta;
   bool per_sequence;
   bool bf16;
+  // per_sequence, bf16: at most this many workgroups resident at a time (0: no limit), fed from `queue`,
+  // eight device counters the launch zeroes; the other compute units stay free for other streams
+  int max_workgroups = 0;
+  unsigned* queue = nullptr;
 };
 // Launch plan of the streaming bf16 contraction (host arithmetic only).
 struct ContractionPlan {

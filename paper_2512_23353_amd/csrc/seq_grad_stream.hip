@@ -60,6 +60,7 @@ struct StreamParams {
   unsigned n_blocks;
   int n_chunks, chunk_tokens;      // sum-over-all-tokens mode: token chunks (1: no split)
   int xcd_start[9];                // XCD x takes (item, tile) pairs [xcd_start[x], xcd_start[x+1]), item-major
+  unsigned* queue;                 // persistent mode: eight work counters, one per XCD, zero at launch
 };
 
 // Raw buffer descriptor over [base, base + bytes): loads beyond it return zero.
@@ -100,8 +101,9 @@ __device__ __forceinline__ float acc_read(float a) {
 
 constexpr int BK = 32;
 
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false>
 __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
+  static_assert(PER_SEQ || !PERSIST, "the persistent mode serves the per-sequence gradients");
   constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
   constexpr unsigned PA = BM * 2, PB = BN * 2;                 // LDS row pitch, bytes (no padding: swizzled)
   constexpr unsigned A_BYTES = BK * PA, B_BYTES = BK * PB, STAGE = A_BYTES + B_BYTES;
@@ -112,290 +114,311 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  int item, tile;
-  const bool split = !PER_SEQ && p.n_chunks > 1;
-  if (PER_SEQ || split) {
-    const int tiles = p.tiles_m * p.tiles_n;
-    const int x = blockIdx.x & 7, e = blockIdx.x >> 3;
-    if (p.xcd_start[8] > 0) {
-      // XCD x (= blockIdx % 8) walks a contiguous range of the item-major (item, tile) list; the host cut
-      // the list into eight ranges of equal work
-      const int id = p.xcd_start[x] + e;
-      if (id >= p.xcd_start[x + 1]) return;
-      item = id / tiles;
-      tile = id - item * tiles;
+  // Persistent mode (per-sequence only): the grid is a chosen number of workgroups, a multiple of eight;
+  // the workgroups of XCD x pull that XCD's work items one at a time from the counter queue[x].  The
+  // launch then occupies that many compute units and no more, and kernels queued on other streams (the
+  // passes over the previous layer's stash) run on the rest.
+  __shared__ int sh_next;
+  for (int round = 0;; ++round) {
+    int e;
+    if constexpr (PERSIST) {
+      if (round > 0) {
+        // nobody still reads the previous item's LDS (epilogue staging) or its sh_next
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+      }
+      if (tid == 0) sh_next = (int)atomicAdd(p.queue + (blockIdx.x & 7), 1u);
+      __syncthreads();
+      e = sh_next;
     } else {
-      // XCD x owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence (or token chunk)
-      const int s0 = x * tiles / 8, cs = (x + 1) * tiles / 8 - s0;
-      if (cs == 0 || e >= (PER_SEQ ? p.n_seq : p.n_chunks) * cs) return;
-      item = e / cs;
-      tile = s0 + e % cs;
+      e = (int)(blockIdx.x >> 3);
     }
-  } else {
-    item = 0;
-    tile = xcd_contiguous(blockIdx.x, p.n_blocks);
-  }
-  // Column-blocked tile order: ids run down 8-column strips of the tile grid, so the 32 workgroups an
-  // XCD runs at a time cover about 4 tile rows x 8 tile columns (12 operand panels) rather than
-  // 2 x 16 (18 panels): fewer L2 misses per flop.
-  int tile_m, tile_n;
-  {
-    constexpr int W = 8;
-    const int strip = tile / (p.tiles_m * W);
-    const int c0 = strip * W;
-    const int w = p.tiles_n - c0 < W ? p.tiles_n - c0 : W;     // the last strip may be narrower
-    const int in_strip = tile - strip * p.tiles_m * W;
-    tile_m = in_strip / w;
-    tile_n = c0 + in_strip % w;
-  }
-  const int m0 = p.row0 + tile_m * BM, n0 = tile_n * BN;
-  const int t0 = PER_SEQ ? p.off[item] : item * p.chunk_tokens;
-  const int t1 = PER_SEQ ? p.off[item + 1] : min(p.n_tokens, t0 + p.chunk_tokens);
-  const int n_rows = t1 - t0;
-  const int n_tiles = (n_rows + BK - 1) / BK;
-  const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
-
-  unsigned offA[LA], offB[LB];
-#pragma unroll
-  for (int q = 0; q < LA; ++q) {
-    const int r = (wave * LA + q) * RA + lane / (64 / RA);
-    const int f = ((r & 3) << 2) ^ (r & 2);
-    const int g = (lane % (64 / RA)) ^ f;
-    offA[q] = (unsigned)r * rbA + (unsigned)(m0 * 2 + g * 16);
-  }
-#pragma unroll
-  for (int q = 0; q < LB; ++q) {
-    const int r = (wave * LB + q) * RB + lane / (64 / RB);
-    const int f = ((r & 3) << 2) ^ (r & 2);
-    const int g = (lane % (64 / RB)) ^ f;
-    offB[q] = (unsigned)r * rbB + (unsigned)(n0 * 2 + g * 16);
-  }
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  const u16* baseA = p.Delta + (size_t)t0 * p.d_out;
-  const u16* baseB = p.X + (size_t)t0 * p.d_in;
-  auto issue_loads = [&](int it) {
-    int rows = n_rows - it * BK;
-    rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
-    v4i ra = make_rsrc(baseA + (size_t)it * BK * p.d_out, (unsigned)rows * rbA);
-    v4i rb = make_rsrc(baseB + (size_t)it * BK * p.d_in, (unsigned)rows * rbB);
-    const unsigned stage = smem_base + (unsigned)(it % NSTAGE) * STAGE;
-#pragma unroll
-    for (int q = 0; q < LA; ++q) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
-#pragma unroll
-    for (int q = 0; q < LB; ++q) load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + q) * 1024, offB[q]);
-  };
-
-  unsigned adA[FM], adB[FN];
-  {
-    const int l = lane & 15, g4 = lane >> 4;
-    const int kr = 8 * (g4 >> 1) + (l >> 2);
-    const int f = ((kr & 3) << 2) ^ (kr & 2);
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      const int ca = wm * WM + i * 32 + 16 * (g4 & 1) + 4 * (l & 3);
-      adA[i] = (unsigned)kr * PA + (unsigned)(((ca >> 3) ^ f) << 4) + (unsigned)((ca & 7) * 2);
-    }
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int cb = wn * WN + j * 32 + 16 * (g4 & 1) + 4 * (l & 3);
-      adB[j] = A_BYTES + (unsigned)kr * PB + (unsigned)(((cb >> 3) ^ f) << 4) + (unsigned)((cb & 7) * 2);
-    }
-  }
-  auto frA = [&](unsigned a) {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PA));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-  };
-  auto frB = [&](unsigned a) {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PB));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-  };
-
-  f32x16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
-  constexpr int LPT = LA + LB;   // loads per wave and tile
-  // Token blocks in flight ahead of the one being multiplied.  The stage a block leaves is free as soon
-  // as the barrier after its second half's fragment reads has been passed, so the ring can carry NSTAGE
-  // blocks ahead; the per-sequence mode, whose stash stores compete with the operand fetches, runs
-  // better one block shallower.
-  constexpr int AHEAD = PER_SEQ ? NSTAGE - 1 : NSTAGE;
-  constexpr int NRD = 2 * (FM + FN), NMF = FM * FN;
-
-  // Per-sequence mode, 256x256 tile: the two waves of the lower tile half read their fragments behind
-  // MFMAs 8..15 of a half block instead of 0..7, in the order the next half block first uses them
-  // (B0, A0, B1, B2, B3, A1, A2, A3), so the LDS serves two waves' reads at a time, not four.
-  // frag_of: the fragment read behind MFMA idx (-1: none).
-  auto frag_of = [](int idx, bool late, bool& is_a) -> int {
-    const int k = idx - (late ? NMF - FM - FN : 0);
-    if (k < 0 || k >= FM + FN) return -1;
-    if (!late) { is_a = k < FM; return is_a ? k : k - FM; }
-    if (k == 0) { is_a = false; return 0; }
-    if (k == 1) { is_a = true; return 0; }
-    if (k <= FN) { is_a = false; return k - 1; }
-    is_a = true; return k - FN;
-  };
-  const bool late_wave = PER_SEQ && NMF >= 2 * (FM + FN) && (wave_s & 2);
-
-#pragma unroll
-  for (int s = 0; s < AHEAD; ++s) issue_loads(s);
-
-  if (n_tiles > 0) {
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 1) * LPT) & 15) | ((((AHEAD - 1) * LPT) >> 4) << 14));
-    __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int i = 0; i < FM; ++i) fa0[i] = frA(smem_base + adA[i]);
-#pragma unroll
-    for (int j = 0; j < FN; ++j) fb0[j] = frB(smem_base + adB[j]);
-    // one token block; LATE: this wave's fragment-read slots (compile-time, so that both bodies stay
-    // straight-line code)
-    auto token_block = [&](int it, auto late_c) {
-      constexpr bool LATE = decltype(late_c)::value;
-      const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
-      if constexpr (PER_SEQ) {
-        // written out MFMA by MFMA: one fragment's reads behind each MFMA of this wave's read slots
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            const int idx = i * FN + j;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
-            bool is_a = false;
-            const int f = frag_of(idx, LATE, is_a);
-            if (f >= 0) {
-              if (is_a) fa1[f] = frA(sb + adA[f] + 16 * PA);
-              else fb1[f] = frB(sb + adB[f] + 16 * PB);
-            }
-          }
-        }
+    int item, tile;
+    const bool split = !PER_SEQ && p.n_chunks > 1;
+    if (PER_SEQ || split) {
+      const int tiles = p.tiles_m * p.tiles_n;
+      const int x = blockIdx.x & 7;
+      if (p.xcd_start[8] > 0) {
+        // XCD x (= blockIdx % 8) walks a contiguous range of the item-major (item, tile) list; the host cut
+        // the list into eight ranges of equal work
+        const int id = p.xcd_start[x] + e;
+        if (id >= p.xcd_start[x + 1]) break;
+        item = id / tiles;
+        tile = id - item * tiles;
       } else {
-        // sum-over-all-tokens mode: the scheduler places the reads, one per MFMA
-#pragma unroll
-        for (int i = 0; i < FM; ++i) fa1[i] = frA(sb + adA[i] + 16 * PA);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) fb1[j] = frB(sb + adB[j] + 16 * PB);
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-        for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
-        }
+        // XCD x owns tiles [x*tiles/8, (x+1)*tiles/8) of every sequence (or token chunk)
+        const int s0 = x * tiles / 8, cs = (x + 1) * tiles / 8 - s0;
+        if (cs == 0 || e >= (PER_SEQ ? p.n_seq : p.n_chunks) * cs) break;
+        item = e / cs;
+        tile = s0 + e % cs;
       }
-      // block it+1 has landed (this wave's part; the barrier makes it everyone's) and this wave's fragment
-      // reads of block it are complete: its stage may be overwritten after the barrier
-      __builtin_amdgcn_s_waitcnt((AHEAD == NSTAGE ? 0x0070 : 0x0f70) | (((AHEAD - 2) * LPT) & 15) | ((((AHEAD - 2) * LPT) >> 4) << 14));
-      __builtin_amdgcn_s_barrier();
-      const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
-      // second half block: its 16 MFMAs carry the fragment reads of the next block's first half and the
-      // DMA instructions of the block AHEAD ahead
-      {
-        const int nb = it + AHEAD;
-        int rows = n_rows - nb * BK;
-        rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
-        const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
-        const v4i rb = make_rsrc(baseB + (size_t)nb * BK * p.d_in, (unsigned)rows * rbB);
-        const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            const int idx = i * FN + j;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-            bool is_a = false;
-            const int f = frag_of(idx, LATE, is_a);
-            if (f >= 0) {
-              if (is_a) fa0[f] = frA(sn + adA[f]);
-              else fb0[f] = frB(sn + adB[f]);
-            }
-            // the LPT DMA instructions spread evenly over the NMF MFMAs
-#pragma unroll
-            for (int q = idx * LPT / NMF; q < (idx + 1) * LPT / NMF; ++q) {
-              if (q < LA) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
-              else load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + (q - LA)) * 1024, offB[q - LA]);
-            }
-          }
-        }
-      }
-    };
-    if (late_wave) {
-      for (int it = 0; it < n_tiles; ++it) token_block(it, std::true_type{});
     } else {
-      for (int it = 0; it < n_tiles; ++it) token_block(it, std::false_type{});
+      item = 0;
+      tile = xcd_contiguous(blockIdx.x, p.n_blocks);
     }
-  }
-  __builtin_amdgcn_s_waitcnt(0x0f70);
+    // Column-blocked tile order: ids run down 8-column strips of the tile grid, so the 32 workgroups an
+    // XCD runs at a time cover about 4 tile rows x 8 tile columns (12 operand panels) rather than
+    // 2 x 16 (18 panels): fewer L2 misses per flop.
+    int tile_m, tile_n;
+    {
+      constexpr int W = 8;
+      const int strip = tile / (p.tiles_m * W);
+      const int c0 = strip * W;
+      const int w = p.tiles_n - c0 < W ? p.tiles_n - c0 : W;     // the last strip may be narrower
+      const int in_strip = tile - strip * p.tiles_m * W;
+      tile_m = in_strip / w;
+      tile_n = c0 + in_strip % w;
+    }
+    const int m0 = p.row0 + tile_m * BM, n0 = tile_n * BN;
+    const int t0 = PER_SEQ ? p.off[item] : item * p.chunk_tokens;
+    const int t1 = PER_SEQ ? p.off[item + 1] : min(p.n_tokens, t0 + p.chunk_tokens);
+    const int n_rows = t1 - t0;
+    const int n_tiles = (n_rows + BK - 1) / BK;
+    const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
 
-  if (PER_SEQ) {
-    __builtin_amdgcn_s_barrier();
-    // the last MFMAs have retired before the accumulators are read by hand (acc_read is opaque to the
-    // compiler's hazard tracking)
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-    constexpr unsigned PT = 80;
-    // a 256-register tile lives in AGPRs (one wave per SIMD); smaller tiles stay in VGPRs
-    auto rd = [](float a) {
-      if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
+    unsigned offA[LA], offB[LB];
+#pragma unroll
+    for (int q = 0; q < LA; ++q) {
+      const int r = (wave * LA + q) * RA + lane / (64 / RA);
+      const int f = ((r & 3) << 2) ^ (r & 2);
+      const int g = (lane % (64 / RA)) ^ f;
+      offA[q] = (unsigned)r * rbA + (unsigned)(m0 * 2 + g * 16);
+    }
+#pragma unroll
+    for (int q = 0; q < LB; ++q) {
+      const int r = (wave * LB + q) * RB + lane / (64 / RB);
+      const int f = ((r & 3) << 2) ^ (r & 2);
+      const int g = (lane % (64 / RB)) ^ f;
+      offB[q] = (unsigned)r * rbB + (unsigned)(n0 * 2 + g * 16);
+    }
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const u16* baseA = p.Delta + (size_t)t0 * p.d_out;
+    const u16* baseB = p.X + (size_t)t0 * p.d_in;
+    auto issue_loads = [&](int it) {
+      int rows = n_rows - it * BK;
+      rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+      v4i ra = make_rsrc(baseA + (size_t)it * BK * p.d_out, (unsigned)rows * rbA);
+      v4i rb = make_rsrc(baseB + (size_t)it * BK * p.d_in, (unsigned)rows * rbB);
+      const unsigned stage = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+#pragma unroll
+      for (int q = 0; q < LA; ++q) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
+#pragma unroll
+      for (int q = 0; q < LB; ++q) load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + q) * 1024, offB[q]);
     };
-    const unsigned W = smem_base + (unsigned)wave * 8192;
-    const int h = lane >> 5, nl = lane & 31;
-    const int l = lane & 15, gq = lane >> 4;
-    u16* outp = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride;
+
+    unsigned adA[FM], adB[FN];
+    {
+      const int l = lane & 15, g4 = lane >> 4;
+      const int kr = 8 * (g4 >> 1) + (l >> 2);
+      const int f = ((kr & 3) << 2) ^ (kr & 2);
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+      for (int i = 0; i < FM; ++i) {
+        const int ca = wm * WM + i * 32 + 16 * (g4 & 1) + 4 * (l & 3);
+        adA[i] = (unsigned)kr * PA + (unsigned)(((ca >> 3) ^ f) << 4) + (unsigned)((ca & 7) * 2);
+      }
 #pragma unroll
-      for (int jp = 0; jp < FN / 2; ++jp) {
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int j = jp * 2 + jj;
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            v2u pk;
-            pk.x = pack_bf16(rd(acc[i][j][4 * g]), rd(acc[i][j][4 * g + 1]));
-            pk.y = pack_bf16(rd(acc[i][j][4 * g + 2]), rd(acc[i][j][4 * g + 3]));
-            const unsigned a = W + (unsigned)(jj * 32 + nl) * PT + (unsigned)(8 * g + 4 * h) * 2;
-            *(v2u __attribute__((address_space(3)))*)(a) = pk;
-          }
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const int rb = s >> 1, pc = (s & 1) * 4 + gq;
-          const unsigned a = W + (unsigned)(8 * pc + (l >> 2)) * PT + (unsigned)(16 * rb + 4 * (l & 3)) * 2;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PT));
-          const int m = m0 + wm * WM + i * 32 + 16 * rb + l;
-          const int n = n0 + wn * WN + jp * 64 + 8 * pc;
-          if (m < p.row_end && n < p.d_in)
-            *(s16x8*)(outp + (size_t)(m - p.out_row0) * p.d_in + n) =
-                __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
+      for (int j = 0; j < FN; ++j) {
+        const int cb = wn * WN + j * 32 + 16 * (g4 & 1) + 4 * (l & 3);
+        adB[j] = A_BYTES + (unsigned)kr * PB + (unsigned)(((cb >> 3) ^ f) << 4) + (unsigned)((cb & 7) * 2);
       }
     }
-  } else {
-    const int col = lane & 31;
+    auto frA = [&](unsigned a) {
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PA));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto frB = [&](unsigned a) {
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PB));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    f32x16 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + col;
-        if (n >= p.d_in) continue;
+      for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          if (m >= p.row_end) continue;
-          float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
-          if (split) atomicAdd(o, acc[i][j][v]);        // beta already applied by the pass before
-          else *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+    constexpr int LPT = LA + LB;   // loads per wave and tile
+    // Token blocks in flight ahead of the one being multiplied.  The stage a block leaves is free as soon
+    // as the barrier after its second half's fragment reads has been passed, so the ring can carry NSTAGE
+    // blocks ahead; the per-sequence mode, whose stash stores compete with the operand fetches, runs
+    // better one block shallower.
+    constexpr int AHEAD = PER_SEQ ? NSTAGE - 1 : NSTAGE;
+    constexpr int NRD = 2 * (FM + FN), NMF = FM * FN;
+
+    // Per-sequence mode, 256x256 tile: the two waves of the lower tile half read their fragments behind
+    // MFMAs 8..15 of a half block instead of 0..7, in the order the next half block first uses them
+    // (B0, A0, B1, B2, B3, A1, A2, A3), so the LDS serves two waves' reads at a time, not four.
+    // frag_of: the fragment read behind MFMA idx (-1: none).
+    auto frag_of = [](int idx, bool late, bool& is_a) -> int {
+      const int k = idx - (late ? NMF - FM - FN : 0);
+      if (k < 0 || k >= FM + FN) return -1;
+      if (!late) { is_a = k < FM; return is_a ? k : k - FM; }
+      if (k == 0) { is_a = false; return 0; }
+      if (k == 1) { is_a = true; return 0; }
+      if (k <= FN) { is_a = false; return k - 1; }
+      is_a = true; return k - FN;
+    };
+    const bool late_wave = PER_SEQ && NMF >= 2 * (FM + FN) && (wave_s & 2);
+
+#pragma unroll
+    for (int s = 0; s < AHEAD; ++s) issue_loads(s);
+
+    if (n_tiles > 0) {
+      __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 1) * LPT) & 15) | ((((AHEAD - 1) * LPT) >> 4) << 14));
+      __builtin_amdgcn_s_barrier();
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa0[i] = frA(smem_base + adA[i]);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb0[j] = frB(smem_base + adB[j]);
+      // one token block; LATE: this wave's fragment-read slots (compile-time, so that both bodies stay
+      // straight-line code)
+      auto token_block = [&](int it, auto late_c) {
+        constexpr bool LATE = decltype(late_c)::value;
+        const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+        if constexpr (PER_SEQ) {
+          // written out MFMA by MFMA: one fragment's reads behind each MFMA of this wave's read slots
+#pragma unroll
+          for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+              const int idx = i * FN + j;
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+              bool is_a = false;
+              const int f = frag_of(idx, LATE, is_a);
+              if (f >= 0) {
+                if (is_a) fa1[f] = frA(sb + adA[f] + 16 * PA);
+                else fb1[f] = frB(sb + adB[f] + 16 * PB);
+              }
+            }
+          }
+        } else {
+          // sum-over-all-tokens mode: the scheduler places the reads, one per MFMA
+#pragma unroll
+          for (int i = 0; i < FM; ++i) fa1[i] = frA(sb + adA[i] + 16 * PA);
+#pragma unroll
+          for (int j = 0; j < FN; ++j) fb1[j] = frB(sb + adB[j] + 16 * PB);
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+          for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
+          }
+        }
+        // block it+1 has landed (this wave's part; the barrier makes it everyone's) and this wave's fragment
+        // reads of block it are complete: its stage may be overwritten after the barrier
+        __builtin_amdgcn_s_waitcnt((AHEAD == NSTAGE ? 0x0070 : 0x0f70) | (((AHEAD - 2) * LPT) & 15) | ((((AHEAD - 2) * LPT) >> 4) << 14));
+        __builtin_amdgcn_s_barrier();
+        const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
+        // second half block: its 16 MFMAs carry the fragment reads of the next block's first half and the
+        // DMA instructions of the block AHEAD ahead
+        {
+          const int nb = it + AHEAD;
+          int rows = n_rows - nb * BK;
+          rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+          const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
+          const v4i rb = make_rsrc(baseB + (size_t)nb * BK * p.d_in, (unsigned)rows * rbB);
+          const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
+#pragma unroll
+          for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+              const int idx = i * FN + j;
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+              bool is_a = false;
+              const int f = frag_of(idx, LATE, is_a);
+              if (f >= 0) {
+                if (is_a) fa0[f] = frA(sn + adA[f]);
+                else fb0[f] = frB(sn + adB[f]);
+              }
+              // the LPT DMA instructions spread evenly over the NMF MFMAs
+#pragma unroll
+              for (int q = idx * LPT / NMF; q < (idx + 1) * LPT / NMF; ++q) {
+                if (q < LA) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
+                else load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + (q - LA)) * 1024, offB[q - LA]);
+              }
+            }
+          }
+        }
+      };
+      if (late_wave) {
+        for (int it = 0; it < n_tiles; ++it) token_block(it, std::true_type{});
+      } else {
+        for (int it = 0; it < n_tiles; ++it) token_block(it, std::false_type{});
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+
+    if (PER_SEQ) {
+      __builtin_amdgcn_s_barrier();
+      // the last MFMAs have retired before the accumulators are read by hand (acc_read is opaque to the
+      // compiler's hazard tracking)
+      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+      constexpr unsigned PT = 80;
+      // a 256-register tile lives in AGPRs (one wave per SIMD); smaller tiles stay in VGPRs
+      auto rd = [](float a) {
+        if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
+      };
+      const unsigned W = smem_base + (unsigned)wave * 8192;
+      const int h = lane >> 5, nl = lane & 31;
+      const int l = lane & 15, gq = lane >> 4;
+      u16* outp = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int jp = 0; jp < FN / 2; ++jp) {
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const int j = jp * 2 + jj;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              v2u pk;
+              pk.x = pack_bf16(rd(acc[i][j][4 * g]), rd(acc[i][j][4 * g + 1]));
+              pk.y = pack_bf16(rd(acc[i][j][4 * g + 2]), rd(acc[i][j][4 * g + 3]));
+              const unsigned a = W + (unsigned)(jj * 32 + nl) * PT + (unsigned)(8 * g + 4 * h) * 2;
+              *(v2u __attribute__((address_space(3)))*)(a) = pk;
+            }
+          }
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const int rb = s >> 1, pc = (s & 1) * 4 + gq;
+            const unsigned a = W + (unsigned)(8 * pc + (l >> 2)) * PT + (unsigned)(16 * rb + 4 * (l & 3)) * 2;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * PT));
+            const int m = m0 + wm * WM + i * 32 + 16 * rb + l;
+            const int n = n0 + wn * WN + jp * 64 + 8 * pc;
+            if (m < p.row_end && n < p.d_in)
+              *(s16x8*)(outp + (size_t)(m - p.out_row0) * p.d_in + n) =
+                  __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          }
         }
       }
+    } else {
+      const int col = lane & 31;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int n = n0 + wn * WN + j * 32 + col;
+          if (n >= p.d_in) continue;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (m >= p.row_end) continue;
+            float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
+            if (split) atomicAdd(o, acc[i][j][v]);        // beta already applied by the pass before
+            else *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
+          }
+        }
+    }
+    if constexpr (!PERSIST) break;
   }
 }
 
@@ -412,9 +435,17 @@ __global__ __launch_bounds__(256) void apply_beta_kernel(float* __restrict__ o, 
   }
 }
 
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ>
-hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStream_t s) {
+__global__ void queue_zero_kernel(unsigned* queue) {
+  if (threadIdx.x < 8) queue[threadIdx.x] = 0u;
+}
+
+// n_wg > 0 (per-sequence mode, 256x256 tile): persistent launch of n_wg workgroups, a multiple of eight,
+// pulling work from `queue` (eight device counters, zeroed here on the stream).
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false>
+hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStream_t s, int n_wg = 0,
+                         unsigned* queue = nullptr) {
   StreamParams p;
+  p.queue = queue;
   p.X = static_cast<const u16*>(a.X); p.Delta = static_cast<const u16*>(a.Delta); p.off = a.off; p.out = a.out;
   p.d_in = a.d_in; p.d_out = a.d_out; p.n_seq = a.n_seq; p.n_tokens = a.n_tokens;
   p.row0 = a.row0; p.row_end = a.row0 + a.rows; p.out_row0 = a.out_row0;
@@ -429,7 +460,7 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   p.n_blocks = (unsigned)pl.blocks;
   constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
   constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
-  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ>;
+  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST>;
   // once per process (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -440,7 +471,12 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
     const long long n = (long long)a.rows * a.d_in;
     hipLaunchKernelGGL(apply_beta_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s, band, n, a.beta);
   }
-  hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(256), smem, s, p);
+  if constexpr (PERSIST) {
+    hipLaunchKernelGGL(queue_zero_kernel, dim3(1), dim3(64), 0, s, queue);
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(256), smem, s, p);
+  } else {
+    hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(256), smem, s, p);
+  }
   return hipGetLastError();
 }
 
@@ -449,6 +485,9 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
 // bf16, unscaled (per-sequence stash, or plain sum over all tokens).
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
   const ContractionPlan pl = plan_contraction(a.rows, a.d_in, a.n_tokens, a.n_seq, a.off_host, a.per_sequence);
+  // a workgroup budget applies to the large tile's per-sequence launches that would not fit it anyway
+  if (a.per_sequence && a.max_workgroups > 0 && a.queue && pl.tile == 256 && pl.blocks > a.max_workgroups)
+    return launch_stream<256, 256, 4, 1, true, true>(a, pl, s, a.max_workgroups / 8 * 8, a.queue);
   if (a.per_sequence)
     return pl.tile == 256 ? launch_stream<256, 256, 4, 1, true>(a, pl, s) : launch_stream<128, 128, 4, 2, true>(a, pl, s);
   return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false>(a, pl, s) : launch_stream<128, 128, 4, 2, false>(a, pl, s);

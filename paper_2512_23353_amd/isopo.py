@@ -28,7 +28,7 @@ _PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALI
 _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
 EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_plan", "isopo_layer_gram",
-           "isopo_transform_ema", "isopo_seq_grads",
+           "isopo_transform_ema", "isopo_seq_grads_limited", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
@@ -81,6 +81,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_layer_gram.restype = ctypes.c_int
     lib.isopo_seq_grads.argtypes = [lp, vp, vp]
     lib.isopo_seq_grads.restype = ctypes.c_int
+    lib.isopo_seq_grads_limited.argtypes = [lp, vp, i32, vp, vp]
+    lib.isopo_seq_grads_limited.restype = ctypes.c_int
     lib.isopo_stash_gram_workspace.argtypes = [i32]
     lib.isopo_stash_gram_workspace.restype = sz
     lib.isopo_stash_gram.argtypes = [vp, ctypes.c_int, i32, ctypes.c_int64, vp, vp, sz, vp]
@@ -240,11 +242,19 @@ def stash_nbytes(layer: Layer) -> int:
     return layer.n_seq * layer.d_out * layer.d_in * (2 if layer.dtype == BF16 else 4)
 
 
-def seq_grads(layer: Layer, stash: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """The stash of per-sequence gradients [n_seq, d_out, d_in] in the input dtype."""
+def seq_grads(layer: Layer, stash: Optional[torch.Tensor] = None, stream=None, max_workgroups: int = 0,
+              queue: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The stash of per-sequence gradients [n_seq, d_out, d_in] in the input dtype.  max_workgroups > 0:
+    at most that many compute units are used (queue: int32/uint32 device tensor of 8 elements, scratch)."""
     if stash is None:
         stash = torch.empty((layer.n_seq, layer.d_out, layer.d_in), dtype=layer.X.dtype, device=layer.device)
-    _check(load().isopo_seq_grads(layer.ref(), stash.data_ptr(), _stream(stream)), "isopo_seq_grads")
+    if max_workgroups:
+        if queue is None:
+            queue = torch.zeros(8, dtype=torch.int32, device=layer.device)
+        _check(load().isopo_seq_grads_limited(layer.ref(), stash.data_ptr(), int(max_workgroups), queue.data_ptr(),
+                                              _stream(stream)), "isopo_seq_grads_limited")
+    else:
+        _check(load().isopo_seq_grads(layer.ref(), stash.data_ptr(), _stream(stream)), "isopo_seq_grads")
     return stash
 
 

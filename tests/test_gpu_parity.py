@@ -371,3 +371,37 @@ def test_hip_graph_replays_match_eager(gpu_device):
                 assert torch.equal(g, w), f"replay {rep}: {name}"
     assert torch.equal(eager[0], K)         # K does not depend on A
     A.copy_(A0)
+
+
+@pytest.mark.parametrize("dims,budget", [((512, 768), 8), ((512, 768), 64), ((1024, 512), 224), ((768, 512), 16)])
+def test_per_sequence_gradients_on_a_compute_unit_budget(gpu_device, dims, budget):
+    """isopo_seq_grads_limited: a persistent launch of `budget` workgroups pulls
+    the (sequence, tile) items from per-XCD counters.  Same arithmetic per item,
+    so the stash must equal the unlimited launch bit for bit - with tile counts
+    that are and are not a multiple of eight, ragged and empty sequences, and
+    twice in a row on the same counters."""
+    d_in, d_out = dims
+    rng = np.random.default_rng(91)
+    n_seq = 80
+    lengths = [int(x) for x in rng.integers(0, 120, n_seq)]
+    lengths[3] = 0
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=13, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    plan = isopo.contraction_plan(layer.ref(), True)
+    assert plan["tile"] == 256 and plan["workgroups"] > budget
+    ref = isopo.seq_grads(layer)
+    queue = torch.full((8,), 12345, dtype=torch.int32, device=gpu_device)       # the call zeroes it
+    got = torch.full_like(ref, float("nan"))
+    for _ in range(2):
+        isopo.seq_grads(layer, got, max_workgroups=budget, queue=queue)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+        got.fill_(float("nan"))
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    assert rel_err(ref.float().cpu().numpy(), G) < 4e-3
+    # a small problem ignores the budget and still answers
+    small = wl.custom_layer(64, 64, [5, 9], dtype="bf16", seed=14, sigma_delta=1e-2)
+    ls, _ = to_device(small, gpu_device)
+    assert torch.equal(isopo.seq_grads(ls, max_workgroups=8).view(torch.int16), isopo.seq_grads(ls).view(torch.int16))
+    with pytest.raises(isopo.IsopoError):
+        isopo.seq_grads(layer, got, max_workgroups=4, queue=queue)
