@@ -76,7 +76,7 @@ def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
 
     t_zero, t_real = time_launches(lz, 4), time_launches(lb, 4)
     power = None
-    if args.clock_probe:
+    if args.board_probe:
         # what the board reports while each case runs for a few seconds: socket power and the XCDs' clocks
         import re
         import subprocess
@@ -120,6 +120,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--no-clock-dependence", action="store_true",
                     help="skip the zero-operand launches of the largest projection (keeps kernel profiles to the step's own launches)")
+    ap.add_argument("--board-probe", action="store_true",
+                    help="with --clock-probe: also sample socket power and XCD clocks (amd-smi, a child process) while "
+                         "each case loops for four seconds; not under rocprofv3, whose preloaded library makes every "
+                         "child a GPU process")
     ap.add_argument("--clock-probe", action="store_true",
                     help="only time the largest projection's stash launch on zero operands and on the workload, then exit")
     ap.add_argument("--steps", type=int, default=10)
@@ -266,7 +270,8 @@ def main() -> int:
     if not args.no_clock_dependence or args.clock_probe:
         zero_operands = clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue)
         if args.clock_probe:
-            # for a counter run (GRBM_GUI_ACTIVE): five launches on zeros, then five on the workload, nothing else after
+            # for a counter run (GRBM_GUI_ACTIVE): five launches on zeros, then five on the workload, nothing else
+            # after; no child processes unless --board-probe asks for them
             print(json.dumps({k: zero_operands[k] for k in ("projection", "zero_ms", "workload_ms", "board") if k in zero_operands}))
             return 0
     total_flops = float(sum(sum(f.values()) for f in fl)) * sweeps
