@@ -113,7 +113,9 @@ isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, do
  *                      work, XCD x walks [xcd_start[x], xcd_start[x+1]).  All zero: no list - per-sequence
  *                      mode with tiles % 8 == 0 gives XCD x the x-th eighth of every sequence's tiles,
  *                      the unsplit unweighted mode has one item
- *   workgroups         grid size (some workgroups may find their XCD's range exhausted and exit) */
+ *   workgroups         grid size of the one-workgroup-per-pair launch (some workgroups may find their XCD's
+ *                      range exhausted and exit); isopo_layer_gram and isopo_seq_grads_limited launch at most
+ *                      256 (or the budget) persistent workgroups over the same list instead */
 typedef struct {
   int32_t tile, workgroups_per_cu, tiles, n_chunks, chunk_tokens;
   int32_t xcd_start[9];
