@@ -405,3 +405,43 @@ def test_per_sequence_gradients_on_a_compute_unit_budget(gpu_device, dims, budge
     assert torch.equal(isopo.seq_grads(ls, max_workgroups=8).view(torch.int16), isopo.seq_grads(ls).view(torch.int16))
     with pytest.raises(isopo.IsopoError):
         isopo.seq_grads(layer, got, max_workgroups=4, queue=queue)
+
+
+def test_hip_graph_replays_of_the_persistent_launch(gpu_device):
+    """isopo_layer_gram on a layer large enough for the persistent launch (one
+    workgroup per compute unit, work counters in the workspace zeroed by a
+    kernel, not a memset), captured in a HIP graph: every replay, with eager
+    work of the same kind between replays, must reproduce K and the stash bit
+    for bit for the buffers' current contents."""
+    rng = np.random.default_rng(23)
+    lengths = [int(x) for x in rng.integers(1, 90, 96)]
+    prob = wl.custom_layer(512, 768, lengths, dtype="bf16", seed=15, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    assert isopo.contraction_plan(layer.ref(), True)["workgroups"] > 256
+    _, full, _ = isopo.gram_plan(layer, "materialised")
+    ws = isopo.alloc_workspace(full, gpu_device)
+    ws_eager = isopo.alloc_workspace(full, gpu_device)
+    K = torch.empty((96, 96), dtype=torch.float32, device=gpu_device)
+    K_eager = torch.empty_like(K)
+    n_stash = isopo.stash_nbytes(layer)
+
+    def run(k, w):
+        isopo.layer_gram(layer, "materialised", K=k, workspace=w, keep_stash=True)
+
+    run(K, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(K, ws)
+    X0 = layer.X.clone()
+    for rep in range(3):
+        layer.X.copy_(X0 * (1.0 + rep))     # the graph reads the buffers' current contents
+        K.fill_(float("nan"))
+        ws.fill_(0xFF)                      # counters included: the launch zeroes them itself
+        graph.replay()
+        torch.cuda.synchronize()
+        run(K_eager, ws_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(K, K_eager), f"replay {rep}"
+        assert torch.equal(ws[:n_stash], ws_eager[:n_stash]), f"replay {rep}: stash"
+    layer.X.copy_(X0)
