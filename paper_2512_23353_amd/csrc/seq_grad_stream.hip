@@ -304,8 +304,11 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 #pragma unroll
           for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < FN; ++j) {
+              // odd rows of the tile walk the B fragments backwards: the fragment of the row change is reused
+              const int js = (i & 1) ? FN - 1 - j : j;
+              acc[i][js] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[js], acc[i][js], 0, 0, 0);
+            }
 #pragma unroll
           for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -331,7 +334,10 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
               const int idx = i * FN + j;
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+              {
+              const int js = (!PER_SEQ && (i & 1)) ? FN - 1 - j : j;      // as in the first half block
+              acc[i][js] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[js], acc[i][js], 0, 0, 0);
+            }
               bool is_a = false;
               const int f = frag_of(idx, LATE, is_a);
               if (f >= 0) {
