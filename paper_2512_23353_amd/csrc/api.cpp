@@ -47,11 +47,14 @@ isopo_status check_layer(const isopo_layer* l, bool need_dev) {
 // Rates of this library's own kernels, measured on one MI355X, used only to rank the two Gram paths.
 // Materialised: the tiled MFMA contraction writes the stash while it computes (whichever of the two takes
 // longer bounds that launch), then the Gram pass reads the stash once.  Ghost: two token-by-token Gram
-// matrices over d_in + d_out features; a workgroup walks all features of its 128x128 token-tile pair
-// serially, which sets a floor however few tokens there are.
+// matrices over d_in + d_out features; a workgroup walks the features of its 128x128 token-tile pair
+// serially (all of them, or one range of them when there are fewer tile pairs than compute units), which
+// sets a floor however few tokens there are.
 constexpr double kRateContraction = 1.0e15;   // flop/s, per-sequence gradient kernel
 constexpr double kRateGhost = 5.5e14;         // token-pair-features/s, ghost kernel
 constexpr double kGhostPerFeature = 9.0e-9;   // s per feature of the serial walk
+constexpr double kGhostParts = 4.0e-6;        // s, the kernel that sums the feature ranges' parts ...
+constexpr double kRateGhostParts = 2.5e12;    // ... plus B/s over the parts
 constexpr double kRateStash = 3.7e12;         // B/s, stash write / read
 constexpr double kLaunch = 6.0e-6;            // s per kernel launch in the chain
 
@@ -60,8 +63,15 @@ void cost_model(const isopo_layer* l, double* t_ghost, double* t_mat) {
   const double D = di * d_o;
   // ghost: the kernel works on 128-token tiles, so a short batch still pays whole tiles
   const double nt = (double)((l->n_tokens + 127) / 128) * 128.0;
-  const double walk = kGhostPerFeature * (di + d_o), pairs = nt * nt * (di + d_o) / kRateGhost;
-  *t_ghost = (walk > pairs ? walk : pairs) + 4 * kLaunch;
+  // few tile pairs: the bf16 kernel cuts the features into `split` ranges (1/split the walk) and a second
+  // kernel sums the ranges' parts
+  const double split = l->dtype == ISOPO_BF16 ? (double)ghost_feature_split((int)l->n_tokens, l->d_in, l->d_out) : 1.0;
+  const double walk = kGhostPerFeature * (di + d_o) / split, pairs = nt * nt * (di + d_o) / kRateGhost;
+  const double parts = split > 1.0 ? kGhostParts + (double)ghost_parts_bytes((int)l->n_tokens, l->d_in, l->d_out) /
+                                                       kRateGhostParts
+                                   : 0.0;
+  // five short launches back to back (fill, token map, products, parts, finish) cost about three isolated ones
+  *t_ghost = (walk > pairs ? walk : pairs) + 3 * kLaunch + parts;
   // materialised: every tile is padded to whole 32-token blocks per sequence
   double n_pad = 0;
   for (int i = 0; i < l->n_seq; ++i) {
@@ -84,7 +94,9 @@ size_t gram_partial_bytes(const isopo_layer* l) {
 size_t partial_bytes(const isopo_layer* l) { return gram_partial_bytes(l) + kAlign; }
 
 size_t ghost_bytes(const isopo_layer* l) {
-  return align_up((size_t)l->n_seq * l->n_seq * sizeof(double)) + align_up((size_t)l->n_tokens * sizeof(int32_t));
+  const size_t parts = l->dtype == ISOPO_BF16 ? ghost_parts_bytes((int)l->n_tokens, l->d_in, l->d_out) : 0;
+  return align_up((size_t)l->n_seq * l->n_seq * sizeof(double)) + align_up((size_t)l->n_tokens * sizeof(int32_t)) +
+         align_up(parts);
 }
 
 isopo_gram_path resolve(const isopo_layer* l, isopo_gram_path req) {
@@ -192,6 +204,8 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
     g.bf16 = bf16;
     g.K64 = reinterpret_cast<double*>(ws);
     g.tok_seq = reinterpret_cast<int32_t*>(ws + align_up((size_t)layer->n_seq * layer->n_seq * sizeof(double)));
+    g.parts = reinterpret_cast<float*>(reinterpret_cast<char*>(g.tok_seq) +
+                                       align_up((size_t)layer->n_tokens * sizeof(int32_t)));
     g.K = K;
     return launch_ghost_gram(g, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
   }

@@ -138,14 +138,14 @@ __device__ __forceinline__ void ghost_load_lds16(const void* gptr, unsigned lds_
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
 
-// acc[bi][bj] (32x32: rows = tokens of tile ti, columns = tokens of tile tj) += over the d features of M
+// acc[bi][bj] (32x32: rows = tokens of tile ti, columns = tokens of tile tj) += over 64-feature slices
+// [k_begin, k_end) of the d features of M
 __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restrict__ M, int d, int n_tokens, int ti,
-                                                   int tj, unsigned smem_base, int lane, int wave,
-                                                   f32x16 (&acc)[2][2]) {
+                                                   int tj, unsigned smem_base, int lane, int wave, int k_begin,
+                                                   int k_end, f32x16 (&acc)[2][2]) {
   constexpr int KW = 64, LPW = 8;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int wi = wave >> 1, wj = wave & 1;
-  const int n_super = (d + KW - 1) / KW;
   const char* src[LPW];
   int vec_off[LPW];
 #pragma unroll
@@ -162,18 +162,18 @@ __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restr
       long long byte = (long long)k * 128 + vec_off[q];
       const long long last = ((long long)d - 8) * 2;
       if (byte > last) byte = last;                                 // tail and look-ahead: stays inside the row
-      ghost_load_lds16(src[q] + byte, smem_base + (unsigned)(k % kGStages) * kGStageBytes +
+      ghost_load_lds16(src[q] + byte, smem_base + (unsigned)((k - k_begin) % kGStages) * kGStageBytes +
                                           (unsigned)(wave_s * LPW + q) * 1024);
     }
   };
 #pragma unroll
-  for (int s = 0; s < kGStages - 1; ++s) issue(s);
+  for (int s = 0; s < kGStages - 1; ++s) issue(k_begin + s);
   const int frow = lane & 31, half = lane >> 5;
-  for (int k = 0; k < n_super; ++k) {
+  for (int k = k_begin; k < k_end; ++k) {
     __builtin_amdgcn_s_waitcnt(0x0f70 | (((kGStages - 2) * LPW) & 15) | ((((kGStages - 2) * LPW) >> 4) << 14));
     __builtin_amdgcn_s_barrier();
     issue(k + kGStages - 1);
-    const unsigned sb = smem_base + (unsigned)(k % kGStages) * kGStageBytes;
+    const unsigned sb = smem_base + (unsigned)((k - k_begin) % kGStages) * kGStageBytes;
     const int valid = d - k * KW;
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
@@ -198,14 +198,72 @@ __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restr
   __builtin_amdgcn_s_barrier();            // the ring is reused by the next pass
 }
 
+// One 32x32 block of the token-pair matrix: rows t0.., columns s0.. .  False when the block lies past the last
+// token or wholly below the diagonal (every pair has t > s); wave-uniform.
+__device__ __forceinline__ bool ghost_block_live(int t0, int s0, int n_tokens) {
+  return t0 < n_tokens && s0 < n_tokens && t0 <= s0;
+}
+
+// K64[seq(t)][seq(s)] += w P Q over the pairs t <= s of a live 32x32 block (w = 2 for the off-diagonal pairs of one
+// sequence, which stand for their mirror images too).  Lane holds column s = s0 + lane%32 and rows
+// t = t0 + acc_row(v, lane).
+__device__ __forceinline__ void ghost_block_reduce(const f32x16& P, const f32x16& Q, int t0, int s0, int lane,
+                                                   const int32_t* __restrict__ tok_seq, int n_tokens, int n_seq,
+                                                   double* __restrict__ K64) {
+  const int s = s0 + (lane & 31);
+  const bool s_ok = s < n_tokens;
+  const int q = s_ok ? tok_seq[s] : -1;
+  const int t_last = min(t0 + 31, n_tokens - 1), s_last = min(s0 + 31, n_tokens - 1);
+  const int r_first = tok_seq[t0], r_last = tok_seq[t_last];
+  const int q_first = tok_seq[s0], q_last = tok_seq[s_last];
+  const bool uniform = (r_first == r_last) && (q_first == q_last);
+  double run = 0.0;
+  int run_r = -1;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int t = t0 + acc_row(v, lane);
+    if (t >= n_tokens || !s_ok || t > s) continue;
+    const int r = uniform ? r_first : tok_seq[t];
+    const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
+    const double h = w * (double)P[v] * (double)Q[v];
+    if (uniform) {
+      run += h;
+    } else {
+      if (r != run_r) {
+        if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+        run_r = r;
+        run = 0.0;
+      }
+      run += h;
+    }
+  }
+  if (uniform) {
+    run = wave_sum(run);
+    if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
+  } else if (run_r >= 0) {
+    atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+  }
+}
+
+constexpr int kGBlockFloats = 16 * 64;            // one wave's 32x32 accumulator block
+constexpr int kGTileFloats = 16 * kGBlockFloats;  // the 16 blocks of a 128x128 tile
+
+// SPLIT = false: one workgroup per tile pair walks all features and adds its pairs to K64.
+// SPLIT = true (few tile pairs, a short microbatch): the 64-feature slices of both operands are cut into `split`
+// ranges and workgroup (pair, a) forms the parts P_a, Q_a of the two products over range a only; the parts go to
+// `parts` [pair][a][P, Q][block][v][lane] in fp32, and ghost_gram_parts_kernel sums them before the Hadamard
+// product, which is not linear in the ranges.
+template <bool SPLIT>
 __global__ __launch_bounds__(256) void ghost_gram_tiled_kernel(const unsigned short* __restrict__ X,
                                                                const unsigned short* __restrict__ Delta,
                                                                const int32_t* __restrict__ tok_seq, int n_tokens,
                                                                int d_in, int d_out, int n_seq, int n_tiles,
+                                                               int split, float* __restrict__ parts,
                                                                double* __restrict__ K64) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
-  int ti = 0, rem = blockIdx.x;              // blockIdx.x enumerates tile pairs (ti <= tj) row by row
+  const int fa = SPLIT ? (int)(blockIdx.x % (unsigned)split) : 0;
+  int ti = 0, rem = SPLIT ? (int)(blockIdx.x / (unsigned)split) : (int)blockIdx.x;   // tile pairs (ti <= tj) row by row
   while (rem >= n_tiles - ti) { rem -= n_tiles - ti; ++ti; }
   const int tj = ti + rem;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -218,52 +276,76 @@ __global__ __launch_bounds__(256) void ghost_gram_tiled_kernel(const unsigned sh
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) { P[a][b][v] = 0.f; Q[a][b][v] = 0.f; }
-  ghost_product_pass(X, d_in, n_tokens, ti, tj, smem_base, lane, wave, P);
-  ghost_product_pass(Delta, d_out, n_tokens, ti, tj, smem_base, lane, wave, Q);
+  const int nx = (d_in + 63) / 64, nd = (d_out + 63) / 64;       // 64-feature slices
+  if constexpr (SPLIT) {
+    ghost_product_pass(X, d_in, n_tokens, ti, tj, smem_base, lane, wave, (int)((long long)nx * fa / split),
+                       (int)((long long)nx * (fa + 1) / split), P);
+    ghost_product_pass(Delta, d_out, n_tokens, ti, tj, smem_base, lane, wave, (int)((long long)nd * fa / split),
+                       (int)((long long)nd * (fa + 1) / split), Q);
+  } else {
+    ghost_product_pass(X, d_in, n_tokens, ti, tj, smem_base, lane, wave, 0, nx, P);
+    ghost_product_pass(Delta, d_out, n_tokens, ti, tj, smem_base, lane, wave, 0, nd, Q);
+  }
 
-  const int r32 = lane & 31;
 #pragma unroll
   for (int bi = 0; bi < 2; ++bi) {
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) {
       const int t0 = ti * kGT + wi * 64 + bi * 32, s0 = tj * kGT + wj * 64 + bj * 32;
-      if (t0 >= n_tokens || s0 >= n_tokens || t0 > s0) continue;      // wave-uniform; t0 > s0: every pair has t > s
-      // lane holds column s = s0 + lane%32 and rows t = t0 + acc_row(v, lane)
-      const int s = s0 + r32;
-      const bool s_ok = s < n_tokens;
-      const int q = s_ok ? tok_seq[s] : -1;
-      const int t_last = min(t0 + 31, n_tokens - 1), s_last = min(s0 + 31, n_tokens - 1);
-      const int r_first = tok_seq[t0], r_last = tok_seq[t_last];
-      const int q_first = tok_seq[s0], q_last = tok_seq[s_last];
-      const bool uniform = (r_first == r_last) && (q_first == q_last);
-      double run = 0.0;
-      int run_r = -1;
+      if (!ghost_block_live(t0, s0, n_tokens)) continue;
+      if constexpr (SPLIT) {
+        float* dst = parts + (size_t)blockIdx.x * (2 * kGTileFloats) + (size_t)(wave * 4 + bi * 2 + bj) * kGBlockFloats;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int t = t0 + acc_row(v, lane);
-        if (t >= n_tokens || !s_ok || t > s) continue;
-        const int r = uniform ? r_first : tok_seq[t];
-        const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
-        const double h = w * (double)P[bi][bj][v] * (double)Q[bi][bj][v];
-        if (uniform) {
-          run += h;
-        } else {
-          if (r != run_r) {
-            if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
-            run_r = r;
-            run = 0.0;
-          }
-          run += h;
+        for (int v = 0; v < 16; ++v) {
+          dst[v * 64 + lane] = P[bi][bj][v];
+          dst[kGTileFloats + v * 64 + lane] = Q[bi][bj][v];
         }
-      }
-      if (uniform) {
-        run = wave_sum(run);
-        if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
-      } else if (run_r >= 0) {
-        atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+      } else {
+        ghost_block_reduce(P[bi][bj], Q[bi][bj], t0, s0, lane, tok_seq, n_tokens, n_seq, K64);
       }
     }
   }
+}
+
+// Second step of the split launch: one workgroup per (tile pair, 32x32 block).  Wave w sums the parts
+// a = w, w + 4, ... of P and of Q; the four partial sums meet in LDS and wave 0 forms the products.
+__global__ __launch_bounds__(256) void ghost_gram_parts_kernel(const float* __restrict__ parts,
+                                                               const int32_t* __restrict__ tok_seq, int n_tokens,
+                                                               int n_seq, int n_tiles, int split,
+                                                               double* __restrict__ K64) {
+  __shared__ float sums[4][2][kGBlockFloats];
+  const int blk = blockIdx.x & 15;                 // wave * 4 + bi * 2 + bj of the first step
+  int ti = 0, rem = blockIdx.x >> 4;
+  while (rem >= n_tiles - ti) { rem -= n_tiles - ti; ++ti; }
+  const int tj = ti + rem;
+  const int w1 = blk >> 2, bi = (blk >> 1) & 1, bj = blk & 1;
+  const int t0 = ti * kGT + (w1 >> 1) * 64 + bi * 32, s0 = tj * kGT + (w1 & 1) * 64 + bj * 32;
+  if (!ghost_block_live(t0, s0, n_tokens)) return;          // uniform over the workgroup
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  f32x16 P, Q;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { P[v] = 0.f; Q[v] = 0.f; }
+  for (int a = wave; a < split; a += 4) {
+    const float* src = parts + ((size_t)(blockIdx.x >> 4) * split + a) * (2 * kGTileFloats) + (size_t)blk * kGBlockFloats;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      P[v] += src[v * 64 + lane];
+      Q[v] += src[kGTileFloats + v * 64 + lane];
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    sums[wave][0][v * 64 + lane] = P[v];
+    sums[wave][1][v * 64 + lane] = Q[v];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    P[v] = (sums[0][0][v * 64 + lane] + sums[1][0][v * 64 + lane]) + (sums[2][0][v * 64 + lane] + sums[3][0][v * 64 + lane]);
+    Q[v] = (sums[0][1][v * 64 + lane] + sums[1][1][v * 64 + lane]) + (sums[2][1][v * 64 + lane] + sums[3][1][v * 64 + lane]);
+  }
+  ghost_block_reduce(P, Q, t0, s0, lane, tok_seq, n_tokens, n_seq, K64);
 }
 
 __global__ void ghost_finish_kernel(const double* __restrict__ K64, int n_seq, float* __restrict__ K) {
@@ -291,12 +373,28 @@ hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s) {
       const int nt = (a.n_tokens + kGT - 1) / kGT;
       constexpr size_t smem = (size_t)kGStages * kGStageBytes;
       // once per process (static initialisation is thread-safe); a failure is returned by every call
-      static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_gram_tiled_kernel),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      static const hipError_t attr = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_gram_tiled_kernel<false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(ghost_gram_tiled_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      }();
       if (attr != hipSuccess) return attr;
-      hipLaunchKernelGGL(ghost_gram_tiled_kernel, dim3((unsigned)((long long)nt * (nt + 1) / 2)), dim3(256), smem, s,
-                         static_cast<const unsigned short*>(a.X), static_cast<const unsigned short*>(a.Delta), a.tok_seq,
-                         a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, a.K64);
+      const int split = ghost_feature_split(a.n_tokens, a.d_in, a.d_out);
+      const unsigned n_pairs = (unsigned)((long long)nt * (nt + 1) / 2);
+      const unsigned short* Xb = static_cast<const unsigned short*>(a.X);
+      const unsigned short* Db = static_cast<const unsigned short*>(a.Delta);
+      if (split > 1) {
+        if (!a.parts) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(ghost_gram_tiled_kernel<true>, dim3(n_pairs * split), dim3(256), smem, s, Xb, Db, a.tok_seq,
+                           a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, split, a.parts, a.K64);
+        hipLaunchKernelGGL(ghost_gram_parts_kernel, dim3(n_pairs * 16), dim3(256), 0, s, a.parts, a.tok_seq, a.n_tokens,
+                           a.n_seq, nt, split, a.K64);
+      } else {
+        hipLaunchKernelGGL(ghost_gram_tiled_kernel<false>, dim3(n_pairs), dim3(256), smem, s, Xb, Db, a.tok_seq,
+                           a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, 1, static_cast<float*>(nullptr), a.K64);
+      }
     } else
       hipLaunchKernelGGL((ghost_gram_kernel<false>), dim3((unsigned)pairs), dim3(256), 0, s, a.X, a.Delta, a.tok_seq,
                          a.n_tokens, a.d_in, a.d_out, a.n_seq, (int)n_tiles, a.K64);

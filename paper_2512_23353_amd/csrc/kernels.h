@@ -86,9 +86,30 @@ struct GhostArgs {
   bool bf16;
   int32_t* tok_seq;          // workspace [n_tokens]
   double* K64;               // workspace [n_seq*n_seq]
+  float* parts;              // workspace [ghost_parts_bytes / 4], bf16 with ghost_feature_split > 1 only
   float* K;
 };
 hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s);
+// bf16 ghost kernel: ranges the 64-feature slices of X and Delta are cut into when the microbatch has too few
+// 128x128 token-tile pairs to give every compute unit a workgroup (1: no split).  A workgroup then forms the
+// two token-by-token products over one range, and a second kernel sums the ranges.  Host arithmetic, shared by
+// the launcher, the workspace size and the cost model.
+inline int ghost_feature_split(int n_tokens, int d_in, int d_out) {
+  const long long nt = (n_tokens + 127) / 128, pairs = nt * (nt + 1) / 2;
+  if (pairs <= 0) return 1;
+  const long long slices = (d_in + 63) / 64 + (d_out + 63) / 64;
+  long long split = 256 / pairs;                       // one workgroup per compute unit (LDS ring: 128 KiB)
+  if (split > slices / 16) split = slices / 16;        // a range is worth its prologue from 16 slices on
+  if (split > 32) split = 32;
+  return split < 1 ? 1 : (int)split;
+}
+// fp32 parts of the split launch: per (tile pair, range) the two 128x128 products
+inline size_t ghost_parts_bytes(int n_tokens, int d_in, int d_out) {
+  const int split = ghost_feature_split(n_tokens, d_in, d_out);
+  if (split <= 1) return 0;
+  const size_t nt = (size_t)(n_tokens + 127) / 128;
+  return nt * (nt + 1) / 2 * (size_t)split * 2 * 128 * 128 * sizeof(float);
+}
 
 // dst[t][:] = c[seq(t)] * src[t][:] (rounded to the storage type).
 hipError_t launch_scale_rows(const void* src, bool bf16, long long n_tokens, int d, const int32_t* off, int n_seq,

@@ -77,6 +77,36 @@ def test_ragged_edge_cases(gpu_device, dtype, case, path):
     _check_step(prob, gpu_device, path, "fisher", 1e-2, isopo.REG_REL_TRACE)
 
 
+GHOST_SPLIT_CASES = [
+    # name, d_in, d_out, lengths: wide layers on few tokens, where the bf16 ghost launch cuts the features
+    # into ranges; 64-feature tails, and an operand with fewer 64-feature slices than ranges
+    ("two_ranges_feature_tails", 1096, 1000, [100, 37, 1, 0, 250, 64]),
+    ("three_ranges_narrow_delta", 3000, 40, [31, 32, 33, 65]),
+    ("many_ranges_one_tile", 4096, 2048, [50, 9, 60]),
+    ("three_tile_pairs", 2048, 1536, [130, 1, 70, 20]),
+]
+
+
+@pytest.mark.parametrize("case", GHOST_SPLIT_CASES, ids=[c[0] for c in GHOST_SPLIT_CASES])
+def test_ghost_feature_ranges(gpu_device, case):
+    _, d_in, d_out, lengths = case
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=23, sigma_delta=1e-2, rho=0.5)
+    layer, _ = to_device(prob, gpu_device)
+    n_tiles = (sum(lengths) + 127) // 128
+    slices = (d_in + 63) // 64 + (d_out + 63) // 64
+    split = min(256 // (n_tiles * (n_tiles + 1) // 2), slices // 16, 32)
+    assert split > 1
+    # the workspace carries the fp32 parts of every (tile pair, range)
+    _, full, _ = isopo.gram_plan(layer, "ghost")
+    assert full >= n_tiles * (n_tiles + 1) // 2 * split * 2 * 128 * 128 * 4
+    _check_step(prob, gpu_device, "ghost", "interacting", 1e-2, isopo.REG_REL_TRACE)
+    Kg, _ = isopo.layer_gram(layer, "ghost")
+    Km, _ = isopo.layer_gram(layer, "materialised")
+    torch.cuda.synchronize()
+    assert torch.equal(Kg, Kg.T)
+    assert rel_err(Km.cpu().numpy(), Kg.cpu().numpy()) < 1e-3
+
+
 def test_both_gram_paths_agree_and_are_symmetric(gpu_device):
     prob = wl.custom_layer(512, 768, [300, 517, 33, 260, 128], dtype="bf16", seed=4, sigma_delta=1e-2, rho=0.7)
     layer, _ = to_device(prob, gpu_device)

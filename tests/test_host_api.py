@@ -96,8 +96,10 @@ def test_cost_model_prefers_ghost_only_for_few_tokens():
         tg, tm = isopo.gram_cost_model(lay)
         assert tg > 0 and tm > 0
         assert (isopo.gram_plan(lay)[0] == "ghost") == (tg < tm)
-    # a handful of sequences on a narrow layer: the stash is small, the ghost walk is not
-    assert isopo.gram_plan(_host_layer([64] * 4, 4096, 1024))[0] == "materialised"
+    # a narrow layer: the stash is small, so the materialised path wins as soon as the token-tile pairs
+    # fill the chip and the ghost kernel no longer cuts its walk over the features into ranges
+    assert isopo.gram_plan(_host_layer([64] * 4, 4096, 1024))[0] == "ghost"
+    assert isopo.gram_plan(_host_layer([512] * 4, 4096, 1024))[0] == "materialised"
     choices, ghost_costs = [], []
     for t in (8, 64, 256, 512, 1024, 4096):
         lay = _host_layer([t] * 16, 5120, 27648)
