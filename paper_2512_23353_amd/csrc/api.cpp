@@ -51,10 +51,7 @@ isopo_status check_layer(const isopo_layer* l, bool need_dev) {
 // serially (all of them, or one range of them when there are fewer tile pairs than compute units), which
 // sets a floor however few tokens there are.
 constexpr double kRateContraction = 1.0e15;   // flop/s, per-sequence gradient kernel
-constexpr double kRateGhost = 5.5e14;         // token-pair-features/s, ghost kernel
-constexpr double kGhostPerFeature = 9.0e-9;   // s per feature of the serial walk
-constexpr double kGhostParts = 4.0e-6;        // s, the kernel that sums the feature ranges' parts ...
-constexpr double kRateGhostParts = 2.5e12;    // ... plus B/s over the parts
+constexpr double kRateGhost = 7.0e14;         // token-pair-features/s, ghost kernel
 constexpr double kRateStash = 3.7e12;         // B/s, stash write / read
 constexpr double kLaunch = 6.0e-6;            // s per kernel launch in the chain
 
@@ -63,15 +60,14 @@ void cost_model(const isopo_layer* l, double* t_ghost, double* t_mat) {
   const double D = di * d_o;
   // ghost: the kernel works on 128-token tiles, so a short batch still pays whole tiles
   const double nt = (double)((l->n_tokens + 127) / 128) * 128.0;
-  // few tile pairs: the bf16 kernel cuts the features into `split` ranges (1/split the walk) and a second
-  // kernel sums the ranges' parts
-  const double split = l->dtype == ISOPO_BF16 ? (double)ghost_feature_split((int)l->n_tokens, l->d_in, l->d_out) : 1.0;
-  const double walk = kGhostPerFeature * (di + d_o) / split, pairs = nt * nt * (di + d_o) / kRateGhost;
-  const double parts = split > 1.0 ? kGhostParts + (double)ghost_parts_bytes((int)l->n_tokens, l->d_in, l->d_out) /
-                                                       kRateGhostParts
-                                   : 0.0;
+  // few tile pairs: the bf16 kernel cuts the features into ranges (a shorter walk) and a second kernel sums
+  // the ranges' parts
+  const long long tiles = (l->n_tokens + 127) / 128, tile_pairs = tiles * (tiles + 1) / 2;
+  const int split = l->dtype == ISOPO_BF16 ? ghost_feature_split((int)l->n_tokens, l->d_in, l->d_out) : 1;
+  const double walk = ghost_walk_time(tile_pairs, l->d_in, l->d_out, split);
+  const double pairs = nt * nt * (di + d_o) / kRateGhost;
   // five short launches back to back (fill, token map, products, parts, finish) cost about three isolated ones
-  *t_ghost = (walk > pairs ? walk : pairs) + 3 * kLaunch + parts;
+  *t_ghost = (walk > pairs ? walk : pairs) + 3 * kLaunch;
   // materialised: every tile is padded to whole 32-token blocks per sequence
   double n_pad = 0;
   for (int i = 0; i < l->n_seq; ++i) {

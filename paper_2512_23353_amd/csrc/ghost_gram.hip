@@ -123,43 +123,57 @@ __global__ __launch_bounds__(256) void ghost_gram_kernel(const void* __restrict_
 // ---- bf16, LDS-tiled ---------------------------------------------------------------------------------
 // One workgroup takes a 128x128 block of token pairs (tile ti <= tj).  The 128 + 128 token rows are
 // streamed global -> LDS in 64-feature slices (row-contiguous DMA, 16-byte columns XOR-swizzled with the
-// row so that the row-per-lane fragment reads spread over the banks) through a four-stage ring, first
-// over the d_in features of X (P), then over the d_out features of Delta (Q).  Each wave owns a 64x64
-// sub-block: two row fragments and two column fragments feed four MFMAs per 16-feature step.
+// row so that the row-per-lane fragment reads spread over the banks) through a two-stage ring, first
+// over the d_in features of X (P), then over the d_out features of Delta (Q).  Two workgroups share a
+// compute unit (64 KiB of LDS, 128 accumulator registers per lane each): one's barrier and DMA wait
+// overlap the other's MFMAs.  Each wave owns a 64x64 sub-block: two row fragments and two column
+// fragments feed four MFMAs per 16-feature step.
 typedef void __attribute__((address_space(3)))* lds_void_ptr;
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef v4u __attribute__((address_space(3)))* lds_v4u_ptr;
 
 constexpr int kGT = 128;                 // tokens per tile side
-constexpr int kGStages = 4;
-constexpr int kGStageBytes = 2 * kGT * 128;      // 256 rows x 128 bytes
+constexpr int kGKW = 64;                 // features per ring stage
+constexpr int kGStages = 2;
+constexpr int kGRowBytes = kGKW * 2;             // LDS row pitch
+constexpr int kGStageBytes = 2 * kGT * kGRowBytes;
+constexpr int kGRun = 64;                        // workgroups an XCD holds at a time: 32 compute units x 2
+static_assert(kGStages * kGStageBytes * 2 <= 160 * 1024, "two workgroups per compute unit share the LDS");
 
 __device__ __forceinline__ void ghost_load_lds16(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
 
-// acc[bi][bj] (32x32: rows = tokens of tile ti, columns = tokens of tile tj) += over 64-feature slices
+// 16-byte column c of LDS row `row` holds global column c ^ ghost_swizzle(row): sixteen consecutive rows read
+// at one global column then touch sixteen different groups of four banks.
+__device__ __forceinline__ int ghost_swizzle(int row) {
+  constexpr int cols = kGRowBytes / 16;          // 4 (64-byte rows) or 8 (128-byte rows)
+  return (row >> (cols == 4 ? 2 : 1)) & (cols - 1);
+}
+
+// acc[bi][bj] (32x32: rows = tokens of tile ti, columns = tokens of tile tj) += over kGKW-feature slices
 // [k_begin, k_end) of the d features of M
 __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restrict__ M, int d, int n_tokens, int ti,
                                                    int tj, unsigned smem_base, int lane, int wave, int k_begin,
                                                    int k_end, f32x16 (&acc)[2][2]) {
-  constexpr int KW = 64, LPW = 8;
+  constexpr int COLS = kGRowBytes / 16, ROWS_PER_LOAD = 64 / COLS;      // one wave-load is 1 KiB of whole rows
+  constexpr int LPW = 2 * kGT / ROWS_PER_LOAD / 4;                      // wave-loads per wave and stage
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int wi = wave >> 1, wj = wave & 1;
   const char* src[LPW];
   int vec_off[LPW];
 #pragma unroll
   for (int q = 0; q < LPW; ++q) {
-    const int row = (wave * LPW + q) * 8 + lane / 8;               // 0..255: tile ti's rows, then tile tj's
+    const int row = (wave * LPW + q) * ROWS_PER_LOAD + lane / COLS;  // 0..255: tile ti's rows, then tile tj's
     int tok = row < kGT ? ti * kGT + row : tj * kGT + (row - kGT);
     if (tok >= n_tokens) tok = n_tokens - 1;                        // rows past the end are masked in the epilogue
     src[q] = reinterpret_cast<const char*>(M + (size_t)tok * d);
-    vec_off[q] = ((lane % 8) ^ ((row >> 1) & 7)) * 16;
+    vec_off[q] = ((lane % COLS) ^ ghost_swizzle(row)) * 16;
   }
   auto issue = [&](int k) {
 #pragma unroll
     for (int q = 0; q < LPW; ++q) {
-      long long byte = (long long)k * 128 + vec_off[q];
+      long long byte = (long long)k * kGRowBytes + vec_off[q];
       const long long last = ((long long)d - 8) * 2;
       if (byte > last) byte = last;                                 // tail and look-ahead: stays inside the row
       ghost_load_lds16(src[q] + byte, smem_base + (unsigned)((k - k_begin) % kGStages) * kGStageBytes +
@@ -174,24 +188,42 @@ __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restr
     __builtin_amdgcn_s_barrier();
     issue(k + kGStages - 1);
     const unsigned sb = smem_base + (unsigned)((k - k_begin) % kGStages) * kGStageBytes;
-    const int valid = d - k * KW;
+    const int valid = d - k * kGKW;
+    // every 16-feature step has its own fragment registers, and the reads of step st + 1 are issued ahead of
+    // the MFMAs of step st: with one or two waves per SIMD nothing else hides the LDS latency
+    constexpr int KS = kGKW / 16;
+    v4u fa[KS][2], fb[KS][2];
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
+    for (int st = 0; st < KS; ++st) {
       const int vec = st * 2 + half;
-      v4u fa[2], fb[2];
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         const int ra = wi * 64 + b * 32 + frow, rb = kGT + wj * 64 + b * 32 + frow;
-        fa[b] = *(lds_v4u_ptr)(sb + (unsigned)ra * 128 + (unsigned)((vec ^ ((ra >> 1) & 7)) * 16));
-        fb[b] = *(lds_v4u_ptr)(sb + (unsigned)rb * 128 + (unsigned)((vec ^ ((rb >> 1) & 7)) * 16));
-        if (valid < KW && vec * 8 >= valid) fa[b] = v4u{0u, 0u, 0u, 0u};
+        fa[st][b] = *(lds_v4u_ptr)(sb + (unsigned)ra * kGRowBytes + (unsigned)((vec ^ ghost_swizzle(ra)) * 16));
+        fb[st][b] = *(lds_v4u_ptr)(sb + (unsigned)rb * kGRowBytes + (unsigned)((vec ^ ghost_swizzle(rb)) * 16));
       }
+    }
+    if (valid < kGKW) {                          // the last stage of a feature count that is not a multiple of 64
+#pragma unroll
+      for (int st = 0; st < KS; ++st)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          if ((st * 2 + half) * 8 >= valid) fa[st][b] = v4u{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int st = 0; st < KS; ++st)
 #pragma unroll
       for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
         for (int bj = 0; bj < 2; ++bj)
-          acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[bi]),
-                                                                __builtin_bit_cast(bf16x8, fb[bj]), acc[bi][bj], 0, 0, 0);
+          acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[st][bi]),
+                                                                __builtin_bit_cast(bf16x8, fb[st][bj]), acc[bi][bj], 0, 0, 0);
+    // order: reads of steps 0 and 1, then four MFMAs and the next step's four reads in turn
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int st = 0; st < KS; ++st) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      if (st + 2 < KS) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);
@@ -216,32 +248,82 @@ __device__ __forceinline__ void ghost_block_reduce(const f32x16& P, const f32x16
   const int t_last = min(t0 + 31, n_tokens - 1), s_last = min(s0 + 31, n_tokens - 1);
   const int r_first = tok_seq[t0], r_last = tok_seq[t_last];
   const int q_first = tok_seq[s0], q_last = tok_seq[s_last];
-  const bool uniform = (r_first == r_last) && (q_first == q_last);
+  if (r_first == r_last && q_first == q_last) {
+    // one sequence pair in the whole block: one wave sum, one atomic
+    double run = 0.0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int t = t0 + acc_row(v, lane);
+      if (t >= n_tokens || !s_ok || t > s) continue;
+      const double w = (t == s) ? 1.0 : ((r_first == q) ? 2.0 : 1.0);
+      run += w * (double)P[v] * (double)Q[v];
+    }
+    run = wave_sum(run);
+    if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
+    return;
+  }
+  const int n_r = r_last - r_first + 1, n_q = q_last - q_first + 1;
+  if (n_r * n_q <= 8) {
+    // a few sequence boundaries cross the block: one wave sum and one atomic per (row sequence, column
+    // sequence) rather than one atomic per lane and run, which would queue on K's few cache lines
+    for (int r = r_first; r <= r_last; ++r) {
+      double part = 0.0;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int t = t0 + acc_row(v, lane);
+        if (t >= n_tokens || !s_ok || t > s || tok_seq[t] != r) continue;
+        const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
+        part += w * (double)P[v] * (double)Q[v];
+      }
+      for (int c = q_first; c <= q_last; ++c) {
+        const double sum = wave_sum(q == c ? part : 0.0);
+        if (lane == 0 && sum != 0.0) atomicAdd(&K64[(size_t)r * n_seq + c], sum);
+      }
+    }
+    return;
+  }
+  // many short sequences: a lane adds each run of rows of one sequence by itself
   double run = 0.0;
   int run_r = -1;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int t = t0 + acc_row(v, lane);
     if (t >= n_tokens || !s_ok || t > s) continue;
-    const int r = uniform ? r_first : tok_seq[t];
+    const int r = tok_seq[t];
     const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
     const double h = w * (double)P[v] * (double)Q[v];
-    if (uniform) {
-      run += h;
-    } else {
-      if (r != run_r) {
-        if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
-        run_r = r;
-        run = 0.0;
-      }
-      run += h;
+    if (r != run_r) {
+      if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+      run_r = r;
+      run = 0.0;
     }
+    run += h;
   }
-  if (uniform) {
-    run = wave_sum(run);
-    if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
-  } else if (run_r >= 0) {
-    atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+  if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+}
+
+// Order of the tile pairs (ti <= tj) in the unsplit launch: bands of kGBand tile rows, column by column inside
+// a band, so that consecutive pairs form compact blocks of the triangle.
+constexpr int kGBand = 8;
+__device__ __forceinline__ void ghost_pair_at(long long pos, int n_tiles, int& ti, int& tj) {
+  int b0 = 0, h;
+  for (;;) {
+    h = min(kGBand, n_tiles - b0);                                           // rows of this band
+    const long long cnt = (long long)h * (h + 1) / 2 + (long long)h * (n_tiles - b0 - h);
+    if (pos < cnt) break;
+    pos -= cnt;
+    b0 += kGBand;
+  }
+  const int head = h * (h + 1) / 2;               // the band's first h columns hold 1, 2, ..., h pairs
+  if (pos < head) {
+    int j = 0;
+    while (pos >= j + 1) { pos -= j + 1; ++j; }
+    tj = b0 + j;
+    ti = b0 + (int)pos;
+  } else {
+    pos -= head;
+    tj = b0 + h + (int)(pos / h);
+    ti = b0 + (int)(pos % h);
   }
 }
 
@@ -251,10 +333,10 @@ constexpr int kGTileFloats = 16 * kGBlockFloats;  // the 16 blocks of a 128x128 
 // SPLIT = false: one workgroup per tile pair walks all features and adds its pairs to K64.
 // SPLIT = true (few tile pairs, a short microbatch): the 64-feature slices of both operands are cut into `split`
 // ranges and workgroup (pair, a) forms the parts P_a, Q_a of the two products over range a only; the parts go to
-// `parts` [pair][a][P, Q][block][v][lane] in fp32, and ghost_gram_parts_kernel sums them before the Hadamard
+// `parts` [pair][a][P, Q][block][lane][v] in fp32, and ghost_gram_parts_kernel sums them before the Hadamard
 // product, which is not linear in the ranges.
 template <bool SPLIT>
-__global__ __launch_bounds__(256) void ghost_gram_tiled_kernel(const unsigned short* __restrict__ X,
+__global__ __launch_bounds__(256, 2) void ghost_gram_tiled_kernel(const unsigned short* __restrict__ X,
                                                                const unsigned short* __restrict__ Delta,
                                                                const int32_t* __restrict__ tok_seq, int n_tokens,
                                                                int d_in, int d_out, int n_seq, int n_tiles,
@@ -262,10 +344,30 @@ __global__ __launch_bounds__(256) void ghost_gram_tiled_kernel(const unsigned sh
                                                                double* __restrict__ K64) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
-  const int fa = SPLIT ? (int)(blockIdx.x % (unsigned)split) : 0;
-  int ti = 0, rem = SPLIT ? (int)(blockIdx.x / (unsigned)split) : (int)blockIdx.x;   // tile pairs (ti <= tj) row by row
-  while (rem >= n_tiles - ti) { rem -= n_tiles - ti; ++ti; }
-  const int tj = ti + rem;
+  int fa = 0, ti = 0, tj, part = 0;
+  if constexpr (SPLIT) {
+    // Workgroups go to the eight XCDs round robin.  XCD x takes the x-th eighth of the range-major list of
+    // (range, tile pair): the columns of X and Delta that a range covers then pass through one or two L2s,
+    // not all eight.
+    const int x = blockIdx.x & 7, e = blockIdx.x >> 3;
+    const int n_pairs = n_tiles * (n_tiles + 1) / 2, total = n_pairs * split;       // at most 512
+    const int first = x * total / 8;
+    if (e >= (x + 1) * total / 8 - first) return;                    // the grid is padded to 8 * ceil(total / 8)
+    fa = (first + e) / n_pairs;
+    int rem = (first + e) % n_pairs;
+    part = rem * split + fa;
+    while (rem >= n_tiles - ti) { rem -= n_tiles - ti; ++ti; }       // tile pairs (ti <= tj) row by row
+    tj = ti + rem;
+  } else {
+    // Workgroups go to the eight XCDs round robin.  XCD x takes the pair list in runs of `split` (here: the
+    // run length, at most kGRun, what its 32 compute units hold at a time) consecutive pairs: with the
+    // banded order a run covers about 8 x 8 tiles, so the workgroups that share an L2 stream 16 row tiles
+    // between them rather than 65.
+    const long long e = blockIdx.x >> 3, x = blockIdx.x & 7, run = split;
+    const long long pos = ((e / run) * 8 + x) * run + e % run;
+    if (pos >= (long long)n_tiles * (n_tiles + 1) / 2) return;       // the grid is padded to whole runs
+    ghost_pair_at(pos, n_tiles, ti, tj);
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wi = wave >> 1, wj = wave & 1;
 
@@ -276,7 +378,7 @@ __global__ __launch_bounds__(256) void ghost_gram_tiled_kernel(const unsigned sh
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) { P[a][b][v] = 0.f; Q[a][b][v] = 0.f; }
-  const int nx = (d_in + 63) / 64, nd = (d_out + 63) / 64;       // 64-feature slices
+  const int nx = (d_in + kGKW - 1) / kGKW, nd = (d_out + kGKW - 1) / kGKW;       // ring stages
   if constexpr (SPLIT) {
     ghost_product_pass(X, d_in, n_tokens, ti, tj, smem_base, lane, wave, (int)((long long)nx * fa / split),
                        (int)((long long)nx * (fa + 1) / split), P);
@@ -294,11 +396,14 @@ __global__ __launch_bounds__(256) void ghost_gram_tiled_kernel(const unsigned sh
       const int t0 = ti * kGT + wi * 64 + bi * 32, s0 = tj * kGT + wj * 64 + bj * 32;
       if (!ghost_block_live(t0, s0, n_tokens)) continue;
       if constexpr (SPLIT) {
-        float* dst = parts + (size_t)blockIdx.x * (2 * kGTileFloats) + (size_t)(wave * 4 + bi * 2 + bj) * kGBlockFloats;
+        float* dst = parts + (size_t)part * (2 * kGTileFloats) + (size_t)(wave * 4 + bi * 2 + bj) * kGBlockFloats;
+        // a lane's sixteen values are contiguous: four 16-byte stores, a wave covers 4 KiB without gaps
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          dst[v * 64 + lane] = P[bi][bj][v];
-          dst[kGTileFloats + v * 64 + lane] = Q[bi][bj][v];
+        for (int v = 0; v < 16; v += 4) {
+          *reinterpret_cast<f32x4*>(dst + lane * 16 + v) =
+              f32x4{P[bi][bj][v], P[bi][bj][v + 1], P[bi][bj][v + 2], P[bi][bj][v + 3]};
+          *reinterpret_cast<f32x4*>(dst + kGTileFloats + lane * 16 + v) =
+              f32x4{Q[bi][bj][v], Q[bi][bj][v + 1], Q[bi][bj][v + 2], Q[bi][bj][v + 3]};
         }
       } else {
         ghost_block_reduce(P[bi][bj], Q[bi][bj], t0, s0, lane, tok_seq, n_tokens, n_seq, K64);
@@ -328,9 +433,11 @@ __global__ __launch_bounds__(256) void ghost_gram_parts_kernel(const float* __re
   for (int a = wave; a < split; a += 4) {
     const float* src = parts + ((size_t)(blockIdx.x >> 4) * split + a) * (2 * kGTileFloats) + (size_t)blk * kGBlockFloats;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      P[v] += src[v * 64 + lane];
-      Q[v] += src[kGTileFloats + v * 64 + lane];
+    for (int v = 0; v < 16; v += 4) {
+      const f32x4 p4 = *reinterpret_cast<const f32x4*>(src + lane * 16 + v);
+      const f32x4 q4 = *reinterpret_cast<const f32x4*>(src + kGTileFloats + lane * 16 + v);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { P[v + u] += p4[u]; Q[v + u] += q4[u]; }
     }
   }
 #pragma unroll
@@ -387,13 +494,17 @@ hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s) {
       const unsigned short* Db = static_cast<const unsigned short*>(a.Delta);
       if (split > 1) {
         if (!a.parts) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(ghost_gram_tiled_kernel<true>, dim3(n_pairs * split), dim3(256), smem, s, Xb, Db, a.tok_seq,
+        const unsigned grid = 8 * ((n_pairs * split + 7) / 8);
+        hipLaunchKernelGGL(ghost_gram_tiled_kernel<true>, dim3(grid), dim3(256), smem, s, Xb, Db, a.tok_seq,
                            a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, split, a.parts, a.K64);
         hipLaunchKernelGGL(ghost_gram_parts_kernel, dim3(n_pairs * 16), dim3(256), 0, s, a.parts, a.tok_seq, a.n_tokens,
                            a.n_seq, nt, split, a.K64);
       } else {
-        hipLaunchKernelGGL(ghost_gram_tiled_kernel<false>, dim3(n_pairs), dim3(256), smem, s, Xb, Db, a.tok_seq,
-                           a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, 1, static_cast<float*>(nullptr), a.K64);
+        // a multiple of eight runs of equal length, so that every XCD gets the same number of pairs
+        const unsigned n_runs = 8 * ((n_pairs + 8 * kGRun - 1) / (8 * kGRun));
+        const unsigned run = (n_pairs + n_runs - 1) / n_runs;
+        hipLaunchKernelGGL(ghost_gram_tiled_kernel<false>, dim3(n_runs * run), dim3(256), smem, s, Xb, Db, a.tok_seq,
+                           a.n_tokens, a.d_in, a.d_out, a.n_seq, nt, (int)run, static_cast<float*>(nullptr), a.K64);
       }
     } else
       hipLaunchKernelGGL((ghost_gram_kernel<false>), dim3((unsigned)pairs), dim3(256), 0, s, a.X, a.Delta, a.tok_seq,

@@ -91,24 +91,44 @@ struct GhostArgs {
 };
 hipError_t launch_ghost_gram(const GhostArgs& a, hipStream_t s);
 // bf16 ghost kernel: ranges the 64-feature slices of X and Delta are cut into when the microbatch has too few
-// 128x128 token-tile pairs to give every compute unit a workgroup (1: no split).  A workgroup then forms the
-// two token-by-token products over one range, and a second kernel sums the ranges.  Host arithmetic, shared by
-// the launcher, the workspace size and the cost model.
+// 128x128 token-tile pairs to fill the compute units (1: no split).  A workgroup then forms the two
+// token-by-token products over one range, and a second kernel sums the ranges' fp32 parts.  The count is the
+// one with the smallest modelled time: a workgroup's serial walk over its features against the pass over the
+// parts (rates measured on one MI355X).  Host arithmetic, shared by the launcher, the workspace size and the
+// cost model.
+constexpr double kGhostParts = 4.0e-6;        // s, the kernel that sums the ranges ...
+constexpr double kRateGhostParts = 2.5e12;    // ... plus B/s over the parts
+constexpr size_t kGhostPartBytes = 2 * 128 * 128 * sizeof(float);   // P and Q of one (tile pair, range)
+// s per 64-feature ring stage of one workgroup while `wgs` of them run: the stages stream through the L2s,
+// whose bandwidth the workgroups share (two fit a compute unit; beyond 512 they queue)
+inline double ghost_stage_time(long long wgs) {
+  const double w = wgs > 512 ? 512.0 : (double)wgs;
+  if (w <= 128.0) return 0.6e-6;
+  if (w <= 256.0) return 0.6e-6 + 0.4e-6 * (w - 128.0) / 128.0;
+  return 1.0e-6 + 0.32e-6 * (w - 256.0) / 256.0;
+}
+inline double ghost_walk_time(long long pairs, int d_in, int d_out, int split) {
+  const double stages = (double)((d_in + 63) / 64 + (d_out + 63) / 64) / split;
+  const double walk = stages * ghost_stage_time(pairs * split);
+  return split > 1 ? walk + kGhostParts + (double)pairs * split * kGhostPartBytes / kRateGhostParts : walk;
+}
 inline int ghost_feature_split(int n_tokens, int d_in, int d_out) {
   const long long nt = (n_tokens + 127) / 128, pairs = nt * (nt + 1) / 2;
   if (pairs <= 0) return 1;
   const long long slices = (d_in + 63) / 64 + (d_out + 63) / 64;
-  long long split = 256 / pairs;                       // one workgroup per compute unit (LDS ring: 128 KiB)
-  if (split > slices / 16) split = slices / 16;        // a range is worth its prologue from 16 slices on
-  if (split > 32) split = 32;
-  return split < 1 ? 1 : (int)split;
+  long long most = 512 / pairs;                        // two workgroups per compute unit (LDS ring: 64 KiB)
+  if (most > slices / 16) most = slices / 16;          // a range is worth its prologue from 16 slices on
+  if (most > 32) most = 32;
+  int best = 1;
+  for (int s = 2; s <= most; ++s)
+    if (ghost_walk_time(pairs, d_in, d_out, s) < ghost_walk_time(pairs, d_in, d_out, best)) best = s;
+  return best;
 }
-// fp32 parts of the split launch: per (tile pair, range) the two 128x128 products
 inline size_t ghost_parts_bytes(int n_tokens, int d_in, int d_out) {
   const int split = ghost_feature_split(n_tokens, d_in, d_out);
   if (split <= 1) return 0;
   const size_t nt = (size_t)(n_tokens + 127) / 128;
-  return nt * (nt + 1) / 2 * (size_t)split * 2 * 128 * 128 * sizeof(float);
+  return nt * (nt + 1) / 2 * (size_t)split * kGhostPartBytes;
 }
 
 // dst[t][:] = c[seq(t)] * src[t][:] (rounded to the storage type).
