@@ -35,6 +35,11 @@ constexpr int kMaxSampleBlocks = 4;            // n_samples <= 128
 __device__ __forceinline__ void load_lds16(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
+// non-temporal cache policy: the token rows, which this pass reads once (the sample rows are re-read by
+// every workgroup and keep the default)
+__device__ __forceinline__ void load_lds16_nt(const void* gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(lds_addr), "v"(gptr) : "memory");
+}
 
 struct Params {
   const void* X;
@@ -111,7 +116,9 @@ __device__ __forceinline__ void product_pass(const void* M, int d, const int32_t
       const long long last = ((long long)d - kV) * kEs;
       if (byte > last) byte = last;          // tail and look-ahead past the end: stays inside the row
       const int load = wave_s * LPW + q;
-      if (load < LOADS) load_lds16(src[q] + byte, smem_base + (unsigned)(k % kStages) * STAGE + (unsigned)load * 1024);
+      const unsigned dst = smem_base + (unsigned)(k % kStages) * STAGE + (unsigned)load * 1024;
+      if (load * 8 < kTok) load_lds16_nt(src[q] + byte, dst);
+      else if (load < LOADS) load_lds16(src[q] + byte, dst);
     }
   };
   // every wave issues the same number of loads per stage only if LOADS is a multiple of 4
