@@ -46,9 +46,10 @@ struct Params {
 __device__ __forceinline__ void load_lds16(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
-// The same with the non-temporal cache policy, for the one-pass kernel: every stash byte is read once, and
-// keeping it out of the caches' replacement order is worth 13 % of the pass (6.2 -> 7.05 TB/s on a 3.8 GB
-// stash).  The kernels for more than 128 sequences read a row once per super-block pair and keep the default.
+// The same with the non-temporal cache policy, for the one-pass kernel for up to 128 sequences: every stash
+// byte is read once, and keeping it out of the caches' replacement order is worth 13 % of the pass (6.2 ->
+// 7.05 TB/s on a 3.8 GB stash).  The kernels for more sequences are bound by their MFMAs (the policy made
+// 2 % on a 5 GB stash and cost time on config 5's 72 GB) or read a row once per super-block pair: default.
 __device__ __forceinline__ void load_lds16_nt(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
