@@ -109,6 +109,10 @@ isopo_status isopo_gram_cost_model(const isopo_layer* layer, double* t_ghost, do
  *   tiles              output tiles of one item (item: a sequence, or a token chunk)
  *   n_chunks, chunk_tokens   token split of the unweighted mode (1, n_tokens: none); partial tiles of a
  *                      split are added to dW with fp32 atomics
+ *   whole_tiles        unweighted mode with more 256x256 tiles than compute units: the first whole_tiles
+ *                      tiles (a multiple of 256, the full rounds of one tile per compute unit) are not
+ *                      split; the chunks apply to the tiles of the last, partial round only.  0: the
+ *                      split, if any, applies to every tile
  *   xcd_start[9]       the item-major list of (item, tile) pairs is cut into 8 contiguous ranges of equal
  *                      work, XCD x walks [xcd_start[x], xcd_start[x+1]).  All zero: no list - per-sequence
  *                      mode with tiles % 8 == 0 gives XCD x the x-th eighth of every sequence's tiles,
@@ -120,6 +124,7 @@ typedef struct {
   int32_t tile, workgroups_per_cu, tiles, n_chunks, chunk_tokens;
   int32_t xcd_start[9];
   int64_t workgroups;
+  int32_t whole_tiles;
 } isopo_contraction_plan_info;
 isopo_status isopo_contraction_plan(const isopo_layer* layer, int per_sequence, isopo_contraction_plan_info* plan);
 

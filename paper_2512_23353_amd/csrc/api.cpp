@@ -153,6 +153,7 @@ isopo_status isopo_contraction_plan(const isopo_layer* layer, int per_sequence, 
   plan->tiles = pl.tiles_m * pl.tiles_n;
   plan->n_chunks = pl.n_chunks;
   plan->chunk_tokens = pl.chunk_tokens;
+  plan->whole_tiles = pl.whole_tiles;
   for (int x = 0; x <= 8; ++x) plan->xcd_start[x] = pl.xcd_start[x];
   plan->workgroups = pl.blocks;
   return ISOPO_OK;

@@ -22,6 +22,35 @@ ContractionPlan plan_contraction(int rows, int d_in, int n_tokens, int n_seq, co
   const long long tiles = (long long)pl.tiles_m * pl.tiles_n;
   pl.n_chunks = 1;
   pl.chunk_tokens = n_tokens;
+  pl.whole_tiles = 0;
+  for (int x = 0; x <= 8; ++x) pl.xcd_start[x] = 0;
+  if (!per_sequence && big && tiles > 256 && tiles % 256 != 0 && tiles <= 0x3fffffffLL) {
+    // More tiles than compute units, and the last round of one tile per compute unit would be partly idle:
+    // the tiles of the full rounds stay whole (direct stores), the `rest` tiles of the last round are cut
+    // into w token chunks that fill it (fp32 atomics on those tiles only).  Modelled time of the last round
+    //   ceil(N / w) * t_token  +  (w > 1) * w * rest * tile outputs * t_atomic,
+    // t_token a workgroup's time per token row, t_atomic the chip's time per fp32 atomic add; the split has
+    // to win 5 %.  Workgroups are dispatched in id order, whole tiles first, so a compute unit takes a chunk
+    // when it has finished its whole tiles.
+    const long long rest = tiles % 256;
+    const double t_token = 2.0e-8, t_atomic = 5.0e-12;
+    long long most = 256 / rest;
+    if (most > n_tokens / 512) most = n_tokens / 512;
+    if (most > 64) most = 64;
+    long long want = 1;
+    double best = 0.95 * (double)n_tokens * t_token;
+    for (long long w = 2; w <= most; ++w) {
+      const double t = (double)((n_tokens + w - 1) / w) * t_token + (double)w * rest * 65536.0 * t_atomic;
+      if (t < best) { best = t; want = w; }
+    }
+    if (want > 1) {
+      pl.whole_tiles = (int)(tiles - rest);
+      pl.chunk_tokens = (int)(((n_tokens + want - 1) / want + kBlockTokens - 1) / kBlockTokens * kBlockTokens);
+      pl.n_chunks = (n_tokens + pl.chunk_tokens - 1) / pl.chunk_tokens;
+      pl.blocks = 8LL * (pl.whole_tiles / 8 + (rest * pl.n_chunks + 7) / 8);
+      return pl;
+    }
+  }
   if (!per_sequence) {
     // Number of token chunks: the count with the smallest modelled time
     //   rounds(w) * ceil(N / w) * t_token  +  (w > 1) * w * outputs * t_atomic,
@@ -49,7 +78,6 @@ ContractionPlan plan_contraction(int rows, int d_in, int n_tokens, int n_seq, co
   const bool mapped = per_sequence || pl.n_chunks > 1;
   const int n_items = per_sequence ? n_seq : pl.n_chunks;
   pl.blocks = mapped ? 8LL * n_items * ((tiles + 7) / 8) : tiles;
-  for (int x = 0; x <= 8; ++x) pl.xcd_start[x] = 0;
   // Per-sequence mode with a tile count that is a multiple of eight: XCD x takes the x-th eighth of the
   // tiles of every sequence (xcd_start stays zero).  Otherwise the item-major list of (item, tile) pairs is
   // cut into eight contiguous ranges of equal work.

@@ -36,6 +36,8 @@ struct ContractionPlan {
   int occupancy;
   int tiles_m, tiles_n;
   int n_chunks, chunk_tokens;  // sum-over-all-tokens mode: token chunks (1: no split)
+  int whole_tiles;             // sum-over-all-tokens mode: tiles [0, whole_tiles) of the tile order are not split
+                               // (one workgroup each, all tokens); the chunks apply to the tiles after them
   int xcd_start[9];            // XCD x walks (item, tile) pairs [xcd_start[x], xcd_start[x+1]) of the item-major
                                // list (items: sequences or chunks); all zero: the x-th eighth of every item's
                                // tiles (per-sequence mode), or no items at all (unsplit)

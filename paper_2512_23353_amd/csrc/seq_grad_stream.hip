@@ -59,6 +59,7 @@ struct StreamParams {
   int tiles_m, tiles_n;
   unsigned n_blocks;
   int n_chunks, chunk_tokens;      // sum-over-all-tokens mode: token chunks (1: no split)
+  int whole_tiles;                 // sum-over-all-tokens mode: tiles before this one are not split
   int xcd_start[9];                // XCD x takes (item, tile) pairs [xcd_start[x], xcd_start[x+1]), item-major
   unsigned* queue;                 // persistent mode: eight work counters, one per XCD, zero at launch
 };
@@ -101,6 +102,19 @@ __device__ __forceinline__ float acc_read(float a) {
 
 constexpr int BK = 32;
 
+// Column-blocked tile order: ids run down 8-column strips of the tile grid, so the 32 workgroups an
+// XCD runs at a time cover about 4 tile rows x 8 tile columns (12 operand panels) rather than
+// 2 x 16 (18 panels): fewer L2 misses per flop.
+__device__ __forceinline__ void strip_tile_coords(int tile, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  constexpr int W = 8;
+  const int strip = tile / (tiles_m * W);
+  const int c0 = strip * W;
+  const int w = tiles_n - c0 < W ? tiles_n - c0 : W;     // the last strip may be narrower
+  const int in_strip = tile - strip * tiles_m * W;
+  tile_m = in_strip / w;
+  tile_n = c0 + in_strip % w;
+}
+
 template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false>
 __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
   static_assert(PER_SEQ || !PERSIST, "the persistent mode serves the per-sequence gradients");
@@ -134,8 +148,24 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       e = (int)(blockIdx.x >> 3);
     }
     int item, tile;
-    const bool split = !PER_SEQ && p.n_chunks > 1;
-    if (PER_SEQ || split) {
+    bool split = !PER_SEQ && p.n_chunks > 1;       // this workgroup adds a token chunk's part with atomics
+    if (!PER_SEQ && p.whole_tiles > 0) {
+      // Whole tiles first, then the token chunks of the remaining tiles; XCD x takes the x-th eighth of
+      // each of the two lists, in id order, so a compute unit gets chunks once its whole tiles are done.
+      const int x = blockIdx.x & 7, wq = p.whole_tiles >> 3;
+      if (e < wq) {
+        item = 0;
+        tile = x * wq + e;
+        split = false;
+      } else {
+        const int rest = p.tiles_m * p.tiles_n - p.whole_tiles, S = rest * p.n_chunks;
+        const int first = (int)((long long)x * S / 8);
+        const int id = first + (e - wq);
+        if (id >= (int)((long long)(x + 1) * S / 8)) break;
+        item = id / rest;
+        tile = p.whole_tiles + id % rest;
+      }
+    } else if (PER_SEQ || split) {
       const int tiles = p.tiles_m * p.tiles_n;
       const int x = blockIdx.x & 7;
       if (p.xcd_start[8] > 0) {
@@ -156,22 +186,11 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       item = 0;
       tile = xcd_contiguous(blockIdx.x, p.n_blocks);
     }
-    // Column-blocked tile order: ids run down 8-column strips of the tile grid, so the 32 workgroups an
-    // XCD runs at a time cover about 4 tile rows x 8 tile columns (12 operand panels) rather than
-    // 2 x 16 (18 panels): fewer L2 misses per flop.
     int tile_m, tile_n;
-    {
-      constexpr int W = 8;
-      const int strip = tile / (p.tiles_m * W);
-      const int c0 = strip * W;
-      const int w = p.tiles_n - c0 < W ? p.tiles_n - c0 : W;     // the last strip may be narrower
-      const int in_strip = tile - strip * p.tiles_m * W;
-      tile_m = in_strip / w;
-      tile_n = c0 + in_strip % w;
-    }
+    strip_tile_coords(tile, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int m0 = p.row0 + tile_m * BM, n0 = tile_n * BN;
-    const int t0 = PER_SEQ ? p.off[item] : item * p.chunk_tokens;
-    const int t1 = PER_SEQ ? p.off[item + 1] : min(p.n_tokens, t0 + p.chunk_tokens);
+    const int t0 = PER_SEQ ? p.off[item] : (split ? item * p.chunk_tokens : 0);
+    const int t1 = PER_SEQ ? p.off[item + 1] : (split ? min(p.n_tokens, t0 + p.chunk_tokens) : p.n_tokens);
     const int n_rows = t1 - t0;
     const int n_tiles = (n_rows + BK - 1) / BK;
     const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
@@ -441,6 +460,27 @@ __global__ __launch_bounds__(256) void apply_beta_kernel(float* __restrict__ o, 
   }
 }
 
+// The same for the 256x256 output tiles from `first_tile` on (tile order as in the contraction): the
+// tiles whose token chunks are accumulated with atomics while the tiles before them are stored whole.
+// One workgroup per 16 rows of a tile.
+__global__ __launch_bounds__(256) void apply_beta_tiles_kernel(float* __restrict__ out, int d_in, int row0, int row_end,
+                                                               int out_row0, int tiles_m, int tiles_n, int first_tile,
+                                                               float beta) {
+  int tile_m, tile_n;
+  strip_tile_coords(first_tile + (int)(blockIdx.x >> 4), tiles_m, tiles_n, tile_m, tile_n);
+  const int n = tile_n * 256 + (threadIdx.x & 63) * 4;
+  if (n >= d_in) return;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int m = row0 + tile_m * 256 + (int)(blockIdx.x & 15) * 16 + rr * 4 + (int)(threadIdx.x >> 6);
+    if (m >= row_end) continue;
+    f32x4* o = reinterpret_cast<f32x4*>(out + (size_t)(m - out_row0) * d_in + n);
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (beta != 0.f) v = *o * beta;
+    *o = v;
+  }
+}
+
 __global__ void queue_zero_kernel(unsigned* queue) {
   if (threadIdx.x < 8) queue[threadIdx.x] = 0u;
 }
@@ -460,6 +500,7 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   p.tiles_n = pl.tiles_n;
   p.n_chunks = pl.n_chunks;
   p.chunk_tokens = pl.chunk_tokens;
+  p.whole_tiles = pl.whole_tiles;
   for (int x = 0; x <= 8; ++x) p.xcd_start[x] = pl.xcd_start[x];
   if (pl.blocks <= 0) return hipSuccess;
   if (pl.blocks > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -471,7 +512,11 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return attr;
-  if (!PER_SEQ && p.n_chunks > 1) {
+  if (!PER_SEQ && p.whole_tiles > 0) {
+    const int rest = p.tiles_m * p.tiles_n - p.whole_tiles;
+    hipLaunchKernelGGL(apply_beta_tiles_kernel, dim3((unsigned)rest * 16), dim3(256), 0, s, static_cast<float*>(a.out),
+                       a.d_in, a.row0, a.row0 + a.rows, a.out_row0, p.tiles_m, p.tiles_n, p.whole_tiles, a.beta);
+  } else if (!PER_SEQ && p.n_chunks > 1) {
     // the band of output rows this launch owns is contiguous in dW
     float* band = static_cast<float*>(a.out) + (size_t)(a.row0 - a.out_row0) * a.d_in;
     const long long n = (long long)a.rows * a.d_in;

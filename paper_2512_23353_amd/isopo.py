@@ -206,7 +206,7 @@ def gram_cost_model(layer: Layer) -> Tuple[float, float]:
 class ContractionPlanInfo(ctypes.Structure):
     _fields_ = [("tile", ctypes.c_int32), ("workgroups_per_cu", ctypes.c_int32), ("tiles", ctypes.c_int32),
                 ("n_chunks", ctypes.c_int32), ("chunk_tokens", ctypes.c_int32), ("xcd_start", ctypes.c_int32 * 9),
-                ("workgroups", ctypes.c_int64)]
+                ("workgroups", ctypes.c_int64), ("whole_tiles", ctypes.c_int32)]
 
 
 def contraction_plan(layer_ref, per_sequence: bool) -> dict:
@@ -217,7 +217,7 @@ def contraction_plan(layer_ref, per_sequence: bool) -> dict:
            "isopo_contraction_plan")
     return {"tile": info.tile, "workgroups_per_cu": info.workgroups_per_cu, "tiles": info.tiles,
             "n_chunks": info.n_chunks, "chunk_tokens": info.chunk_tokens, "xcd_start": list(info.xcd_start),
-            "workgroups": info.workgroups}
+            "workgroups": info.workgroups, "whole_tiles": info.whole_tiles}
 
 
 def alloc_workspace(nbytes: int, device) -> torch.Tensor:

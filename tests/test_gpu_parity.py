@@ -319,6 +319,31 @@ def test_prescaled_weighted_grad(gpu_device, dtype, dims):
     assert np.all(np.abs(got - exact) <= ulp * np.abs(exact) + 1e-300)
 
 
+@pytest.mark.parametrize("beta", [0.0, 0.75])
+def test_unweighted_contraction_whole_tiles_then_split_tail(gpu_device, beta):
+    """More 256x256 output tiles than compute units (17 x 16 = 272, ragged last tile row): the 256 tiles of
+    the full round are stored whole, the 16 of the partial round are cut into token chunks and accumulated
+    with atomics.  beta = 0 over a NaN-filled dW (must not be read, neither by whole nor by split tiles)
+    and beta != 0; every element is compared."""
+    d_in, d_out = 4096, 4200
+    lengths = [700, 1, 0, 900, 447]
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=37, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    plan = isopo.contraction_plan(layer.ref(), False)
+    assert plan["tiles"] == 272 and plan["whole_tiles"] == 256 and plan["n_chunks"] > 1
+    rng = np.random.default_rng(8)
+    dW0 = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    dW = torch.from_numpy(dW0).to(gpu_device) if beta != 0.0 else torch.full((d_out, d_in), float("nan"),
+                                                                           device=gpu_device)
+    isopo.weighted_grad(layer, None, None, beta, dW)
+    torch.cuda.synchronize()
+    Xo, Do = wl.to_oracle(prob.X), wl.to_oracle(prob.Delta)
+    ones = np.ones(prob.n_seq)
+    ref = orc.weighted_grad_tokens(Xo, Do, prob.seq_offsets, ones) + beta * dW0.astype(np.float64)
+    mag = orc.weighted_grad_tokens(np.abs(orc.widen(Xo)), np.abs(orc.widen(Do)), prob.seq_offsets, ones) + np.abs(beta * dW0)
+    assert_dW_close(dW.cpu().numpy(), ref, TOL["bf16"], f"whole tiles + split tail beta={beta}", mag)
+
+
 @pytest.mark.parametrize("dims", [(256, 384), (512, 256), (200, 136)])
 @pytest.mark.parametrize("beta", [0.0, 0.75])
 def test_unweighted_contraction_with_token_split(gpu_device, dims, beta):

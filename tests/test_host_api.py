@@ -111,6 +111,41 @@ def test_cost_model_prefers_ghost_only_for_few_tokens():
     assert all(a <= b for a, b in zip(ghost_costs, ghost_costs[1:]))
 
 
+def test_contraction_plan_whole_tiles_then_split_tail():
+    """Unweighted contraction with more 256x256 tiles than compute units and a partial last round: the tiles
+    of the full rounds stay whole, the rest is cut into token chunks that fill the round.  The kernel's
+    decoding of (workgroup id -> tile, chunk), repeated here, must cover every whole tile once and every
+    (chunk, tail tile) pair once."""
+    for d_in, d_out, n_tok in ((4096, 14336, 70107), (5120, 27648, 412293), (4096, 4200, 2048)):
+        lay = _host_layer([n_tok], d_in, d_out)
+        pl = isopo.contraction_plan(lay.ref(), False)
+        tiles, whole, w, ct = pl["tiles"], pl["whole_tiles"], pl["n_chunks"], pl["chunk_tokens"]
+        assert tiles == -(-d_in // 256) * -(-d_out // 256)
+        assert whole == tiles // 256 * 256 and w > 1
+        rest = tiles - whole
+        assert rest * w <= 256 and ct % 32 == 0 and (w - 1) * ct < n_tok <= w * ct
+        assert pl["workgroups"] % 8 == 0
+        seen_whole, seen_split = [], []
+        for b in range(pl["workgroups"]):
+            x, e = b & 7, b >> 3
+            wq = whole >> 3
+            if e < wq:
+                seen_whole.append(x * wq + e)
+                continue
+            S = rest * w
+            first, last = x * S // 8, (x + 1) * S // 8
+            idx = first + (e - wq)
+            if idx < last:
+                seen_split.append((idx // rest, whole + idx % rest))
+        assert sorted(seen_whole) == list(range(whole))
+        assert sorted(seen_split) == [(c, t) for c in range(w) for t in range(whole, tiles)]
+    # a multiple of 256 tiles, or fewer than 256: nothing to fill
+    assert isopo.contraction_plan(_host_layer([70107], 4096, 4096).ref(), False)["whole_tiles"] == 0
+    assert isopo.contraction_plan(_host_layer([131072], 1536, 8960).ref(), False)["whole_tiles"] == 0
+    # per-sequence mode never splits tokens
+    assert isopo.contraction_plan(_host_layer([70107], 4096, 14336).ref(), True)["whole_tiles"] == 0
+
+
 def test_contraction_plan_ranges_partition_the_work():
     """Launch plan of the per-sequence contraction.  Tile counts that are a
     multiple of eight keep the tile-eighths mapping (no range list); otherwise
