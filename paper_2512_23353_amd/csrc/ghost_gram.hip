@@ -36,6 +36,78 @@ __global__ void fill_f64_kernel(double* p, long long n) {
   if (i < n) p[i] = 0.0;
 }
 
+// One 32x32 block of the token-pair matrix: rows t0.., columns s0.. .  False when the block lies past the last
+// token or wholly below the diagonal (every pair has t > s); wave-uniform.
+__device__ __forceinline__ bool ghost_block_live(int t0, int s0, int n_tokens) {
+  return t0 < n_tokens && s0 < n_tokens && t0 <= s0;
+}
+
+// K64[seq(t)][seq(s)] += w P Q over the pairs t <= s of a live 32x32 block (w = 2 for the off-diagonal pairs of one
+// sequence, which stand for their mirror images too).  Lane holds column s = s0 + lane%32 and rows
+// t = t0 + acc_row(v, lane).
+__device__ __forceinline__ void ghost_block_reduce(const f32x16& P, const f32x16& Q, int t0, int s0, int lane,
+                                                   const int32_t* __restrict__ tok_seq, int n_tokens, int n_seq,
+                                                   double* __restrict__ K64) {
+  const int s = s0 + (lane & 31);
+  const bool s_ok = s < n_tokens;
+  const int q = s_ok ? tok_seq[s] : -1;
+  const int t_last = min(t0 + 31, n_tokens - 1), s_last = min(s0 + 31, n_tokens - 1);
+  const int r_first = tok_seq[t0], r_last = tok_seq[t_last];
+  const int q_first = tok_seq[s0], q_last = tok_seq[s_last];
+  if (r_first == r_last && q_first == q_last) {
+    // one sequence pair in the whole block: one wave sum, one atomic
+    double run = 0.0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int t = t0 + acc_row(v, lane);
+      if (t >= n_tokens || !s_ok || t > s) continue;
+      const double w = (t == s) ? 1.0 : ((r_first == q) ? 2.0 : 1.0);
+      run += w * (double)P[v] * (double)Q[v];
+    }
+    run = wave_sum(run);
+    if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
+    return;
+  }
+  const int n_r = r_last - r_first + 1, n_q = q_last - q_first + 1;
+  if (n_r * n_q <= 8) {
+    // a few sequence boundaries cross the block: one wave sum and one atomic per (row sequence, column
+    // sequence) rather than one atomic per lane and run, which would queue on K's few cache lines
+    for (int r = r_first; r <= r_last; ++r) {
+      double part = 0.0;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int t = t0 + acc_row(v, lane);
+        if (t >= n_tokens || !s_ok || t > s || tok_seq[t] != r) continue;
+        const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
+        part += w * (double)P[v] * (double)Q[v];
+      }
+      for (int c = q_first; c <= q_last; ++c) {
+        const double sum = wave_sum(q == c ? part : 0.0);
+        if (lane == 0 && sum != 0.0) atomicAdd(&K64[(size_t)r * n_seq + c], sum);
+      }
+    }
+    return;
+  }
+  // many short sequences: a lane adds each run of rows of one sequence by itself
+  double run = 0.0;
+  int run_r = -1;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int t = t0 + acc_row(v, lane);
+    if (t >= n_tokens || !s_ok || t > s) continue;
+    const int r = tok_seq[t];
+    const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
+    const double h = w * (double)P[v] * (double)Q[v];
+    if (r != run_r) {
+      if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+      run_r = r;
+      run = 0.0;
+    }
+    run += h;
+  }
+  if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
+}
+
 template <bool BF16>
 __device__ __forceinline__ void gram_block(const void* __restrict__ M, int d, int t_row, int s_row, bool t_ok,
                                            bool s_ok, int half, f32x16& acc) {
@@ -84,40 +156,7 @@ __global__ __launch_bounds__(256) void ghost_gram_kernel(const void* __restrict_
   gram_block<BF16>(X, d_in, t_ok ? t_row : 0, s_ok ? s_row : 0, t_ok, s_ok, half, P);
   gram_block<BF16>(Delta, d_out, t_ok ? t_row : 0, s_ok ? s_row : 0, t_ok, s_ok, half, Q);
 
-  // Lane holds column s = s0 + lane%32 and rows t = t0 + acc_row(v, lane).
-  const int s = s0 + r32;
-  const int q = s_ok ? tok_seq[s] : -1;
-  const int t_last = min(t0 + 31, n_tokens - 1), s_last = min(s0 + 31, n_tokens - 1);
-  const int r_first = tok_seq[t0], r_last = tok_seq[t_last];
-  const int q_first = tok_seq[s0], q_last = tok_seq[s_last];
-  const bool uniform = (r_first == r_last) && (q_first == q_last);   // same for the whole wave
-
-  double run = 0.0;
-  int run_r = -1;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int t = t0 + acc_row(v, lane);
-    if (t >= n_tokens || !s_ok || t > s) continue;
-    const int r = uniform ? r_first : tok_seq[t];
-    const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
-    const double h = w * (double)P[v] * (double)Q[v];
-    if (uniform) {
-      run += h;
-    } else {
-      if (r != run_r) {
-        if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
-        run_r = r;
-        run = 0.0;
-      }
-      run += h;
-    }
-  }
-  if (uniform) {
-    run = wave_sum(run);
-    if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
-  } else if (run_r >= 0) {
-    atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
-  }
+  ghost_block_reduce(P, Q, t0, s0, lane, tok_seq, n_tokens, n_seq, K64);
 }
 
 // ---- bf16, LDS-tiled ---------------------------------------------------------------------------------
@@ -230,78 +269,6 @@ __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restr
   __builtin_amdgcn_s_barrier();            // the ring is reused by the next pass
 }
 
-// One 32x32 block of the token-pair matrix: rows t0.., columns s0.. .  False when the block lies past the last
-// token or wholly below the diagonal (every pair has t > s); wave-uniform.
-__device__ __forceinline__ bool ghost_block_live(int t0, int s0, int n_tokens) {
-  return t0 < n_tokens && s0 < n_tokens && t0 <= s0;
-}
-
-// K64[seq(t)][seq(s)] += w P Q over the pairs t <= s of a live 32x32 block (w = 2 for the off-diagonal pairs of one
-// sequence, which stand for their mirror images too).  Lane holds column s = s0 + lane%32 and rows
-// t = t0 + acc_row(v, lane).
-__device__ __forceinline__ void ghost_block_reduce(const f32x16& P, const f32x16& Q, int t0, int s0, int lane,
-                                                   const int32_t* __restrict__ tok_seq, int n_tokens, int n_seq,
-                                                   double* __restrict__ K64) {
-  const int s = s0 + (lane & 31);
-  const bool s_ok = s < n_tokens;
-  const int q = s_ok ? tok_seq[s] : -1;
-  const int t_last = min(t0 + 31, n_tokens - 1), s_last = min(s0 + 31, n_tokens - 1);
-  const int r_first = tok_seq[t0], r_last = tok_seq[t_last];
-  const int q_first = tok_seq[s0], q_last = tok_seq[s_last];
-  if (r_first == r_last && q_first == q_last) {
-    // one sequence pair in the whole block: one wave sum, one atomic
-    double run = 0.0;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int t = t0 + acc_row(v, lane);
-      if (t >= n_tokens || !s_ok || t > s) continue;
-      const double w = (t == s) ? 1.0 : ((r_first == q) ? 2.0 : 1.0);
-      run += w * (double)P[v] * (double)Q[v];
-    }
-    run = wave_sum(run);
-    if (lane == 0) atomicAdd(&K64[(size_t)r_first * n_seq + q_first], run);
-    return;
-  }
-  const int n_r = r_last - r_first + 1, n_q = q_last - q_first + 1;
-  if (n_r * n_q <= 8) {
-    // a few sequence boundaries cross the block: one wave sum and one atomic per (row sequence, column
-    // sequence) rather than one atomic per lane and run, which would queue on K's few cache lines
-    for (int r = r_first; r <= r_last; ++r) {
-      double part = 0.0;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int t = t0 + acc_row(v, lane);
-        if (t >= n_tokens || !s_ok || t > s || tok_seq[t] != r) continue;
-        const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
-        part += w * (double)P[v] * (double)Q[v];
-      }
-      for (int c = q_first; c <= q_last; ++c) {
-        const double sum = wave_sum(q == c ? part : 0.0);
-        if (lane == 0 && sum != 0.0) atomicAdd(&K64[(size_t)r * n_seq + c], sum);
-      }
-    }
-    return;
-  }
-  // many short sequences: a lane adds each run of rows of one sequence by itself
-  double run = 0.0;
-  int run_r = -1;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int t = t0 + acc_row(v, lane);
-    if (t >= n_tokens || !s_ok || t > s) continue;
-    const int r = tok_seq[t];
-    const double w = (t == s) ? 1.0 : ((r == q) ? 2.0 : 1.0);
-    const double h = w * (double)P[v] * (double)Q[v];
-    if (r != run_r) {
-      if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
-      run_r = r;
-      run = 0.0;
-    }
-    run += h;
-  }
-  if (run_r >= 0) atomicAdd(&K64[(size_t)run_r * n_seq + q], run);
-}
-
 // Order of the tile pairs (ti <= tj) in the unsplit launch: bands of kGBand tile rows, column by column inside
 // a band, so that consecutive pairs form compact blocks of the triangle.
 constexpr int kGBand = 8;
@@ -330,19 +297,21 @@ __device__ __forceinline__ void ghost_pair_at(long long pos, int n_tiles, int& t
 constexpr int kGBlockFloats = 16 * 64;            // one wave's 32x32 accumulator block
 constexpr int kGTileFloats = 16 * kGBlockFloats;  // the 16 blocks of a 128x128 tile
 
-// SPLIT = false: one workgroup per tile pair walks all features and adds its pairs to K64.
-// SPLIT = true (few tile pairs, a short microbatch): the 64-feature slices of both operands are cut into `split`
-// ranges and workgroup (pair, a) forms the parts P_a, Q_a of the two products over range a only; the parts go to
-// `parts` [pair][a][P, Q][block][lane][v] in fp32, and ghost_gram_parts_kernel sums them before the Hadamard
-// product, which is not linear in the ranges.
+// SPLIT = false: one workgroup per tile pair walks all features and adds its pairs to K64; `count` is the
+// length of the runs of consecutive pairs an XCD takes.
+// SPLIT = true (few tile pairs, a short microbatch): the 64-feature slices of both operands are cut into
+// `count` ranges and workgroup (pair, a) forms the parts P_a, Q_a of the two products over range a only; the
+// parts go to `parts` [pair][a][P, Q][block][lane][v] in fp32, and ghost_gram_parts_kernel sums them before
+// the Hadamard product, which is not linear in the ranges.
 template <bool SPLIT>
 __global__ __launch_bounds__(256, 2) void ghost_gram_tiled_kernel(const unsigned short* __restrict__ X,
                                                                const unsigned short* __restrict__ Delta,
                                                                const int32_t* __restrict__ tok_seq, int n_tokens,
                                                                int d_in, int d_out, int n_seq, int n_tiles,
-                                                               int split, float* __restrict__ parts,
+                                                               int count, float* __restrict__ parts,
                                                                double* __restrict__ K64) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int split = SPLIT ? count : 1;
   const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
   int fa = 0, ti = 0, tj, part = 0;
   if constexpr (SPLIT) {
@@ -359,11 +328,10 @@ __global__ __launch_bounds__(256, 2) void ghost_gram_tiled_kernel(const unsigned
     while (rem >= n_tiles - ti) { rem -= n_tiles - ti; ++ti; }       // tile pairs (ti <= tj) row by row
     tj = ti + rem;
   } else {
-    // Workgroups go to the eight XCDs round robin.  XCD x takes the pair list in runs of `split` (here: the
-    // run length, at most kGRun, what its 32 compute units hold at a time) consecutive pairs: with the
-    // banded order a run covers about 8 x 8 tiles, so the workgroups that share an L2 stream 16 row tiles
-    // between them rather than 65.
-    const long long e = blockIdx.x >> 3, x = blockIdx.x & 7, run = split;
+    // Workgroups go to the eight XCDs round robin.  XCD x takes the pair list in runs of `count` consecutive
+    // pairs (at most kGRun, what its 32 compute units hold at a time): with the banded order a run covers
+    // about 8 x 8 tiles, so the workgroups that share an L2 stream 16 row tiles between them rather than 65.
+    const long long e = blockIdx.x >> 3, x = blockIdx.x & 7, run = count;
     const long long pos = ((e / run) * 8 + x) * run + e % run;
     if (pos >= (long long)n_tiles * (n_tiles + 1) / 2) return;       // the grid is padded to whole runs
     ghost_pair_at(pos, n_tiles, ti, tj);
