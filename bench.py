@@ -68,7 +68,8 @@ def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
         for _ in range(n + 1):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            isopo.seq_grads(layer, stash_views[big], stream=stream, max_workgroups=256, queue=wg_queue)
+            isopo.seq_grads(layer, stash_views[big], stream=stream, max_workgroups=256, queue=wg_queue,
+                            layout=isopo.stash_layout(layer)[0])
             e1.record(stream)
             ev.append((e0, e1))
         torch.cuda.synchronize()
@@ -104,7 +105,8 @@ def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
             th.start()
             while time.time() < stop:
                 for _ in range(20):
-                    isopo.seq_grads(layer, stash_views[big], stream=stream, max_workgroups=256, queue=wg_queue)
+                    isopo.seq_grads(layer, stash_views[big], stream=stream, max_workgroups=256, queue=wg_queue,
+                            layout=isopo.stash_layout(layer)[0])
                 torch.cuda.synchronize()
             th.join()
             return [x for x in samples if x]
@@ -180,17 +182,21 @@ def main() -> int:
     stream = torch.cuda.current_stream()
     assert all(pl[0] == "materialised" for pl in plans), "the benchmark shapes all take the materialised path"
 
+    # the kept stash in the layout the library prefers for each layer (tile order for these shapes)
+    layouts = [isopo.stash_layout(l)[0] for l in layers]
+
     def make_step(variant, lam):
         def step():
             for _ in range(sweeps):
                 for b in range(len(blocks)):
                     for j in range(npj):
-                        isopo.layer_gram(layers[b * npj + j], "auto", K=Kb[b][j], workspace=wss[j], keep_stash=True,
-                                         stream=stream)
+                        isopo.layer_gram(layers[b * npj + j], "auto", K=Kb[b][j], workspace=wss[j],
+                                         keep_stash=isopo.KEEP_FAST, stream=stream)
                     isopo.transform(Kb[b], Ab, variant, lam, isopo.REG_REL_TRACE, c=cb[b], info=infob[b], workspace=tws,
                                     stream=stream)
                     for j in range(npj):
-                        isopo.weighted_grad(layers[b * npj + j], cb[b][j], wss[j], 0.0, dWs[b * npj + j], stream=stream)
+                        isopo.weighted_grad(layers[b * npj + j], cb[b][j], wss[j], 0.0, dWs[b * npj + j], stream=stream,
+                                            layout=layouts[b * npj + j])
         return step
 
     step = make_step(args.variant, args.lam)
@@ -253,7 +259,7 @@ def main() -> int:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             # the launch isopo_layer_gram makes: one persistent workgroup per compute unit
-            isopo.seq_grads(l, sv, stream=stream, max_workgroups=256, queue=wg_queue)
+            isopo.seq_grads(l, sv, stream=stream, max_workgroups=256, queue=wg_queue, layout=isopo.stash_layout(l)[0])
             e1.record(stream)
             durs.append((e0, e1))
     torch.cuda.synchronize()
@@ -302,13 +308,14 @@ def main() -> int:
                     for li, (l, pl, K, info) in enumerate(zip(layers, plans, Ks, infos)):
                         assert pl[0] == "materialised"
                         wsl = wss[li % npj]
-                        isopo.layer_gram(l, "auto", K=K, workspace=wsl, keep_stash=True, stream=stream)
+                        isopo.layer_gram(l, "auto", K=K, workspace=wsl, keep_stash=isopo.KEEP_FAST, stream=stream)
                         for vi, variant in enumerate(("fisher", "interacting")):
                             for k, lam in enumerate(lams):
                                 isopo.transform(K, A, variant, lam, isopo.REG_REL_TRACE, c=c6[li][3 * vi + k], info=info,
                                                 stream=stream)
                         for k in range(6):
-                            isopo.weighted_grad(l, c6[li][k], wsl, 0.0, dW6[li % len(dW6)][k], stream=stream)
+                            isopo.weighted_grad(l, c6[li][k], wsl, 0.0, dW6[li % len(dW6)][k], stream=stream,
+                                                layout=layouts[li])
 
             t_shared = timed(shared_sweep_step, 2, 1)
             variants["sweep_with_shared_gram"] = {
@@ -363,7 +370,7 @@ def main() -> int:
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
                       "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
-        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true> (per-sequence gradients -> stash, persistent launch)",
+        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true,true> (per-sequence gradients -> stash in tile order, persistent launch)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
                      "flops_per_launch": seq_grad_flops_per_launch,

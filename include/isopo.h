@@ -128,12 +128,29 @@ typedef struct {
 } isopo_contraction_plan_info;
 isopo_status isopo_contraction_plan(const isopo_layer* layer, int per_sequence, isopo_contraction_plan_info* plan);
 
+/* Layout of a stash that isopo_layer_gram keeps.
+ *   ROW_MAJOR   [n_seq, d_out, d_in], what `torch.stack(seq_grads)` of the interacting listing holds.
+ *   TILE_ORDER  per sequence the same d_out * d_in elements in the order the matrix cores' accumulators
+ *               hold them, so that the contraction stores them without a transpose (bf16 layers whose
+ *               d_out and d_in are multiples of 256): T x T tiles (T = 256 or 128, as the contraction
+ *               plan chooses) in row-major tile order; inside a tile its four (T/2 x T/2) quadrants (upper
+ *               left, upper right, lower left, lower right); inside a quadrant its 32x32 blocks row by row,
+ *               each as two pieces of 512 elements; element 8 l + q (l = 0..63, q = 0..7) of piece k is
+ *               row 16 k + 8 (q / 4) + 4 (l / 32) + q % 4, column l % 32 of the block.
+ * isopo_stash_layout_of tells which of the two keep_stash = 2 leaves for a layer (a pure host function of
+ * dtype, shape and sequence offsets; *tile = T, or 0 for ROW_MAJOR).  The Gram matrix does not depend on
+ * the order of the elements; isopo_weighted_grad_stash forms dW (row-major, as always) from either. */
+typedef enum { ISOPO_STASH_ROW_MAJOR = 0, ISOPO_STASH_TILE_ORDER = 1 } isopo_stash_layout;
+isopo_status isopo_stash_layout_of(const isopo_layer* layer, isopo_stash_layout* layout, int32_t* tile);
+
 /* K [n_seq, n_seq] fp32, both triangles written, bit-symmetric.
  *   workspace/ws_bytes  device scratch, >= ws_min of the plan.
  *   keep_stash          non-zero: leave the per-sequence gradients in the
- *                       workspace, starting at its first byte, as
- *                       [n_seq, d_out, d_in] in the stash dtype (bf16 for bf16
- *                       inputs, fp32 for fp32 inputs), for isopo_weighted_grad.
+ *                       workspace, starting at its first byte, in the stash dtype
+ *                       (bf16 for bf16 inputs, fp32 for fp32 inputs).
+ *                       1: as [n_seq, d_out, d_in], for isopo_weighted_grad;
+ *                       2: in the layout isopo_stash_layout_of reports for the
+ *                       layer (the faster one), for isopo_weighted_grad_stash.
  *                       Needs ws_bytes >= ws_full and the MATERIALISED path
  *                       (forced, or AUTO resolving to it); otherwise
  *                       ISOPO_ERR_WORKSPACE_TOO_SMALL / ISOPO_ERR_INVALID_ARG. */
@@ -163,6 +180,13 @@ isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream
  *                   (work counters); must not be shared by launches that may run concurrently */
 isopo_status isopo_seq_grads_limited(const isopo_layer* layer, void* stash, int32_t max_workgroups,
                                      uint32_t* queue_dev, void* stream);
+
+/* isopo_seq_grads_limited with the layout of the stash as an argument: ROW_MAJOR is that call; TILE_ORDER
+ * writes the same per-sequence gradients (`grad_out.T @ act_in`) in the order isopo_layer_gram(keep_stash =
+ * 2) leaves them (ISOPO_ERR_UNSUPPORTED where isopo_stash_layout_of reports ROW_MAJOR for the layer).
+ * max_workgroups = 0 and queue_dev = NULL: no budget. */
+isopo_status isopo_seq_grads_stash(const isopo_layer* layer, void* stash, isopo_stash_layout layout,
+                                   int32_t max_workgroups, uint32_t* queue_dev, void* stream);
 size_t isopo_stash_gram_workspace(int32_t n_seq);
 isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_seq, int64_t n_elem, float* K,
                               void* workspace, size_t ws_bytes, void* stream);
@@ -208,6 +232,14 @@ isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, 
  * tiles are added with fp32 atomics, so dW can then differ between runs by fp32 rounding. */
 isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const void* stash,
                                  float beta, float* dW, void* stream);
+
+/* The same sum over a kept stash, `stack(seq_grads) @ coef` of the interacting listing, from a stash in
+ * either layout: ROW_MAJOR is isopo_weighted_grad with that stash; TILE_ORDER reads the stash that
+ * isopo_layer_gram(keep_stash = 2) left for this layer (ISOPO_ERR_UNSUPPORTED if isopo_stash_layout_of
+ * reports ROW_MAJOR for it).  c and stash must not be NULL.  dW is row-major [d_out, d_in] in both cases;
+ * fixed summation order, bit-identical from run to run. */
+isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
+                                       isopo_stash_layout layout, float beta, float* dW, void* stream);
 
 /* The non-interacting update's coefficients with the paper's own Fisher-norm estimate (eq.
  * formal-F-norm; F_norm of the non-interacting listing): from n_samples sampled token rows j of the

@@ -207,7 +207,13 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
     return launch_ghost_gram(g, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
   }
 
+  if (keep_stash < 0 || keep_stash > 2) return ISOPO_ERR_INVALID_ARG;
   if (keep_stash && ws_bytes < ws_full) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  // Tile order whenever nobody asked for the row-major stash (a stash that is not kept is nobody's business).
+  // With the chunk cap the bands could pick different tile sizes, which a kept stash must not mix.
+  const bool tile_order = keep_stash != 1 && !(keep_stash == 2 && chunk_cap_bytes()) && bf16 &&
+                          stash_tile_order_ok(layer->d_out, layer->d_in, (int)layer->n_tokens, layer->n_seq,
+                                              layer->seq_offsets_host) != 0;
   const size_t pbytes = partial_bytes(layer);
   const size_t row_bytes = stash_bytes(layer, 1);
   // rows of d_out whose gradients are formed and reduced per pass
@@ -235,7 +241,7 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
     a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.off_host = layer->seq_offsets_host; a.c = nullptr;
     a.out = ws; a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
     a.row0 = r0; a.rows = rows; a.out_row0 = whole ? 0 : r0; a.out_seq_stride = seq_stride;
-    a.beta = 0.f; a.per_sequence = true; a.bf16 = bf16;
+    a.beta = 0.f; a.per_sequence = true; a.bf16 = bf16; a.tile_order = tile_order;
     // one persistent workgroup per compute unit, fed from counters behind the Gram partials
     a.max_workgroups = kComputeUnits;
     a.queue = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(partials) + gram_partial_bytes(layer));
@@ -256,8 +262,20 @@ isopo_status isopo_seq_grads(const isopo_layer* layer, void* stash, void* stream
 
 isopo_status isopo_seq_grads_limited(const isopo_layer* layer, void* stash, int32_t max_workgroups,
                                      uint32_t* queue_dev, void* stream) {
+  return isopo_seq_grads_stash(layer, stash, ISOPO_STASH_ROW_MAJOR, max_workgroups, queue_dev, stream);
+}
+
+isopo_status isopo_seq_grads_stash(const isopo_layer* layer, void* stash, isopo_stash_layout layout,
+                                   int32_t max_workgroups, uint32_t* queue_dev, void* stream) {
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
+  if (layout != ISOPO_STASH_ROW_MAJOR && layout != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_INVALID_ARG;
+  if (layout == ISOPO_STASH_TILE_ORDER) {
+    isopo_stash_layout have;
+    st = isopo_stash_layout_of(layer, &have, nullptr);
+    if (st != ISOPO_OK) return st;
+    if (have != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_UNSUPPORTED;
+  }
   if (!stash || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
   if (max_workgroups != 0 && (max_workgroups < 8 || max_workgroups > 256 || !queue_dev ||
                               (reinterpret_cast<uintptr_t>(queue_dev) & 3u)))
@@ -269,6 +287,7 @@ isopo_status isopo_seq_grads_limited(const isopo_layer* layer, void* stash, int3
   a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0;
   a.out_seq_stride = (long long)layer->d_out * layer->d_in;
   a.beta = 0.f; a.per_sequence = true; a.bf16 = layer->dtype == ISOPO_BF16;
+  a.tile_order = layout == ISOPO_STASH_TILE_ORDER;
   return launch_seq_grad(a, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
@@ -490,6 +509,37 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
   a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0; a.out_seq_stride = 0;
   a.beta = beta; a.per_sequence = false; a.bf16 = bf16;
   return launch_seq_grad(a, s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_stash_layout_of(const isopo_layer* layer, isopo_stash_layout* layout, int32_t* tile) {
+  isopo_status st = check_layer(layer, false);
+  if (st != ISOPO_OK) return st;
+  const int t = (layer->dtype == ISOPO_BF16 && !chunk_cap_bytes())
+                    ? stash_tile_order_ok(layer->d_out, layer->d_in, (int)layer->n_tokens, layer->n_seq,
+                                          layer->seq_offsets_host)
+                    : 0;
+  if (layout) *layout = t ? ISOPO_STASH_TILE_ORDER : ISOPO_STASH_ROW_MAJOR;
+  if (tile) *tile = t;
+  return ISOPO_OK;
+}
+
+isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
+                                       isopo_stash_layout layout, float beta, float* dW, void* stream) {
+  if (layout == ISOPO_STASH_ROW_MAJOR) {
+    if (!stash) return ISOPO_ERR_INVALID_ARG;
+    return isopo_weighted_grad(layer, c, stash, beta, dW, stream);
+  }
+  if (layout != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_INVALID_ARG;
+  isopo_status st = check_layer(layer, true);
+  if (st != ISOPO_OK) return st;
+  if (!c || !stash || !dW || !aligned16(dW) || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
+  isopo_stash_layout have;
+  int32_t tile;
+  st = isopo_stash_layout_of(layer, &have, &tile);
+  if (st != ISOPO_OK) return st;
+  if (have != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_UNSUPPORTED;      // this layer's kept stash is row-major
+  return launch_stash_weighted_sum_tiled(stash, tile, layer->d_out, layer->d_in, layer->n_seq, c, beta, dW,
+                                         static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
 }
 
 size_t isopo_weighted_grad_scratch(const isopo_layer* layer) {

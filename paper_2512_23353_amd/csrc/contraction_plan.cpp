@@ -110,4 +110,10 @@ ContractionPlan plan_contraction(int rows, int d_in, int n_tokens, int n_seq, co
   return pl;
 }
 
+int stash_tile_order_ok(int d_out, int d_in, int n_tokens, int n_seq, const int32_t* off_host) {
+  // multiples of the larger tile, so that a band of output rows may pick either tile size
+  if (d_out % 256 || d_in % 256) return 0;
+  return plan_contraction(d_out, d_in, n_tokens, n_seq, off_host, true).tile;
+}
+
 }  // namespace isopo

@@ -29,7 +29,17 @@ struct SeqGradArgs {
   // eight device counters the launch zeroes; the other compute units stay free for other streams
   int max_workgroups = 0;
   unsigned* queue = nullptr;
+  // per_sequence, bf16: store every sequence's gradient in the order the accumulators hold it (see
+  // stash_tile_order_ok) instead of row-major
+  bool tile_order = false;
 };
+// The per-sequence bf16 contraction can leave its result in tile order: tiles of T x T outputs (T the plan's
+// tile, 256 or 128) in row-major tile order; inside a tile the four waves' (T/2 x T/2) quadrants one after the
+// other (upper left, upper right, lower left, lower right); inside a quadrant its 32x32 blocks row by row, each
+// as two 1 KiB pieces; piece k of a block holds, at 16 bytes per lane l, rows 16 k + 8 (q / 4) + 4 (l / 32) +
+// q % 4 (q = 0..7) of column l % 32.  That is what the matrix cores' accumulators hold, so the epilogue stores
+// 16 bytes per lane without a transpose.  Possible when d_out and d_in are multiples of T: returns T, else 0.
+int stash_tile_order_ok(int d_out, int d_in, int n_tokens, int n_seq, const int32_t* off_host);
 // Launch plan of the streaming bf16 contraction (host arithmetic only).
 struct ContractionPlan {
   int tile;                    // 256 (one workgroup per CU) or 128 (two)
@@ -78,6 +88,9 @@ hipError_t launch_stash_gram_stream(const StashGramArgs& a, hipStream_t s);
 // dW[p] = beta*dW[p] + sum_i c[i] * stash[i][p],  p in [0, n_elem).
 hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq_stride, long long n_elem,
                                      int n_seq, const float* c, float beta, float* dW, hipStream_t s);
+// The same from a bf16 stash in tile order (tile 256 or 128, d_out and d_in multiples of it); dW row-major.
+hipError_t launch_stash_weighted_sum_tiled(const void* stash, int tile, int d_out, int d_in, int n_seq, const float* c,
+                                           float beta, float* dW, hipStream_t s);
 
 // Ghost Gram: K_ij = sum_{t in i, s in j} (x_t.x_s)(delta_t.delta_s).
 struct GhostArgs {

@@ -115,8 +115,9 @@ __device__ __forceinline__ void strip_tile_coords(int tile, int tiles_m, int til
   tile_n = c0 + in_strip % w;
 }
 
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false>
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false>
 __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
+  static_assert(PER_SEQ || !TILED, "tile order is a layout of the per-sequence stash");
   static_assert(PER_SEQ || !PERSIST, "the persistent mode serves the per-sequence gradients");
   constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
   constexpr unsigned PA = BM * 2, PB = BN * 2;                 // LDS row pitch, bytes (no padding: swizzled)
@@ -381,16 +382,36 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     }
     __builtin_amdgcn_s_waitcnt(0x0f70);
 
-    if (PER_SEQ) {
+    // a 256-register tile lives in AGPRs (one wave per SIMD); smaller tiles stay in VGPRs
+    [[maybe_unused]] auto rd = [](float a) {
+      if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
+    };
+    if constexpr (PER_SEQ && TILED) {
+      // Tile order: every lane stores what it holds, 16 bytes (eight rows of one column) at a time; the
+      // whole dimensions are multiples of the tile, so nothing is masked.  No LDS, no barrier.
+      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");       // the last MFMAs have retired (as below)
+      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+      const int tile_row = (m0 - p.out_row0) / BM;
+      u16* tb = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride +
+                ((size_t)tile_row * p.tiles_n + tile_n) * (BM * BN) + (size_t)wave * (WM * WN);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int k = 0; k < 2; ++k) {
+            u32x4 pk;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              pk[q] = pack_bf16(rd(acc[i][j][8 * k + 2 * q]), rd(acc[i][j][8 * k + 2 * q + 1]));
+            *(u32x4*)(tb + ((i * FN + j) * 2 + k) * 512 + lane * 8) = pk;
+          }
+    } else if (PER_SEQ) {
       __builtin_amdgcn_s_barrier();
       // the last MFMAs have retired before the accumulators are read by hand (acc_read is opaque to the
       // compiler's hazard tracking)
       asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
       constexpr unsigned PT = 80;
-      // a 256-register tile lives in AGPRs (one wave per SIMD); smaller tiles stay in VGPRs
-      auto rd = [](float a) {
-        if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
-      };
       const unsigned W = smem_base + (unsigned)wave * 8192;
       const int h = lane >> 5, nl = lane & 31;
       const int l = lane & 15, gq = lane >> 4;
@@ -487,7 +508,7 @@ __global__ void queue_zero_kernel(unsigned* queue) {
 
 // n_wg > 0 (per-sequence mode, 256x256 tile): persistent launch of n_wg workgroups, a multiple of eight,
 // pulling work from `queue` (eight device counters, zeroed here on the stream).
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false>
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false>
 hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStream_t s, int n_wg = 0,
                          unsigned* queue = nullptr) {
   StreamParams p;
@@ -507,7 +528,7 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   p.n_blocks = (unsigned)pl.blocks;
   constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
   constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
-  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST>;
+  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST, TILED>;
   // once per process (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -537,6 +558,14 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
   const ContractionPlan pl = plan_contraction(a.rows, a.d_in, a.n_tokens, a.n_seq, a.off_host, a.per_sequence);
   // a workgroup budget applies to the large tile's per-sequence launches that would not fit it anyway
+  if (a.per_sequence && a.tile_order) {
+    // the caller has checked stash_tile_order_ok; anything else would scatter the stores
+    if (a.rows % pl.tile || a.d_in % pl.tile || a.row0 % pl.tile || a.out_row0 % pl.tile) return hipErrorInvalidValue;
+    if (a.max_workgroups > 0 && a.queue && pl.tile == 256 && pl.blocks > a.max_workgroups)
+      return launch_stream<256, 256, 4, 1, true, true, true>(a, pl, s, a.max_workgroups / 8 * 8, a.queue);
+    return pl.tile == 256 ? launch_stream<256, 256, 4, 1, true, false, true>(a, pl, s)
+                          : launch_stream<128, 128, 4, 2, true, false, true>(a, pl, s);
+  }
   if (a.per_sequence && a.max_workgroups > 0 && a.queue && pl.tile == 256 && pl.blocks > a.max_workgroups)
     return launch_stream<256, 256, 4, 1, true, true>(a, pl, s, a.max_workgroups / 8 * 8, a.queue);
   if (a.per_sequence)

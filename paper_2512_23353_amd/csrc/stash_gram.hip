@@ -189,6 +189,47 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __r
   }
 }
 
+// The same from a stash in tile order (see stash_tile_order_ok): a thread's eight values are eight rows of
+// one column of dW; a wave stores, per value, two rows' runs of 32 consecutive floats.
+template <int T>
+__global__ __launch_bounds__(256) void stash_weighted_sum_tiled_kernel(const void* __restrict__ stash, long long seq_stride,
+                                                                       long long n_vec, int n_seq,
+                                                                       const float* __restrict__ c, float beta,
+                                                                       float* __restrict__ dW, int d_in, int tiles_n) {
+  constexpr int FN = T / 64;                       // 32x32 blocks per quadrant side
+  constexpr int QV = (T / 2) * (T / 2) / 8;        // 16-byte vectors per quadrant
+  constexpr int TV = T * T / 8;                    // ... per tile
+  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < n_vec;
+       vi += (long long)gridDim.x * blockDim.x) {
+    float s[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] = 0.f;
+    const char* src = static_cast<const char*>(stash) + vi * 16;
+#pragma unroll 8
+    for (int i = 0; i < n_seq; ++i) {
+      const float ci = c[i];
+      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+      const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)i * seq_stride * 2));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s[2 * e] += ci * __builtin_bit_cast(float, w[e] << 16);
+        s[2 * e + 1] += ci * __builtin_bit_cast(float, w[e] & 0xffff0000u);
+      }
+    }
+    const long long tile = vi / TV;
+    const int r = (int)(vi % TV), quad = r / QV, r2 = r % QV, piece = r2 / 64, lane = r2 % 64;
+    const int blk = piece >> 1, k = piece & 1, bi = blk / FN, bj = blk % FN;
+    const int tile_m = (int)(tile / tiles_n), tile_n = (int)(tile % tiles_n);
+    const int n = tile_n * T + (quad & 1) * (T / 2) + bj * 32 + (lane & 31);
+    const int m0 = tile_m * T + (quad >> 1) * (T / 2) + bi * 32 + 16 * k + 4 * (lane >> 5);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float* o = dW + (size_t)(m0 + 8 * (q >> 2) + (q & 3)) * d_in + n;
+      *o = (beta != 0.f ? beta * *o : 0.f) + s[q];
+    }
+  }
+}
+
 template <int NB>
 hipError_t launch_gram_nb(const GramParams& p, bool bf16, hipStream_t s) {
   if (bf16)
@@ -253,6 +294,22 @@ hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq
   else
     hipLaunchKernelGGL((stash_weighted_sum_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
                        n_vec, n_seq, c, beta, dW);
+  return hipGetLastError();
+}
+
+hipError_t launch_stash_weighted_sum_tiled(const void* stash, int tile, int d_out, int d_in, int n_seq, const float* c,
+                                           float beta, float* dW, hipStream_t s) {
+  if ((tile != 256 && tile != 128) || d_out % tile || d_in % tile) return hipErrorInvalidValue;
+  const long long D = (long long)d_out * d_in, n_vec = D / 8;
+  if (n_vec <= 0) return hipSuccess;
+  long long blocks = (n_vec + 255) / 256;
+  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
+  if (tile == 256)
+    hipLaunchKernelGGL((stash_weighted_sum_tiled_kernel<256>), dim3((unsigned)blocks), dim3(256), 0, s, stash, D, n_vec,
+                       n_seq, c, beta, dW, d_in, d_in / tile);
+  else
+    hipLaunchKernelGGL((stash_weighted_sum_tiled_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, s, stash, D, n_vec,
+                       n_seq, c, beta, dW, d_in, d_in / tile);
   return hipGetLastError();
 }
 

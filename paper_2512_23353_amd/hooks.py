@@ -42,20 +42,20 @@ def _hip_layer_step(X, Delta, seq_offsets, A, cfg) -> torch.Tensor:
     if variant == "interacting_ema":
         # the interacting experiment's regulariser: lam * trailing mean over steps of the layer's mean eigenvalue,
         # the state living on the device with the hooks object (one per module)
-        K, ws = isopo.layer_gram(layer, "materialised", keep_stash=True)
+        K, ws = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_FAST)
         c, _ = isopo.transform_ema(K, A, "interacting", cfg["lam"], cfg["ema_state"], cfg["ema_decay"])
-        return isopo.weighted_grad(layer, c, ws)
+        return isopo.weighted_grad(layer, c, ws, layout=isopo.stash_layout(layer)[0])
     if variant == "fisher_token_samples":
         n_s = min(cfg["n_samples"], layer.n_tokens)
         idx = torch.randperm(layer.n_tokens, generator=cfg["generator"], device="cpu")[:n_s]
         c, _ = isopo.fisher_samples(layer, idx.to(torch.int32).to(X.device), A, cfg["lam"], reg_mode)
         return isopo.weighted_grad_prescaled(layer, c)
     if variant == "rescaled":
-        K, ws = isopo.layer_gram(layer, "materialised", keep_stash=True)
+        K, ws = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_FAST)
         f2, g2 = isopo.gram_norms(K)
         p, q, r = cfg["pqr"]
         c = isopo.rescale(f2, g2, A, p, q, r, reg=cfg["reg3"])
-        return isopo.weighted_grad(layer, c, ws)
+        return isopo.weighted_grad(layer, c, ws, layout=isopo.stash_layout(layer)[0])
     raise ValueError(f"unknown variant {variant!r}")
 
 

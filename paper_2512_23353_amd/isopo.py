@@ -19,6 +19,8 @@ _lib = None
 OK = 0
 F32, BF16 = 0, 1
 GRAM_AUTO, GRAM_GHOST, GRAM_MATERIALISED = 0, 1, 2
+STASH_ROW_MAJOR, STASH_TILE_ORDER = 0, 1
+KEEP_ROW_MAJOR, KEEP_FAST = 1, 2          # keep_stash values of layer_gram
 VARIANT_FISHER, VARIANT_INTERACTING = 0, 1
 REG_ABSOLUTE, REG_REL_TRACE, REG_EMA_TRACE = 0, 1, 2
 MAX_SEQ = 1024
@@ -28,6 +30,7 @@ _PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALI
 _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
 EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_plan", "isopo_layer_gram",
+           "isopo_stash_layout_of", "isopo_weighted_grad_stash", "isopo_seq_grads_stash",
            "isopo_transform_ema", "isopo_seq_grads_limited", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
@@ -83,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_seq_grads.restype = ctypes.c_int
     lib.isopo_seq_grads_limited.argtypes = [lp, vp, i32, vp, vp]
     lib.isopo_seq_grads_limited.restype = ctypes.c_int
+    lib.isopo_seq_grads_stash.argtypes = [lp, vp, ctypes.c_int, i32, vp, vp]
+    lib.isopo_seq_grads_stash.restype = ctypes.c_int
     lib.isopo_stash_gram_workspace.argtypes = [i32]
     lib.isopo_stash_gram_workspace.restype = sz
     lib.isopo_stash_gram.argtypes = [vp, ctypes.c_int, i32, ctypes.c_int64, vp, vp, sz, vp]
@@ -95,6 +100,10 @@ def load() -> ctypes.CDLL:
     lib.isopo_transform_ema.restype = ctypes.c_int
     lib.isopo_weighted_grad.argtypes = [lp, vp, vp, f32, vp, vp]
     lib.isopo_weighted_grad.restype = ctypes.c_int
+    lib.isopo_stash_layout_of.argtypes = [lp, vp, vp]
+    lib.isopo_stash_layout_of.restype = ctypes.c_int
+    lib.isopo_weighted_grad_stash.argtypes = [lp, vp, vp, ctypes.c_int, f32, vp, vp]
+    lib.isopo_weighted_grad_stash.restype = ctypes.c_int
     lib.isopo_scale_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int64, i32, vp, i32, vp, vp, vp]
     lib.isopo_scale_rows.restype = ctypes.c_int
     lib.isopo_fisher_samples_workspace.argtypes = [lp, i32]
@@ -225,9 +234,10 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
 
 
 def layer_gram(layer: Layer, path="auto", K: Optional[torch.Tensor] = None,
-               workspace: Optional[torch.Tensor] = None, keep_stash: bool = False, stream=None):
+               workspace: Optional[torch.Tensor] = None, keep_stash=False, stream=None):
     """K [n_seq, n_seq] fp32.  Returns (K, workspace); with keep_stash the stash
-    lies at the start of the workspace."""
+    lies at the start of the workspace: True / KEEP_ROW_MAJOR as [n_seq, d_out, d_in],
+    KEEP_FAST in the layout stash_layout(layer) reports (for weighted_grad's `layout`)."""
     if K is None:
         K = torch.empty((layer.n_seq, layer.n_seq), dtype=torch.float32, device=layer.device)
     if workspace is None:
@@ -243,12 +253,19 @@ def stash_nbytes(layer: Layer) -> int:
 
 
 def seq_grads(layer: Layer, stash: Optional[torch.Tensor] = None, stream=None, max_workgroups: int = 0,
-              queue: Optional[torch.Tensor] = None) -> torch.Tensor:
+              queue: Optional[torch.Tensor] = None, layout: Optional[int] = None) -> torch.Tensor:
     """The stash of per-sequence gradients [n_seq, d_out, d_in] in the input dtype.  max_workgroups > 0:
-    at most that many compute units are used (queue: int32/uint32 device tensor of 8 elements, scratch)."""
+    at most that many compute units are used (queue: int32/uint32 device tensor of 8 elements, scratch).
+    layout = STASH_TILE_ORDER: the same elements in tile order (see stash_layout)."""
     if stash is None:
         stash = torch.empty((layer.n_seq, layer.d_out, layer.d_in), dtype=layer.X.dtype, device=layer.device)
-    if max_workgroups:
+    if layout is not None:
+        if max_workgroups and queue is None:
+            queue = torch.zeros(8, dtype=torch.int32, device=layer.device)
+        _check(load().isopo_seq_grads_stash(layer.ref(), stash.data_ptr(), int(layout), int(max_workgroups),
+                                            _ptr(queue) if max_workgroups else None, _stream(stream)),
+               "isopo_seq_grads_stash")
+    elif max_workgroups:
         if queue is None:
             queue = torch.zeros(8, dtype=torch.int32, device=layer.device)
         _check(load().isopo_seq_grads_limited(layer.ref(), stash.data_ptr(), int(max_workgroups), queue.data_ptr(),
@@ -323,14 +340,25 @@ def transform_ema(K: torch.Tensor, A: torch.Tensor, variant, factor: float, ema_
     return c, info
 
 
+def stash_layout(layer: Layer):
+    """(layout, tile) of the stash layer_gram(keep_stash=KEEP_FAST) leaves for this layer."""
+    layout, tile = ctypes.c_int(0), ctypes.c_int32(0)
+    _check(load().isopo_stash_layout_of(layer.ref(), ctypes.byref(layout), ctypes.byref(tile)), "isopo_stash_layout_of")
+    return layout.value, tile.value
+
+
 def weighted_grad(layer: Layer, c: Optional[torch.Tensor], stash: Optional[torch.Tensor] = None, beta: float = 0.0,
-                  dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                  dW: Optional[torch.Tensor] = None, stream=None, layout: Optional[int] = None) -> torch.Tensor:
     """dW [d_out, d_in] fp32 = beta dW + sum_i c_i G_i (from the stash if given,
-    else by contracting X and Delta again)."""
+    else by contracting X and Delta again).  `layout`: the kept stash's layout, if not row-major."""
     if dW is None:
         if beta != 0.0:
             raise ValueError("beta != 0 needs an existing dW")
         dW = torch.empty((layer.d_out, layer.d_in), dtype=torch.float32, device=layer.device)
+    if layout is not None:
+        _check(load().isopo_weighted_grad_stash(layer.ref(), _ptr(c), _ptr(stash), int(layout), float(beta),
+                                                dW.data_ptr(), _stream(stream)), "isopo_weighted_grad_stash")
+        return dW
     _check(load().isopo_weighted_grad(layer.ref(), _ptr(c), _ptr(stash), float(beta), dW.data_ptr(),
                                       _stream(stream)), "isopo_weighted_grad")
     return dW
@@ -484,12 +512,17 @@ def weighted_grad_prescaled(layer: Layer, c: torch.Tensor, scratch: Optional[tor
 def layer_step(layer: Layer, A: torch.Tensor, variant="interacting", lam: float = 0.0,
                reg_mode: int = REG_ABSOLUTE, path="auto", beta: float = 0.0, dW: Optional[torch.Tensor] = None,
                workspace: Optional[torch.Tensor] = None, stream=None) -> dict:
-    """The three calls chained on one stream with no host synchronisation."""
+    """The three calls chained on one stream with no host synchronisation.  The returned workspace holds
+    the stash in layout `stash_layout` (None: no stash was kept)."""
     chosen, full, _ = gram_plan(layer, path)
     if workspace is None:
         workspace = alloc_workspace(full, layer.device)
     keep = chosen == "materialised" and workspace.numel() >= full
-    K, workspace = layer_gram(layer, path, workspace=workspace, keep_stash=keep, stream=stream)
+    K, workspace = layer_gram(layer, path, workspace=workspace, keep_stash=KEEP_FAST if keep else 0, stream=stream)
     c, info = transform(K, A, variant, lam, reg_mode, stream=stream)
-    dW = weighted_grad(layer, c, workspace if keep else None, beta, dW, stream=stream)
-    return {"K": K, "c": c, "info": info, "dW": dW, "path": chosen, "workspace": workspace}
+    layout = stash_layout(layer)[0] if keep else None
+    if keep:
+        dW = weighted_grad(layer, c, workspace, beta, dW, stream=stream, layout=layout)
+    else:
+        dW = weighted_grad(layer, c, None, beta, dW, stream=stream)
+    return {"K": K, "c": c, "info": info, "dW": dW, "path": chosen, "workspace": workspace, "stash_layout": layout}

@@ -33,7 +33,7 @@ def test_config2_block_full(gpu_device, rho):
         assert isopo.gram_plan(layer)[0] == "materialised"
         out = isopo.layer_step(layer, A, "interacting", 1e-3, isopo.REG_REL_TRACE, "auto")
         cf, _ = isopo.transform(out["K"], A, "fisher", 1e-3, isopo.REG_REL_TRACE)
-        dWf = isopo.weighted_grad(layer, cf, out["workspace"])
+        dWf = isopo.weighted_grad(layer, cf, out["workspace"], layout=out["stash_layout"])
         torch.cuda.synchronize()
         ref = oracle_step(prob, "interacting", 1e-3, isopo.REG_REL_TRACE, chunk_rows=2048)
         assert_K_close(out["K"].cpu().numpy(), ref["K"], tol, prob.name)
@@ -53,9 +53,11 @@ def _sampled_checks(prob, gpu_device, rng, n_k_entries, full_k=False):
     tol = TOL[prob.dtype]
     layer, A = to_device(prob, gpu_device)
     chosen, full, _ = isopo.gram_plan(layer)
-    K, ws = isopo.layer_gram(layer, "auto", keep_stash=(chosen == "materialised"))
+    # the stash in the layout the benchmark's step uses (tile order for these shapes)
+    K, ws = isopo.layer_gram(layer, "auto", keep_stash=isopo.KEEP_FAST if chosen == "materialised" else 0)
     c_rand = torch.from_numpy(rng.standard_normal(prob.n_seq).astype(np.float32)).to(gpu_device)
-    dW_stash = isopo.weighted_grad(layer, c_rand, ws) if chosen == "materialised" else None
+    dW_stash = (isopo.weighted_grad(layer, c_rand, ws, layout=isopo.stash_layout(layer)[0])
+                if chosen == "materialised" else None)
     dW_re = isopo.weighted_grad(layer, c_rand)
     c_int, info = isopo.transform(K, A, "interacting", 1e-3, isopo.REG_REL_TRACE)
     torch.cuda.synchronize()

@@ -80,6 +80,95 @@ def test_ragged_edge_cases(gpu_device, dtype, case, path):
     _check_step(prob, gpu_device, path, "fisher", 1e-2, isopo.REG_REL_TRACE)
 
 
+def _tile_order_index(d_out, d_in, T):
+    """Row-major element index of every position of a stash in tile order (the layout include/isopo.h
+    documents for ISOPO_STASH_TILE_ORDER), written out from that description."""
+    idx = np.empty(d_out * d_in, dtype=np.int64)
+    pos = 0
+    l = np.arange(64)
+    q = np.arange(8)
+    for tm in range(d_out // T):
+        for tn in range(d_in // T):
+            for quad in range(4):
+                r0, c0 = tm * T + (quad >> 1) * (T // 2), tn * T + (quad & 1) * (T // 2)
+                for bi in range(T // 64):
+                    for bj in range(T // 64):
+                        for k in range(2):
+                            rows = r0 + bi * 32 + 16 * k + 8 * (q[None, :] // 4) + 4 * (l[:, None] // 32) + q[None, :] % 4
+                            cols = c0 + bj * 32 + (l[:, None] % 32) + 0 * q[None, :]
+                            idx[pos:pos + 512] = (rows * d_in + cols).reshape(-1)
+                            pos += 512
+    assert pos == d_out * d_in
+    return idx
+
+
+TILE_ORDER_CASES = [
+    # name, d_in, d_out, lengths: 256x256 tiles with the persistent launch (6 tiles x 48 sequences), 128x128 tiles
+    ("tile256_persistent", 768, 512, [int(x) for x in np.random.default_rng(3).integers(0, 90, 48)]),
+    ("tile128", 256, 512, [70, 0, 129, 33, 300]),
+]
+
+
+@pytest.mark.parametrize("case", TILE_ORDER_CASES, ids=[c[0] for c in TILE_ORDER_CASES])
+def test_stash_in_tile_order(gpu_device, case):
+    """A bf16 layer whose dimensions are multiples of 256 keeps its stash in the matrix cores' own order.
+    The elements are the row-major stash's, bit for bit, at the documented positions; K, c and dW of the
+    whole step match the oracle; the stash-weighted sum gives the same bits from either layout."""
+    name, d_in, d_out, lengths = case
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=29, sigma_delta=1e-2, rho=0.4)
+    layer, A = to_device(prob, gpu_device)
+    layout, T = isopo.stash_layout(layer)
+    assert layout == isopo.STASH_TILE_ORDER and T == (256 if name.startswith("tile256") else 128)
+    plan = isopo.contraction_plan(layer.ref(), True)
+    assert plan["tile"] == T
+    row_major = isopo.seq_grads(layer)
+    tiled = isopo.seq_grads(layer, layout=isopo.STASH_TILE_ORDER)
+    budget = isopo.seq_grads(layer, layout=isopo.STASH_TILE_ORDER, max_workgroups=256)
+    torch.cuda.synchronize()
+    idx = _tile_order_index(d_out, d_in, T)
+    rm = row_major.view(torch.int16).cpu().numpy().reshape(prob.n_seq, -1)
+    for got in (tiled, budget):
+        assert np.array_equal(got.view(torch.int16).cpu().numpy().reshape(prob.n_seq, -1), rm[:, idx])
+    # the whole step through the kept stash
+    _check_step(prob, gpu_device, "materialised", "interacting", 1e-2, isopo.REG_REL_TRACE)
+    K_fast, ws = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_FAST)
+    K_rm, ws_rm = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_ROW_MAJOR)
+    torch.cuda.synchronize()
+    n = prob.n_seq * d_out * d_in
+    assert np.array_equal(ws[: 2 * n].view(torch.int16).cpu().numpy().reshape(prob.n_seq, -1), rm[:, idx])
+    assert np.array_equal(ws_rm[: 2 * n].view(torch.int16).cpu().numpy().reshape(prob.n_seq, -1), rm)
+    assert rel_err(K_fast.cpu().numpy(), K_rm.cpu().numpy()) < 1e-5
+    c = torch.from_numpy(np.random.default_rng(4).standard_normal(prob.n_seq).astype(np.float32)).to(gpu_device)
+    dW0 = torch.from_numpy(np.random.default_rng(5).standard_normal((d_out, d_in)).astype(np.float32)).to(gpu_device)
+    for beta in (0.0, 0.5):
+        a = isopo.weighted_grad(layer, c, ws, beta, dW0.clone(), layout=isopo.STASH_TILE_ORDER)
+        b = isopo.weighted_grad(layer, c, ws_rm, beta, dW0.clone())
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), f"beta={beta}"
+    # a row-major stash through the same entry point
+    assert torch.equal(isopo.weighted_grad(layer, c, ws_rm, layout=isopo.STASH_ROW_MAJOR), isopo.weighted_grad(layer, c, ws_rm))
+
+
+def test_stash_layout_falls_back_to_row_major(gpu_device):
+    """Dimensions that are not multiples of 256, or fp32 inputs: keep_stash = 2 leaves the row-major stash,
+    and asking for tile order is refused."""
+    for dtype, d_in, d_out in (("bf16", 264, 512), ("f32", 256, 256)):
+        prob = wl.custom_layer(d_in, d_out, [40, 3, 77], dtype=dtype, seed=30, sigma_delta=1e-2)
+        layer, _ = to_device(prob, gpu_device)
+        assert isopo.stash_layout(layer) == (isopo.STASH_ROW_MAJOR, 0)
+        _, ws = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_FAST)
+        ref = isopo.seq_grads(layer)
+        torch.cuda.synchronize()
+        nbytes = ref.numel() * ref.element_size()
+        assert torch.equal(ws[:nbytes], ref.view(torch.uint8).reshape(-1))
+        c = torch.ones(prob.n_seq, device=gpu_device)
+        for call in (lambda: isopo.seq_grads(layer, layout=isopo.STASH_TILE_ORDER),
+                     lambda: isopo.weighted_grad(layer, c, ws, layout=isopo.STASH_TILE_ORDER)):
+            with pytest.raises(isopo.IsopoError) as e:
+                call()
+            assert e.value.status == 3
+
+
 GHOST_SPLIT_CASES = [
     # name, d_in, d_out, lengths: wide layers on few tokens, where the bf16 ghost launch cuts the features
     # into ranges; 64-feature tails, and an operand with fewer 64-feature slices than ranges

@@ -111,6 +111,18 @@ def test_cost_model_prefers_ghost_only_for_few_tokens():
     assert all(a <= b for a, b in zip(ghost_costs, ghost_costs[1:]))
 
 
+def test_stash_layout_is_a_host_function_of_dtype_and_shape():
+    """Tile order for bf16 layers whose dimensions are multiples of 256 (the tile is the contraction plan's);
+    row-major otherwise."""
+    many = [64] * 48
+    assert isopo.stash_layout(_host_layer(many, 768, 512)) == (isopo.STASH_TILE_ORDER, 256)
+    assert isopo.stash_layout(_host_layer([70, 129, 33], 256, 512)) == (isopo.STASH_TILE_ORDER, 128)
+    assert isopo.stash_layout(_host_layer(many, 4096, 14336)) == (isopo.STASH_TILE_ORDER, 256)
+    assert isopo.stash_layout(_host_layer(many, 768, 520)) == (isopo.STASH_ROW_MAJOR, 0)
+    assert isopo.stash_layout(_host_layer(many, 264, 512)) == (isopo.STASH_ROW_MAJOR, 0)
+    assert isopo.stash_layout(_host_layer(many, 768, 512, dtype=isopo.F32)) == (isopo.STASH_ROW_MAJOR, 0)
+
+
 def test_contraction_plan_whole_tiles_then_split_tail():
     """Unweighted contraction with more 256x256 tiles than compute units and a partial last round: the tiles
     of the full rounds stay whole, the rest is cut into token chunks that fill the round.  The kernel's
