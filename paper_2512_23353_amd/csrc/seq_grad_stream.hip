@@ -25,14 +25,18 @@
 //    count is no multiple of eight that would leave XCDs unevenly loaded (or
 //    idle); the host then cuts the sequence-major list of (sequence, tile) pairs
 //    into eight contiguous ranges of equal work (tokens plus a fixed charge per
-//    workgroup) and each XCD walks one.  The bf16 tile is transposed through LDS
-//    in the epilogue so that every lane stores 16 bytes.
+//    workgroup) and each XCD walks one.  For a row-major stash the bf16 tile is
+//    transposed through LDS in the epilogue so that every lane stores 16 bytes;
+//    for a stash in tile order (TILED) every lane stores the 16 bytes it holds,
+//    with no LDS round trip at all.
 //  * Sum-over-all-tokens mode with few output tiles (narrow projections, long
 //    microbatches): the token range is split into chunks, a workgroup takes one
 //    (chunk, tile) pair from its XCD's range of the same kind of list, and the
 //    fp32 partial tiles are added to dW with hardware float atomics after a pass
 //    that applies beta.  This mode keeps one more token block in flight: a block's
-//    stage is free once the barrier after its last fragment read is passed.
+//    stage is free once the barrier after its last fragment read is passed.  With
+//    more tiles than compute units only the tiles of the last, partial round of
+//    one tile per unit are split; the others stay whole.
 #include "common.h"
 #include "kernels.h"
 
