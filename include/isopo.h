@@ -134,9 +134,9 @@ isopo_status isopo_contraction_plan(const isopo_layer* layer, int per_sequence, 
  *               hold them, so that the contraction stores them without a transpose (bf16 layers whose
  *               d_out and d_in are multiples of 256): T x T tiles (T = 256 or 128, as the contraction
  *               plan chooses) in row-major tile order; inside a tile its four (T/2 x T/2) quadrants (upper
- *               left, upper right, lower left, lower right); inside a quadrant its 32x32 blocks row by row,
- *               each as two pieces of 512 elements; element 8 l + q (l = 0..63, q = 0..7) of piece k is
- *               row 16 k + 8 (q / 4) + 4 (l / 32) + q % 4, column l % 32 of the block.
+ *               left, upper right, lower left, lower right); inside a quadrant its strips of 16 rows, top
+ *               down, each strip as pieces of 16 rows x 32 columns, left to right; element 8 l + q
+ *               (l = 0..63, q = 0..7) of a piece is its row 4 (l / 16) + q % 4, column l % 16 + 16 (q / 4).
  * isopo_stash_layout_of tells which of the two keep_stash = 2 leaves for a layer (a pure host function of
  * dtype, shape and sequence offsets; *tile = T, or 0 for ROW_MAJOR).  The Gram matrix does not depend on
  * the order of the elements; isopo_weighted_grad_stash forms dW (row-major, as always) from either. */

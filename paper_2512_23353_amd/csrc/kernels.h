@@ -35,10 +35,11 @@ struct SeqGradArgs {
 };
 // The per-sequence bf16 contraction can leave its result in tile order: tiles of T x T outputs (T the plan's
 // tile, 256 or 128) in row-major tile order; inside a tile the four waves' (T/2 x T/2) quadrants one after the
-// other (upper left, upper right, lower left, lower right); inside a quadrant its 32x32 blocks row by row, each
-// as two 1 KiB pieces; piece k of a block holds, at 16 bytes per lane l, rows 16 k + 8 (q / 4) + 4 (l / 32) +
-// q % 4 (q = 0..7) of column l % 32.  That is what the matrix cores' accumulators hold, so the epilogue stores
-// 16 bytes per lane without a transpose.  Possible when d_out and d_in are multiples of T: returns T, else 0.
+// other (upper left, upper right, lower left, lower right); inside a quadrant its strips of 16 rows, top down,
+// each strip as pieces of 16 rows x 32 columns, left to right; a piece is 1 KiB, 16 bytes per lane l: its
+// element 8 l + q (q = 0..7) is row 4 (l / 16) + q % 4, column l % 16 + 16 (q / 4) of the piece.  That is what
+// the 16x16 accumulator blocks of two neighbouring MFMA outputs hold, so the epilogue stores 16 bytes per lane
+// without a transpose.  Possible when d_out and d_in are multiples of 256: returns T, else 0.
 int stash_tile_order_ok(int d_out, int d_in, int n_tokens, int n_seq, const int32_t* off_host);
 // Launch plan of the streaming bf16 contraction (host arithmetic only).
 struct ContractionPlan {

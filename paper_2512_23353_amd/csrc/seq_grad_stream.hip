@@ -200,19 +200,20 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     const int n_tiles = (n_rows + BK - 1) / BK;
     const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
 
+    // 16-byte column swizzle of token row r.  The 16x16x32 fragments (TILED) are read by lane groups whose
+    // rows lie 8 apart, so that variant also moves rows 8..15 and 24..31 by two columns.
+    auto swz = [](int r) { return ((r & 3) << 2) ^ (r & 2) ^ (TILED ? ((r >> 3) & 1) << 1 : 0); };
     unsigned offA[LA], offB[LB];
 #pragma unroll
     for (int q = 0; q < LA; ++q) {
       const int r = (wave * LA + q) * RA + lane / (64 / RA);
-      const int f = ((r & 3) << 2) ^ (r & 2);
-      const int g = (lane % (64 / RA)) ^ f;
+      const int g = (lane % (64 / RA)) ^ swz(r);
       offA[q] = (unsigned)r * rbA + (unsigned)(m0 * 2 + g * 16);
     }
 #pragma unroll
     for (int q = 0; q < LB; ++q) {
       const int r = (wave * LB + q) * RB + lane / (64 / RB);
-      const int f = ((r & 3) << 2) ^ (r & 2);
-      const int g = (lane % (64 / RB)) ^ f;
+      const int g = (lane % (64 / RB)) ^ swz(r);
       offB[q] = (unsigned)r * rbB + (unsigned)(n0 * 2 + g * 16);
     }
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -230,6 +231,145 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       for (int q = 0; q < LB; ++q) load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + q) * 1024, offB[q]);
     };
 
+    if constexpr (TILED) {
+      // ---- stash in tile order: the 16x16x32 MFMA, which draws less power per flop than the 32x32x16 one
+      // (a loop of either on random operands in registers sustains 1.97 against 1.70 PFLOP/s under the
+      // board's power cap).  A token block is one K = 32 step: 8 + 8 fragments (16 features x 32 tokens
+      // each), FM16 x FN16 MFMAs row by row.  Behind row i go the next block's B fragment i (into the other
+      // of two register sets) and, once the row is done with it, the next block's A fragment i (in place),
+      // and a share of the eight DMA instructions of the block AHEAD ahead.  One barrier per block.
+      constexpr int FM16 = WM / 16, FN16 = WN / 16, NMF16 = FM16 * FN16;
+      static_assert(FM16 == FN16, "square wave tile");
+      constexpr int LPT = LA + LB, AHEAD = NSTAGE - 1;
+      typedef float f32x4v __attribute__((ext_vector_type(4)));
+      unsigned adA[FM16], adB[FN16];
+      {
+        // lane (l, g4): token rows 8 g4 + l / 4 (+ 4 for the second read), features 4 (l % 4) ..+3 of the
+        // fragment's 16; the transposing read leaves lane l with tokens 8 g4 ..+7 of feature l
+        const int l = lane & 15, g4 = lane >> 4;
+        const int kr = 8 * g4 + (l >> 2);
+        const int f = swz(kr);
+#pragma unroll
+        for (int i = 0; i < FM16; ++i) {
+          const int ca = wm * WM + i * 16 + 4 * (l & 3);
+          adA[i] = (unsigned)kr * PA + (unsigned)(((ca >> 3) ^ f) << 4) + (unsigned)((ca & 7) * 2);
+        }
+#pragma unroll
+        for (int j = 0; j < FN16; ++j) {
+          const int cb = wn * WN + j * 16 + 4 * (l & 3);
+          adB[j] = A_BYTES + (unsigned)kr * PB + (unsigned)(((cb >> 3) ^ f) << 4) + (unsigned)((cb & 7) * 2);
+        }
+      }
+      auto frag = [&](unsigned a, unsigned pitch) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * pitch));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      };
+      f32x4v acc[FM16][FN16];
+#pragma unroll
+      for (int i = 0; i < FM16; ++i)
+#pragma unroll
+        for (int j = 0; j < FN16; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+      bf16x8 fa[FM16], fb[2][FN16];
+#pragma unroll
+      for (int s = 0; s < AHEAD; ++s) issue_loads(s);
+      if (n_tiles > 0) {
+        __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 1) * LPT) & 15) | ((((AHEAD - 1) * LPT) >> 4) << 14));
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int i = 0; i < FM16; ++i) fa[i] = frag(smem_base + adA[i], PA);
+#pragma unroll
+        for (int j = 0; j < FN16; ++j) fb[0][j] = frag(smem_base + adB[j], PB);
+        auto token_block = [&](int it, auto cur_c) {
+          constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+          const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
+          const int nb = it + AHEAD;
+          int rows = n_rows - nb * BK;
+          rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+          const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
+          const v4i rb = make_rsrc(baseB + (size_t)nb * BK * p.d_in, (unsigned)rows * rbB);
+          const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
+          // When the accumulator tile fills the AGPRs the MFMA is written as asm, so that every accumulator
+          // stays where it is (left to itself the register allocator shuttles them through VGPRs).
+#define ISOPO_MFMA16(i, j)                                                                                            \
+  do {                                                                                                                \
+    if constexpr (NMF16 * 4 > 128) {                                                                                  \
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fa[i]), "v"(fb[CUR][j]));       \
+    } else {                                                                                                          \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[CUR][j], acc[i][j], 0, 0, 0);                     \
+    }                                                                                                                 \
+  } while (0)
+          // the first RB rows of the wave tile: their MFMAs carry the DMA instructions of the block AHEAD ahead
+          // (its stage, that of block it - 1, was last read before the barrier of block it - 1)
+          constexpr int RB = FM16 / 2, HEAD = RB * FN16, REST = NMF16 - HEAD;
+#pragma unroll
+          for (int i = 0; i < RB; ++i)
+#pragma unroll
+            for (int j = 0; j < FN16; ++j) {
+              const int idx = i * FN16 + j;
+              ISOPO_MFMA16(i, j);
+#pragma unroll
+              for (int q = idx * LPT / HEAD; q < (idx + 1) * LPT / HEAD; ++q) {
+                if (q < LA) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
+                else load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + (q - LA)) * 1024, offB[q - LA]);
+              }
+            }
+          // block it + 1 has landed (this wave's part; the barrier makes it everyone's)
+          __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 1) * LPT) & 15) | ((((AHEAD - 1) * LPT) >> 4) << 14));
+          __builtin_amdgcn_s_barrier();
+          // the other rows: behind their MFMAs the fragments of block it + 1, the B ones into the other register
+          // set, the A ones in place: those of the first RB rows at once, the others as their rows end
+#pragma unroll
+          for (int i = RB; i < FM16; ++i)
+#pragma unroll
+            for (int j = 0; j < FN16; ++j) {
+              ISOPO_MFMA16(i, j);
+              const int k = (i - RB) * FN16 + j;                      // 0 .. REST - 1
+              constexpr int PER = REST / (FN16 + RB);                 // MFMAs per fragment slot
+              if (j == 0 && i > RB) fa[i - 1] = frag(sn + adA[i - 1], PA);
+              if (k % PER == PER - 1) {
+                const int f = k / PER;
+                if (f < FN16) fb[NXT][f] = frag(sn + adB[f], PB);
+                else if (f < FN16 + RB) fa[f - FN16] = frag(sn + adA[f - FN16], PA);
+              }
+            }
+          fa[FM16 - 1] = frag(sn + adA[FM16 - 1], PA);
+#undef ISOPO_MFMA16
+        };
+        // two blocks per trip (the B fragments alternate between two register sets); an odd count runs one
+        // block past the end, whose rows are all out of range and arrive as zeros
+        for (int it = 0; it < n_tiles; it += 2) {
+          token_block(it, std::integral_constant<int, 0>{});
+          token_block(it + 1, std::integral_constant<int, 1>{});
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+      // Epilogue: lane l holds, of block (i, j), rows 4 (l / 16) ..+3 of column l % 16.  Two blocks side by
+      // side make the lane's 16 bytes; a piece (two blocks, 512 elements) is one 1 KiB store of the wave.
+      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");       // the last MFMAs have retired
+      auto rd16 = [](float a) {
+        if constexpr (NMF16 * 4 > 128) return acc_read(a); else return a;
+      };
+      (void)rd16;
+      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+      const int tile_row = (m0 - p.out_row0) / BM;
+      u16* tb = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride +
+                ((size_t)tile_row * p.tiles_n + tile_n) * (BM * BN) + (size_t)wave * (WM * WN);
+#pragma unroll
+      for (int i = 0; i < FM16; ++i)
+#pragma unroll
+        for (int jp = 0; jp < FN16 / 2; ++jp) {
+          u32x4 pk;
+          pk[0] = pack_bf16(rd16(acc[i][2 * jp][0]), rd16(acc[i][2 * jp][1]));
+          pk[1] = pack_bf16(rd16(acc[i][2 * jp][2]), rd16(acc[i][2 * jp][3]));
+          pk[2] = pack_bf16(rd16(acc[i][2 * jp + 1][0]), rd16(acc[i][2 * jp + 1][1]));
+          pk[3] = pack_bf16(rd16(acc[i][2 * jp + 1][2]), rd16(acc[i][2 * jp + 1][3]));
+          *(u32x4*)(tb + (i * (FN16 / 2) + jp) * 512 + lane * 8) = pk;
+        }
+      if constexpr (PERSIST) continue; else break;
+    }
     unsigned adA[FM], adB[FN];
     {
       const int l = lane & 15, g4 = lane >> 4;
@@ -390,27 +530,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     [[maybe_unused]] auto rd = [](float a) {
       if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
     };
-    if constexpr (PER_SEQ && TILED) {
-      // Tile order: every lane stores what it holds, 16 bytes (eight rows of one column) at a time; the
-      // whole dimensions are multiples of the tile, so nothing is masked.  No LDS, no barrier.
-      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");       // the last MFMAs have retired (as below)
-      typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-      const int tile_row = (m0 - p.out_row0) / BM;
-      u16* tb = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride +
-                ((size_t)tile_row * p.tiles_n + tile_n) * (BM * BN) + (size_t)wave * (WM * WN);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int k = 0; k < 2; ++k) {
-            u32x4 pk;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-              pk[q] = pack_bf16(rd(acc[i][j][8 * k + 2 * q]), rd(acc[i][j][8 * k + 2 * q + 1]));
-            *(u32x4*)(tb + ((i * FN + j) * 2 + k) * 512 + lane * 8) = pk;
-          }
-    } else if (PER_SEQ) {
+    if (PER_SEQ) {
       __builtin_amdgcn_s_barrier();
       // the last MFMAs have retired before the accumulators are read by hand (acc_read is opaque to the
       // compiler's hazard tracking)

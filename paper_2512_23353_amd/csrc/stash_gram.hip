@@ -189,14 +189,15 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __r
   }
 }
 
-// The same from a stash in tile order (see stash_tile_order_ok): a thread's eight values are eight rows of
-// one column of dW; a wave stores, per value, two rows' runs of 32 consecutive floats.
+// The same from a stash in tile order (see stash_tile_order_ok): a thread's eight values are four rows of
+// two columns of dW, 16 apart; a wave stores, per value, four rows' runs of 16 consecutive floats, and the
+// values q and q + 4 complete each other's 128-byte lines.
 template <int T>
 __global__ __launch_bounds__(256) void stash_weighted_sum_tiled_kernel(const void* __restrict__ stash, long long seq_stride,
                                                                        long long n_vec, int n_seq,
                                                                        const float* __restrict__ c, float beta,
                                                                        float* __restrict__ dW, int d_in, int tiles_n) {
-  constexpr int FN = T / 64;                       // 32x32 blocks per quadrant side
+  constexpr int NP = T / 64;                       // 16x32 pieces per 16-row strip of a quadrant
   constexpr int QV = (T / 2) * (T / 2) / 8;        // 16-byte vectors per quadrant
   constexpr int TV = T * T / 8;                    // ... per tile
   for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < n_vec;
@@ -218,13 +219,13 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_tiled_kernel(const voi
     }
     const long long tile = vi / TV;
     const int r = (int)(vi % TV), quad = r / QV, r2 = r % QV, piece = r2 / 64, lane = r2 % 64;
-    const int blk = piece >> 1, k = piece & 1, bi = blk / FN, bj = blk % FN;
+    const int strip = piece / NP, jp = piece % NP;
     const int tile_m = (int)(tile / tiles_n), tile_n = (int)(tile % tiles_n);
-    const int n = tile_n * T + (quad & 1) * (T / 2) + bj * 32 + (lane & 31);
-    const int m0 = tile_m * T + (quad >> 1) * (T / 2) + bi * 32 + 16 * k + 4 * (lane >> 5);
+    const int n0 = tile_n * T + (quad & 1) * (T / 2) + jp * 32 + (lane & 15);
+    const int m0 = tile_m * T + (quad >> 1) * (T / 2) + strip * 16 + 4 * (lane >> 4);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      float* o = dW + (size_t)(m0 + 8 * (q >> 2) + (q & 3)) * d_in + n;
+      float* o = dW + (size_t)(m0 + (q & 3)) * d_in + n0 + 16 * (q >> 2);
       *o = (beta != 0.f ? beta * *o : 0.f) + s[q];
     }
   }
