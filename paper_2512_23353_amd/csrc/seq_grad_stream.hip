@@ -282,8 +282,12 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         for (int i = 0; i < FM16; ++i) fa[i] = frag(smem_base + adA[i], PA);
 #pragma unroll
         for (int j = 0; j < FN16; ++j) fb[0][j] = frag(smem_base + adB[j], PB);
-        auto token_block = [&](int it, auto cur_c) {
+        // LATE: the two waves of the lower tile half take the other of every two read slots, so that the LDS
+        // serves two waves' fragment reads at a time, not four (compile-time, as CUR, so that the bodies stay
+        // straight-line code)
+        auto token_block = [&](int it, auto cur_c, auto late_c) {
           constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+          constexpr bool LATE = decltype(late_c)::value;
           const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
           const int nb = it + AHEAD;
           int rows = n_rows - nb * BK;
@@ -328,8 +332,8 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
               ISOPO_MFMA16(i, j);
               const int k = (i - RB) * FN16 + j;                      // 0 .. REST - 1
               constexpr int PER = REST / (FN16 + RB);                 // MFMAs per fragment slot
-              if (j == 0 && i > RB) fa[i - 1] = frag(sn + adA[i - 1], PA);
-              if (k % PER == PER - 1) {
+              if (j == (LATE && PER > 1 ? 1 : 0) && i > RB) fa[i - 1] = frag(sn + adA[i - 1], PA);
+              if (k % PER == (LATE ? 0 : PER - 1)) {
                 const int f = k / PER;
                 if (f < FN16) fb[NXT][f] = frag(sn + adB[f], PB);
                 else if (f < FN16 + RB) fa[f - FN16] = frag(sn + adA[f - FN16], PA);
@@ -340,9 +344,16 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         };
         // two blocks per trip (the B fragments alternate between two register sets); an odd count runs one
         // block past the end, whose rows are all out of range and arrive as zeros
-        for (int it = 0; it < n_tiles; it += 2) {
-          token_block(it, std::integral_constant<int, 0>{});
-          token_block(it + 1, std::integral_constant<int, 1>{});
+        if (NMF16 * 4 > 128 && (wave_s & 2)) {
+          for (int it = 0; it < n_tiles; it += 2) {
+            token_block(it, std::integral_constant<int, 0>{}, std::true_type{});
+            token_block(it + 1, std::integral_constant<int, 1>{}, std::true_type{});
+          }
+        } else {
+          for (int it = 0; it < n_tiles; it += 2) {
+            token_block(it, std::integral_constant<int, 0>{}, std::false_type{});
+            token_block(it + 1, std::integral_constant<int, 1>{}, std::false_type{});
+          }
         }
       }
       __builtin_amdgcn_s_waitcnt(0x0f70);
