@@ -122,6 +122,9 @@ __device__ __forceinline__ void strip_tile_coords(int tile, int tiles_m, int til
 template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false>
 __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
   static_assert(PER_SEQ || !TILED, "tile order is a layout of the per-sequence stash");
+  // the 16x16x32 inner loop: the tile-order stash and the sum over all tokens (the row-major stash keeps the
+  // 32x32x16 loop, whose accumulator blocks its transposing epilogue is written for)
+  constexpr bool MF16 = TILED || !PER_SEQ;
   static_assert(PER_SEQ || !PERSIST, "the persistent mode serves the per-sequence gradients");
   constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
   constexpr unsigned PA = BM * 2, PB = BN * 2;                 // LDS row pitch, bytes (no padding: swizzled)
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 
     // 16-byte column swizzle of token row r.  The 16x16x32 fragments (TILED) are read by lane groups whose
     // rows lie 8 apart, so that variant also moves rows 8..15 and 24..31 by two columns.
-    auto swz = [](int r) { return ((r & 3) << 2) ^ (r & 2) ^ (TILED ? ((r >> 3) & 1) << 1 : 0); };
+    auto swz = [](int r) { return ((r & 3) << 2) ^ (r & 2) ^ (MF16 ? ((r >> 3) & 1) << 1 : 0); };
     unsigned offA[LA], offB[LB];
 #pragma unroll
     for (int q = 0; q < LA; ++q) {
@@ -231,8 +234,8 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       for (int q = 0; q < LB; ++q) load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + q) * 1024, offB[q]);
     };
 
-    if constexpr (TILED) {
-      // ---- stash in tile order: the 16x16x32 MFMA, which draws less power per flop than the 32x32x16 one
+    if constexpr (MF16) {
+      // ---- stash in tile order, and the sum over all tokens: the 16x16x32 MFMA, which draws less power per flop than the 32x32x16 one
       // (a loop of either on random operands in registers sustains 1.97 against 1.70 PFLOP/s under the
       // board's power cap).  A token block is one K = 32 step: 8 + 8 fragments (16 features x 32 tokens
       // each), FM16 x FN16 MFMAs row by row.  Behind row i go the next block's B fragment i (into the other
@@ -357,13 +360,35 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         }
       }
       __builtin_amdgcn_s_waitcnt(0x0f70);
-      // Epilogue: lane l holds, of block (i, j), rows 4 (l / 16) ..+3 of column l % 16.  Two blocks side by
-      // side make the lane's 16 bytes; a piece (two blocks, 512 elements) is one 1 KiB store of the wave.
+      // Epilogue: lane l holds, of block (i, j), rows 4 (l / 16) ..+3 of column l % 16.
       asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");       // the last MFMAs have retired
       auto rd16 = [](float a) {
         if constexpr (NMF16 * 4 > 128) return acc_read(a); else return a;
       };
       (void)rd16;
+      if constexpr (!PER_SEQ) {
+        // dW: sixteen lanes store (or add) sixteen consecutive floats of a row
+        const int col = lane & 15, rq = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < FM16; ++i)
+#pragma unroll
+          for (int j = 0; j < FN16; ++j) {
+            const int n = n0 + wn * WN + j * 16 + col;
+            if (n >= p.d_in) continue;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const int m = m0 + wm * WM + i * 16 + 4 * rq + v;
+              if (m >= p.row_end) continue;
+              float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
+              const float val = rd16(acc[i][j][v]);
+              if (split) atomicAdd(o, val);        // beta already applied by the pass before
+              else *o = (p.beta != 0.f ? p.beta * *o : 0.f) + val;
+            }
+          }
+        if constexpr (PERSIST) continue; else break;
+      }
+      // Tile order: two blocks side by side make the lane's 16 bytes; a piece (two blocks, 512 elements) is
+      // one 1 KiB store of the wave.
       typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
       const int tile_row = (m0 - p.out_row0) / BM;
       u16* tb = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride +
