@@ -15,10 +15,16 @@
 //    the 16-byte column index is XOR-swizzled with the token row
 //    (f(r) = 4*(r&3) ^ (r&2)), which makes both the linear DMA writes and the
 //    transpose reads bank-conflict free.
-//  * Fragments are double-buffered in registers and the reads of the next half
-//    block are interleaved one-to-one with the MFMAs of the current one; the
-//    eight DMA instructions of the block NSTAGE-1 ahead go out between the MFMAs
-//    of the second half block, so the matrix pipe never waits on their issue.
+//  * Two inner loops.  The tile-order stash and the sum over all tokens use the
+//    16x16x32 MFMA (less energy per flop, and the part runs at its power cap): a
+//    token block is one K = 32 step of 64 MFMAs per wave; the eight DMA
+//    instructions of the block NSTAGE-1 ahead go out behind the first half of
+//    them, the barrier sits mid-block, the next block's fragments are read behind
+//    the second half.  The row-major stash keeps the 32x32x16 MFMA, whose
+//    accumulator blocks its transposing epilogue is written for: fragments
+//    double-buffered in registers, the reads of the next half block interleaved
+//    one-to-one with the MFMAs of the current one, the DMA instructions between
+//    the MFMAs of the second half block.
 //  * Per-sequence mode: XCD x owns the x-th eighth of the output tiles of every
 //    sequence, so all eight L2s see every sequence (balanced under ragged
 //    lengths) and neighbouring workgroups share operand panels.  When the tile
@@ -33,10 +39,8 @@
 //    microbatches): the token range is split into chunks, a workgroup takes one
 //    (chunk, tile) pair from its XCD's range of the same kind of list, and the
 //    fp32 partial tiles are added to dW with hardware float atomics after a pass
-//    that applies beta.  This mode keeps one more token block in flight: a block's
-//    stage is free once the barrier after its last fragment read is passed.  With
-//    more tiles than compute units only the tiles of the last, partial round of
-//    one tile per unit are split; the others stay whole.
+//    that applies beta.  With more tiles than compute units only the tiles of the
+//    last, partial round of one tile per unit are split; the others stay whole.
 #include "common.h"
 #include "kernels.h"
 
