@@ -114,7 +114,7 @@ def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
     return {"projection": block[big].name, **({"board": power} if power else {}), "tflops_on_the_workload": fl[big]["seq_grads"] / t_real / 1e12,
             "tflops_on_zero_operands": fl[big]["seq_grads"] / t_zero / 1e12,
             "zero_ms": t_zero * 1e3, "workload_ms": t_real * 1e3,
-            "what": "same launch, same cycles; the clock under random operands is about 1.75 GHz, on zeros 2.4 GHz (profiles/)"}
+            "what": "same launch, same cycles; the clock under random operands is 1.84 - 1.89 GHz, on zeros 2.4 GHz (profiles/)"}
 
 
 def main() -> int:
@@ -363,7 +363,7 @@ def main() -> int:
                    "compute_units": torch.cuda.get_device_properties(dev).multi_processor_count,
                    "hbm_gib": round(torch.cuda.get_device_properties(dev).total_memory / 2 ** 30, 1),
                    "peaks_used": {"bf16_mfma_tflops": PEAK_BF16_MFMA / 1e12, "hbm_tb_s": PEAK_HBM / 1e12},
-                   "clocks": "as found (not pinned); under the contraction the part runs near 1.75 GHz with the workload's random operands and at 2.4 GHz with zero operands, see profiles/"},
+                   "clocks": "as found (not pinned); under the contraction the part runs at 1.84 - 1.89 GHz (board power cap) with the workload's random operands and at 2.4 GHz with zero operands, see profiles/"},
         "tflops": total_flops / t_step / 1e12,
         "pct_bf16_mfma_peak": 100.0 * total_flops / t_step / PEAK_BF16_MFMA,
         "algorithmic_flops_per_step": total_flops,
