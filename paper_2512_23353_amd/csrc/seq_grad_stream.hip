@@ -406,7 +406,9 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           pk[1] = pack_bf16(rd16(acc[i][2 * jp][2]), rd16(acc[i][2 * jp][3]));
           pk[2] = pack_bf16(rd16(acc[i][2 * jp + 1][0]), rd16(acc[i][2 * jp + 1][1]));
           pk[3] = pack_bf16(rd16(acc[i][2 * jp + 1][2]), rd16(acc[i][2 * jp + 1][3]));
-          *(u32x4*)(tb + (i * (FN16 / 2) + jp) * 512 + lane * 8) = pk;
+          // written once and read after the launch: non-temporal, so the stash does not push the operand
+          // panels out of the L2
+          __builtin_nontemporal_store(pk, (u32x4*)(tb + (i * (FN16 / 2) + jp) * 512 + lane * 8));
         }
       if constexpr (PERSIST) continue; else break;
     }
