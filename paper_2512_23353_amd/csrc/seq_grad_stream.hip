@@ -412,6 +412,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         }
       if constexpr (PERSIST) continue; else break;
     }
+    // ---- row-major stash: the 32x32x16 MFMA (every other mode has left the round above)
     unsigned adA[FM], adB[FN];
     {
       const int l = lane & 15, g4 = lane >> 4;
@@ -448,12 +449,10 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
     constexpr int LPT = LA + LB;   // loads per wave and tile
-    // Token blocks in flight ahead of the one being multiplied.  The stage a block leaves is free as soon
-    // as the barrier after its second half's fragment reads has been passed, so the ring can carry NSTAGE
-    // blocks ahead; the per-sequence mode, whose stash stores compete with the operand fetches, runs
-    // better one block shallower.
-    constexpr int AHEAD = PER_SEQ ? NSTAGE - 1 : NSTAGE;
-    constexpr int NRD = 2 * (FM + FN), NMF = FM * FN;
+    // Token blocks in flight ahead of the one being multiplied: one less than the ring holds (the stash
+    // stores compete with the operand fetches; a fourth block in flight made this mode slower).
+    constexpr int AHEAD = NSTAGE - 1;
+    constexpr int NMF = FM * FN;
 
     // Per-sequence mode, 256x256 tile: the two waves of the lower tile half read their fragments behind
     // MFMAs 8..15 of a half block instead of 0..7, in the order the next half block first uses them
@@ -468,7 +467,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       if (k <= FN) { is_a = false; return k - 1; }
       is_a = true; return k - FN;
     };
-    const bool late_wave = PER_SEQ && NMF >= 2 * (FM + FN) && (wave_s & 2);
+    const bool late_wave = NMF >= 2 * (FM + FN) && (wave_s & 2);
 
 #pragma unroll
     for (int s = 0; s < AHEAD; ++s) issue_loads(s);
@@ -485,7 +484,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       auto token_block = [&](int it, auto late_c) {
         constexpr bool LATE = decltype(late_c)::value;
         const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
-        if constexpr (PER_SEQ) {
+        {
           // written out MFMA by MFMA: one fragment's reads behind each MFMA of this wave's read slots
 #pragma unroll
           for (int i = 0; i < FM; ++i) {
@@ -501,29 +500,10 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
               }
             }
           }
-        } else {
-          // sum-over-all-tokens mode: the scheduler places the reads, one per MFMA
-#pragma unroll
-          for (int i = 0; i < FM; ++i) fa1[i] = frA(sb + adA[i] + 16 * PA);
-#pragma unroll
-          for (int j = 0; j < FN; ++j) fb1[j] = frB(sb + adB[j] + 16 * PB);
-#pragma unroll
-          for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-              // odd rows of the tile walk the B fragments backwards: the fragment of the row change is reused
-              const int js = (i & 1) ? FN - 1 - j : j;
-              acc[i][js] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[js], acc[i][js], 0, 0, 0);
-            }
-#pragma unroll
-          for (int q = 0; q < (NMF < NRD ? NMF : NRD); ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, (NRD + NMF - 1) / NMF, 0);
-          }
         }
         // block it+1 has landed (this wave's part; the barrier makes it everyone's) and this wave's fragment
         // reads of block it are complete: its stage may be overwritten after the barrier
-        __builtin_amdgcn_s_waitcnt((AHEAD == NSTAGE ? 0x0070 : 0x0f70) | (((AHEAD - 2) * LPT) & 15) | ((((AHEAD - 2) * LPT) >> 4) << 14));
+        __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 2) * LPT) & 15) | ((((AHEAD - 2) * LPT) >> 4) << 14));
         __builtin_amdgcn_s_barrier();
         const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
         // second half block: its 16 MFMAs carry the fragment reads of the next block's first half and the
@@ -541,8 +521,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
             for (int j = 0; j < FN; ++j) {
               const int idx = i * FN + j;
               {
-              const int js = (!PER_SEQ && (i & 1)) ? FN - 1 - j : j;      // as in the first half block
-              acc[i][js] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[js], acc[i][js], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
             }
               bool is_a = false;
               const int f = frag_of(idx, LATE, is_a);
@@ -572,7 +551,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     [[maybe_unused]] auto rd = [](float a) {
       if constexpr (FM * FN * 16 > 128) return acc_read(a); else return a;
     };
-    if (PER_SEQ) {
+    {
       __builtin_amdgcn_s_barrier();
       // the last MFMAs have retired before the accumulators are read by hand (acc_read is opaque to the
       // compiler's hazard tracking)
@@ -607,28 +586,11 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
             const int m = m0 + wm * WM + i * 32 + 16 * rb + l;
             const int n = n0 + wn * WN + jp * 64 + 8 * pc;
             if (m < p.row_end && n < p.d_in)
-              *(s16x8*)(outp + (size_t)(m - p.out_row0) * p.d_in + n) =
-                  __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+              __builtin_nontemporal_store(__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7),
+                                          (s16x8*)(outp + (size_t)(m - p.out_row0) * p.d_in + n));
           }
         }
       }
-    } else {
-      const int col = lane & 31;
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int n = n0 + wn * WN + j * 32 + col;
-          if (n >= p.d_in) continue;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (m >= p.row_end) continue;
-            float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
-            if (split) atomicAdd(o, acc[i][j][v]);        // beta already applied by the pass before
-            else *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
-          }
-        }
     }
     if constexpr (!PERSIST) break;
   }
