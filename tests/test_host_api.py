@@ -235,3 +235,20 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in (r.stderr + r.stdout)
     assert not r.stdout.strip().startswith("{")
+
+
+def test_bench_reads_the_committed_traffic_summary():
+    # roofline.traffic comes from the counter summary under profiles/: the line bench.py parses is there and
+    # equals the sum of the read and written bytes the same file states
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    traffic = bench.read_traffic("seq_grad_config3")
+    assert traffic is not None and traffic > 0
+    text = open(os.path.join(root, "profiles", "seq_grad_config3_hbm_traffic.txt")).read()
+    read = float(re.search(r"FETCH_SIZE mean .*-> ([0-9.e]+) B read", text).group(1))
+    written = float(re.search(r"WRITE_SIZE mean .*-> ([0-9.e]+) B written", text).group(1))
+    assert abs(traffic - (read + written)) <= 0.005 * traffic
+    assert bench.read_traffic("no_such_kernel") is None
