@@ -24,7 +24,9 @@ token-by-token contraction, duplicate sequences, (token-sample Fisher
 estimate) the listing's own formula in torch plus a one-token closed form,
 (generalised re-scaling) a hand-worked fixture, the explicit-Fisher minimiser
 for r = -2 and unit norms for p = -1 / q = -1, and (eigh route) agreement with
-the Cholesky solve plus a hand-iterated EMA.  Every public function
+the Cholesky solve plus a hand-iterated EMA, (K = J J^T as one matrix product)
+the double loop and the hand-worked fixture, (the seqs= restriction of the
+token-sample estimate) the unrestricted call.  Every public function
 below is pinned by at least one of them; none is "parity unpinned".
 """
 from __future__ import annotations
@@ -94,6 +96,17 @@ def ntk_from_seq_grads(G) -> np.ndarray:
     return K
 
 
+def ntk_as_matrix_product(G) -> np.ndarray:
+    """The same K as the printed definition K = J J^T (interacting-variant
+    section), J being the m x P matrix whose row i is G_i flattened: one
+    library matrix product instead of the listing's double loop, so that K of a
+    wide layer at full size takes seconds.  Pinned against the double loop and
+    the hand-worked fixture."""
+    J = G.reshape(G.shape[0], -1)
+    K = J @ J.T
+    return 0.5 * (K + K.T)          # the product is symmetric up to summation order; make it exactly so
+
+
 def ntk_ghost(X, Delta, seq_offsets) -> np.ndarray:
     """The same K from the rank-one structure of token gradients
     (efficient-implementation paragraph: each token gradient is the outer
@@ -115,19 +128,21 @@ def ntk_ghost(X, Delta, seq_offsets) -> np.ndarray:
     return K
 
 
-def layer_ntk(X, Delta, seq_offsets, chunk_rows=None) -> np.ndarray:
+def layer_ntk(X, Delta, seq_offsets, chunk_rows=None, matrix_product=False) -> np.ndarray:
     """K for one layer.  For large layers the G_i are held d_out-rows-chunk by
     chunk (all sequences at once) and K accumulates over the chunks; every
-    chunk of every G_i is still materialised."""
+    chunk of every G_i is still materialised.  matrix_product: form each
+    chunk's K as J J^T (ntk_as_matrix_product) instead of the double loop."""
     d_out = np.asarray(Delta).shape[1]
+    gram = ntk_as_matrix_product if matrix_product else ntk_from_seq_grads
     if chunk_rows is None or chunk_rows >= d_out:
-        return ntk_from_seq_grads(seq_logprob_grads(X, Delta, seq_offsets))
+        return gram(seq_logprob_grads(X, Delta, seq_offsets))
     Xw, Dw = widen(X), widen(Delta)
     m = len(seq_offsets) - 1
     K = np.zeros((m, m), dtype=np.float64)
     for r0 in range(0, d_out, chunk_rows):
         r1 = min(d_out, r0 + chunk_rows)
-        K += ntk_from_seq_grads(seq_logprob_grads(Xw, Dw, seq_offsets, rows=(r0, r1)))
+        K += gram(seq_logprob_grads(Xw, Dw, seq_offsets, rows=(r0, r1)))
     return K
 
 
@@ -142,15 +157,23 @@ def ntk_entry(X, Delta, seq_offsets, i: int, j: int) -> float:
     return float(np.sum(Gi * Gj))
 
 
-def effective_reg(K, lam: float, reg_mode: int = REG_ABSOLUTE) -> float:
+def effective_reg(K, lam: float, reg_mode: int = REG_ABSOLUTE, variant: str = "interacting") -> float:
     """The regulariser actually added.  ABSOLUTE: lam itself (the Tikhonov c of
-    v = J^T (K + cI)^-1 A).  REL_TRACE: lam * tr(K)/m, the current batch's
-    mean eigenvalue standing in for the trailing mean the interacting
-    experiment uses (regulariser = factor * E[mean(D)])."""
+    v = J^T (K + cI)^-1 A; reg_l of the update u_l).  REL_TRACE scales lam by
+    this batch's typical value of the quantity it is added to, the current
+    batch standing in for the trailing mean over minibatches:
+      interacting  lam * tr(K)/m, the mean eigenvalue of K (the interacting
+                   experiment's regulariser = factor * E[mean(D)]);
+      fisher       lam * mean_i ||g_i||_F^2 (the non-interacting derivation
+                   compares reg_l with the typical value of ||.||_F^2)."""
     K = np.asarray(K, dtype=np.float64)
     if reg_mode == REG_ABSOLUTE:
         return float(lam)
     if reg_mode == REG_REL_TRACE:
+        if variant == "fisher":
+            return float(lam) * float(np.mean(fisher_norm_sq(K)))
+        if variant != "interacting":
+            raise ValueError("variant must be 'fisher' or 'interacting'")
         return float(lam) * float(np.trace(K)) / K.shape[0]
     raise ValueError("unknown reg_mode")
 
@@ -169,7 +192,7 @@ def coeff_fisher(K, A, lam: float, reg_mode: int = REG_ABSOLUTE) -> np.ndarray:
     of the non-interacting listing).  A zero denominator (empty sequence with
     reg = 0) gives c_i = 0 by convention."""
     A = np.asarray(A, dtype=np.float64)
-    den = fisher_norm_sq(K) + effective_reg(K, lam, reg_mode)
+    den = fisher_norm_sq(K) + effective_reg(K, lam, reg_mode, "fisher")
     c = np.zeros_like(A)
     nz = den > 0
     c[nz] = A[nz] / np.sqrt(den[nz])
@@ -439,4 +462,4 @@ def layer_step(X, Delta, seq_offsets, A, variant: str, lam: float,
     else:
         dW[:] = np.nan
     return {"K": K, "c": c, "info": info, "dW": dW, "dW_reinforce": dW_R, "dW_abs": dW_abs,
-            "reg_eff": effective_reg(K, lam, reg_mode)}
+            "reg_eff": effective_reg(K, lam, reg_mode, variant)}

@@ -181,6 +181,31 @@ def test_p7_solve_residual_and_eigh_route():
     assert orc.effective_reg(K, 0.5, orc.REG_REL_TRACE) == pytest.approx(0.5 * np.trace(K) / 5)
 
 
+def test_relative_regulariser_is_scale_free_in_both_variants():
+    """A relative regulariser has the dimension of what it is added to: under
+    Delta -> a Delta (K -> a^2 K, Fisher norms -> a^4) the interacting
+    coefficients scale by a^-2 and so do the non-interacting ones, for any
+    lambda.  Also pinned by value: reg = lam * mean_i F_i^2 (non-interacting,
+    the typical value of ||.||_F^2) and lam * tr(K)/m (interacting)."""
+    rng = np.random.default_rng(61)
+    X, D, off = _rand_layer(rng, [4, 6, 3, 7, 5], 6, 6)
+    A = rng.standard_normal(5)
+    K = orc.layer_ntk(X, D, off)
+    f2 = np.sum(K * K, axis=1) / 5
+    assert orc.effective_reg(K, 0.3, orc.REG_REL_TRACE, "fisher") == pytest.approx(0.3 * f2.mean(), rel=1e-14)
+    assert orc.effective_reg(K, 0.3, orc.REG_REL_TRACE, "interacting") == pytest.approx(0.3 * np.trace(K) / 5, rel=1e-14)
+    np.testing.assert_allclose(orc.coeff_fisher(K, A, 0.3, orc.REG_REL_TRACE), A / np.sqrt(f2 + 0.3 * f2.mean()), rtol=1e-13)
+    for a in (0.01, 7.0):
+        Ka = orc.layer_ntk(X, a * D, off)
+        for lam in (1e-3, 0.5, 4.0):
+            np.testing.assert_allclose(orc.coeff_fisher(Ka, A, lam, orc.REG_REL_TRACE) * a ** 2,
+                                       orc.coeff_fisher(K, A, lam, orc.REG_REL_TRACE), rtol=1e-11)
+            np.testing.assert_allclose(orc.coeff_interacting(Ka, A, lam, orc.REG_REL_TRACE)[0] * a ** 2,
+                                       orc.coeff_interacting(K, A, lam, orc.REG_REL_TRACE)[0], rtol=1e-9)
+    step = orc.layer_step(X, D, off, A, "fisher", 0.3, orc.REG_REL_TRACE)
+    assert step["reg_eff"] == pytest.approx(0.3 * f2.mean(), rel=1e-14)
+
+
 def test_p8_minsr_property():
     """<dW, G_i> = (K c)_i = A_i - reg c_i."""
     rng = np.random.default_rng(7)
@@ -343,12 +368,14 @@ def test_token_sample_fisher_estimate():
     X, D, off = _rand_layer(rng, [5, 3, 6, 2], 7, 6)
     idx = rng.permutation(16)[:9]
     f2 = orc.fisher_norm_sq_token_samples(X, D, off, idx)
-    Xt, Dt = torch.from_numpy(X), torch.from_numpy(D)
-    a0, g0 = Xt[idx], Dt[idx]
+    # the fast forms the paper derives for rank-one sample gradients: eq. (one), v . g^(j) = g0_j^T V a0_j,
+    # and eq. (two), ||g^(j)||^2 = ||g0_j||^2 ||a0_j||^2 (the oracle materialises every g^(j) instead)
+    a0, g0 = X[idx], D[idx]
+    den = np.sum(np.sum(g0 ** 2, axis=1) * np.sum(a0 ** 2, axis=1))
     for i in range(4):
-        G = Dt[off[i]:off[i + 1]].T @ Xt[off[i]:off[i + 1]]
-        F_norm = torch.norm(torch.sum((g0 @ G) * a0, dim=1)) / torch.norm(torch.norm(g0, dim=1) * torch.norm(a0, dim=1))
-        assert f2[i] == pytest.approx(float(F_norm) ** 2, rel=1e-12)
+        V = D[off[i]:off[i + 1]].T @ X[off[i]:off[i + 1]]
+        proj = np.einsum("jo,ok,jk->j", g0, V, a0)
+        assert f2[i] == pytest.approx(float(np.sum(proj ** 2) / den), rel=1e-12)
     # one sample equal to the only token of a one-token sequence: v = g^(j), so
     # ||v||_F^2 = (v.v)^2 / (v.v) = ||x||^2 ||delta||^2 (eq. (two))
     X1, D1, off1 = _rand_layer(rng, [1, 4], 5, 4)
@@ -379,6 +406,51 @@ def test_token_sample_fisher_estimate():
     X2, D2, off2 = _rand_layer(rng, [3, 0, 4], 5, 4)
     c, f2 = orc.coeff_fisher_token_samples(X2, D2, off2, [0, 5], np.ones(3), 0.0)
     assert f2[1] == 0.0 and c[1] == 0.0
+
+
+def test_token_sample_estimate_restricted_to_some_sequences():
+    """seqs= evaluates only the named sequences (the form the full-size checks
+    use): their entries equal the unrestricted call's, the others are NaN; an
+    empty named sequence gives 0; bf16 bit patterns are widened per sequence."""
+    rng = np.random.default_rng(21)
+    X, D, off = _rand_layer(rng, [5, 0, 6, 2, 7], 9, 6)
+    idx = rng.permutation(20)[:7]
+    full = orc.fisher_norm_sq_token_samples(X, D, off, idx)
+    for seqs in ([2], [4, 0], [1, 3], np.array([0, 1, 2, 3, 4])):
+        part = orc.fisher_norm_sq_token_samples(X, D, off, idx, seqs=seqs)
+        named = np.zeros(5, bool)
+        named[np.asarray(seqs)] = True
+        np.testing.assert_array_equal(part[named], full[named])
+        assert np.all(np.isnan(part[~named]))
+    assert full[1] == 0.0
+    Xb = torch.from_numpy(X).to(torch.bfloat16)
+    Db = torch.from_numpy(D).to(torch.bfloat16)
+    bits = lambda t: t.view(torch.int16).numpy().view(np.uint16)
+    part = orc.fisher_norm_sq_token_samples(bits(Xb), bits(Db), off, idx, seqs=[3])
+    full_b = orc.fisher_norm_sq_token_samples(Xb.double().numpy(), Db.double().numpy(), off, idx)
+    assert part[3] == pytest.approx(full_b[3], rel=1e-13)
+
+
+def test_ntk_as_one_matrix_product():
+    """K = J J^T (interacting-variant section) formed as one matrix product:
+    the hand-worked K, the listing's double loop on random gradients, and the
+    chunked accumulation over output rows."""
+    with open(os.path.join(GOLDEN, "hand_worked_two_sequences.json")) as f:
+        g = json.load(f)
+    G = orc.seq_logprob_grads(np.array(g["X"], float), np.array(g["Delta"], float), g["seq_offsets"])
+    np.testing.assert_array_equal(orc.ntk_as_matrix_product(G), np.array(g["K"], float))
+    rng = np.random.default_rng(22)
+    X, D, off = _rand_layer(rng, [4, 1, 0, 6, 3], 8, 10)
+    G = orc.seq_logprob_grads(X, D, off)
+    K_loop = orc.ntk_from_seq_grads(G)
+    K_mat = orc.ntk_as_matrix_product(G)
+    np.testing.assert_allclose(K_mat, K_loop, rtol=1e-13, atol=1e-13 * np.abs(K_loop).max())
+    assert np.array_equal(K_mat, K_mat.T) and np.all(K_mat[2] == 0)
+    for chunk in (3, 4, 10):
+        np.testing.assert_allclose(orc.layer_ntk(X, D, off, chunk_rows=chunk, matrix_product=True), K_loop,
+                                   rtol=1e-13, atol=1e-13 * np.abs(K_loop).max())
+    np.testing.assert_allclose(orc.layer_ntk(X, D, off, matrix_product=True), K_loop, rtol=1e-13,
+                               atol=1e-13 * np.abs(K_loop).max())
 
 
 def test_generalised_rescaling_fixture():
