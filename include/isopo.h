@@ -67,10 +67,14 @@ typedef enum {
 } isopo_variant;
 
 typedef enum {
-  ISOPO_REG_ABSOLUTE = 0,           /* reg = lambda (the Tikhonov constant as printed) */
-  ISOPO_REG_REL_TRACE = 1,          /* reg = lambda * tr(K)/m (relative to the mean eigenvalue,
-                                       as the interacting experiment's regulariser is) */
-  ISOPO_REG_EMA_TRACE = 2           /* reg = lambda * trailing mean over minibatches of tr(K)/m
+  ISOPO_REG_ABSOLUTE = 0,           /* reg = lambda (the Tikhonov constant as printed; reg_l of the update u_l) */
+  ISOPO_REG_REL_TRACE = 1,          /* reg = lambda * this batch's typical value of the quantity reg is added to:
+                                       INTERACTING: tr(K)/m, the mean eigenvalue of K (as the interacting
+                                       experiment's regulariser is relative to);
+                                       FISHER: mean_i ||g_i||_F^2 (the non-interacting derivation compares reg_l
+                                       with the typical value of ||.||_F^2).  Either way c scales like 1/K under a
+                                       rescaling of Delta, whatever lambda is */
+  ISOPO_REG_EMA_TRACE = 2           /* reg = lambda * trailing mean over minibatches of the same value
                                        (interacting experiment: factor * E[mean(D)], decay 0.9);
                                        isopo_transform_ema, isopo_transform_eigh and
                                        isopo_fisher_samples (there: of the batch mean of F^2) */
@@ -207,10 +211,11 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
 
 /* isopo_transform with the interacting experiment's regulariser, reg = factor * E[mean(D)]: the
  * trailing mean over minibatches (this one included) of the Gram matrix's mean eigenvalue, which is
- * tr(K)/n_seq, so the fast factorisation route serves it too.
+ * tr(K)/n_seq, so the fast factorisation route serves it too.  For FISHER the value averaged is the batch
+ * mean of the Fisher norms, mean_i (1/m) sum_j K_ij^2, as under ISOPO_REG_REL_TRACE.
  *   ema_state  device float [batch, 2] per problem {E, number of minibatches seen}; zero it before the
- *              first minibatch.  Updated by the call: E <- tr(K)/n_seq on the first minibatch,
- *              E <- decay E + (1 - decay) tr(K)/n_seq after (decay 0.9 in the experiment)
+ *              first minibatch.  Updated by the call: E <- this batch's value v on the first minibatch,
+ *              E <- decay E + (1 - decay) v after (decay 0.9 in the experiment)
  *   factor     >= 0 (1.0 in the experiment);  0 <= ema_decay < 1
  * Everything else as isopo_transform. */
 isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, int32_t batch,

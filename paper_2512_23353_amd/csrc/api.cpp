@@ -3,7 +3,6 @@
 // lives here; every step runs in the kernels.
 #include "../../include/isopo.h"
 
-#include <cstdlib>
 #include <cstring>
 
 #include <cmath>
@@ -103,16 +102,6 @@ isopo_gram_path resolve(const isopo_layer* l, isopo_gram_path req) {
   return tg < tm ? ISOPO_GRAM_GHOST : ISOPO_GRAM_MATERIALISED;
 }
 
-// Optional cap (MiB) on the stash bytes formed per pass, so that the Gram pass
-// over a chunk finds it still in the memory-side cache.  0 = no cap.
-size_t chunk_cap_bytes() {
-  static const size_t cap = [] {
-    const char* e = std::getenv("ISOPO_STASH_CHUNK_MB");
-    return e ? (size_t)std::strtoull(e, nullptr, 10) << 20 : (size_t)0;
-  }();
-  return cap;
-}
-
 }  // namespace
 
 extern "C" {
@@ -210,8 +199,7 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
   if (keep_stash < 0 || keep_stash > 2) return ISOPO_ERR_INVALID_ARG;
   if (keep_stash && ws_bytes < ws_full) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
   // Tile order whenever nobody asked for the row-major stash (a stash that is not kept is nobody's business).
-  // With the chunk cap the bands could pick different tile sizes, which a kept stash must not mix.
-  const bool tile_order = keep_stash != 1 && !(keep_stash == 2 && chunk_cap_bytes()) && bf16 &&
+  const bool tile_order = keep_stash != 1 && bf16 &&
                           stash_tile_order_ok(layer->d_out, layer->d_in, (int)layer->n_tokens, layer->n_seq,
                                               layer->seq_offsets_host) != 0;
   const size_t pbytes = partial_bytes(layer);
@@ -221,8 +209,6 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
   const bool whole = rows_fit >= (size_t)layer->d_out;
   if (whole) rows_fit = layer->d_out;
   size_t chunk_rows = rows_fit;
-  const size_t cap = chunk_cap_bytes();
-  if (cap && chunk_rows * row_bytes > cap) chunk_rows = cap / row_bytes;
   if (chunk_rows < (size_t)layer->d_out) {
     chunk_rows = chunk_rows / kTileRows * kTileRows;
     if (chunk_rows < (size_t)kTileRows) chunk_rows = kTileRows;
@@ -514,7 +500,7 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
 isopo_status isopo_stash_layout_of(const isopo_layer* layer, isopo_stash_layout* layout, int32_t* tile) {
   isopo_status st = check_layer(layer, false);
   if (st != ISOPO_OK) return st;
-  const int t = (layer->dtype == ISOPO_BF16 && !chunk_cap_bytes())
+  const int t = layer->dtype == ISOPO_BF16
                     ? stash_tile_order_ok(layer->d_out, layer->d_in, (int)layer->n_tokens, layer->n_seq,
                                           layer->seq_offsets_host)
                     : 0;

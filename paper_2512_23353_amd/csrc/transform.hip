@@ -6,9 +6,12 @@
 //                included)
 //   INTERACTING  c = (K + reg I)^-1 A          (v = J^T (K + cI)^-1 A)
 //
-// reg = lambda, or lambda * tr(K)/m, or lambda * the trailing mean over minibatches
-// of tr(K)/m (the interacting experiment's regulariser, factor * E[mean(D)]: the
-// mean eigenvalue is the trace over m, so no decomposition is needed for it).
+// reg = lambda, or lambda times this batch's typical value of the quantity reg is
+// added to, or lambda times the trailing mean over minibatches of that value.  For
+// INTERACTING the value is tr(K)/m (the interacting experiment's regulariser,
+// factor * E[mean(D)]: the mean eigenvalue is the trace over m, so no
+// decomposition is needed for it); for FISHER it is mean_i ||g_i||_F^2 (the
+// non-interacting derivation compares reg_l with the typical ||.||_F^2).
 // The m x m problem is tiny next to the
 // contractions around it, so one workgroup per problem works in fp64: a
 // right-looking Cholesky factorisation in LDS (m <= 128) or in a caller-provided
@@ -20,6 +23,8 @@
 
 namespace isopo {
 namespace {
+
+constexpr int ISOPO_MAX_SEQ_TRANSFORM = 1024;     // the header's ISOPO_MAX_SEQ
 
 template <int kThreads>
 __device__ double block_sum(double x, double* red /* [kThreads/64] */) {
@@ -46,11 +51,27 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
   const float* A = Ab + (size_t)prob * m;
   float* c = cb + (size_t)prob * m;
 
+  // FISHER: the norms first; the relative regulariser is measured against their mean
+  __shared__ double f2s[ISOPO_MAX_SEQ_TRANSFORM];
+  if (variant == 0) {
+    for (int i = tid; i < m; i += kThreads) {
+      double s = 0.0;
+      for (int j = 0; j < m; ++j) {
+        const double k = (double)K[(size_t)i * m + j];
+        s += k * k;
+      }
+      f2s[i] = s / (double)m;
+    }
+    __syncthreads();
+  }
+
   double reg = (double)lambda;
   if (reg_mode != 0) {
-    double tr = 0.0;
-    for (int i = tid; i < m; i += kThreads) tr += (double)K[(size_t)i * m + i];
-    double scale = block_sum<kThreads>(tr, red) / (double)m;          // this batch's mean eigenvalue
+    // this batch's typical value of what reg is added to: the mean eigenvalue tr(K)/m of K (INTERACTING),
+    // the mean of the Fisher norms (FISHER)
+    double part = 0.0;
+    for (int i = tid; i < m; i += kThreads) part += variant == 0 ? f2s[i] : (double)K[(size_t)i * m + i];
+    double scale = block_sum<kThreads>(part, red) / (double)m;
     if (reg_mode == 2) {
       // trailing mean over minibatches, this one included; every thread forms the same value from the
       // state as it was, then one thread stores the new state
@@ -66,12 +87,7 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
 
   if (variant == 0) {
     for (int i = tid; i < m; i += kThreads) {
-      double s = 0.0;
-      for (int j = 0; j < m; ++j) {
-        const double k = (double)K[(size_t)i * m + j];
-        s += k * k;
-      }
-      const double den = s / (double)m + reg;
+      const double den = f2s[i] + reg;
       c[i] = den > 0.0 ? (float)((double)A[i] / sqrt(den)) : 0.f;
     }
     if (info && tid == 0) info[prob] = 0;

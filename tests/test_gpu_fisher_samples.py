@@ -97,7 +97,7 @@ def test_whole_non_interacting_update(gpu_device, dtype):
 
 
 def test_config3_full_size_sampled_sequences(gpu_device):
-    """The 7B-class gate projection at full size (3584 -> 18944, B = 32, lengths
+    """The 7B-class gate projection at full size (4096 -> 14336, B = 32, lengths
     in [512, 4096]) with the listing's default of 32 samples: F^2 of the three
     shortest sequences against the oracle, and properties of the rest."""
     w = wl.CONFIGS["config3"]

@@ -196,7 +196,7 @@ def test_trailing_mean_regulariser_on_the_factorisation_route(gpu_device, m):
                 if variant == "interacting":
                     c_ref, states[b] = orc.coeff_interacting_ema(K64, A[b], 0.5, states[b], 0.9)
                 else:
-                    states[b] = orc.ema_update(states[b], float(np.trace(K64)) / m, 0.9)
+                    states[b] = orc.ema_update(states[b], float(np.mean(orc.fisher_norm_sq(K64))), 0.9)
                     c_ref = orc.coeff_fisher(K64, A[b], 0.5 * states[b], orc.REG_ABSOLUTE)
                 assert ema[b, 0].item() == pytest.approx(states[b], rel=1e-6)
                 assert rel_err(c[b].cpu().numpy(), c_ref) <= 1e-5, (variant, scale, b)
