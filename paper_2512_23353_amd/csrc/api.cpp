@@ -22,9 +22,19 @@ constexpr int kComputeUnits = 256;        // MI355X
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 size_t elem_size(isopo_dtype t) { return t == ISOPO_BF16 ? 2 : 4; }
 
+// An enum argument arrives through a C ABI and may hold any int.  Its bytes are read as an int before
+// anything touches it as the enum type (for which a value outside the enumerators' range is undefined).
+template <class E>
+bool enum_in(const E& e, int lo, int hi) {
+  static_assert(sizeof(E) == sizeof(int), "C enums of this header are ints");
+  int v;
+  std::memcpy(&v, &e, sizeof v);
+  return v >= lo && v <= hi;
+}
+
 isopo_status check_layer(const isopo_layer* l, bool need_dev) {
   if (!l) return ISOPO_ERR_INVALID_ARG;
-  if (l->dtype != ISOPO_F32 && l->dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  if (!enum_in(l->dtype, ISOPO_F32, ISOPO_BF16)) return ISOPO_ERR_UNSUPPORTED;
   if (l->d_in <= 0 || l->d_out <= 0 || l->n_seq <= 0 || l->n_tokens < 0) return ISOPO_ERR_INVALID_ARG;
   if (l->n_tokens >= (int64_t)1 << 31) return ISOPO_ERR_UNSUPPORTED;
   if (l->n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
@@ -152,8 +162,7 @@ isopo_status isopo_layer_gram_plan(const isopo_layer* layer, isopo_gram_path req
                                    size_t* ws_full, size_t* ws_min) {
   isopo_status st = check_layer(layer, false);
   if (st != ISOPO_OK) return st;
-  if (requested != ISOPO_GRAM_AUTO && requested != ISOPO_GRAM_GHOST && requested != ISOPO_GRAM_MATERIALISED)
-    return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(requested, ISOPO_GRAM_AUTO, ISOPO_GRAM_MATERIALISED)) return ISOPO_ERR_INVALID_ARG;
   const isopo_gram_path path = resolve(layer, requested);
   if (path == ISOPO_GRAM_MATERIALISED && !materialised_ok(layer->n_seq, layer->dtype)) return ISOPO_ERR_UNSUPPORTED;
   if (chosen) *chosen = path;
@@ -173,6 +182,7 @@ isopo_status isopo_layer_gram(const isopo_layer* layer, isopo_gram_path path, fl
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
   if (!K || !workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1))) return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(path, ISOPO_GRAM_AUTO, ISOPO_GRAM_MATERIALISED)) return ISOPO_ERR_INVALID_ARG;
   isopo_gram_path chosen;
   size_t ws_full, ws_min;
   st = isopo_layer_gram_plan(layer, path, &chosen, &ws_full, &ws_min);
@@ -255,7 +265,7 @@ isopo_status isopo_seq_grads_stash(const isopo_layer* layer, void* stash, isopo_
                                    int32_t max_workgroups, uint32_t* queue_dev, void* stream) {
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
-  if (layout != ISOPO_STASH_ROW_MAJOR && layout != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(layout, ISOPO_STASH_ROW_MAJOR, ISOPO_STASH_TILE_ORDER)) return ISOPO_ERR_INVALID_ARG;
   if (layout == ISOPO_STASH_TILE_ORDER) {
     isopo_stash_layout have;
     st = isopo_stash_layout_of(layer, &have, nullptr);
@@ -285,7 +295,7 @@ size_t isopo_stash_gram_workspace(int32_t n_seq) {
 isopo_status isopo_stash_gram(const void* stash, isopo_dtype dtype, int32_t n_seq, int64_t n_elem, float* K,
                               void* workspace, size_t ws_bytes, void* stream) {
   if (!stash || !K || !workspace || n_seq <= 0 || n_elem <= 0 || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
-  if (dtype != ISOPO_F32 && dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  if (!enum_in(dtype, ISOPO_F32, ISOPO_BF16)) return ISOPO_ERR_UNSUPPORTED;
   if (!materialised_ok(n_seq, dtype) || n_seq > ISOPO_MAX_SEQ || n_elem % (dtype == ISOPO_BF16 ? 8 : 4))
     return ISOPO_ERR_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return ISOPO_ERR_INVALID_ARG;
@@ -308,8 +318,8 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
                              size_t ws_bytes, void* stream) {
   if (!K || !A || !c || n_seq <= 0 || batch <= 0) return ISOPO_ERR_INVALID_ARG;
   if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
-  if (variant != ISOPO_VARIANT_FISHER && variant != ISOPO_VARIANT_INTERACTING) return ISOPO_ERR_INVALID_ARG;
-  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE) return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(variant, ISOPO_VARIANT_FISHER, ISOPO_VARIANT_INTERACTING)) return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(reg_mode, ISOPO_REG_ABSOLUTE, ISOPO_REG_REL_TRACE)) return ISOPO_ERR_INVALID_ARG;
   if (!(lambda >= 0.f)) return ISOPO_ERR_INVALID_ARG;
   if (variant == ISOPO_VARIANT_INTERACTING) {
     const size_t need = isopo_transform_workspace(n_seq, batch);
@@ -327,7 +337,7 @@ isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, 
                                  void* workspace, size_t ws_bytes, void* stream) {
   if (!K || !A || !c || !ema_state || n_seq <= 0 || batch <= 0) return ISOPO_ERR_INVALID_ARG;
   if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
-  if (variant != ISOPO_VARIANT_FISHER && variant != ISOPO_VARIANT_INTERACTING) return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(variant, ISOPO_VARIANT_FISHER, ISOPO_VARIANT_INTERACTING)) return ISOPO_ERR_INVALID_ARG;
   if (!(factor >= 0.f) || !(ema_decay >= 0.f && ema_decay < 1.f)) return ISOPO_ERR_INVALID_ARG;
   if (variant == ISOPO_VARIANT_INTERACTING) {
     const size_t need = isopo_transform_workspace(n_seq, batch);
@@ -375,8 +385,7 @@ isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_
   if (!sample_idx_dev || !A || !c || !workspace || !(lambda >= 0.f)) return ISOPO_ERR_INVALID_ARG;
   if (n_samples < 1) return ISOPO_ERR_INVALID_ARG;
   if (n_samples > ISOPO_MAX_SAMPLES) return ISOPO_ERR_UNSUPPORTED;
-  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE && reg_mode != ISOPO_REG_EMA_TRACE)
-    return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(reg_mode, ISOPO_REG_ABSOLUTE, ISOPO_REG_EMA_TRACE)) return ISOPO_ERR_INVALID_ARG;
   if (reg_mode == ISOPO_REG_EMA_TRACE && (!ema_state || !(ema_decay >= 0.f && ema_decay < 1.f)))
     return ISOPO_ERR_INVALID_ARG;
   if (first->n_tokens == 0) return ISOPO_ERR_INVALID_ARG;     // nothing to sample from
@@ -449,8 +458,7 @@ isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_se
                                   float ema_decay, float* c, int32_t* info, void* stream) {
   if (!D || !U || !A || !lambdas || !c || n_seq <= 0 || batch <= 0 || n_lambda < 1) return ISOPO_ERR_INVALID_ARG;
   if (n_seq > ISOPO_MAX_SEQ || n_lambda > ISOPO_MAX_LAMBDAS) return ISOPO_ERR_UNSUPPORTED;
-  if (reg_mode != ISOPO_REG_ABSOLUTE && reg_mode != ISOPO_REG_REL_TRACE && reg_mode != ISOPO_REG_EMA_TRACE)
-    return ISOPO_ERR_INVALID_ARG;
+  if (!enum_in(reg_mode, ISOPO_REG_ABSOLUTE, ISOPO_REG_EMA_TRACE)) return ISOPO_ERR_INVALID_ARG;
   if (reg_mode == ISOPO_REG_EMA_TRACE && (!ema_state || !(ema_decay >= 0.f && ema_decay < 1.f)))
     return ISOPO_ERR_INVALID_ARG;
   EighSolveArgs e;
@@ -468,7 +476,7 @@ isopo_status isopo_scale_rows(const void* src, isopo_dtype dtype, int64_t n_toke
                               void* stream) {
   if (!src || !dst || !c || !seq_offsets_dev || src == dst || n_tokens < 0 || d <= 0 || n_seq <= 0)
     return ISOPO_ERR_INVALID_ARG;
-  if (dtype != ISOPO_F32 && dtype != ISOPO_BF16) return ISOPO_ERR_UNSUPPORTED;
+  if (!enum_in(dtype, ISOPO_F32, ISOPO_BF16)) return ISOPO_ERR_UNSUPPORTED;
   if (d % (dtype == ISOPO_BF16 ? 8 : 4) || n_seq > ISOPO_MAX_SEQ || n_tokens >= (int64_t)1 << 31)
     return ISOPO_ERR_UNSUPPORTED;
   if (!aligned16(src) || !aligned16(dst)) return ISOPO_ERR_INVALID_ARG;
@@ -511,11 +519,11 @@ isopo_status isopo_stash_layout_of(const isopo_layer* layer, isopo_stash_layout*
 
 isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
                                        isopo_stash_layout layout, float beta, float* dW, void* stream) {
+  if (!enum_in(layout, ISOPO_STASH_ROW_MAJOR, ISOPO_STASH_TILE_ORDER)) return ISOPO_ERR_INVALID_ARG;
   if (layout == ISOPO_STASH_ROW_MAJOR) {
     if (!stash) return ISOPO_ERR_INVALID_ARG;
     return isopo_weighted_grad(layer, c, stash, beta, dW, stream);
   }
-  if (layout != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_INVALID_ARG;
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
   if (!c || !stash || !dW || !aligned16(dW) || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
