@@ -50,7 +50,8 @@ typedef enum {
   ISOPO_ERR_BAD_OFFSETS = 2,        /* host offsets not 0-based, not non-decreasing or not ending at n_tokens */
   ISOPO_ERR_UNSUPPORTED = 3,        /* dtype / shape the kernels do not cover */
   ISOPO_ERR_WORKSPACE_TOO_SMALL = 4,
-  ISOPO_ERR_HIP = 5                 /* a HIP launch or query failed */
+  ISOPO_ERR_HIP = 5,                /* a HIP launch or query failed */
+  ISOPO_ERR_SCRATCH_LIMIT = 6       /* isopo_transform_noalloc: the problem needs more than the library's static scratch */
 } isopo_status;
 
 typedef enum { ISOPO_F32 = 0, ISOPO_BF16 = 1 } isopo_dtype;
@@ -208,6 +209,24 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
                              isopo_variant variant, float lambda, isopo_reg_mode reg_mode,
                              float* c, int32_t* info_dev, void* workspace, size_t ws_bytes,
                              void* stream);
+
+/* isopo_transform for callers that cannot allocate or pass device scratch: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same kernels,
+ * same results bit for bit.  The fp64 work matrices that n_seq > 128 needs live in an array the library
+ * holds on each GPU it runs on (ISOPO_NOALLOC_SCRATCH_BYTES per GPU, until the process ends); the call
+ * allocates and frees nothing.
+ *   limit   isopo_transform_workspace(n_seq, batch) <= ISOPO_NOALLOC_SCRATCH_BYTES, e.g. a block's seven
+ *           256-sequence problems, or one problem of 1024 sequences; beyond it ISOPO_ERR_SCRATCH_LIMIT,
+ *           nothing enqueued
+ *   device  the array of the device that is current at the call is used: the stream must belong to it.  The
+ *           first call on a device looks the array's address up (make it outside stream capture)
+ *   races   all calls on one GPU share that GPU's array: calls that may overlap in time (two streams, two
+ *           threads) race on it; order them, or use isopo_transform with workspaces of their own.  The
+ *           array keeps the last call's contents; no call depends on them */
+#define ISOPO_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+isopo_status isopo_transform_noalloc(const float* K, const float* A, int32_t n_seq, int32_t batch,
+                                     isopo_variant variant, float lambda, isopo_reg_mode reg_mode,
+                                     float* c, int32_t* info_dev, void* stream);
 
 /* isopo_transform with the interacting experiment's regulariser, reg = factor * E[mean(D)]: the
  * trailing mean over minibatches (this one included) of the Gram matrix's mean eigenvalue, which is

@@ -6,7 +6,15 @@
 #include <cstring>
 
 #include <cmath>
+#include <mutex>
 #include "kernels.h"
+
+// Scratch of isopo_transform_noalloc: the fp64 work matrices and right-hand sides that isopo_transform takes
+// from its workspace argument when n_seq > 128.  One copy per GPU, at its own address on each, resident
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the device
+// address it resolves to (static_scratch below) is what kernels and copies get.
+constexpr size_t kStaticScratchBytes = ISOPO_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -112,6 +120,28 @@ isopo_gram_path resolve(const isopo_layer* l, isopo_gram_path req) {
   return tg < tm ? ISOPO_GRAM_GHOST : ISOPO_GRAM_MATERIALISED;
 }
 
+// Device address of `scratch` on the current device, resolved once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -126,6 +156,7 @@ const char* isopo_status_string(isopo_status s) {
     case ISOPO_ERR_UNSUPPORTED: return "unsupported dtype or shape";
     case ISOPO_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case ISOPO_ERR_HIP: return "HIP error";
+    case ISOPO_ERR_SCRATCH_LIMIT: return "problem exceeds the library's static scratch";
   }
   return "unknown status";
 }
@@ -330,6 +361,21 @@ isopo_status isopo_transform(const float* K, const float* A, int32_t n_seq, int3
   t.K = K; t.A = A; t.n_seq = n_seq; t.batch = batch; t.variant = (int)variant; t.reg_mode = (int)reg_mode;
   t.lambda = lambda; t.c = c; t.info = info_dev; t.workspace = static_cast<double*>(workspace);
   return launch_transform(t, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_transform_noalloc(const float* K, const float* A, int32_t n_seq, int32_t batch,
+                                     isopo_variant variant, float lambda, isopo_reg_mode reg_mode, float* c,
+                                     int32_t* info_dev, void* stream) {
+  if (!K || !A || !c || n_seq <= 0 || batch <= 0) return ISOPO_ERR_INVALID_ARG;
+  if (n_seq > ISOPO_MAX_SEQ) return ISOPO_ERR_UNSUPPORTED;
+  if (!enum_in(variant, ISOPO_VARIANT_FISHER, ISOPO_VARIANT_INTERACTING)) return ISOPO_ERR_INVALID_ARG;
+  const size_t need = variant == ISOPO_VARIANT_INTERACTING ? isopo_transform_workspace(n_seq, batch) : 0;
+  if (need > kStaticScratchBytes) return ISOPO_ERR_SCRATCH_LIMIT;
+  void* ptr = nullptr;
+  if (need && static_scratch(&ptr) != hipSuccess) return ISOPO_ERR_HIP;
+  // Nothing in the scratch has to start at zero: the kernel writes the lower triangle of K + reg I and the
+  // right-hand side before it reads them, and reads nothing else.
+  return isopo_transform(K, A, n_seq, batch, variant, lambda, reg_mode, c, info_dev, ptr, need, stream);
 }
 
 isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, int32_t batch, isopo_variant variant,

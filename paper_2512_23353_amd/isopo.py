@@ -33,7 +33,7 @@ EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_
            "isopo_stash_layout_of", "isopo_weighted_grad_stash", "isopo_seq_grads_stash",
            "isopo_transform_ema", "isopo_seq_grads_limited", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
-           "isopo_transform", "isopo_weighted_grad", "isopo_scale_rows",
+           "isopo_transform", "isopo_transform_noalloc", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
            "isopo_fisher_samples_group_workspace", "isopo_fisher_samples_group",
            "isopo_weighted_grad_scratch", "isopo_weighted_grad_prescaled",
@@ -96,6 +96,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_transform_workspace.restype = sz
     lib.isopo_transform.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, ctypes.c_int, vp, vp, vp, sz, vp]
     lib.isopo_transform.restype = ctypes.c_int
+    lib.isopo_transform_noalloc.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, ctypes.c_int, vp, vp, vp]
+    lib.isopo_transform_noalloc.restype = ctypes.c_int
     lib.isopo_transform_ema.argtypes = [vp, vp, i32, i32, ctypes.c_int, f32, vp, f32, vp, vp, vp, sz, vp]
     lib.isopo_transform_ema.restype = ctypes.c_int
     lib.isopo_weighted_grad.argtypes = [lp, vp, vp, f32, vp, vp]
@@ -312,6 +314,23 @@ def transform(K: torch.Tensor, A: torch.Tensor, variant="fisher", lam: float = 0
     _check(load().isopo_transform(K.data_ptr(), A.data_ptr(), m, batch, _VARIANTS[variant], float(lam),
                                   int(reg_mode), c.data_ptr(), info.data_ptr(), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _stream(stream)), "isopo_transform")
+    return c, info
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def transform_noalloc(K: torch.Tensor, A: torch.Tensor, variant, lam: float, reg_mode: int, c: torch.Tensor,
+                      info: Optional[torch.Tensor] = None, stream=None):
+    """isopo_transform_noalloc: every buffer comes from the caller (c and info included), nothing is allocated
+    here or in the library; the scratch is the library's per-GPU array.  Returns (c, info)."""
+    m = K.shape[-1]
+    batch = 1 if K.dim() == 2 else K.shape[0]
+    if K.dtype != torch.float32 or A.dtype != torch.float32 or not K.is_contiguous() or not A.is_contiguous():
+        raise ValueError("K and A must be contiguous fp32")
+    _check(load().isopo_transform_noalloc(K.data_ptr(), A.data_ptr(), m, batch, _VARIANTS[variant], float(lam),
+                                          int(reg_mode), c.data_ptr(), _ptr(info), _stream(stream)),
+           "isopo_transform_noalloc")
     return c, info
 
 
