@@ -128,8 +128,8 @@ def main() -> int:
                          "child a GPU process")
     ap.add_argument("--clock-probe", action="store_true",
                     help="only time the largest projection's stash launch on zero operands and on the workload, then exit")
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4", "config5"])
     ap.add_argument("--variant", default="interacting", choices=["fisher", "interacting"])
     ap.add_argument("--lam", type=float, default=1e-3)
@@ -222,7 +222,6 @@ def main() -> int:
                                                                                         args.n_samples)
                                       for g in groups), dev)
     f2b = [torch.empty((npj, n_seq), dtype=torch.float32, device=dev) for _ in blocks]
-    scr = torch.empty(n_tokens * max(min(l.d_in, l.d_out) for l in layers), dtype=block[0].X.dtype, device=dev)
 
     def token_sample_step():
         for _ in range(sweeps):
@@ -231,21 +230,31 @@ def main() -> int:
                 isopo.fisher_samples_group([layers[i] for i in g], sample_idx, A, args.lam, isopo.REG_REL_TRACE,
                                            cb[b][j0:j0 + len(g)], f2b[b][j0:j0 + len(g)], fs_ws, stream=stream)
                 for i in g:
-                    isopo.weighted_grad_prescaled(layers[i], cs[i], scr, 0.0, dWs[i], stream=stream)
+                    isopo.weighted_grad(layers[i], cs[i], None, 0.0, dWs[i], stream=stream)
 
-    def timed(fn, steps, warmup):
+    medians = {}
+
+    def timed(fn, steps, warmup, tag=None):
+        """Seconds per step: wall clock over exactly `steps` steps between two device synchronisations.
+        Every step is also bracketed by HIP events on the launch stream; their median goes to medians[tag]."""
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         t0 = time.perf_counter()
-        for _ in range(steps):
+        for e0, e1 in ev:
+            e0.record(stream)
             fn()
+            e1.record(stream)
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        wall = (time.perf_counter() - t0) / steps
+        if tag is not None:
+            medians[tag] = float(np.median([a.elapsed_time(b) for a, b in ev]))
+        return wall
 
-    t_step = timed(step, args.steps, args.warmup)
+    t_step = timed(step, args.steps, args.warmup, "step")
     assert all(int(i.sum().item()) == 0 for i in infob), "transform reported a non-positive pivot"
-    t_reinforce = timed(reinforce_step, max(3, args.steps // 2), 1)
+    t_reinforce = timed(reinforce_step, max(3, args.steps // 2), 2, "reinforce")
 
     # Dominant kernel: the per-sequence gradient contraction, one launch per projection.
     # Average launch duration over the block's seven launches, HIP events on the launch stream.
@@ -287,14 +296,42 @@ def main() -> int:
     if not args.no_variants:
         reps = max(2, args.steps // 3)
         other = "fisher" if args.variant == "interacting" else "interacting"
-        t_other = timed(make_step(other, args.lam), reps, 1)
-        t_ts = timed(token_sample_step, reps, 1)
+        t_other = timed(make_step(other, args.lam), reps, 2, "other")
+        t_ts = timed(token_sample_step, reps, 2, "token_samples")
+
+        def variant_step(reg_mode=isopo.REG_REL_TRACE, beta=0.0, recompute=False):
+            def fn():
+                for _ in range(sweeps):
+                    for b in range(len(blocks)):
+                        for j in range(npj):
+                            isopo.layer_gram(layers[b * npj + j], "auto", K=Kb[b][j], workspace=wss[j],
+                                             keep_stash=0 if recompute else isopo.KEEP_FAST, stream=stream)
+                        isopo.transform(Kb[b], Ab, args.variant, args.lam, reg_mode, c=cb[b], info=infob[b], workspace=tws,
+                                        stream=stream)
+                        for j in range(npj):
+                            i = b * npj + j
+                            if recompute:
+                                isopo.weighted_grad(layers[i], cb[b][j], None, beta, dWs[i], stream=stream)
+                            else:
+                                isopo.weighted_grad(layers[i], cb[b][j], wss[j], beta, dWs[i], stream=stream, layout=layouts[i])
+            return fn
+        t_abs = timed(variant_step(reg_mode=isopo.REG_ABSOLUTE), reps, 2, "absolute")
+        t_beta = timed(variant_step(beta=1.0), reps, 2, "beta1")
+        t_rec = timed(variant_step(recompute=True), reps, 2, "recompute")
+        for dW in dWs:
+            dW.zero_()          # beta = 1 accumulated into them
+
+        def entry(t, tag, **more):
+            return {"ms_per_step": t * 1e3, "ms_per_step_median_hip_events": medians.get(tag),
+                    "overhead_over_reinforce": t / t_reinforce - 1.0, **more}
         variants = {
-            f"{args.variant}_from_stash_gram": {"ms_per_step": t_step * 1e3, "overhead_over_reinforce": t_step / t_reinforce - 1.0},
-            f"{other}_from_stash_gram": {"ms_per_step": t_other * 1e3, "overhead_over_reinforce": t_other / t_reinforce - 1.0},
-            "fisher_from_token_samples": {"ms_per_step": t_ts * 1e3, "overhead_over_reinforce": t_ts / t_reinforce - 1.0,
-                                          "n_samples": args.n_samples,
-                                          "what": "isopo_fisher_samples_group per set of projections sharing an input, then isopo_weighted_grad_prescaled (rows of the narrower operand scaled, one unweighted contraction) per projection"},
+            f"{args.variant}_from_stash_gram": entry(t_step, "step"),
+            f"{other}_from_stash_gram": entry(t_other, "other"),
+            f"{args.variant}_absolute_lambda": entry(t_abs, "absolute", what="the headline route with reg = lambda as printed (numerically nil at these shapes: K_ii ~ 1e4..1e6)"),
+            f"{args.variant}_beta_1": entry(t_beta, "beta1", what="the headline route accumulating into dW (mod.grad += of the listings): one more read of dW per projection"),
+            f"{args.variant}_without_stash": entry(t_rec, "recompute", what="isopo_layer_gram with no stash kept, then isopo_weighted_grad(c, stash = NULL): the weighted contraction from X and Delta again (the route for a workspace too small to keep the stash)"),
+            "fisher_from_token_samples": entry(t_ts, "token_samples", n_samples=args.n_samples,
+                                               what="isopo_fisher_samples_group per set of projections sharing an input, then isopo_weighted_grad(c, stash = NULL) per projection: ONE weighted contraction, no stash, no scaled copy"),
         }
         if n_layers > 1:
             # The sweep with K and the stash formed once per layer: six transforms (both variants x three
@@ -352,7 +389,7 @@ def main() -> int:
     out = {
         "metric": "ISOPO layer-step tokens/sec and TFLOP/s (% bf16 MFMA peak), 1 MI355X",
         "value": n_tokens / t_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": t_step * 1e3, "ms_per_step_median_hip_events": medians.get("step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: {('one transformer block' if len(w.projections) > 1 else 'one layer') if n_layers == 1 else f'{n_layers} transformer blocks swept layer by layer'}, {len(w.projections)} projection{'s' if len(w.projections) > 1 else ''} "
                                f"({', '.join(f'{p.name} {p.d_in}x{p.d_out}' for p in w.projections)}), "
@@ -367,12 +404,14 @@ def main() -> int:
         "tflops": total_flops / t_step / 1e12,
         "pct_bf16_mfma_peak": 100.0 * total_flops / t_step / PEAK_BF16_MFMA,
         "algorithmic_flops_per_step": total_flops,
-        "reinforce": {"ms_per_step": t_reinforce * 1e3, "tflops": reinforce_flops / t_reinforce / 1e12,
+        "reinforce": {"ms_per_step": t_reinforce * 1e3, "ms_per_step_median_hip_events": medians.get("reinforce"), "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
                       "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
         "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true,true> (per-sequence gradients -> stash in tile order, persistent launch)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
+                     "whole_step_frac": total_flops / t_step / PEAK_BF16_MFMA,
+                     "note": "frac is the dominant kernel alone; whole_step_frac is the step's algorithmic flops over its time (pct_bf16_mfma_peak / 100)",
                      "flops_per_launch": seq_grad_flops_per_launch,
                      "traffic": read_traffic(f"seq_grad_{args.config}"),
                      **({"clock_dependence": zero_operands} if zero_operands else {})},
@@ -398,7 +437,7 @@ def main() -> int:
         share = total_flops / sum(algorithmic_flops(n_tokens, sample.d_in, sample.d_out, n_seq).values())
         threads = max([ti.get("num_threads", 1) for ti in threadpool_info() if ti.get("user_api") == "blas"] or [1])
         out["cpu_baseline"] = {
-            "value": n_tokens / (t_cpu * share), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "value": n_tokens / (t_cpu * share), "unit": "tokens/s", "cores": int(threads), "kind": "oracle, one projection, scaled by flops",
             "sample": f"the block's {sample.name.split('/')[-1]} projection ({sample.d_in}x{sample.d_out}, all {n_seq} sequences, "
                       f"{n_tokens} tokens) took {t_cpu:.1f} s; scaled to the whole step by the "
                       f"algorithmic-FLOP ratio {share:.1f}"}

@@ -242,12 +242,18 @@ isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, 
                                  float* c, int32_t* info_dev, void* workspace, size_t ws_bytes, void* stream);
 
 /* dW [d_out, d_in] fp32 = beta * dW + sum_i c_i G_i.
- *   stash  NULL: contract X and Delta again, dW = Delta^T diag(c_tok) X.
- *          bf16 inputs: the scaled rows c_tok[t] * Delta[t,:] are rounded to
- *          bf16 before the MFMA, as a bf16 pre-scaling of Delta would.
+ *   stash  NULL: contract X and Delta again, dW = Delta^T diag(c_tok) X
+ *          (`grad += advantages[seq_id] * rescaling(...) * seq_logprob_grad`, summed over the sequences).
+ *          bf16 inputs: one launch of the matrix-core contraction that walks the tokens sequence by
+ *          sequence; the tokens enter unscaled and the fp32 accumulators are re-expressed in units of each
+ *          sequence's coefficient where a sequence ends, so no operand is scaled, copied or rounded and no
+ *          scratch is needed.  A sequence with c_i = 0 is skipped (it contributes exactly 0, whatever its
+ *          rows hold); the ratios c_i / c_j of the non-zero coefficients must be representable in fp32
+ *          next to the sums (a span of 2^60 is safe).  fp32 inputs: the rows of Delta are scaled in
+ *          registers.
  *          non-NULL: the stash isopo_layer_gram left (keep_stash), read once.
  *   c      device [n_seq].  NULL (only with stash == NULL) means all ones:
- *          dW = beta dW + Delta^T X with no scaling pass at all.  That is the
+ *          dW = beta dW + Delta^T X with no scaling at all.  That is the
  *          plain REINFORCE weight gradient when the advantages were folded into
  *          the loss (so Delta already carries them), and it is the baseline the
  *          layer step's overhead is measured against.
@@ -366,9 +372,9 @@ isopo_status isopo_transform_eigh(const double* D, const double* U, int32_t n_se
 /* dst[t, :] = c[seq(t)] * src[t, :] for a token-major matrix [n_tokens, d] (X or Delta), rounded to
  * the storage type; dst may not alias src.  Since Delta^T diag(c_tok) X = (diag(c_tok) Delta)^T X =
  * Delta^T (diag(c_tok) X), scaling the narrower operand once and then calling isopo_weighted_grad with
- * c = NULL gives the weighted update (`grad += advantages[i] * scale_i * seq_logprob_grad`) at the speed
- * of the unweighted contraction.  For bf16 this is the same single rounding of the scaled rows that
- * isopo_weighted_grad(c != NULL) applies to Delta. */
+ * c = NULL gives the weighted update (`grad += advantages[i] * scale_i * seq_logprob_grad`) from a
+ * scaled copy; the scaled rows are rounded to the storage type once.  isopo_weighted_grad(c != NULL) needs
+ * no such copy. */
 isopo_status isopo_scale_rows(const void* src, isopo_dtype dtype, int64_t n_tokens, int32_t d,
                               const int32_t* seq_offsets_dev, int32_t n_seq, const float* c, void* dst,
                               void* stream);

@@ -270,14 +270,7 @@ hipError_t launch_cfg(const SeqGradArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s) {
-  typedef unsigned short bf;
-  if (a.bf16 && (a.per_sequence || a.c == nullptr)) return launch_seq_grad_stream(a, s);
-  if (a.bf16) {
-    const bool small = (a.rows <= 128 || a.d_in <= 128);
-    if (a.per_sequence)
-      return small ? launch_cfg<bf, 128, 128, 32, 16, false>(a, s) : launch_cfg<bf, 256, 256, 32, 16, false>(a, s);
-    return small ? launch_cfg<bf, 128, 128, 32, 16, true>(a, s) : launch_cfg<bf, 256, 256, 32, 16, true>(a, s);
-  }
+  if (a.bf16) return launch_seq_grad_stream(a, s);
   if (a.per_sequence) return launch_cfg<float, 64, 64, 16, 4, false>(a, s);
   return launch_cfg<float, 64, 64, 16, 4, true>(a, s);
 }

@@ -59,6 +59,7 @@ struct StreamParams {
   const u16* X;
   const u16* Delta;
   const int32_t* off;
+  const float* c;                  // weighted sum over all tokens: one coefficient per sequence
   void* out;
   int d_in, d_out, n_seq, n_tokens;
   int row0, row_end, out_row0;
@@ -123,9 +124,10 @@ __device__ __forceinline__ void strip_tile_coords(int tile, int tiles_m, int til
   tile_n = c0 + in_strip % w;
 }
 
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false>
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false>
 __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
   static_assert(PER_SEQ || !TILED, "tile order is a layout of the per-sequence stash");
+  static_assert(!PER_SEQ || !WTD, "the coefficients weight the sum over all tokens");
   // the 16x16x32 inner loop: the tile-order stash and the sum over all tokens (the row-major stash keeps the
   // 32x32x16 loop, whose accumulator blocks its transposing epilogue is written for)
   constexpr bool MF16 = TILED || !PER_SEQ;
@@ -204,7 +206,112 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
     const int t0 = PER_SEQ ? p.off[item] : (split ? item * p.chunk_tokens : 0);
     const int t1 = PER_SEQ ? p.off[item + 1] : (split ? min(p.n_tokens, t0 + p.chunk_tokens) : p.n_tokens);
     const int n_rows = t1 - t0;
-    const int n_tiles = (n_rows + BK - 1) / BK;
+    int n_tiles = (n_rows + BK - 1) / BK;
+    // Weighted sum over all tokens: the token range is walked segment by segment (a segment: the part of one
+    // sequence inside [t0, t1), if it has tokens and a non-zero coefficient), each segment in token blocks of
+    // its own, so that no block mixes two sequences (rows past a segment's end arrive as zeros).  The
+    // accumulators hold the sum in units of the current segment's coefficient: tokens enter the MFMAs
+    // unscaled, and where a new segment opens the accumulators are multiplied once by c_previous / c_new.
+    // The epilogue multiplies by the last segment's coefficient.  No operand is scaled or rounded.
+    constexpr int kMaxSeg = 1024;            // the library's limit on sequences per layer
+    struct Cursor { int k, tok, end, left; };
+    [[maybe_unused]] int n_seg = 0;
+    [[maybe_unused]] float last_c = 0.f;
+    [[maybe_unused]] int* seg_tok = nullptr;
+    [[maybe_unused]] int* seg_end = nullptr;
+    [[maybe_unused]] float* seg_ratio = nullptr;
+    if constexpr (WTD) {
+      __shared__ int sh_seg_tok[kMaxSeg], sh_seg_end[kMaxSeg];
+      __shared__ float sh_seg_c[kMaxSeg];
+      __shared__ int sh_meta[2];
+      __shared__ float sh_last_c;
+      seg_tok = sh_seg_tok; seg_end = sh_seg_end; seg_ratio = sh_seg_c;
+      if (wave == 0) {
+        // the first sequence that reaches beyond t0
+        int s_lo = 0;
+        if (t0 > 0) {
+          int lo = 0, hi = p.n_seq;
+          while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (p.off[mid + 1] > t0) hi = mid; else lo = mid + 1;
+          }
+          s_lo = lo;
+        }
+        int count = 0, blocks = 0;
+        for (int base = s_lo; base < p.n_seq; base += 64) {
+          const int sq = base + lane;
+          int a = 0, b = 0, o0 = 0x7fffffff;
+          float cs = 0.f;
+          if (sq < p.n_seq) {
+            o0 = p.off[sq];
+            a = max(o0, t0); b = min(p.off[sq + 1], t1); cs = p.c[sq];
+          }
+          const bool valid = b > a && cs != 0.f;          // a NaN coefficient is kept and spreads
+          const unsigned long long mask = __ballot(valid);
+          const int pos = count + __popcll(mask & ((1ull << lane) - 1ull));
+          if (valid) {
+            sh_seg_tok[pos] = a; sh_seg_end[pos] = b; sh_seg_c[pos] = cs;
+            blocks += ((b - a + BK - 1) / BK + 1) & ~1;      // walked in an even number of blocks
+          }
+          count += __popcll(mask);
+          if (__builtin_amdgcn_readfirstlane(o0) >= t1) break;    // this and all later sequences lie beyond t1
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) blocks += __shfl_xor(blocks, o, 64);
+        if (lane == 0) { sh_meta[0] = count; sh_meta[1] = blocks; }
+      }
+      __syncthreads();
+      n_seg = __builtin_amdgcn_readfirstlane(sh_meta[0]);
+      n_tiles = __builtin_amdgcn_readfirstlane(sh_meta[1]);
+      // coefficient -> ratio to the segment before (1 for the first), in place
+      float ratio[kMaxSeg / 256];
+#pragma unroll
+      for (int q = 0; q < kMaxSeg / 256; ++q) {
+        const int k = tid + 256 * q;
+        ratio[q] = (k > 0 && k < n_seg) ? sh_seg_c[k - 1] / sh_seg_c[k] : 1.f;
+      }
+      if (tid == 0) sh_last_c = n_seg > 0 ? sh_seg_c[n_seg - 1] : 0.f;
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < kMaxSeg / 256; ++q) {
+        const int k = tid + 256 * q;
+        if (k < n_seg) sh_seg_c[k] = ratio[q];
+      }
+      __syncthreads();
+      last_c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sh_last_c)));
+    }
+    // The next token block the loads take (they run ahead of the multiplications): first token row and valid
+    // rows (0: an all-zero block).  Every segment is walked in an even number of blocks, the last one all
+    // zero if need be, because the main loop takes two blocks per trip.  One branch per block, taken only
+    // where a segment ends (the wave has nothing else to issue while a branch resolves).
+    auto segment_open = [&](Cursor& cur) {
+      if (cur.k < n_seg) {
+        cur.tok = __builtin_amdgcn_readfirstlane(seg_tok[cur.k]);
+        cur.end = __builtin_amdgcn_readfirstlane(seg_end[cur.k]);
+        cur.left = ((cur.end - cur.tok + BK - 1) / BK + 1) & ~1;
+      } else {
+        cur.tok = 0; cur.end = 0; cur.left = 0x7fffffff;       // past the last segment: all-zero blocks
+      }
+    };
+    auto next_block = [&](Cursor& cur, int it, int& tok0, int& rows) {
+      if constexpr (WTD) {
+        const int rem = cur.end - cur.tok;
+        rows = rem < 0 ? 0 : (rem > BK ? BK : rem);
+        tok0 = rows > 0 ? cur.tok : 0;
+        cur.tok += BK;
+        if (__builtin_expect(--cur.left == 0, 0)) {
+          ++cur.k;
+          segment_open(cur);
+        }
+      } else {
+        tok0 = t0 + it * BK;
+        rows = n_rows - it * BK;
+        rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+      }
+    };
+    Cursor ld;
+    ld.k = 0; ld.tok = 0; ld.end = 0; ld.left = 0;
+    if constexpr (WTD) segment_open(ld);
     const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
 
     // 16-byte column swizzle of token row r.  The 16x16x32 fragments (TILED) are read by lane groups whose
@@ -224,13 +331,11 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       offB[q] = (unsigned)r * rbB + (unsigned)(n0 * 2 + g * 16);
     }
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-    const u16* baseA = p.Delta + (size_t)t0 * p.d_out;
-    const u16* baseB = p.X + (size_t)t0 * p.d_in;
     auto issue_loads = [&](int it) {
-      int rows = n_rows - it * BK;
-      rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
-      v4i ra = make_rsrc(baseA + (size_t)it * BK * p.d_out, (unsigned)rows * rbA);
-      v4i rb = make_rsrc(baseB + (size_t)it * BK * p.d_in, (unsigned)rows * rbB);
+      int tok0, rows;
+      next_block(ld, it, tok0, rows);
+      v4i ra = make_rsrc(p.Delta + (size_t)tok0 * p.d_out, (unsigned)rows * rbA);
+      v4i rb = make_rsrc(p.X + (size_t)tok0 * p.d_in, (unsigned)rows * rbB);
       const unsigned stage = smem_base + (unsigned)(it % NSTAGE) * STAGE;
 #pragma unroll
       for (int q = 0; q < LA; ++q) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
@@ -297,10 +402,10 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           constexpr bool LATE = decltype(late_c)::value;
           const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
           const int nb = it + AHEAD;
-          int rows = n_rows - nb * BK;
-          rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
-          const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
-          const v4i rb = make_rsrc(baseB + (size_t)nb * BK * p.d_in, (unsigned)rows * rbB);
+          int tok_nb, rows;
+          next_block(ld, nb, tok_nb, rows);
+          const v4i ra = make_rsrc(p.Delta + (size_t)tok_nb * p.d_out, (unsigned)rows * rbA);
+          const v4i rb = make_rsrc(p.X + (size_t)tok_nb * p.d_in, (unsigned)rows * rbB);
           const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
           // When the accumulator tile fills the AGPRs the MFMA is written as asm, so that every accumulator
           // stays where it is (left to itself the register allocator shuttles them through VGPRs).
@@ -351,17 +456,63 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         };
         // two blocks per trip (the B fragments alternate between two register sets); an odd count runs one
         // block past the end, whose rows are all out of range and arrive as zeros
-        if (NMF16 * 4 > 128 && (wave_s & 2)) {
-          for (int it = 0; it < n_tiles; it += 2) {
-            token_block(it, std::integral_constant<int, 0>{}, std::true_type{});
-            token_block(it + 1, std::integral_constant<int, 1>{}, std::true_type{});
+        auto walk = [&](auto late_c) {
+          if constexpr (WTD) {
+            // segment by segment; where a segment opens the sum so far changes its unit from the previous
+            // segment's coefficient to this one's (ratio 1 for the first).  The multiplication sits between
+            // the inner loops, on every path, so that the accumulators stay where they are.
+            int it = 0;
+            for (int k = 0; k < n_seg; ++k) {
+              const float r = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seg_ratio[k])));
+              const int len = __builtin_amdgcn_readfirstlane(seg_end[k]) - __builtin_amdgcn_readfirstlane(seg_tok[k]);
+              const int blocks = ((len + BK - 1) / BK + 1) & ~1;
+              if constexpr (NMF16 * 4 > 128) {
+                // by hand, in the accumulation registers: the MFMAs of the block before have retired (the
+                // hazard tracking does not see through the asm on either side)
+                asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+                // eight elements per statement, so that no instruction waits for the one before it
+#pragma unroll
+                for (int i = 0; i < FM16; ++i)
+#pragma unroll
+                  for (int jp = 0; jp < FN16; jp += 2) {
+                    float e0 = acc[i][jp][0], e1 = acc[i][jp][1], e2 = acc[i][jp][2], e3 = acc[i][jp][3];
+                    float e4 = acc[i][jp + 1][0], e5 = acc[i][jp + 1][1], e6 = acc[i][jp + 1][2], e7 = acc[i][jp + 1][3];
+                    float t0, t1, t2, t3, t4, t5, t6, t7;
+                    asm volatile(
+                        "v_accvgpr_read_b32 %8, %0\n\tv_accvgpr_read_b32 %9, %1\n\tv_accvgpr_read_b32 %10, %2\n\t"
+                        "v_accvgpr_read_b32 %11, %3\n\tv_accvgpr_read_b32 %12, %4\n\tv_accvgpr_read_b32 %13, %5\n\t"
+                        "v_accvgpr_read_b32 %14, %6\n\tv_accvgpr_read_b32 %15, %7\n\t"
+                        "v_mul_f32 %8, %16, %8\n\tv_mul_f32 %9, %16, %9\n\tv_mul_f32 %10, %16, %10\n\tv_mul_f32 %11, %16, %11\n\t"
+                        "v_mul_f32 %12, %16, %12\n\tv_mul_f32 %13, %16, %13\n\tv_mul_f32 %14, %16, %14\n\tv_mul_f32 %15, %16, %15\n\t"
+                        "v_accvgpr_write_b32 %0, %8\n\tv_accvgpr_write_b32 %1, %9\n\tv_accvgpr_write_b32 %2, %10\n\t"
+                        "v_accvgpr_write_b32 %3, %11\n\tv_accvgpr_write_b32 %4, %12\n\tv_accvgpr_write_b32 %5, %13\n\t"
+                        "v_accvgpr_write_b32 %6, %14\n\tv_accvgpr_write_b32 %7, %15"
+                        : "+a"(e0), "+a"(e1), "+a"(e2), "+a"(e3), "+a"(e4), "+a"(e5), "+a"(e6), "+a"(e7), "=&v"(t0),
+                          "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7)
+                        : "s"(r));
+                    acc[i][jp][0] = e0; acc[i][jp][1] = e1; acc[i][jp][2] = e2; acc[i][jp][3] = e3;
+                    acc[i][jp + 1][0] = e4; acc[i][jp + 1][1] = e5; acc[i][jp + 1][2] = e6; acc[i][jp + 1][3] = e7;
+                  }
+                asm volatile("s_nop 7" ::: "memory");
+              } else {
+#pragma unroll
+                for (int i = 0; i < FM16; ++i)
+#pragma unroll
+                  for (int j = 0; j < FN16; ++j) acc[i][j] = acc[i][j] * r;
+              }
+              for (int b = 0; b < blocks; b += 2, it += 2) {
+                token_block(it, std::integral_constant<int, 0>{}, late_c);
+                token_block(it + 1, std::integral_constant<int, 1>{}, late_c);
+              }
+            }
+          } else {
+            for (int it = 0; it < n_tiles; it += 2) {
+              token_block(it, std::integral_constant<int, 0>{}, late_c);
+              token_block(it + 1, std::integral_constant<int, 1>{}, late_c);
+            }
           }
-        } else {
-          for (int it = 0; it < n_tiles; it += 2) {
-            token_block(it, std::integral_constant<int, 0>{}, std::false_type{});
-            token_block(it + 1, std::integral_constant<int, 1>{}, std::false_type{});
-          }
-        }
+        };
+        if (NMF16 * 4 > 128 && (wave_s & 2)) walk(std::true_type{}); else walk(std::false_type{});
       }
       __builtin_amdgcn_s_waitcnt(0x0f70);
       // Epilogue: lane l holds, of block (i, j), rows 4 (l / 16) ..+3 of column l % 16.
@@ -384,7 +535,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
               const int m = m0 + wm * WM + i * 16 + 4 * rq + v;
               if (m >= p.row_end) continue;
               float* o = static_cast<float*>(p.out) + (size_t)(m - p.out_row0) * p.d_in + n;
-              const float val = rd16(acc[i][j][v]);
+              const float val = WTD ? last_c * rd16(acc[i][j][v]) : rd16(acc[i][j][v]);
               if (split) atomicAdd(o, val);        // beta already applied by the pass before
               else *o = (p.beta != 0.f ? p.beta * *o : 0.f) + val;
             }
@@ -510,10 +661,10 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
         // DMA instructions of the block AHEAD ahead
         {
           const int nb = it + AHEAD;
-          int rows = n_rows - nb * BK;
-          rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
-          const v4i ra = make_rsrc(baseA + (size_t)nb * BK * p.d_out, (unsigned)rows * rbA);
-          const v4i rb = make_rsrc(baseB + (size_t)nb * BK * p.d_in, (unsigned)rows * rbB);
+          int tok_nb, rows;
+          next_block(ld, nb, tok_nb, rows);
+          const v4i ra = make_rsrc(p.Delta + (size_t)tok_nb * p.d_out, (unsigned)rows * rbA);
+          const v4i rb = make_rsrc(p.X + (size_t)tok_nb * p.d_in, (unsigned)rows * rbB);
           const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
 #pragma unroll
           for (int i = 0; i < FM; ++i) {
@@ -636,11 +787,12 @@ __global__ void queue_zero_kernel(unsigned* queue) {
 
 // n_wg > 0 (per-sequence mode, 256x256 tile): persistent launch of n_wg workgroups, a multiple of eight,
 // pulling work from `queue` (eight device counters, zeroed here on the stream).
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false>
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false>
 hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStream_t s, int n_wg = 0,
                          unsigned* queue = nullptr) {
   StreamParams p;
   p.queue = queue;
+  p.c = a.c;
   p.X = static_cast<const u16*>(a.X); p.Delta = static_cast<const u16*>(a.Delta); p.off = a.off; p.out = a.out;
   p.d_in = a.d_in; p.d_out = a.d_out; p.n_seq = a.n_seq; p.n_tokens = a.n_tokens;
   p.row0 = a.row0; p.row_end = a.row0 + a.rows; p.out_row0 = a.out_row0;
@@ -656,7 +808,7 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   p.n_blocks = (unsigned)pl.blocks;
   constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
   constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
-  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST, TILED>;
+  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST, TILED, WTD>;
   // once per process (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -682,7 +834,7 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
 
 }  // namespace
 
-// bf16, unscaled (per-sequence stash, or plain sum over all tokens).
+// bf16: the per-sequence stash, the plain sum over all tokens, or (c != nullptr) the weighted sum.
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
   const ContractionPlan pl = plan_contraction(a.rows, a.d_in, a.n_tokens, a.n_seq, a.off_host, a.per_sequence);
   // a workgroup budget applies to the large tile's per-sequence launches that would not fit it anyway
@@ -698,6 +850,9 @@ hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
     return launch_stream<256, 256, 4, 1, true, true>(a, pl, s, a.max_workgroups / 8 * 8, a.queue);
   if (a.per_sequence)
     return pl.tile == 256 ? launch_stream<256, 256, 4, 1, true>(a, pl, s) : launch_stream<128, 128, 4, 2, true>(a, pl, s);
+  if (a.c != nullptr)       // the weighted sum: segments of one sequence each, accumulators rescaled in between
+    return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false, false, false, true>(a, pl, s)
+                          : launch_stream<128, 128, 4, 2, false, false, false, true>(a, pl, s);
   return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false>(a, pl, s) : launch_stream<128, 128, 4, 2, false>(a, pl, s);
 }
 

@@ -417,6 +417,70 @@ def test_prescaled_weighted_grad(gpu_device, dtype, dims):
     assert np.all(np.abs(got - exact) <= ulp * np.abs(exact) + 1e-300)
 
 
+WEIGHTED_CASES = [
+    # d_in, d_out, lengths: whole 256x256 tiles then a split tail; token split on both tile sizes (a dozen or
+    # more chunks whose boundaries fall inside sequences); one tile, no split; many short sequences
+    (4096, 4200, [700, 1, 0, 900, 447]),
+    (256, 384, [3000, 1400, 1, 4200, 333, 4100]),
+    (512, 256, [3000, 1400, 1, 4200, 333, 4100]),
+    (200, 136, [3000, 1400, 1, 4200, 333, 4100]),
+    (1024, 768, [31, 32, 33, 0, 64, 65, 1, 2, 500, 95, 97]),
+    (768, 512, [5] * 70 + [0, 0, 129] + [1] * 40),
+]
+
+
+@pytest.mark.parametrize("case", range(len(WEIGHTED_CASES)))
+@pytest.mark.parametrize("beta", [0.0, 0.75])
+def test_weighted_contraction_from_x_and_delta(gpu_device, case, beta):
+    """dW = beta dW + Delta^T diag(c_tok) X for bf16 inputs with no stash and no scaled copy: the kernel walks
+    the tokens sequence by sequence and re-expresses its accumulators in units of each sequence's
+    coefficient.  Coefficients of both signs spanning nine orders of magnitude, exact zeros (their sequences
+    are skipped), empty sequences, ragged tails, every launch shape of the sum over all tokens; beta = 0 over
+    a NaN-filled dW.  No operand is rounded, so the result is held to the fp32-input tolerance scaled to the
+    terms."""
+    d_in, d_out, lengths = WEIGHTED_CASES[case]
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=70 + case, sigma_delta=1e-2, rho=0.3)
+    layer, _ = to_device(prob, gpu_device)
+    rng = np.random.default_rng(90 + case)
+    m = prob.n_seq
+    c = (rng.standard_normal(m) * 10.0 ** rng.uniform(-6, 3, m)).astype(np.float32)
+    c[rng.random(m) < 0.2] = 0.0
+    if m > 4:
+        c[2] = 0.0
+    cd = torch.from_numpy(c).to(gpu_device)
+    dW0 = rng.standard_normal((d_out, d_in)).astype(np.float32)
+    dW = torch.from_numpy(dW0).to(gpu_device) if beta != 0.0 else torch.full((d_out, d_in), float("nan"),
+                                                                           device=gpu_device)
+    isopo.weighted_grad(layer, cd, None, beta, dW)
+    torch.cuda.synchronize()
+    Xo, Do = wl.to_oracle(prob.X), wl.to_oracle(prob.Delta)
+    c64 = c.astype(np.float64)
+    ref = orc.weighted_grad_tokens(Xo, Do, prob.seq_offsets, c64) + beta * dW0.astype(np.float64)
+    mag = orc.weighted_grad_tokens(np.abs(orc.widen(Xo)), np.abs(orc.widen(Do)), prob.seq_offsets, np.abs(c64)) + np.abs(beta * dW0)
+    got = dW.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    # fp32 accumulation of exact bf16 products: a few 1e-6 of the terms (atomics of the split add a little)
+    assert np.all(np.abs(got - ref) <= 1e-4 * (mag + mag.mean())), f"case {case}: worst {np.max(np.abs(got - ref) / (mag + mag.mean())):.2e}"
+    assert_dW_close(got, ref, 1e-4, f"weighted from X, Delta case {case} beta={beta}", mag)
+    # all coefficients zero: dW = beta dW exactly
+    dW2 = torch.from_numpy(dW0).to(gpu_device) if beta != 0.0 else torch.full((d_out, d_in), float("nan"), device=gpu_device)
+    isopo.weighted_grad(layer, torch.zeros(m, device=gpu_device), None, beta, dW2)
+    torch.cuda.synchronize()
+    assert torch.equal(dW2, torch.from_numpy(dW0).to(gpu_device) * beta if beta != 0.0 else torch.zeros_like(dW2))
+
+
+def test_weighted_contraction_equals_the_unweighted_one_for_unit_coefficients(gpu_device):
+    """c = 1 everywhere: every ratio is one, so the weighted kernel must reproduce the unweighted launch up to the
+    zero padding of each sequence's last block (same products, same order within a sequence)."""
+    prob = wl.custom_layer(768, 512, [300, 17, 0, 250, 64, 1, 90], dtype="bf16", seed=77, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    ones = torch.ones(prob.n_seq, device=gpu_device)
+    a = isopo.weighted_grad(layer, ones)
+    b = isopo.weighted_grad(layer, None)
+    torch.cuda.synchronize()
+    assert torch.allclose(a, b, rtol=1e-5, atol=1e-6 * float(b.abs().max()))
+
+
 @pytest.mark.parametrize("beta", [0.0, 0.75])
 def test_unweighted_contraction_whole_tiles_then_split_tail(gpu_device, beta):
     """More 256x256 output tiles than compute units (17 x 16 = 272, ragged last tile row): the 256 tiles of
