@@ -117,6 +117,47 @@ def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
             "what": "same launch, same cycles; the clock under random operands is 1.84 - 1.89 GHz, on zeros 2.4 GHz (profiles/)"}
 
 
+def mfma_ceiling(dev, board_probe=False) -> dict:
+    """What the matrix cores sustain on this board when they do nothing else: isopo_probe_mfma_loop (one wave
+    per SIMD, 256 accumulator registers, operands in registers, no memory traffic in the loop) for the two bf16
+    MFMA shapes, on random operands (sign, mantissa and a few exponents random: every operand bit toggles) and on
+    zeros.  The rate on random operands is the ceiling a contraction of this register shape can reach under the
+    board's power limit; the rate on zeros shows the clock the part holds when the operands do not toggle."""
+    import numpy as np
+    import torch
+    from paper_2512_23353_amd import isopo
+    stream = torch.cuda.current_stream()
+    n_words = isopo.PROBE_THREADS * 64                       # 16 vectors of four 32-bit words per thread
+    g = torch.Generator(device="cpu").manual_seed(7)
+
+    def half_words():
+        sign = torch.randint(0, 2, (n_words,), generator=g, dtype=torch.int32) << 15
+        expo = (0x7e + torch.randint(0, 3, (n_words,), generator=g, dtype=torch.int32)) << 7    # values near 1
+        mant = torch.randint(0, 128, (n_words,), generator=g, dtype=torch.int32)
+        return sign | expo | mant
+    rand_ops = (half_words() | (half_words() << 16)).to(dev)
+    zero_ops = torch.zeros_like(rand_ops)
+    sink = torch.empty(isopo.PROBE_THREADS, dtype=torch.float32, device=dev)
+    iters = 20000
+    flops = 2.0 * 128 * 128 * 32 * iters * (isopo.PROBE_THREADS // 64)
+    out = {"what": "loop of bf16 MFMAs only: 256 workgroups x 4 waves, 256 accumulator registers per lane, operands in "
+                   "registers; TFLOP/s sustained over launches of about 40 ms", "iters_per_launch": iters, "rates": {}}
+    for shape, name in ((32, "v_mfma_f32_32x32x16_bf16"), (16, "v_mfma_f32_16x16x32_bf16")):
+        for ops, kind in ((rand_ops, "random_operands"), (zero_ops, "zero_operands")):
+            ms = []
+            for rep in range(6):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                isopo.probe_mfma_loop(shape, ops, sink, iters, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            t = float(np.median(ms[1:])) * 1e-3
+            out["rates"][f"{name}/{kind}"] = {"tflops": flops / t / 1e12, "ms": t * 1e3,
+                                               "frac_of_2.5_pflops": flops / t / PEAK_BF16_MFMA}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +169,9 @@ def main() -> int:
                          "child a GPU process")
     ap.add_argument("--clock-probe", action="store_true",
                     help="only time the largest projection's stash launch on zero operands and on the workload, then exit")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="only time a loop of nothing but bf16 MFMAs (both shapes, random and zero operands, the "
+                         "contraction's register shape) and print the sustained rates, then exit")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4", "config5"])
@@ -152,6 +196,9 @@ def main() -> int:
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.mfma_ceiling:
+        print(json.dumps(mfma_ceiling(dev, args.board_probe)))
+        return 0
     w = wl.CONFIGS[args.config]
     lengths = wl.draw_lengths(w)
     # a multi-layer stack is swept layer by layer; two distinct layers' inputs alternate (28 would not fit HBM)

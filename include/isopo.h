@@ -389,6 +389,17 @@ size_t isopo_weighted_grad_scratch(const isopo_layer* layer);
 isopo_status isopo_weighted_grad_prescaled(const isopo_layer* layer, const float* c, float beta, float* dW,
                                            void* scratch, size_t scratch_bytes, void* stream);
 
+/* Diagnostic, not a step of the method: a loop of nothing but bf16 matrix-core instructions on operands held
+ * in registers, one wave per SIMD with 256 accumulator registers per lane (the register shape of the
+ * contraction behind isopo_layer_gram).  The benchmark times it on random and on zero operands to find the
+ * rate the board sustains at its power limit, against which the contraction's own rate is to be read.
+ *   shape     32: v_mfma_f32_32x32x16_bf16, 16: v_mfma_f32_16x16x32_bf16
+ *   operands  device, ISOPO_PROBE_THREADS * 256 bytes, 16-byte aligned (16 vectors of 8 bf16 per thread)
+ *   sink      device float [ISOPO_PROBE_THREADS], overwritten
+ *   iters     trips; each is 2 * 128 * 128 * 32 flop per wave, ISOPO_PROBE_THREADS / 64 waves */
+#define ISOPO_PROBE_THREADS (256 * 256)
+isopo_status isopo_probe_mfma_loop(int32_t shape, const void* operands, float* sink, int32_t iters, void* stream);
+
 const char* isopo_status_string(isopo_status s);
 
 /* Library version, "major.minor". */

@@ -14,7 +14,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libisopo.so")
 
-SOURCES = ["api.cpp", "contraction_plan.cpp", "seq_grad.hip", "seq_grad_stream.hip", "stash_gram.hip", "stash_gram_stream.hip", "ghost_gram.hip", "transform.hip", "scale_rows.hip", "fisher_samples.hip", "rescale.hip", "eigh.hip"]
+SOURCES = ["api.cpp", "contraction_plan.cpp", "seq_grad.hip", "seq_grad_stream.hip", "stash_gram.hip", "stash_gram_stream.hip", "ghost_gram.hip", "transform.hip", "scale_rows.hip", "fisher_samples.hip", "rescale.hip", "eigh.hip", "probe_mfma.hip"]
 
 # Packed-fp32 VALU forms are switched off on purpose for all device code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result", "-Wno-int-to-pointer-cast",

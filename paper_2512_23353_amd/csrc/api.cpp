@@ -605,4 +605,11 @@ isopo_status isopo_weighted_grad_prescaled(const isopo_layer* layer, const float
   return isopo_weighted_grad(&scaled, nullptr, nullptr, beta, dW, stream);
 }
 
+isopo_status isopo_probe_mfma_loop(int32_t shape, const void* operands, float* sink, int32_t iters, void* stream) {
+  if (!operands || !sink || iters < 1 || !aligned16(operands)) return ISOPO_ERR_INVALID_ARG;
+  if (shape != 16 && shape != 32) return ISOPO_ERR_INVALID_ARG;
+  return launch_mfma_loop(shape, operands, sink, iters, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK
+                                                                                                         : ISOPO_ERR_HIP;
+}
+
 }  // extern "C"

@@ -228,4 +228,9 @@ hipError_t launch_ntk_eigh(const float* K, int m, int batch, double* D, double* 
                            hipStream_t s);
 hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s);
 
+// Diagnostic: a loop of nothing but bf16 MFMAs (shape 32: 32x32x16, shape 16: 16x16x32) on register operands,
+// kProbeWorkgroups workgroups of 256 threads; 2 * 128 * 128 * 32 flop per wave and trip.
+constexpr int kProbeWorkgroups = 256;
+hipError_t launch_mfma_loop(int shape, const void* operands, float* sink, int iters, hipStream_t s);
+
 }  // namespace isopo

@@ -1,16 +1,15 @@
-// Token-reduction contraction on the matrix cores:
+// Token-reduction contraction on the matrix cores, fp32 inputs:
 //     out[o][k] = sum_t scale(t) * Delta[t][o] * X[t][k]
 // which is the per-sequence log-probability gradient G_i = Delta_i^T X_i of both
 // hook listings (`grad_out.T @ act_in`) when t runs over one sequence, and the
 // weighted contraction dW = Delta^T diag(c_tok) X (`grad += advantages[i] *
-// scale_i * seq_logprob_grad`) when t runs over all tokens.
+// scale_i * seq_logprob_grad`) when t runs over all tokens.  (bf16 inputs, the
+// benchmark's case, take the streaming kernel in seq_grad_stream.hip.)
 //
 // Both operands are token-major: the reduction index is the slow index of X and
 // of Delta.  Tiles are staged in LDS as [token][feature], exactly as they lie in
-// HBM (coalesced 16-byte loads along the feature axis).  The MFMA wants every
-// lane to hold 8 consecutive reduction-index values of one feature; for bf16
-// that register layout comes from the LDS transpose read (ds_read_b64_tr_b16),
-// for fp32 (one value per lane) a plain 32-bit LDS read already has it.
+// HBM (coalesced 16-byte loads along the feature axis).  The fp32 MFMA takes one
+// value per lane, so a plain 32-bit LDS read already has the register layout.
 //
 // Work item = (sequence range, 2-D tile of the [d_out, d_in] output).  The
 // K-loop walks the tokens of the range sequence by sequence, BK rows at a time;
@@ -18,8 +17,6 @@
 // host-side padding.
 #include "common.h"
 #include "kernels.h"
-
-#include <type_traits>
 
 namespace isopo {
 namespace {
@@ -39,35 +36,10 @@ struct SeqGradParams {
   unsigned n_blocks;
 };
 
-template <typename T>
-struct Elem;
-template <>
-struct Elem<float> {
-  static constexpr int kVec = 4;      // elements per 16-byte vector
-};
-template <>
-struct Elem<unsigned short> {         // bf16 bit patterns
-  static constexpr int kVec = 8;
-};
-
-// One A- or B-operand fragment of a 32-wide block, bf16: lane l ends up holding
-// feature (l%32) at reduction rows k0 + 8*(l/32) + 0..7.  Within each group of
-// 16 lanes the transpose read hands lane i element (i%4) of the 8 bytes that
-// lane 4*j + i/4 addressed, for j = 0..3; so lane s of a group addresses row
-// (s/4), features 4*(s%4)..+3, and receives 4 rows of feature (s%16).
-__device__ __forceinline__ bf16x8 read_frag_bf16(const unsigned short* tile, int pitch, int lane) {
-  const int l = lane & 15, g = lane >> 4;
-  const unsigned short* p = tile + (8 * (g >> 1) + (l >> 2)) * pitch + 16 * (g & 1) + 4 * (l & 3);
-  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * pitch));
-  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-template <typename T, int BM, int BN, int BK, int PAD, bool WEIGHTED>
+template <int BM, int BN, int BK, int PAD, bool WEIGHTED>
 __global__ __launch_bounds__(256) void seq_grad_kernel(SeqGradParams p) {
-  constexpr int kVec = Elem<T>::kVec;
+  typedef float T;
+  constexpr int kVec = 4;                        // elements per 16-byte vector
   constexpr int WM = BM / 2, WN = BN / 2;        // 2x2 waves
   constexpr int FM = WM / 32, FN = WN / 32;      // 32x32 MFMA blocks per wave
   constexpr int PA = BM + PAD, PB = BN + PAD;    // LDS row pitch in elements
@@ -122,13 +94,9 @@ __global__ __launch_bounds__(256) void seq_grad_kernel(SeqGradParams p) {
     for (int i = 0; i < NA; ++i) {
       uint4 v = ra[i];
       if constexpr (WEIGHTED) {
-        if constexpr (std::is_same<T, float>::value) {
-          float4 f = __builtin_bit_cast(float4, v);
-          f.x *= scale; f.y *= scale; f.z *= scale; f.w *= scale;
-          v = __builtin_bit_cast(uint4, f);
-        } else {
-          v = scale_bf16x8(v, scale);
-        }
+        float4 f = __builtin_bit_cast(float4, v);
+        f.x *= scale; f.y *= scale; f.z *= scale; f.w *= scale;
+        v = __builtin_bit_cast(uint4, f);
       }
       *reinterpret_cast<uint4*>(As + (buf * BK + a_r + i * RA) * PA + a_cv * kVec) = v;
     }
@@ -148,35 +116,19 @@ __global__ __launch_bounds__(256) void seq_grad_kernel(SeqGradParams p) {
   auto compute = [&](int buf) {
     const T* at = As + buf * BK * PA + wm * WM;
     const T* bt = Bs + buf * BK * PB + wn * WN;
-    if constexpr (std::is_same<T, float>::value) {
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        float af[FM], bf[FN];
-        const int kr = kk + (lane >> 5), col = lane & 31;
+    for (int kk = 0; kk < BK; kk += 2) {
+      float af[FM], bf[FN];
+      const int kr = kk + (lane >> 5), col = lane & 31;
 #pragma unroll
-        for (int i = 0; i < FM; ++i) af[i] = at[kr * PA + i * 32 + col];
+      for (int i = 0; i < FM; ++i) af[i] = at[kr * PA + i * 32 + col];
 #pragma unroll
-        for (int j = 0; j < FN; ++j) bf[j] = bt[kr * PB + j * 32 + col];
+      for (int j = 0; j < FN; ++j) bf[j] = bt[kr * PB + j * 32 + col];
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+      for (int i = 0; i < FM; ++i)
 #pragma unroll
-          for (int j = 0; j < FN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
-      }
-    } else {
-#pragma unroll
-      for (int kk = 0; kk < BK; kk += 16) {
-        bf16x8 af[FM], bf[FN];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) af[i] = read_frag_bf16(at + kk * PA + i * 32, PA, lane);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) bf[j] = read_frag_bf16(bt + kk * PB + j * 32, PB, lane);
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-      }
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -232,18 +184,15 @@ __global__ __launch_bounds__(256) void seq_grad_kernel(SeqGradParams p) {
         if constexpr (WEIGHTED) {
           float* o = static_cast<float*>(p.out) + idx;
           *o = (p.beta != 0.f ? p.beta * *o : 0.f) + acc[i][j][v];
-        } else if constexpr (std::is_same<T, float>::value) {
-          static_cast<float*>(p.out)[(size_t)item * p.out_seq_stride + idx] = acc[i][j][v];
         } else {
-          static_cast<unsigned short*>(p.out)[(size_t)item * p.out_seq_stride + idx] =
-              f32_to_bf16_bits(acc[i][j][v]);
+          static_cast<float*>(p.out)[(size_t)item * p.out_seq_stride + idx] = acc[i][j][v];
         }
       }
     }
   }
 }
 
-template <typename T, int BM, int BN, int BK, int PAD, bool WEIGHTED>
+template <int BM, int BN, int BK, int PAD, bool WEIGHTED>
 hipError_t launch_cfg(const SeqGradArgs& a, hipStream_t s) {
   SeqGradParams p;
   p.X = a.X; p.Delta = a.Delta; p.off = a.off; p.c = a.c; p.out = a.out;
@@ -257,8 +206,8 @@ hipError_t launch_cfg(const SeqGradArgs& a, hipStream_t s) {
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   p.n_blocks = (unsigned)blocks;
-  constexpr size_t smem = 2ull * BK * ((BM + PAD) + (BN + PAD)) * sizeof(T);
-  auto kern = seq_grad_kernel<T, BM, BN, BK, PAD, WEIGHTED>;
+  constexpr size_t smem = 2ull * BK * ((BM + PAD) + (BN + PAD)) * sizeof(float);
+  auto kern = seq_grad_kernel<BM, BN, BK, PAD, WEIGHTED>;
   // once per process and instantiation (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -271,8 +220,8 @@ hipError_t launch_cfg(const SeqGradArgs& a, hipStream_t s) {
 
 hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s) {
   if (a.bf16) return launch_seq_grad_stream(a, s);
-  if (a.per_sequence) return launch_cfg<float, 64, 64, 16, 4, false>(a, s);
-  return launch_cfg<float, 64, 64, 16, 4, true>(a, s);
+  if (a.per_sequence) return launch_cfg<64, 64, 16, 4, false>(a, s);
+  return launch_cfg<64, 64, 16, 4, true>(a, s);
 }
 
 }  // namespace isopo

@@ -38,7 +38,7 @@ EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_
            "isopo_fisher_samples_group_workspace", "isopo_fisher_samples_group",
            "isopo_weighted_grad_scratch", "isopo_weighted_grad_prescaled",
            "isopo_gram_norms", "isopo_rescale", "isopo_ntk_eigh_workspace", "isopo_ntk_eigh",
-           "isopo_transform_eigh", "isopo_status_string", "isopo_version")
+           "isopo_transform_eigh", "isopo_probe_mfma_loop", "isopo_status_string", "isopo_version")
 
 
 class IsopoError(RuntimeError):
@@ -132,6 +132,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_transform_eigh.argtypes = [vp, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.c_int, vp, f32,
                                          vp, vp, vp]
     lib.isopo_transform_eigh.restype = ctypes.c_int
+    lib.isopo_probe_mfma_loop.argtypes = [i32, vp, vp, i32, vp]
+    lib.isopo_probe_mfma_loop.restype = ctypes.c_int
     lib.isopo_status_string.argtypes = [ctypes.c_int]
     lib.isopo_status_string.restype = ctypes.c_char_p
     lib.isopo_version.argtypes = []
@@ -526,6 +528,17 @@ def weighted_grad_prescaled(layer: Layer, c: torch.Tensor, scratch: Optional[tor
                                                 scratch.data_ptr(), scratch.numel() * scratch.element_size(),
                                                 _stream(stream)), "isopo_weighted_grad_prescaled")
     return dW
+
+
+PROBE_THREADS = 256 * 256
+
+
+def probe_mfma_loop(shape: int, operands: torch.Tensor, sink: torch.Tensor, iters: int, stream=None) -> None:
+    """Diagnostic: `iters` trips of nothing but bf16 MFMAs of the given shape (32 or 16) on register operands."""
+    if operands.numel() * operands.element_size() < PROBE_THREADS * 256 or sink.numel() < PROBE_THREADS:
+        raise ValueError("operands / sink too small for the probe")
+    _check(load().isopo_probe_mfma_loop(int(shape), operands.data_ptr(), sink.data_ptr(), int(iters), _stream(stream)),
+           "isopo_probe_mfma_loop")
 
 
 def layer_step(layer: Layer, A: torch.Tensor, variant="interacting", lam: float = 0.0,
