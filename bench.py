@@ -158,6 +158,35 @@ def mfma_ceiling(dev, board_probe=False) -> dict:
     return out
 
 
+def ghost_case(dev) -> dict:
+    """The ghost Gram path where it is the chosen one: a short microbatch (8 sequences of 1024 tokens) on the
+    stress layer 5120 -> 27648.  Algorithmic work N^2 (d_in + d_out) flop (both token-by-token products over the
+    pairs t <= s)."""
+    import numpy as np
+    import torch
+    from paper_2512_23353_amd import isopo, workloads as wl
+    stream = torch.cuda.current_stream()
+    w = wl.CONFIGS["config5"]
+    prob = wl.make_layer(w, w.projections[0], np.full(8, 1024, dtype=np.int64), device=dev)
+    layer = isopo.Layer(prob.X, prob.Delta, prob.seq_offsets)
+    chosen, full, _ = isopo.gram_plan(layer, "auto")
+    ws = isopo.alloc_workspace(isopo.gram_plan(layer, "ghost")[1], dev)
+    K = torch.empty((prob.n_seq, prob.n_seq), dtype=torch.float32, device=dev)
+    ms = []
+    for _ in range(12):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        isopo.layer_gram(layer, "ghost", K=K, workspace=ws, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    t = float(np.median(ms[2:])) * 1e-3
+    flops = float(prob.n_tokens) ** 2 * (prob.d_in + prob.d_out)
+    return {"workload": f"ghost Gram, {prob.d_in}x{prob.d_out}, {prob.n_seq} sequences, N={prob.n_tokens} tokens, bf16",
+            "auto_choice": chosen, "ms": t * 1e3, "tflops": flops / t / 1e12, "frac_of_bf16_peak": flops / t / PEAK_BF16_MFMA,
+            "what": "isopo_layer_gram(path = GHOST): fill, token -> sequence map, ghost_gram_tiled_kernel, finish"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,6 +201,9 @@ def main() -> int:
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="only time a loop of nothing but bf16 MFMAs (both shapes, random and zero operands, the "
                          "contraction's register shape) and print the sustained rates, then exit")
+    ap.add_argument("--ghost-case", action="store_true",
+                    help="only time isopo_layer_gram on the ghost path for a short microbatch on the stress layer "
+                         "(5120 -> 27648, 8 sequences of 1024 tokens) and print its rate, then exit")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4", "config5"])
@@ -198,6 +230,9 @@ def main() -> int:
     torch.cuda.set_device(dev)
     if args.mfma_ceiling:
         print(json.dumps(mfma_ceiling(dev, args.board_probe)))
+        return 0
+    if args.ghost_case:
+        print(json.dumps(ghost_case(dev)))
         return 0
     w = wl.CONFIGS[args.config]
     lengths = wl.draw_lengths(w)

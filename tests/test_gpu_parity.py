@@ -205,6 +205,37 @@ def test_ghost_feature_ranges(gpu_device, case):
     assert rel_err(Km.cpu().numpy(), Kg.cpu().numpy()) < 1e-3
 
 
+GHOST_LONG_CASES = [
+    # microbatches long enough for more tile pairs than resident workgroups (several rounds, XCD runs): whole
+    # tiles; a ragged last tile with a feature count that is no multiple of 64; many short sequences whose
+    # boundaries cross the 32 x 32 blocks, empty ones among them; one long sequence against short ones
+    ("whole_tiles", 256, 384, [512] * 8),
+    ("ragged_end_odd_features", 264, 200, [700, 3, 1500, 0, 1100, 801]),
+    ("many_short_sequences", 128, 256, [37, 5, 90, 0, 1, 64, 33, 150] * 10 + [1000]),
+    ("one_long_sequence", 512, 128, [4000, 60, 60, 120]),
+]
+
+
+@pytest.mark.parametrize("case", GHOST_LONG_CASES, ids=[c[0] for c in GHOST_LONG_CASES])
+def test_ghost_long_microbatches(gpu_device, case):
+    """The ghost form on 4000 tokens and more (hundreds of 128 x 128 token-pair tiles, no feature ranges): K
+    against the oracle in full, bit-symmetric, and equal to the materialised path's within rounding."""
+    _, d_in, d_out, lengths = case
+    assert sum(lengths) >= 4000
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=29, sigma_delta=1e-2, rho=0.5)
+    layer, _ = to_device(prob, gpu_device)
+    Kg, _ = isopo.layer_gram(layer, "ghost")
+    Km, _ = isopo.layer_gram(layer, "materialised")
+    torch.cuda.synchronize()
+    K_ref = orc.layer_ntk(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets, chunk_rows=64,
+                          matrix_product=True)
+    assert_K_close(Kg.cpu().numpy(), K_ref, TOL["bf16"], f"ghost long {case[0]}")
+    assert torch.equal(Kg, Kg.T)
+    assert rel_err(Km.cpu().numpy(), Kg.cpu().numpy()) < 1e-3
+    empty = [i for i, n in enumerate(lengths) if n == 0]
+    assert all(not Kg[i].any() for i in empty)
+
+
 def test_both_gram_paths_agree_and_are_symmetric(gpu_device):
     prob = wl.custom_layer(512, 768, [300, 517, 33, 260, 128], dtype="bf16", seed=4, sigma_delta=1e-2, rho=0.7)
     layer, _ = to_device(prob, gpu_device)
