@@ -114,7 +114,7 @@ def clock_dependence(args, block, layers, stash_views, fl, stream, wg_queue):
     return {"projection": block[big].name, **({"board": power} if power else {}), "tflops_on_the_workload": fl[big]["seq_grads"] / t_real / 1e12,
             "tflops_on_zero_operands": fl[big]["seq_grads"] / t_zero / 1e12,
             "zero_ms": t_zero * 1e3, "workload_ms": t_real * 1e3,
-            "what": "same launch, same cycles; the clock under random operands is 1.84 - 1.89 GHz, on zeros 2.4 GHz (profiles/)"}
+            "what": "same launch, same cycles; the clock under random operands is 1.85 - 2.0 GHz, on zeros 2.4 GHz (profiles/)"}
 
 
 def mfma_ceiling(dev, board_probe=False) -> dict:
@@ -314,6 +314,33 @@ def main() -> int:
                 for i in g:
                     isopo.weighted_grad(layers[i], cs[i], None, 0.0, dWs[i], stream=stream)
 
+    # The same with the Fisher passes of a block's groups on streams of their own (default priority): they are
+    # independent of one another, and run side by side the nearly empty last round of one launch's workgroups
+    # (a quarter of a launch at this size) overlaps the others' main rounds.  The contractions follow on the
+    # launch stream once all coefficients are there.
+    n_side = max(len([g for g in groups if g[0] // npj == b]) for b in range(len(blocks)))
+    side = [torch.cuda.Stream(device=dev) for _ in range(n_side)]
+    fs_wss = [isopo.alloc_workspace(fs_ws.numel(), dev) for _ in range(n_side)]
+    ev_go = torch.cuda.Event()
+    ev_done = [torch.cuda.Event() for _ in range(n_side)]
+
+    def token_sample_step_side_streams():
+        for _ in range(sweeps):
+            for b in range(len(blocks)):
+                mine = [g for g in groups if g[0] // npj == b]
+                ev_go.record(stream)
+                for k, g in enumerate(mine):
+                    j0 = g[0] % npj
+                    side[k].wait_event(ev_go)
+                    isopo.fisher_samples_group([layers[i] for i in g], sample_idx, A, args.lam, isopo.REG_REL_TRACE,
+                                               cb[b][j0:j0 + len(g)], f2b[b][j0:j0 + len(g)], fs_wss[k], stream=side[k])
+                    ev_done[k].record(side[k])
+                for k in range(len(mine)):
+                    stream.wait_event(ev_done[k])
+                for g in mine:
+                    for i in g:
+                        isopo.weighted_grad(layers[i], cs[i], None, 0.0, dWs[i], stream=stream)
+
     medians = {}
 
     def timed(fn, steps, warmup, tag=None):
@@ -380,6 +407,7 @@ def main() -> int:
         other = "fisher" if args.variant == "interacting" else "interacting"
         t_other = timed(make_step(other, args.lam), reps, 2, "other")
         t_ts = timed(token_sample_step, reps, 2, "token_samples")
+        t_ts2 = timed(token_sample_step_side_streams, reps, 2, "token_samples_side")
 
         def variant_step(reg_mode=isopo.REG_REL_TRACE, beta=0.0, recompute=False):
             def fn():
@@ -414,6 +442,8 @@ def main() -> int:
             f"{args.variant}_without_stash": entry(t_rec, "recompute", what="isopo_layer_gram with no stash kept, then isopo_weighted_grad(c, stash = NULL): the weighted contraction from X and Delta again (the route for a workspace too small to keep the stash)"),
             "fisher_from_token_samples": entry(t_ts, "token_samples", n_samples=args.n_samples,
                                                what="isopo_fisher_samples_group per set of projections sharing an input, then isopo_weighted_grad(c, stash = NULL) per projection: ONE weighted contraction, no stash, no scaled copy"),
+            "fisher_from_token_samples_side_streams": entry(t_ts2, "token_samples_side", n_samples=args.n_samples,
+                                                            what="the same calls; the block's Fisher passes run on streams of their own, side by side, before the contractions on the launch stream"),
         }
         if n_layers > 1:
             # The sweep with K and the stash formed once per layer: six transforms (both variants x three
@@ -482,7 +512,7 @@ def main() -> int:
                    "compute_units": torch.cuda.get_device_properties(dev).multi_processor_count,
                    "hbm_gib": round(torch.cuda.get_device_properties(dev).total_memory / 2 ** 30, 1),
                    "peaks_used": {"bf16_mfma_tflops": PEAK_BF16_MFMA / 1e12, "hbm_tb_s": PEAK_HBM / 1e12},
-                   "clocks": "as found (not pinned); under the contraction the part runs at 1.84 - 1.89 GHz (board power cap) with the workload's random operands and at 2.4 GHz with zero operands, see profiles/"},
+                   "clocks": "as found (not pinned); under the contraction the part runs at 1.85 - 2.0 GHz (board power cap) with the workload's random operands and at 2.4 GHz with zero operands, see profiles/"},
         "tflops": total_flops / t_step / 1e12,
         "pct_bf16_mfma_peak": 100.0 * total_flops / t_step / PEAK_BF16_MFMA,
         "algorithmic_flops_per_step": total_flops,
