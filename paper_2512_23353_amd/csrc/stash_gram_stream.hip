@@ -46,10 +46,10 @@ struct Params {
 __device__ __forceinline__ void load_lds16(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
-// The same with the non-temporal cache policy, for the one-pass kernel for up to 128 sequences: every stash
-// byte is read once, and keeping it out of the caches' replacement order is worth 13 % of the pass (6.2 ->
-// 7.05 TB/s on a 3.8 GB stash).  The kernels for more sequences are bound by their MFMAs (the policy made
-// 2 % on a 5 GB stash and cost time on config 5's 72 GB) or read a row once per super-block pair: default.
+// The same with the non-temporal cache policy, for the one-pass kernels (up to 256 sequences): every stash
+// byte is read once, and keeping it out of the caches' replacement order is worth 13 % of the pass for up
+// to 128 sequences (6.2 -> 7.05 TB/s on a 3.8 GB stash) and 3 % for 129..256 (72 GB stash).  The super-block
+// pair kernel reads a row once per pair and keeps the default policy.
 __device__ __forceinline__ void load_lds16_nt(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
@@ -296,7 +296,9 @@ __global__ __launch_bounds__(256) void stash_gram_pair_kernel(LargeParams p) {
 // half-stages: two are multiplied while three are in flight.  The 36 upper-triangle 32x32 blocks of the
 // 8x8 block grid are dealt to the four waves by block row: wave w takes rows w and 7-w, nine blocks
 // each, and reads the row-block fragments it needs per 16-element step.  Every wave walks every step.
-// The stash is read exactly once; partials have the large path's layout.
+// The fragments of step s + 1 are read between the MFMAs of step s (two register sets), so no MFMA
+// waits for the LDS.  A slice that is not whole (only the last one of [p0, p1) can be) takes a plain
+// masking loop after the main one.  The stash is read exactly once; partials have the large path's layout.
 constexpr int kWideHalves = 5;
 
 template <int W>
@@ -315,7 +317,7 @@ __device__ __forceinline__ void wide_body(const LargeParams& p, unsigned smem_ba
       const long long last = (n_elems - 8) * 2;
       if (byte > last) byte = last;
       if ((j >> 1) >= my_count) byte = 0;
-      load_lds16((h ? src[1][q] : src[0][q]) + byte, stage + (unsigned)(wave_s * LPW + q) * 1024);
+      load_lds16_nt((h ? src[1][q] : src[0][q]) + byte, stage + (unsigned)(wave_s * LPW + q) * 1024);
     }
   };
   f32x16 acc[9];
@@ -324,9 +326,33 @@ __device__ __forceinline__ void wide_body(const LargeParams& p, unsigned smem_ba
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
   const int frow = lane & 31, half = lane >> 5;
+  // the nine products of one 16-element step from this wave's fragments of row blocks R0..7
+  auto multiply = [&](const v4u (&frag)[8]) {
+    int q = 0;
+#pragma unroll
+    for (int bj = R0; bj < 8; ++bj, ++q)
+      acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[R0]),
+                                                       __builtin_bit_cast(bf16x8, frag[bj]), acc[q], 0, 0, 0);
+#pragma unroll
+    for (int bj = R1; bj < 8; ++bj, ++q)
+      acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[R1]),
+                                                       __builtin_bit_cast(bf16x8, frag[bj]), acc[q], 0, 0, 0);
+  };
+  auto read_step = [&](v4u (&frag)[8], unsigned sb0, unsigned sb1, int st) {
+    const int vec = st * 2 + half;
+#pragma unroll
+    for (int b = R0; b < 8; ++b) {                   // row blocks below R0 pair with no block of this wave
+      const int row = (b & 3) * 32 + frow;
+      frag[b] = *(lds_v4u_ptr)((b < 4 ? sb0 : sb1) + (unsigned)row * RB + (unsigned)((vec ^ (row & (VPR - 1))) * 16));
+    }
+  };
+
+  // Only the very last slice of [p0, p1) can be short; it goes through the masking loop below.
+  const bool short_tail = (n_elems % KW) != 0 && my_first + my_count == (n_elems + KW - 1) / KW;
+  const long long n_whole = my_count - (short_tail ? 1 : 0);
 
   issue(0); issue(1); issue(2);
-  for (long long k = 0; k < my_count; ++k) {
+  for (long long k = 0; k < n_whole; ++k) {
     // half-stages 2k and 2k+1 landed (only 2k+2 may still be out), then everyone's; the two half-stages of
     // slice k-1 are free after the barrier and take 2k+3 and 2k+4
     __builtin_amdgcn_s_waitcnt(0x0f70 | LPW);
@@ -335,27 +361,46 @@ __device__ __forceinline__ void wide_body(const LargeParams& p, unsigned smem_ba
     issue(2 * k + 4);
     const unsigned sb0 = smem_base + (unsigned)((2 * k) % kWideHalves) * kStageBytes;
     const unsigned sb1 = smem_base + (unsigned)((2 * k + 1) % kWideHalves) * kStageBytes;
-    const long long valid = n_elems - (my_first + k) * KW;
+    // Two fragment sets: the reads of step st + 1 go out between the MFMAs of step st, one read behind each
+    // of the first MFMAs, so that no MFMA waits for the LDS and the four waves' reads are spread out.
+    v4u frag[2][8];
+    read_step(frag[0], sb0, sb1, 0);
 #pragma unroll
     for (int st = 0; st < STEPS; ++st) {
-      const int vec = st * 2 + half;
-      const bool dead = valid < KW && (long long)vec * 8 >= valid;
-      v4u frag[8];
+      if (st + 1 < STEPS) read_step(frag[(st + 1) & 1], sb0, sb1, st + 1);
+      multiply(frag[st & 1]);
+      if (st == 0) __builtin_amdgcn_sched_group_barrier(0x100, 8 - R0, 0);      // step 0's own reads first
+      if (st + 1 < STEPS) {
 #pragma unroll
-      for (int b = R0; b < 8; ++b) {                 // row blocks below R0 pair with no block of this wave
-        const int row = (b & 3) * 32 + frow;
-        frag[b] = *(lds_v4u_ptr)((b < 4 ? sb0 : sb1) + (unsigned)row * RB + (unsigned)((vec ^ (row & (VPR - 1))) * 16));
-        if (dead) frag[b] = v4u{0u, 0u, 0u, 0u};
+        for (int r = 0; r < 8 - R0; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 9 - (8 - R0), 0);
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x008, 9, 0);
       }
-      int q = 0;
+    }
+  }
+  if (short_tail) {
+    const long long k = n_whole;
+    __builtin_amdgcn_s_waitcnt(0x0f70 | LPW);
+    __builtin_amdgcn_s_barrier();
+    issue(2 * k + 3);
+    issue(2 * k + 4);
+    const unsigned sb0 = smem_base + (unsigned)((2 * k) % kWideHalves) * kStageBytes;
+    const unsigned sb1 = smem_base + (unsigned)((2 * k + 1) % kWideHalves) * kStageBytes;
+    const long long valid = n_elems - (my_first + k) * KW;
+#pragma unroll 1
+    for (int st = 0; st < STEPS; ++st) {
+      const int vec = st * 2 + half;
+      const bool dead = (long long)vec * 8 >= valid;
+      v4u frag[8];
+      read_step(frag, sb0, sb1, st);
 #pragma unroll
-      for (int bj = R0; bj < 8; ++bj, ++q)
-        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[R0]),
-                                                         __builtin_bit_cast(bf16x8, frag[bj]), acc[q], 0, 0, 0);
-#pragma unroll
-      for (int bj = R1; bj < 8; ++bj, ++q)
-        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, frag[R1]),
-                                                         __builtin_bit_cast(bf16x8, frag[bj]), acc[q], 0, 0, 0);
+      for (int b = R0; b < 8; ++b)
+        if (dead) frag[b] = v4u{0u, 0u, 0u, 0u};
+      multiply(frag);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);
