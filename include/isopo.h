@@ -340,13 +340,15 @@ isopo_status isopo_rescale(const float* fisher_sq, const float* grad_sq, int64_t
 
 /* Eigendecomposition of the layers' Gram matrices (interacting listing: D, U = eigh(ntk)), so that a
  * sweep over regularisers costs one decomposition.  `batch` independent problems laid out back to back
- * (the projections of a block), one workgroup each, cyclic Jacobi in fp64.
+ * (the projections of a block), one workgroup each, in fp64: cyclic Jacobi in LDS up to 94 sequences,
+ * Householder tridiagonalisation and implicit QL in the workspace from 95.
  *   K     device fp32 [batch, n_seq, n_seq], symmetric (the mean of K and K^T is decomposed)
  *   D     device fp64 [batch, n_seq], ascending
  *   U     device fp64 [batch, n_seq, n_seq] row-major, eigenvectors as columns: K = U diag(D) U^T
- *   info  optional device int32 [batch]: 0 converged, 1 not converged within the sweep limit
- *   workspace  device, isopo_ntk_eigh_workspace(n_seq, batch) bytes, 256-byte aligned (used when the
- *              work matrices do not fit LDS) */
+ *   info  optional device int32 [batch]: 0 converged, 1 not converged within the iteration limit (40 Jacobi
+ *         sweeps, 60 QL steps per eigenvalue; a K with NaN or infinite entries ends there)
+ *   workspace  device, isopo_ntk_eigh_workspace(n_seq, batch) bytes, 256-byte aligned (the work matrices
+ *              of problems with 95 sequences and more) */
 size_t isopo_ntk_eigh_workspace(int32_t n_seq, int32_t batch);
 isopo_status isopo_ntk_eigh(const float* K, int32_t n_seq, int32_t batch, double* D, double* U, int32_t* info,
                             void* workspace, size_t ws_bytes, void* stream);

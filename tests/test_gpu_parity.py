@@ -457,6 +457,10 @@ WEIGHTED_CASES = [
     (200, 136, [3000, 1400, 1, 4200, 333, 4100]),
     (1024, 768, [31, 32, 33, 0, 64, 65, 1, 2, 500, 95, 97]),
     (768, 512, [5] * 70 + [0, 0, 129] + [1] * 40),
+    # the library's limit of 1024 sequences, most of them one or two tokens long, some empty: a boundary in nearly
+    # every token block; and 300 sequences on a layer that takes the token split
+    (512, 256, [int(x) for x in np.random.default_rng(1).integers(0, 6, 1024)]),
+    (256, 256, [int(x) for x in np.random.default_rng(2).integers(0, 90, 300)]),
 ]
 
 

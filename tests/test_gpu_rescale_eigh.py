@@ -74,10 +74,11 @@ def test_rescaled_layer_update(gpu_device, dtype):
     assert_dW_close(dW.cpu().numpy(), dW_ref, tol, "rescaled dW", mag)
 
 
-@pytest.mark.parametrize("m", [1, 2, 3, 4, 16, 31, 32, 64, 65, 94, 95, 128, 200, 256])
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 16, 31, 32, 64, 65, 94, 95, 96, 128, 135, 200, 256, 511, 1024])
 def test_eigh_sizes(gpu_device, m):
-    """Every storage regime (LDS with 256 or 1024 threads, global scratch), odd
-    sizes (one idle index in the pairing) and the degenerate m = 1."""
+    """Both routes (Jacobi in LDS with 256 or 1024 threads up to 94 sequences, tridiagonalisation
+    and implicit QL in global scratch from 95), odd sizes (one idle index in the Jacobi pairing),
+    the degenerate m = 1 and the library's limit of 1024 sequences."""
     rng = np.random.default_rng(1000 + m)
     K = _random_gram(rng, m)
     A = rng.standard_normal(m).astype(np.float32)
@@ -205,6 +206,45 @@ def test_trailing_mean_regulariser_on_the_factorisation_route(gpu_device, m):
         isopo.transform_ema(torch.from_numpy(K0).to(gpu_device), Ad, "interacting", 0.5, ema, 1.0)     # decay < 1
     with pytest.raises(isopo.IsopoError):
         isopo.transform_ema(torch.from_numpy(K0).to(gpu_device), Ad, "interacting", -1.0, ema, 0.9)
+
+
+@pytest.mark.parametrize("kind", ["rank_deficient", "diagonal", "tridiagonal", "zero", "clustered", "scaled"])
+def test_eigh_large_route_on_special_matrices(gpu_device, kind):
+    """The tridiagonal route on matrices that exercise its special paths: a Gram matrix of rank 40 (eighty
+    eigenvalues at rounding level), a diagonal and a tridiagonal matrix (nothing to reduce: every reflector is
+    skipped), the zero matrix, a cluster of nearly equal eigenvalues, and entries of order 1e12 and 1e-12 (the
+    power-of-two scaling)."""
+    rng = np.random.default_rng(77)
+    m = 120
+    if kind == "rank_deficient":
+        J = rng.standard_normal((m, 40))
+        K = J @ J.T
+    elif kind == "diagonal":
+        K = np.diag(rng.uniform(0.5, 3.0, m))
+    elif kind == "tridiagonal":
+        K = np.diag(rng.uniform(2.0, 3.0, m)) + np.diag(rng.uniform(-1, 1, m - 1), 1)
+        K = K + np.triu(K, 1).T
+    elif kind == "zero":
+        K = np.zeros((m, m))
+    elif kind == "clustered":
+        Q, _ = np.linalg.qr(rng.standard_normal((m, m)))
+        K = (Q * (1.0 + 1e-9 * rng.standard_normal(m))) @ Q.T
+    else:
+        J = rng.standard_normal((m, 300))
+        K = J @ J.T
+    for scale in ((1e12, 1e-12) if kind == "scaled" else (1.0,)):
+        K32 = (scale * K).astype(np.float32)
+        D, U, info = isopo.ntk_eigh(torch.from_numpy(K32).to(gpu_device))
+        torch.cuda.synchronize()
+        assert info.item() == 0
+        Dh, Uh = D.cpu().numpy(), U.cpu().numpy()
+        K64 = 0.5 * (K32.astype(np.float64) + K32.astype(np.float64).T)
+        D_ref, _ = orc.ntk_eigh(K64)
+        size = max(np.abs(D_ref).max(), 1e-300)
+        assert np.all(np.diff(Dh) >= 0)
+        np.testing.assert_allclose(Dh, D_ref, atol=1e-12 * size, rtol=0)
+        np.testing.assert_allclose(Uh.T @ Uh, np.eye(m), atol=1e-12)
+        np.testing.assert_allclose(Uh @ np.diag(Dh) @ Uh.T, K64, atol=1e-12 * size)
 
 
 def test_eigh_semidefinite_and_bad_arguments(gpu_device):
