@@ -206,31 +206,33 @@ __global__ __launch_bounds__(THREADS) void tridiag_eigh_kernel(const float* __re
   for (int el = tid; el < n * n; el += THREADS) A[el] *= down;
   __syncthreads();
 
-  // ---- tridiagonalisation ----
+  // ---- tridiagonalisation: three barriers per column ----
   for (int k = 0; k + 2 < n; ++k) {
     // trailing block: indices k+1 .. n-1; row k holds the column to reduce (the matrix is symmetric)
-    const double* rowk = A + (size_t)k * n;
-    const double x0 = rowk[k + 1];                            // read by everyone before row k is overwritten below
-    if (tid == 0) d[k] = rowk[k];
-    double sig = 0.0;
-    for (int j = k + 2 + tid; j < n; j += THREADS) { const double x = rowk[j]; sig += x * x; }
-    sig = block_sum<THREADS>(sig, red);
-    if (sig == 0.0) {                                         // column already reduced (uniform branch)
-      if (tid == 0) { e[k] = x0; tau[k] = 0.0; }
-      __syncthreads();
-      continue;
-    }
-    const double nrm = sqrt(x0 * x0 + sig);
-    const double alpha = x0 > 0.0 ? -nrm : nrm;
-    const double v0 = x0 - alpha;
-    const double tk = 2.0 / (v0 * v0 + sig);
-    if (tid == 0) { e[k] = alpha; tau[k] = tk; }
-    for (int j = k + 1 + tid; j < n; j += THREADS) {
-      const double vj = j == k + 1 ? v0 : rowk[j];
-      v[j] = vj;
-      A[(size_t)k * n + j] = vj;                              // kept for the accumulation of Q
+    if (wave == 0) {                                          // the reflector, by one wave
+      double* rowk = A + (size_t)k * n;
+      double sig = 0.0;
+      for (int j = k + 2 + lane; j < n; j += 64) { const double x = rowk[j]; sig += x * x; }
+      sig = wave_sum(sig);
+      const double x0 = rowk[k + 1];
+      if (lane == 0) d[k] = rowk[k];
+      if (sig == 0.0) {                                       // column already reduced
+        if (lane == 0) { e[k] = x0; tau[k] = 0.0; }
+      } else {
+        const double nrm = sqrt(x0 * x0 + sig);
+        const double alpha = x0 > 0.0 ? -nrm : nrm;
+        const double v0 = x0 - alpha;
+        if (lane == 0) { e[k] = alpha; tau[k] = 2.0 / (v0 * v0 + sig); }
+        for (int j = k + 1 + lane; j < n; j += 64) {
+          const double vj = j == k + 1 ? v0 : rowk[j];
+          v[j] = vj;
+          rowk[j] = vj;                                       // kept for the accumulation of Q
+        }
+      }
     }
     __syncthreads();
+    const double tk = tau[k];
+    if (tk == 0.0) continue;                                  // uniform
     // p = tau A22 v: a wave takes four rows at a time (four independent streams of loads), lanes along the row
     for (int i0 = k + 1 + wave; i0 < n; i0 += 4 * WAVES) {
       double acc[4] = {0.0, 0.0, 0.0, 0.0};
@@ -249,25 +251,22 @@ __global__ __launch_bounds__(THREADS) void tridiag_eigh_kernel(const float* __re
       }
     }
     __syncthreads();
+    // every wave forms p.v by itself (the same sum in the same order: the same bits), then
+    // A22 -= v w^T + w v^T with w = p - (tau/2)(p.v) v formed where it is used; the two products are added
+    // before they are subtracted, so (i, j) and (j, i) get the same bits
     double pv = 0.0;
-    for (int j = k + 1 + tid; j < n; j += THREADS) pv += w[j] * v[j];
-    pv = block_sum<THREADS>(pv, red);
-    const double kk = 0.5 * tk * pv;
-    __syncthreads();
-    for (int j = k + 1 + tid; j < n; j += THREADS) w[j] -= kk * v[j];
-    __syncthreads();
-    // A22 -= v w^T + w v^T; the two products are added before they are subtracted, so (i, j) and (j, i)
-    // get the same bits
+    for (int j = k + 1 + lane; j < n; j += 64) pv += w[j] * v[j];
+    const double kk = 0.5 * tk * wave_sum(pv);
     for (int i0 = k + 1 + wave; i0 < n; i0 += 4 * WAVES) {
       double* row[4];
       double vi[4], wi[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int i = i0 + q * WAVES < n ? i0 + q * WAVES : n - 1;
-        row[q] = A + (size_t)i * n; vi[q] = v[i]; wi[q] = w[i];
+        row[q] = A + (size_t)i * n; vi[q] = v[i]; wi[q] = __dsub_rn(w[i], __dmul_rn(kk, v[i]));
       }
       for (int j = k + 1 + lane; j < n; j += 64) {
-        const double vj = v[j], wj = w[j];
+        const double vj = v[j], wj = __dsub_rn(w[j], __dmul_rn(kk, vj));
         double a[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) a[q] = row[q][j];
@@ -288,34 +287,46 @@ __global__ __launch_bounds__(THREADS) void tridiag_eigh_kernel(const float* __re
   __syncthreads();
 
   // ---- Zt = Q^T = H_{n-3} ... H_0, accumulated from the last reflector: Zt <- Zt H_k ----
-  for (int k = n - 3; k >= 0; --k) {
-    const double tk = tau[k];
-    if (tk == 0.0) continue;                                   // uniform
-    for (int j = k + 1 + tid; j < n; j += THREADS) v[j] = A[(size_t)k * n + j];
+  // One barrier per reflector: v_k sits in one of two LDS buffers (v, w) while the next one is fetched into the other.
+  {
+    int kq = n - 3;
+    while (kq >= 0 && tau[kq] == 0.0) --kq;                   // uniform
+    if (kq >= 0)
+      for (int j = kq + 1 + tid; j < n; j += THREADS) v[j] = A[(size_t)kq * n + j];
     __syncthreads();
-    for (int i0 = k + 1 + wave; i0 < n; i0 += 4 * WAVES) {
-      double acc[4] = {0.0, 0.0, 0.0, 0.0};
-      double* row[4];
+    for (int par = 0; kq >= 0; par ^= 1) {
+      const int k = kq;
+      const double tk = tau[k];
+      const double* vk = par ? w : v;
+      double* vnext = par ? v : w;
+      kq = k - 1;
+      while (kq >= 0 && tau[kq] == 0.0) --kq;                 // the next reflector that does anything (uniform)
+      if (kq >= 0)
+        for (int j = kq + 1 + tid; j < n; j += THREADS) vnext[j] = A[(size_t)kq * n + j];
+      for (int i0 = k + 1 + wave; i0 < n; i0 += 4 * WAVES) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        double* row[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) row[q] = Zt + (size_t)(i0 + q * WAVES < n ? i0 + q * WAVES : n - 1) * n;
-      for (int j = k + 1 + lane; j < n; j += 64) {
-        const double vj = v[j];
+        for (int q = 0; q < 4; ++q) row[q] = Zt + (size_t)(i0 + q * WAVES < n ? i0 + q * WAVES : n - 1) * n;
+        for (int j = k + 1 + lane; j < n; j += 64) {
+          const double vj = vk[j];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q] += row[q][j] * vj;
+          for (int q = 0; q < 4; ++q) acc[q] += row[q][j] * vj;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = tk * wave_sum(acc[q]);
+        for (int j = k + 1 + lane; j < n; j += 64) {
+          const double vj = vk[j];
+          double a[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) a[q] = row[q][j];
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (i0 + q * WAVES < n) row[q][j] = a[q] - acc[q] * vj;
+        }
       }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[q] = tk * wave_sum(acc[q]);
-      for (int j = k + 1 + lane; j < n; j += 64) {
-        const double vj = v[j];
-        double a[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) a[q] = row[q][j];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (i0 + q * WAVES < n) row[q][j] = a[q] - acc[q] * vj;
-      }
+      __syncthreads();
     }
-    __syncthreads();
   }
 
   // ---- implicit QL with Wilkinson's shift ----

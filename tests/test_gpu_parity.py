@@ -108,6 +108,35 @@ TILE_ORDER_CASES = [
 ]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("path", ["materialised", "ghost"])
+def test_layer_without_tokens(gpu_device, dtype, path):
+    """The empty input: every sequence has length zero (X and Delta have no rows, their device pointers may be
+    null).  K = 0 and dW = beta dW exactly; with an absolute regulariser both variants have coefficients
+    (A / lambda, A / sqrt(lambda)); with the relative one reg = 0: the Fisher variant gives c = 0, the interacting
+    one reports the failing pivot.  One shape whose bf16 stash is kept in tile order, one that is row-major only."""
+    for d_in, d_out in ((256, 512), (72, 200)):
+        prob = wl.custom_layer(d_in, d_out, [0, 0, 0, 0, 0], dtype=dtype, seed=3)
+        for variant in ("interacting", "fisher"):
+            out, ref = _check_step(prob, gpu_device, path, variant, 0.5, isopo.REG_ABSOLUTE)
+            assert not out["K"].any() and not out["dW"].any()
+            assert np.abs(ref["c"]).min() > 0.1
+        layer, A = to_device(prob, gpu_device)
+        out = isopo.layer_step(layer, A, "fisher", 0.5, isopo.REG_REL_TRACE, path)
+        assert int(out["info"].item()) == 0 and not out["c"].any() and not out["dW"].any()
+        out = isopo.layer_step(layer, A, "interacting", 0.5, isopo.REG_REL_TRACE, path)
+        assert int(out["info"].item()) == 1 and bool(torch.isnan(out["c"]).all())
+        # the contractions from X and Delta alone: beta dW, bit for bit
+        dW0 = torch.randn((d_out, d_in), device=gpu_device)
+        for c in (None, torch.ones(prob.n_seq, device=gpu_device)):
+            dW = dW0.clone()
+            isopo.weighted_grad(layer, c, None, 0.5, dW)
+            assert torch.equal(dW, 0.5 * dW0)
+            dW = torch.full_like(dW0, float("nan"))
+            isopo.weighted_grad(layer, c, None, 0.0, dW)
+            assert not dW.any()
+
+
 @pytest.mark.parametrize("case", TILE_ORDER_CASES, ids=[c[0] for c in TILE_ORDER_CASES])
 def test_stash_in_tile_order(gpu_device, case):
     """A bf16 layer whose dimensions are multiples of 256 keeps its stash in the matrix cores' own order.
