@@ -519,7 +519,7 @@ def main() -> int:
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "ms_per_step_median_hip_events": medians.get("reinforce"), "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
                       "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
-        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true,true> (per-sequence gradients -> stash in tile order, persistent launch)",
+        "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true,true,false> (per-sequence gradients -> stash in tile order, persistent launch)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA, "avg_launch_ms": avg_launch_s * 1e3,
                      "whole_step_frac": total_flops / t_step / PEAK_BF16_MFMA,

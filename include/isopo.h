@@ -277,7 +277,7 @@ isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c,
  *     F_i^2 = sum_j (g0_j . G_i a0_j)^2 / sum_j (||g0_j|| ||a0_j||)^2,   c_i = A_i / sqrt(F_i^2 + reg).
  * Evaluated in ghost form, G_i a0_j = sum_{t in i} delta_t (x_t . a0_j) (eq. (one)): no per-sequence
  * gradient is formed, the cost is 2 N n_samples (d_in + d_out) flop, and c is known before any
- * contraction, so the whole update is one weighted contraction (isopo_scale_rows + isopo_weighted_grad).
+ * contraction, so the whole update is one weighted contraction (isopo_weighted_grad with c and no stash).
  *   sample_idx_dev  device int32 [n_samples], token row indices in [0, n_tokens) (the caller draws
  *                   them, e.g. randperm(N)[:n_samples]; an index outside the range is clamped
  *                   into it); 1 <= n_samples <= ISOPO_MAX_SAMPLES

@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 
     if constexpr (MF16) {
       // ---- stash in tile order, and the sum over all tokens: the 16x16x32 MFMA, which draws less power per flop than the 32x32x16 one
-      // (a loop of either on random operands in registers sustains 1.97 against 1.70 PFLOP/s under the
+      // (a loop of either on random operands in registers sustains 2.04 against 1.81 PFLOP/s under the
       // board's power cap).  A token block is one K = 32 step: 8 + 8 fragments (16 features x 32 tokens
       // each), FM16 x FN16 MFMAs row by row.  Behind row i go the next block's B fragment i (into the other
       // of two register sets) and, once the row is done with it, the next block's A fragment i (in place),
