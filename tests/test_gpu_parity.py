@@ -613,6 +613,7 @@ def test_hip_graph_replays_match_eager(gpu_device):
     info = torch.zeros(1, dtype=torch.int32, device=gpu_device)
     dW = torch.empty((prob.d_out, prob.d_in), dtype=torch.float32, device=gpu_device)
     dWf = torch.empty_like(dW)
+    dWw = torch.empty_like(dW)
     idx = torch.arange(0, 16 * 40, 40, dtype=torch.int32, device=gpu_device)
     fws = isopo.alloc_workspace(isopo.load().isopo_fisher_samples_workspace(layer.ref(), 16), gpu_device)
     scratch = torch.empty_like(layer.X)
@@ -624,10 +625,11 @@ def test_hip_graph_replays_match_eager(gpu_device):
         isopo.weighted_grad(layer, c, ws, 0.0, dW)
         isopo.fisher_samples(layer, idx, A, 1e-2, isopo.REG_REL_TRACE, cf, f2, fws)
         isopo.weighted_grad_prescaled(layer, cf, scratch, 0.0, dWf)
+        isopo.weighted_grad(layer, cf, None, 0.0, dWw)          # the weighted contraction from X and Delta
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (K, Kg, c, dW, cf, dWf)]
+        return [t.clone() for t in (K, Kg, c, dW, cf, dWf, dWw)]
 
     run()                                   # warm-up outside the capture (kernel attributes are set once)
     eager = snapshot()
@@ -637,13 +639,13 @@ def test_hip_graph_replays_match_eager(gpu_device):
     A0 = A.clone()
     for rep in range(3):
         A.copy_(A0 * (1.0 + rep))           # the graph reads the buffers' current contents
-        for t in (K, Kg, c, dW, cf, dWf):
+        for t in (K, Kg, c, dW, cf, dWf, dWw):
             t.fill_(float("nan"))
         graph.replay()
         got = snapshot()
         run()                               # eager work between replays, same inputs
         want = snapshot()
-        for name, g, w in zip(("K", "K ghost", "c", "dW", "c samples", "dW samples"), got, want):
+        for name, g, w in zip(("K", "K ghost", "c", "dW", "c samples", "dW samples", "dW samples"), got, want):
             if name == "K ghost":           # fp64 atomics: order varies, one fp32 rounding at most
                 assert torch.allclose(g, w, rtol=1e-6, atol=0), f"replay {rep}: {name}"
             elif name == "dW samples":      # may use the token split's fp32 atomics

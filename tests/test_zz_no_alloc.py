@@ -73,6 +73,31 @@ def test_two_calls_in_a_row_match_the_workspace_entry_point(gpu_device):
     assert torch.equal(c, c_ws)
 
 
+def test_replays_from_a_hip_graph(gpu_device):
+    """The callers this entry point is for: captured once, replayed on the buffers' current contents, with
+    eager calls of the workspace entry point in between (they do not touch the library's array)."""
+    rng = np.random.default_rng(778)
+    m, batch = 200, 2
+    K, A, Kd, Ad = _problem(rng, m, batch, gpu_device)
+    c = torch.empty_like(Ad)
+    info = torch.zeros(batch, dtype=torch.int32, device=gpu_device)
+    isopo.transform_noalloc(Kd, Ad, "interacting", 1e-2, isopo.REG_REL_TRACE, c, info)     # resolves the array's address
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        isopo.transform_noalloc(Kd, Ad, "interacting", 1e-2, isopo.REG_REL_TRACE, c, info,
+                                stream=torch.cuda.current_stream())
+    A0 = Ad.clone()
+    for rep in range(3):
+        Ad.copy_(A0 * (1.0 + rep))
+        c.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        want, winfo = isopo.transform(Kd, Ad, "interacting", 1e-2, isopo.REG_REL_TRACE)
+        torch.cuda.synchronize()
+        assert torch.equal(c, want) and info.cpu().tolist() == winfo.cpu().tolist() == [0, 0], rep
+
+
 def test_limit_and_bad_arguments(gpu_device):
     lib = isopo.load()
     dev = gpu_device
