@@ -187,6 +187,44 @@ def ghost_case(dev) -> dict:
             "what": "isopo_layer_gram(path = GHOST): fill, token -> sequence map, ghost_gram_tiled_kernel, finish"}
 
 
+def eigh_case(dev) -> dict:
+    """The eigendecomposition route against the Cholesky transform it competes with: one Gram matrix of B
+    sequences (a spread spectrum, as Gram matrices of gradients have), D, U = eigh(K) once, then the sweep of three
+    regularisers from it; beside it three Cholesky transforms.  Both routes at every B on the same matrix."""
+    import numpy as np
+    import torch
+    from paper_2512_23353_amd import isopo
+    stream = torch.cuda.current_stream()
+    lambdas = [1e-4, 1e-3, 1e-2]
+    out = {"what": "isopo_ntk_eigh + isopo_transform_eigh(3 lambdas) against 3 x isopo_transform(INTERACTING); ms, "
+                   "median of 5 after one warm-up", "sizes": {}}
+    for m in (32, 64, 94, 96, 128, 200, 256, 512):
+        rng = np.random.default_rng(m)
+        J = rng.standard_normal((m, 4 * m)) * np.logspace(0, -2, 4 * m)[None, :]
+        K = torch.from_numpy((J @ J.T).astype(np.float32)).to(dev)
+        A = torch.from_numpy(rng.standard_normal(m).astype(np.float32)).to(dev)
+        ws = isopo.alloc_workspace(isopo.load().isopo_ntk_eigh_workspace(m, 1), dev)
+        tws = isopo.alloc_workspace(max(isopo.transform_workspace(m, 1), 256), dev)
+
+        def med(fn):
+            ms = []
+            for _ in range(6):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                fn()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            return float(np.median(ms[1:]))
+        D, U, info = isopo.ntk_eigh(K, workspace=ws)
+        t_eigh = med(lambda: isopo.ntk_eigh(K, workspace=ws))
+        t_sweep = med(lambda: isopo.transform_eigh(D, U, A, lambdas, isopo.REG_REL_TRACE))
+        t_chol = med(lambda: [isopo.transform(K, A, "interacting", lam, isopo.REG_REL_TRACE, workspace=tws) for lam in lambdas])
+        out["sizes"][str(m)] = {"eigh_ms": t_eigh, "sweep_of_3_from_eigh_ms": t_sweep, "three_cholesky_transforms_ms": t_chol,
+                                "route": "jacobi" if m <= 94 else "tridiagonal + QL", "info": int(info.item())}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,6 +242,9 @@ def main() -> int:
     ap.add_argument("--ghost-case", action="store_true",
                     help="only time isopo_layer_gram on the ghost path for a short microbatch on the stress layer "
                          "(5120 -> 27648, 8 sequences of 1024 tokens) and print its rate, then exit")
+    ap.add_argument("--eigh-case", action="store_true",
+                    help="only time the eigendecomposition route (decomposition, sweep of three regularisers) against "
+                         "three Cholesky transforms for 32 to 512 sequences, then exit")
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="config3", choices=["config2", "config3", "config4", "config5"])
@@ -230,6 +271,9 @@ def main() -> int:
     torch.cuda.set_device(dev)
     if args.mfma_ceiling:
         print(json.dumps(mfma_ceiling(dev, args.board_probe)))
+        return 0
+    if args.eigh_case:
+        print(json.dumps(eigh_case(dev)))
         return 0
     if args.ghost_case:
         print(json.dumps(ghost_case(dev)))
