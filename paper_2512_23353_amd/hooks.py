@@ -49,7 +49,7 @@ def _hip_layer_step(X, Delta, seq_offsets, A, cfg) -> torch.Tensor:
         n_s = min(cfg["n_samples"], layer.n_tokens)
         idx = torch.randperm(layer.n_tokens, generator=cfg["generator"], device="cpu")[:n_s]
         c, _ = isopo.fisher_samples(layer, idx.to(torch.int32).to(X.device), A, cfg["lam"], reg_mode)
-        return isopo.weighted_grad_prescaled(layer, c)
+        return isopo.weighted_grad(layer, c)            # one weighted contraction from X and Delta, no stash
     if variant == "rescaled":
         K, ws = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_FAST)
         f2, g2 = isopo.gram_norms(K)
