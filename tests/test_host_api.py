@@ -225,6 +225,54 @@ def test_contraction_plan_token_split():
     assert e.value.status == 3
 
 
+def test_contraction_plan_invariants_on_random_shapes():
+    """Four hundred random layers (widths multiples of 8 from 8 to 9000, 1 to 300 sequences of 0 to 5000
+    tokens) through the launch plan in both modes: whatever the plan, it must describe a launch that
+    covers every (item, tile) pair once and every token once."""
+    rng = np.random.default_rng(2024)
+    for case in range(400):
+        d_in = int(rng.choice([8, 64, 72, 256, 384, 1024, 1536, 4096, 8960])) if case % 3 else 8 * int(rng.integers(1, 1125))
+        d_out = int(rng.choice([8, 136, 256, 512, 1536, 4096, 14336])) if case % 2 else 8 * int(rng.integers(1, 1125))
+        n_seq = int(rng.integers(1, 300)) if case % 5 else int(rng.integers(1, 9))
+        lengths = rng.integers(0, int(rng.choice([3, 40, 600, 5000])), n_seq)
+        if case % 7 == 0:
+            lengths[:] = 0
+        n_tok = int(lengths.sum())
+        lay = _host_layer(list(lengths), d_in, d_out)
+        for per_seq in (True, False):
+            pl = isopo.contraction_plan(lay.ref(), per_seq)
+            what = (case, d_in, d_out, n_seq, n_tok, per_seq, pl)
+            T = pl["tile"]
+            assert T in (128, 256), what
+            tiles = -(-d_in // T) * -(-d_out // T)
+            assert pl["tiles"] == tiles and pl["workgroups_per_cu"] in (1, 2), what
+            st, w, ct, whole = pl["xcd_start"], pl["n_chunks"], pl["chunk_tokens"], pl["whole_tiles"]
+            assert w >= 1 and 0 <= whole <= tiles, what
+            if per_seq:
+                assert w == 1 and whole == 0, what
+                items = n_seq
+            else:
+                items = w
+                if w > 1:
+                    assert ct % 32 == 0 and (w - 1) * ct < n_tok <= w * ct, what
+                else:
+                    assert ct >= n_tok, what
+            if whole:
+                # whole tiles in rounds of 256, the rest cut into chunks that fit one more round
+                assert not per_seq and whole % 256 == 0 and whole < tiles and w > 1 and (tiles - whole) * w <= 256, what
+                assert st == [0] * 9, what
+                continue
+            if st[8] > 0:
+                assert st[0] == 0 and st[8] == items * tiles and all(a <= b for a, b in zip(st, st[1:])), what
+                assert pl["workgroups"] == 8 * max(b - a for a, b in zip(st, st[1:])), what
+            else:
+                assert st == [0] * 9, what
+                if per_seq or w > 1:
+                    assert tiles % 8 == 0 and pl["workgroups"] == items * tiles, what      # eighths of every item's tiles
+                else:
+                    assert pl["workgroups"] == tiles, what
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The layer step has no cross-GPU part: bench.py --gpus N > 1 exits with a
     message instead of printing a number (and touches no GPU on the way)."""
