@@ -444,6 +444,7 @@ def main() -> int:
             return 0
     total_flops = float(sum(sum(f.values()) for f in fl)) * sweeps
     reinforce_flops = float(sum(f["seq_grads"] for f in fl)) * sweeps
+    stash_bytes_per_step = float(sum(2.0 * n_seq * l.d_in * l.d_out for l in layers)) * sweeps
 
     variants, sweep_report = {}, None
     if not args.no_variants:
@@ -562,6 +563,10 @@ def main() -> int:
         "algorithmic_flops_per_step": total_flops,
         "reinforce": {"ms_per_step": t_reinforce * 1e3, "ms_per_step_median_hip_events": medians.get("reinforce"), "tflops": reinforce_flops / t_reinforce / 1e12,
                       "overhead_of_isopo": t_step / t_reinforce - 1.0,
+                      "overhead_floor_of_routes_through_K": stash_bytes_per_step * 3.0 / PEAK_HBM / t_reinforce,
+                      "overhead_floor_what": "any route that forms K from a materialised stash writes the stash once and reads "
+                                             "it twice (Gram pass, weighted sum): 3 x 2 B D bytes per projection at the 8 TB/s "
+                                             "HBM peak, over this run's REINFORCE time; nothing else counted",
                       "what": "this library's own unweighted dW = Delta^T X over the same projections (advantages folded into Delta, as plain REINFORCE backprop does)", **context},
         "roofline": {"bound": "mfma", "kernel": "seq_grad_stream_kernel<256,256,4,1,true,true,true,false> (per-sequence gradients -> stash in tile order, persistent launch)",
                      "achieved": achieved / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s",
