@@ -349,13 +349,27 @@ def main() -> int:
                                       for g in groups), dev)
     f2b = [torch.empty((npj, n_seq), dtype=torch.float32, device=dev) for _ in blocks]
 
-    def token_sample_step():
+    def token_sample_step_group_calls():
         for _ in range(sweeps):
             for g in groups:
                 b, j0 = g[0] // npj, g[0] % npj
                 isopo.fisher_samples_group([layers[i] for i in g], sample_idx, A, args.lam, isopo.REG_REL_TRACE,
                                            cb[b][j0:j0 + len(g)], f2b[b][j0:j0 + len(g)], fs_ws, stream=stream)
                 for i in g:
+                    isopo.weighted_grad(layers[i], cs[i], None, 0.0, dWs[i], stream=stream)
+
+    # A block's groups in one launch (isopo_fisher_samples_block): their workgroups fill the chip one group after
+    # the other, and only the last group's last round leaves compute units idle.
+    block_groups = [[[layers[i] for i in g] for g in groups if g[0] // npj == b] for b in range(len(blocks))]
+    fsb_ws = isopo.alloc_workspace(isopo.load().isopo_fisher_samples_block_workspace(layers[0].ref(), npj, args.n_samples), dev)
+
+    def token_sample_step():
+        for _ in range(sweeps):
+            for b in range(len(blocks)):
+                isopo.fisher_samples_block(block_groups[b], sample_idx, A, args.lam, isopo.REG_REL_TRACE, cb[b], f2b[b],
+                                           fsb_ws, stream=stream)
+                for j in range(npj):
+                    i = b * npj + j
                     isopo.weighted_grad(layers[i], cs[i], None, 0.0, dWs[i], stream=stream)
 
     # The same with the Fisher passes of a block's groups on streams of their own (default priority): they are
@@ -452,6 +466,7 @@ def main() -> int:
         other = "fisher" if args.variant == "interacting" else "interacting"
         t_other = timed(make_step(other, args.lam), reps, 2, "other")
         t_ts = timed(token_sample_step, reps, 2, "token_samples")
+        t_tsg = timed(token_sample_step_group_calls, reps, 2, "token_samples_groups")
         t_ts2 = timed(token_sample_step_side_streams, reps, 2, "token_samples_side")
 
         def variant_step(reg_mode=isopo.REG_REL_TRACE, beta=0.0, recompute=False):
@@ -486,9 +501,11 @@ def main() -> int:
             f"{args.variant}_beta_1": entry(t_beta, "beta1", what="the headline route accumulating into dW (mod.grad += of the listings): one more read of dW per projection"),
             f"{args.variant}_without_stash": entry(t_rec, "recompute", what="isopo_layer_gram with no stash kept, then isopo_weighted_grad(c, stash = NULL): the weighted contraction from X and Delta again (the route for a workspace too small to keep the stash)"),
             "fisher_from_token_samples": entry(t_ts, "token_samples", n_samples=args.n_samples,
-                                               what="isopo_fisher_samples_group per set of projections sharing an input, then isopo_weighted_grad(c, stash = NULL) per projection: ONE weighted contraction, no stash, no scaled copy"),
+                                               what="isopo_fisher_samples_block once per block (the sets of projections sharing an input in one launch), then isopo_weighted_grad(c, stash = NULL) per projection: ONE weighted contraction, no stash, no scaled copy"),
+            "fisher_from_token_samples_group_calls": entry(t_tsg, "token_samples_groups", n_samples=args.n_samples,
+                                                           what="the same with one isopo_fisher_samples_group call per set of projections sharing an input"),
             "fisher_from_token_samples_side_streams": entry(t_ts2, "token_samples_side", n_samples=args.n_samples,
-                                                            what="the same calls; the block's Fisher passes run on streams of their own, side by side, before the contractions on the launch stream"),
+                                                            what="the group calls on streams of their own, side by side, before the contractions on the launch stream"),
         }
         if n_layers > 1:
             # The sweep with K and the stash formed once per layer: six transforms (both variants x three

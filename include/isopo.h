@@ -309,6 +309,25 @@ isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_
                                         isopo_reg_mode reg_mode, float* ema_state, float ema_decay, float* c,
                                         float* fisher_sq, void* workspace, size_t ws_bytes, void* stream);
 
+/* The same for several such groups of one microbatch in one launch - the projections of a transformer
+ * block, {q, k, v}, {o}, {gate, up}, {down}: the non-interacting update is formed "in each layer
+ * individually", but nothing in one layer's estimate waits for another's, and launched together the groups'
+ * workgroups fill the chip one after the other, so that only the last group's last round leaves compute
+ * units idle (a quarter of a launch per group otherwise, at 7e4 tokens).
+ *   layers        the groups' layers back to back (group 0's first); within a group as for
+ *                 isopo_fisher_samples_group (one X, one d_in); all layers share dtype, n_tokens, n_seq
+ *                 and the offsets
+ *   group_sizes   host [n_groups], each 1..ISOPO_MAX_GROUP; 1 <= n_groups <= ISOPO_MAX_GROUPS
+ *   c, fisher_sq  device [sum of group_sizes, n_seq], in the order of `layers`
+ *   ema_state     device float[sum of group_sizes][2] (EMA_TRACE)
+ *   workspace     isopo_fisher_samples_block_workspace(layers[0], sum of group_sizes, n_samples) bytes */
+#define ISOPO_MAX_GROUPS 8
+size_t isopo_fisher_samples_block_workspace(const isopo_layer* layer, int32_t n_layers_total, int32_t n_samples);
+isopo_status isopo_fisher_samples_block(const isopo_layer* const* layers, const int32_t* group_sizes, int32_t n_groups,
+                                        const int32_t* sample_idx_dev, int32_t n_samples, const float* A, float lambda,
+                                        isopo_reg_mode reg_mode, float* ema_state, float ema_decay, float* c,
+                                        float* fisher_sq, void* workspace, size_t ws_bytes, void* stream);
+
 /* Norms the re-scalings are built from, read off the Gram matrix: fisher_sq[i] = (1/m) sum_j K_ij^2
  * (eq. F-norm-basic with the batch's reduced gradients as samples) and grad_sq[i] = K_ii = ||G_i||^2.
  * Device pointers, either output may be NULL. */

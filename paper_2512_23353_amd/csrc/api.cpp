@@ -398,6 +398,7 @@ isopo_status isopo_transform_ema(const float* K, const float* A, int32_t n_seq, 
 }
 
 static_assert(kFisherMaxGroup == ISOPO_MAX_GROUP, "group size of the kernel and of the header");
+static_assert(kFisherMaxGroups == ISOPO_MAX_GROUPS, "number of groups of the kernel and of the header");
 
 size_t isopo_fisher_samples_group_workspace(const isopo_layer* layer, int32_t n_layers, int32_t n_samples) {
   if (!layer || n_samples < 1 || n_samples > ISOPO_MAX_SAMPLES || layer->n_seq <= 0 || layer->n_tokens < 0 ||
@@ -410,24 +411,40 @@ size_t isopo_fisher_samples_workspace(const isopo_layer* layer, int32_t n_sample
   return isopo_fisher_samples_group_workspace(layer, 1, n_samples);
 }
 
-isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_t n_layers,
+size_t isopo_fisher_samples_block_workspace(const isopo_layer* layer, int32_t n_layers_total, int32_t n_samples) {
+  if (!layer || n_samples < 1 || n_samples > ISOPO_MAX_SAMPLES || layer->n_seq <= 0 || layer->n_tokens < 0 ||
+      n_layers_total < 1 || n_layers_total > ISOPO_MAX_GROUP * ISOPO_MAX_GROUPS)
+    return 0;
+  return fisher_samples_workspace((int)layer->n_tokens, layer->n_seq, n_samples, n_layers_total);
+}
+
+isopo_status isopo_fisher_samples_block(const isopo_layer* const* layers, const int32_t* group_sizes, int32_t n_groups,
                                         const int32_t* sample_idx_dev, int32_t n_samples, const float* A, float lambda,
                                         isopo_reg_mode reg_mode, float* ema_state, float ema_decay, float* c,
                                         float* fisher_sq, void* workspace, size_t ws_bytes, void* stream) {
-  if (!layers || n_layers < 1) return ISOPO_ERR_INVALID_ARG;
-  if (n_layers > ISOPO_MAX_GROUP) return ISOPO_ERR_UNSUPPORTED;
-  for (int l = 0; l < n_layers; ++l) {
+  if (!layers || !group_sizes || n_groups < 1) return ISOPO_ERR_INVALID_ARG;
+  if (n_groups > ISOPO_MAX_GROUPS) return ISOPO_ERR_UNSUPPORTED;
+  int total = 0;
+  for (int g = 0; g < n_groups; ++g) {
+    if (group_sizes[g] < 1) return ISOPO_ERR_INVALID_ARG;
+    if (group_sizes[g] > ISOPO_MAX_GROUP) return ISOPO_ERR_UNSUPPORTED;
+    total += group_sizes[g];
+  }
+  for (int l = 0; l < total; ++l) {
     isopo_status st = check_layer(layers[l], true);
     if (st != ISOPO_OK) return st;
   }
   const isopo_layer* first = layers[0];
-  for (int l = 1; l < n_layers; ++l) {          // one input, one ragged layout for the whole group
+  for (int l = 1; l < total; ++l) {             // one microbatch: one dtype, one ragged layout
     const isopo_layer* o = layers[l];
-    if (o->X != first->X || o->dtype != first->dtype || o->n_tokens != first->n_tokens || o->d_in != first->d_in ||
-        o->n_seq != first->n_seq || o->seq_offsets_dev != first->seq_offsets_dev ||
+    if (o->dtype != first->dtype || o->n_tokens != first->n_tokens || o->n_seq != first->n_seq ||
+        o->seq_offsets_dev != first->seq_offsets_dev ||
         std::memcmp(o->seq_offsets_host, first->seq_offsets_host, sizeof(int32_t) * (size_t)(first->n_seq + 1)) != 0)
       return ISOPO_ERR_INVALID_ARG;
   }
+  for (int g = 0, l0 = 0; g < n_groups; l0 += group_sizes[g], ++g)      // one input per group
+    for (int l = l0 + 1; l < l0 + group_sizes[g]; ++l)
+      if (layers[l]->X != layers[l0]->X || layers[l]->d_in != layers[l0]->d_in) return ISOPO_ERR_INVALID_ARG;
   if (!sample_idx_dev || !A || !c || !workspace || !(lambda >= 0.f)) return ISOPO_ERR_INVALID_ARG;
   if (n_samples < 1) return ISOPO_ERR_INVALID_ARG;
   if (n_samples > ISOPO_MAX_SAMPLES) return ISOPO_ERR_UNSUPPORTED;
@@ -436,18 +453,36 @@ isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_
     return ISOPO_ERR_INVALID_ARG;
   if (first->n_tokens == 0) return ISOPO_ERR_INVALID_ARG;     // nothing to sample from
   if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return ISOPO_ERR_INVALID_ARG;
-  if (ws_bytes < isopo_fisher_samples_group_workspace(first, n_layers, n_samples)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < isopo_fisher_samples_block_workspace(first, total, n_samples)) return ISOPO_ERR_WORKSPACE_TOO_SMALL;
   FisherSamplesArgs f;
-  f.X = first->X; f.off = first->seq_offsets_dev; f.sample_idx = sample_idx_dev; f.n_layers = n_layers;
-  for (int l = 0; l < kFisherMaxGroup; ++l) {
-    f.Delta[l] = l < n_layers ? layers[l]->Delta : nullptr;
-    f.d_out[l] = l < n_layers ? layers[l]->d_out : 0;
+  f.n_groups = n_groups;
+  for (int g = 0, l0 = 0; g < kFisherMaxGroups; ++g) {
+    FisherGroup& q = f.group[g];
+    const int n = g < n_groups ? group_sizes[g] : 0;
+    q.X = n ? layers[l0]->X : nullptr;
+    q.d_in = n ? layers[l0]->d_in : 0;
+    q.n_layers = n;
+    for (int l = 0; l < kFisherMaxGroup; ++l) {
+      q.Delta[l] = l < n ? layers[l0 + l]->Delta : nullptr;
+      q.d_out[l] = l < n ? layers[l0 + l]->d_out : 0;
+    }
+    l0 += n;
   }
-  f.n_tokens = (int)first->n_tokens; f.d_in = first->d_in; f.n_seq = first->n_seq;
+  f.off = first->seq_offsets_dev; f.sample_idx = sample_idx_dev;
+  f.n_tokens = (int)first->n_tokens; f.n_seq = first->n_seq;
   f.n_samples = n_samples; f.bf16 = first->dtype == ISOPO_BF16; f.A = A; f.lambda = lambda;
   f.reg_mode = (int)reg_mode; f.ema_state = ema_state; f.ema_decay = ema_decay; f.c = c; f.fisher_sq = fisher_sq;
   f.workspace = workspace;
   return launch_fisher_samples(f, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_fisher_samples_group(const isopo_layer* const* layers, int32_t n_layers,
+                                        const int32_t* sample_idx_dev, int32_t n_samples, const float* A, float lambda,
+                                        isopo_reg_mode reg_mode, float* ema_state, float ema_decay, float* c,
+                                        float* fisher_sq, void* workspace, size_t ws_bytes, void* stream) {
+  if (n_layers < 1) return ISOPO_ERR_INVALID_ARG;
+  return isopo_fisher_samples_block(layers, &n_layers, 1, sample_idx_dev, n_samples, A, lambda, reg_mode, ema_state,
+                                    ema_decay, c, fisher_sq, workspace, ws_bytes, stream);
 }
 
 isopo_status isopo_fisher_samples(const isopo_layer* layer, const int32_t* sample_idx_dev, int32_t n_samples,

@@ -41,17 +41,21 @@ __device__ __forceinline__ void load_lds16_nt(const void* gptr, unsigned lds_add
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(lds_addr), "v"(gptr) : "memory");
 }
 
-struct Params {
+struct GroupParams {
   const void* X;
   const void* Delta[kFisherMaxGroup];
   int d_out[kFisherMaxGroup];
-  int n_layers;
+  int d_in, n_layers;
+  double* S64;           // [n_layers][n_seq][32*NBS] segment sums s_ij of this group's layers
+  double* den;           // [n_layers][n_samples] ||g0_j||^2 ||a0_j||^2
+};
+struct Params {
+  GroupParams group[kFisherMaxGroups];     // blockIdx.y picks the group
   const int32_t* off;
   const int32_t* idx;
-  int n_tokens, d_in, n_seq, n_samples;
+  int n_tokens, n_seq, n_samples;
   int32_t* tok_seq;      // [n_tokens]
-  double* S64;           // [n_layers][n_seq][32*NBS] segment sums s_ij
-  double* den;           // [n_layers][n_samples] ||g0_j||^2 ||a0_j||^2
+  double* S64;           // all groups' segment sums, back to back
 };
 
 // The sequence of every token (binary search in the offsets) and zeros in the segment-sum accumulator.
@@ -164,6 +168,7 @@ __global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
   const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int t0 = blockIdx.x * kTok;
+  const GroupParams& g = p.group[blockIdx.y];
 
   // Q = X A0^T once for the group, then per layer P = Delta G0^T, H = P o Q and the segment sums
   f32x16 Q[NBS];
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
   for (int b = 0; b < NBS; ++b)
 #pragma unroll
     for (int v = 0; v < 16; ++v) Q[b][v] = 0.f;
-  product_pass<NBS, BF16>(p.X, p.d_in, p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, Q);
+  product_pass<NBS, BF16>(g.X, g.d_in, p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, Q);
 
   // lane holds sample column (lane & 31) of each block and token rows acc_row(v, lane) of the wave's 32 tokens
   const int tw = t0 + wave * 32;
@@ -179,16 +184,16 @@ __global__ __launch_bounds__(256) void fisher_samples_kernel(Params p) {
   const int t_last = min(tw + 31, p.n_tokens - 1);
   const int r_first = live ? p.tok_seq[tw] : 0, r_last = live ? p.tok_seq[t_last] : 0;
   const int ncol = 32 * NBS;
-  for (int l = 0; l < p.n_layers; ++l) {
+  for (int l = 0; l < g.n_layers; ++l) {
     f32x16 P[NBS];
 #pragma unroll
     for (int b = 0; b < NBS; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) P[b][v] = 0.f;
-    product_pass<NBS, BF16>(p.Delta[l], p.d_out[l], p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, P);
+    product_pass<NBS, BF16>(g.Delta[l], g.d_out[l], p.idx, p.n_samples, p.n_tokens, t0, smem_base, lane, wave, P);
     if (!live) continue;
-    double* S64 = p.S64 + (size_t)l * p.n_seq * ncol;
-    double* den = p.den + (size_t)l * p.n_samples;
+    double* S64 = g.S64 + (size_t)l * p.n_seq * ncol;
+    double* den = g.den + (size_t)l * p.n_samples;
 #pragma unroll
     for (int b = 0; b < NBS; ++b) {
       const int j = b * 32 + (lane & 31);
@@ -289,14 +294,14 @@ __global__ __launch_bounds__(256) void fisher_samples_finish_kernel(const double
 }
 
 template <int NBS, bool BF16>
-hipError_t launch_main(const Params& p, hipStream_t s) {
+hipError_t launch_main(const Params& p, int n_groups, hipStream_t s) {
   constexpr size_t smem = (size_t)kStages * (kTok + 32 * NBS) * kRowBytes;
   auto kern = fisher_samples_kernel<NBS, BF16>;
   // once per process (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL(kern, dim3((p.n_tokens + kTok - 1) / kTok), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(kern, dim3((p.n_tokens + kTok - 1) / kTok, n_groups), dim3(256), smem, s, p);
   return hipGetLastError();
 }
 
@@ -312,46 +317,64 @@ size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples, int n_la
 
 hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
   const int nbs = (a.n_samples + 31) / 32;
-  if (nbs < 1 || nbs > kMaxSampleBlocks || a.n_layers < 1 || a.n_layers > kFisherMaxGroup) return hipErrorInvalidValue;
+  if (nbs < 1 || nbs > kMaxSampleBlocks || a.n_groups < 1 || a.n_groups > kFisherMaxGroups) return hipErrorInvalidValue;
+  int n_layers = 0;
+  for (int g = 0; g < a.n_groups; ++g) {
+    if (a.group[g].n_layers < 1 || a.group[g].n_layers > kFisherMaxGroup) return hipErrorInvalidValue;
+    n_layers += a.group[g].n_layers;
+  }
   const int ncol = 32 * nbs;
+  // workspace: token -> sequence map, then per layer (all groups' layers back to back, in group order) the
+  // segment sums, the sample norms and the fp64 F^2
   char* ws = static_cast<char*>(a.workspace);
   Params p;
-  p.X = a.X; p.off = a.off; p.idx = a.sample_idx; p.n_layers = a.n_layers;
-  for (int l = 0; l < kFisherMaxGroup; ++l) {
-    p.Delta[l] = l < a.n_layers ? a.Delta[l] : nullptr;
-    p.d_out[l] = l < a.n_layers ? a.d_out[l] : 0;
-  }
-  p.n_tokens = a.n_tokens; p.d_in = a.d_in; p.n_seq = a.n_seq; p.n_samples = a.n_samples;
+  p.off = a.off; p.idx = a.sample_idx;
+  p.n_tokens = a.n_tokens; p.n_seq = a.n_seq; p.n_samples = a.n_samples;
   p.tok_seq = reinterpret_cast<int32_t*>(ws);
   ws += align256((size_t)a.n_tokens * 4);
   p.S64 = reinterpret_cast<double*>(ws);
-  ws += align256((size_t)a.n_layers * a.n_seq * ncol * 8);
-  p.den = reinterpret_cast<double*>(ws);
-  ws += align256((size_t)a.n_layers * a.n_samples * 8);
+  ws += align256((size_t)n_layers * a.n_seq * ncol * 8);
+  double* den = reinterpret_cast<double*>(ws);
+  ws += align256((size_t)n_layers * a.n_samples * 8);
   double* f2_tmp = reinterpret_cast<double*>(ws);
+  int first = 0;
+  for (int g = 0; g < kFisherMaxGroups; ++g) {
+    GroupParams& q = p.group[g];
+    const bool live = g < a.n_groups;
+    q.X = live ? a.group[g].X : nullptr;
+    q.d_in = live ? a.group[g].d_in : 0;
+    q.n_layers = live ? a.group[g].n_layers : 0;
+    for (int l = 0; l < kFisherMaxGroup; ++l) {
+      q.Delta[l] = live && l < q.n_layers ? a.group[g].Delta[l] : nullptr;
+      q.d_out[l] = live && l < q.n_layers ? a.group[g].d_out[l] : 0;
+    }
+    q.S64 = p.S64 + (size_t)first * a.n_seq * ncol;
+    q.den = den + (size_t)first * a.n_samples;
+    first += q.n_layers;
+  }
 
-  const long long ns = (long long)a.n_layers * a.n_seq * ncol;
+  const long long ns = (long long)n_layers * a.n_seq * ncol;
   if (a.n_tokens > 0) {
     const long long items = ns > a.n_tokens ? ns : (long long)a.n_tokens;
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, p, ns);
     hipError_t e;
     switch (nbs * 2 + (a.bf16 ? 1 : 0)) {
-      case 2: e = launch_main<1, false>(p, s); break;
-      case 3: e = launch_main<1, true>(p, s); break;
-      case 4: e = launch_main<2, false>(p, s); break;
-      case 5: e = launch_main<2, true>(p, s); break;
-      case 6: e = launch_main<3, false>(p, s); break;
-      case 7: e = launch_main<3, true>(p, s); break;
-      case 8: e = launch_main<4, false>(p, s); break;
-      default: e = launch_main<4, true>(p, s); break;
+      case 2: e = launch_main<1, false>(p, a.n_groups, s); break;
+      case 3: e = launch_main<1, true>(p, a.n_groups, s); break;
+      case 4: e = launch_main<2, false>(p, a.n_groups, s); break;
+      case 5: e = launch_main<2, true>(p, a.n_groups, s); break;
+      case 6: e = launch_main<3, false>(p, a.n_groups, s); break;
+      case 7: e = launch_main<3, true>(p, a.n_groups, s); break;
+      case 8: e = launch_main<4, false>(p, a.n_groups, s); break;
+      default: e = launch_main<4, true>(p, a.n_groups, s); break;
     }
     if (e != hipSuccess) return e;
   } else {
     hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, s, p.S64, ns);
-    const long long nd = (long long)a.n_layers * a.n_samples;
-    hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, p.den, nd);
+    const long long nd = (long long)n_layers * a.n_samples;
+    hipLaunchKernelGGL(zero_f64_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, s, den, nd);
   }
-  hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(a.n_layers), dim3(256), 0, s, p.S64, p.den, a.n_seq,
+  hipLaunchKernelGGL(fisher_samples_finish_kernel, dim3(n_layers), dim3(256), 0, s, p.S64, den, a.n_seq,
                      a.n_samples, ncol, a.A, a.lambda, a.reg_mode, a.ema_state, a.ema_decay, a.c, a.fisher_sq, f2_tmp);
   return hipGetLastError();
 }

@@ -153,23 +153,30 @@ hipError_t launch_scale_rows(const void* src, bool bf16, long long n_tokens, int
 
 // Token-position-sample Fisher norms and the coefficients c_i = A_i / sqrt(F_i^2 + reg), for a group of
 // layers that share their input X (q/k/v, gate/up): X is streamed once for the whole group.
+// Several such groups of one microbatch (a transformer block's {q,k,v}, {o}, {gate,up}, {down}) go in one
+// launch, so that only the last group's last round of workgroups leaves compute units idle.
 constexpr int kFisherMaxGroup = 4;
-struct FisherSamplesArgs {
+constexpr int kFisherMaxGroups = 8;
+struct FisherGroup {
   const void* X;
   const void* Delta[kFisherMaxGroup];
   int d_out[kFisherMaxGroup];
-  int n_layers;
+  int d_in, n_layers;
+};
+struct FisherSamplesArgs {
+  FisherGroup group[kFisherMaxGroups];
+  int n_groups;
   const int32_t* off;
   const int32_t* sample_idx;   // device [n_samples], token rows
-  int n_tokens, d_in, n_seq, n_samples;
+  int n_tokens, n_seq, n_samples;
   bool bf16;
   const float* A;
   float lambda;
   int reg_mode;                // 0 absolute, 1 times this batch's mean F^2, 2 times its trailing mean
-  float* ema_state;            // [n_layers][2]: trailing mean, number of minibatches seen (reg_mode 2)
+  float* ema_state;            // [layers of all groups][2]: trailing mean, number of minibatches seen (reg_mode 2)
   float ema_decay;
-  float* c;                    // [n_layers][n_seq]
-  float* fisher_sq;            // optional [n_layers][n_seq]
+  float* c;                    // [layers of all groups][n_seq], group after group
+  float* fisher_sq;            // optional, same shape
   void* workspace;
 };
 size_t fisher_samples_workspace(int n_tokens, int n_seq, int n_samples, int n_layers);

@@ -36,6 +36,7 @@ EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_
            "isopo_transform", "isopo_transform_noalloc", "isopo_weighted_grad", "isopo_scale_rows",
            "isopo_fisher_samples_workspace", "isopo_fisher_samples",
            "isopo_fisher_samples_group_workspace", "isopo_fisher_samples_group",
+           "isopo_fisher_samples_block_workspace", "isopo_fisher_samples_block",
            "isopo_weighted_grad_scratch", "isopo_weighted_grad_prescaled",
            "isopo_gram_norms", "isopo_rescale", "isopo_ntk_eigh_workspace", "isopo_ntk_eigh",
            "isopo_transform_eigh", "isopo_probe_mfma_loop", "isopo_status_string", "isopo_version")
@@ -117,6 +118,11 @@ def load() -> ctypes.CDLL:
     lib.isopo_fisher_samples_group.argtypes = [ctypes.POINTER(lp), i32, vp, i32, vp, f32, ctypes.c_int, vp, f32, vp, vp,
                                                vp, sz, vp]
     lib.isopo_fisher_samples_group.restype = ctypes.c_int
+    lib.isopo_fisher_samples_block_workspace.argtypes = [lp, i32, i32]
+    lib.isopo_fisher_samples_block_workspace.restype = sz
+    lib.isopo_fisher_samples_block.argtypes = [ctypes.POINTER(lp), ctypes.POINTER(i32), i32, vp, i32, vp, f32, ctypes.c_int,
+                                               vp, f32, vp, vp, vp, sz, vp]
+    lib.isopo_fisher_samples_block.restype = ctypes.c_int
     lib.isopo_weighted_grad_scratch.argtypes = [lp]
     lib.isopo_weighted_grad_scratch.restype = sz
     lib.isopo_weighted_grad_prescaled.argtypes = [lp, vp, f32, vp, vp, sz, vp]
@@ -499,6 +505,32 @@ def fisher_samples_group(layers, sample_idx: torch.Tensor, A: torch.Tensor, lam:
                                              _ptr(ema_state), float(ema_decay), c.data_ptr(), fisher_sq.data_ptr(),
                                              workspace.data_ptr(), workspace.numel(), _stream(stream)),
            "isopo_fisher_samples_group")
+    return c, fisher_sq
+
+
+def fisher_samples_block(groups, sample_idx: torch.Tensor, A: torch.Tensor, lam: float = 0.0,
+                         reg_mode: int = REG_ABSOLUTE, c: Optional[torch.Tensor] = None,
+                         fisher_sq: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
+                         ema_state: Optional[torch.Tensor] = None, ema_decay: float = 0.9):
+    """fisher_samples_group for several groups of one microbatch in one launch (`groups`: a list of lists of
+    layers, each inner list sharing its X).  Returns (c, F^2), both [total layers, n_seq] in the groups' order."""
+    layers = [l for g in groups for l in g]
+    n, first = len(layers), layers[0]
+    n_s = int(sample_idx.numel())
+    if sample_idx.dtype != torch.int32 or not sample_idx.is_contiguous():
+        raise ValueError("sample_idx must be a contiguous int32 tensor")
+    if c is None:
+        c = torch.empty((n, first.n_seq), dtype=torch.float32, device=first.device)
+    if fisher_sq is None:
+        fisher_sq = torch.empty((n, first.n_seq), dtype=torch.float32, device=first.device)
+    if workspace is None:
+        workspace = alloc_workspace(load().isopo_fisher_samples_block_workspace(first.ref(), n, n_s), first.device)
+    arr = (ctypes.POINTER(_Layer) * n)(*[ctypes.pointer(l.c) for l in layers])
+    sizes = (ctypes.c_int32 * len(groups))(*[len(g) for g in groups])
+    _check(load().isopo_fisher_samples_block(arr, sizes, len(groups), sample_idx.data_ptr(), n_s, A.data_ptr(), float(lam),
+                                             int(reg_mode), _ptr(ema_state), float(ema_decay), c.data_ptr(),
+                                             fisher_sq.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "isopo_fisher_samples_block")
     return c, fisher_sq
 
 

@@ -155,6 +155,61 @@ def test_group_sharing_the_input(gpu_device, dtype):
         isopo.fisher_samples_group(layers + [layers[0]], idx_d, A)      # more than ISOPO_MAX_GROUP
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_block_of_groups_in_one_launch(gpu_device, dtype):
+    """A transformer block's groups ({three layers on one input}, {one}, {two}, {one}, with different
+    input widths) in one launch: every layer against the oracle and against the group-by-group calls;
+    token counts that do and do not fill the last workgroup; the trailing-mean state kept per layer."""
+    rng = np.random.default_rng(95)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    for lengths in ([130, 70, 1, 0, 200, 45], [128] * 9, [3, 0, 0, 2]):
+        seq_offsets = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+        n_tok, m = int(seq_offsets[-1]), len(lengths)
+        g = torch.Generator().manual_seed(62)
+        shapes = [(256, [320, 64, 136]), (320, [256]), (72, [512, 8]), (512, [72])]
+        groups, Xs, Ds = [], [], []
+        first = None
+        for d_in, d_outs in shapes:
+            X = torch.randn(n_tok, d_in, generator=g).to(tdt).to(gpu_device)
+            grp = []
+            for d in d_outs:
+                D = (torch.randn(n_tok, d, generator=g) * 1e-2).to(tdt).to(gpu_device)
+                lay = isopo.Layer(X, D, seq_offsets) if first is None else isopo.Layer(X, D, seq_offsets, seq_offsets_dev=first.off_dev)
+                first = first or lay
+                grp.append(lay)
+                Xs.append(X)
+                Ds.append(D)
+            groups.append(grp)
+        A_h = rng.standard_normal(m).astype(np.float32)
+        A = torch.from_numpy(A_h).to(gpu_device)
+        idx = _draw_samples(rng, n_tok, min(24, n_tok))
+        idx_d = torch.from_numpy(idx).to(gpu_device)
+        c, f2 = isopo.fisher_samples_block(groups, idx_d, A, 1e-3, isopo.REG_REL_TRACE)
+        torch.cuda.synchronize()
+        l = 0
+        for grp in groups:
+            cg, fg = isopo.fisher_samples_group(grp, idx_d, A, 1e-3, isopo.REG_REL_TRACE)
+            torch.cuda.synchronize()
+            for k in range(len(grp)):
+                c_ref, f2_ref = orc.coeff_fisher_token_samples(wl.to_oracle(Xs[l]), wl.to_oracle(Ds[l]), seq_offsets, idx,
+                                                               A_h, 1e-3, isopo.REG_REL_TRACE)
+                what = f"lengths {lengths[:3]}.., layer {l}"
+                assert rel_err(f2[l].cpu().numpy(), f2_ref) <= TOL[dtype], what
+                assert_c_close(c[l].cpu().numpy(), c_ref, TOL[dtype], what)
+                assert torch.allclose(fg[k], f2[l], rtol=1e-5, atol=0) and torch.allclose(cg[k], c[l], rtol=1e-5, atol=0), what
+                l += 1
+        assert l == 7
+    # one trailing mean per layer, in the order of the layers
+    ema = torch.zeros((7, 2), dtype=torch.float32, device=gpu_device)
+    c1, f1 = isopo.fisher_samples_block(groups, idx_d, A, 0.5, isopo.REG_EMA_TRACE, ema_state=ema, ema_decay=0.9)
+    torch.cuda.synchronize()
+    assert torch.allclose(ema[:, 0], f1.mean(dim=1), rtol=1e-5) and bool((ema[:, 1] == 1).all())
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples_block([groups[0] + groups[1]], idx_d, A)          # a group on two inputs
+    with pytest.raises(isopo.IsopoError):
+        isopo.fisher_samples_block([[l_] for l_ in (groups[0] * 3)], idx_d, A)  # more than ISOPO_MAX_GROUPS groups
+
+
 def test_trailing_mean_regulariser(gpu_device):
     """reg = factor * E[mean F^2] with the trailing mean kept on the device over
     three minibatches of different scale."""
