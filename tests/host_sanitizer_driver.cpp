@@ -64,8 +64,23 @@ static void replay(const char* name, const std::vector<int32_t>& lengths, int d_
     EXPECT(pl.whole_tiles >= 0 && pl.whole_tiles <= pl.tiles && pl.whole_tiles % 256 == 0);
     EXPECT(pl.workgroups >= 0);
   }
-  std::printf("%s scratch=%zu fisher_ws=%zu fisher_group_ws=%zu\n", name, isopo_weighted_grad_scratch(&l),
-              isopo_fisher_samples_workspace(&l, 32), isopo_fisher_samples_group_workspace(&l, 3, 64));
+  std::printf("%s scratch=%zu fisher_ws=%zu fisher_group_ws=%zu fisher_block_ws=%zu\n", name, isopo_weighted_grad_scratch(&l),
+              isopo_fisher_samples_workspace(&l, 32), isopo_fisher_samples_group_workspace(&l, 3, 64),
+              isopo_fisher_samples_block_workspace(&l, 7, 32));
+  // the block call validates on the host before it looks at any device pointer: no device offsets -> rejected
+  {
+    const isopo_layer* ls[3] = {&l, &l, &l};
+    const int32_t sizes[2] = {2, 1};
+    const int32_t too_big[1] = {ISOPO_MAX_GROUP + 1};
+    EXPECT(isopo_fisher_samples_block(ls, sizes, 2, nullptr, 8, nullptr, 0.f, ISOPO_REG_ABSOLUTE, nullptr, 0.9f, nullptr, nullptr,
+                                      nullptr, 0, nullptr) != ISOPO_OK);
+    EXPECT(isopo_fisher_samples_block(ls, too_big, 1, nullptr, 8, nullptr, 0.f, ISOPO_REG_ABSOLUTE, nullptr, 0.9f, nullptr,
+                                      nullptr, nullptr, 0, nullptr) == ISOPO_ERR_UNSUPPORTED);
+    EXPECT(isopo_fisher_samples_block(ls, sizes, ISOPO_MAX_GROUPS + 1, nullptr, 8, nullptr, 0.f, ISOPO_REG_ABSOLUTE, nullptr, 0.9f,
+                                      nullptr, nullptr, nullptr, 0, nullptr) == ISOPO_ERR_UNSUPPORTED);
+    EXPECT(isopo_fisher_samples_block(ls, nullptr, 1, nullptr, 8, nullptr, 0.f, ISOPO_REG_ABSOLUTE, nullptr, 0.9f, nullptr, nullptr,
+                                      nullptr, 0, nullptr) == ISOPO_ERR_INVALID_ARG);
+  }
 }
 
 int main() {
