@@ -491,20 +491,25 @@ def main() -> int:
         for dW in dWs:
             dW.zero_()          # beta = 1 accumulated into them
 
-        def entry(t, tag, **more):
+        # algorithmic flops of the token-sample route: the contraction and the two token-by-sample products
+        ts_flops = reinforce_flops + sweeps * 2.0 * n_tokens * args.n_samples * float(
+            sum(layers[g[0]].d_in + sum(layers[i].d_out for i in g) for g in groups))
+
+        def entry(t, tag, flops=None, **more):
+            rate = {} if flops is None else {"tflops": flops / t / 1e12, "pct_bf16_mfma_peak": 100.0 * flops / t / PEAK_BF16_MFMA}
             return {"ms_per_step": t * 1e3, "ms_per_step_median_hip_events": medians.get(tag),
-                    "overhead_over_reinforce": t / t_reinforce - 1.0, **more}
+                    "overhead_over_reinforce": t / t_reinforce - 1.0, **rate, **more}
         variants = {
-            f"{args.variant}_from_stash_gram": entry(t_step, "step"),
-            f"{other}_from_stash_gram": entry(t_other, "other"),
+            f"{args.variant}_from_stash_gram": entry(t_step, "step", total_flops),
+            f"{other}_from_stash_gram": entry(t_other, "other", total_flops),
             f"{args.variant}_absolute_lambda": entry(t_abs, "absolute", what="the headline route with reg = lambda as printed (numerically nil at these shapes: K_ii ~ 1e4..1e6)"),
             f"{args.variant}_beta_1": entry(t_beta, "beta1", what="the headline route accumulating into dW (mod.grad += of the listings): one more read of dW per projection"),
             f"{args.variant}_without_stash": entry(t_rec, "recompute", what="isopo_layer_gram with no stash kept, then isopo_weighted_grad(c, stash = NULL): the weighted contraction from X and Delta again (the route for a workspace too small to keep the stash)"),
-            "fisher_from_token_samples": entry(t_ts, "token_samples", n_samples=args.n_samples,
+            "fisher_from_token_samples": entry(t_ts, "token_samples", ts_flops, n_samples=args.n_samples,
                                                what="isopo_fisher_samples_block once per block (the sets of projections sharing an input in one launch), then isopo_weighted_grad(c, stash = NULL) per projection: ONE weighted contraction, no stash, no scaled copy"),
-            "fisher_from_token_samples_group_calls": entry(t_tsg, "token_samples_groups", n_samples=args.n_samples,
+            "fisher_from_token_samples_group_calls": entry(t_tsg, "token_samples_groups", ts_flops, n_samples=args.n_samples,
                                                            what="the same with one isopo_fisher_samples_group call per set of projections sharing an input"),
-            "fisher_from_token_samples_side_streams": entry(t_ts2, "token_samples_side", n_samples=args.n_samples,
+            "fisher_from_token_samples_side_streams": entry(t_ts2, "token_samples_side", ts_flops, n_samples=args.n_samples,
                                                             what="the group calls on streams of their own, side by side, before the contractions on the launch stream"),
         }
         if n_layers > 1:
