@@ -162,7 +162,9 @@ def test_block_of_groups_in_one_launch(gpu_device, dtype):
     token counts that do and do not fill the last workgroup; the trailing-mean state kept per layer."""
     rng = np.random.default_rng(95)
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
-    for lengths in ([130, 70, 1, 0, 200, 45], [128] * 9, [3, 0, 0, 2]):
+    # the first three microbatches are short enough for the launch to make every layer a group of its own; the
+    # last one (175 token tiles x 7 layers) keeps the groups
+    for lengths in ([130, 70, 1, 0, 200, 45], [128] * 9, [3, 0, 0, 2], [2800] * 8 + [13]):
         seq_offsets = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
         n_tok, m = int(seq_offsets[-1]), len(lengths)
         g = torch.Generator().manual_seed(62)
