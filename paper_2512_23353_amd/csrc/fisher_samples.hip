@@ -340,9 +340,10 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
   // A short microbatch does not fill the chip with one workgroup per (128 tokens, group), and a lone workgroup
   // is bound by the latency of its walk over the features, not by bandwidth: then every layer becomes a group
   // of its own (its input's product is formed once per layer instead of once per group, the walks are shorter
-  // and there are more of them: 0.18 -> 0.10 ms for a 1.5B-class block at 3200 tokens, no gain from 10^4 on).
+  // and there are more of them: 0.18 -> 0.10 ms for a 1.5B-class block at 3200 tokens, 0.21 -> 0.15 ms at 10^4,
+  // a loss of 4 - 10 % from 1.6 * 10^4 tokens on).
   const int token_tiles = (a.n_tokens + kTok - 1) / kTok;
-  const bool one_layer_per_group = n_layers > a.n_groups && n_layers <= kFisherMaxGroups && token_tiles * n_layers <= 512;
+  const bool one_layer_per_group = n_layers > a.n_groups && n_layers <= kFisherMaxGroups && token_tiles * n_layers <= 640;
   int n_launch_groups = a.n_groups;
   if (one_layer_per_group) {
     n_launch_groups = n_layers;
@@ -378,6 +379,20 @@ hipError_t launch_fisher_samples(const FisherSamplesArgs& a, hipStream_t s) {
       first += q.n_layers;
     }
   }
+
+  // Longest walk first: the workgroups of the launch's last group are the ones that run on a half-empty chip
+  // at the end, so that group should be the one with the fewest features to walk.
+  auto features = [](const GroupParams& q) {
+    long long f = q.d_in;
+    for (int l = 0; l < q.n_layers; ++l) f += q.d_out[l];
+    return f;
+  };
+  for (int i = 1; i < n_launch_groups; ++i)          // insertion sort, descending, stable
+    for (int j = i; j > 0 && features(p.group[j]) > features(p.group[j - 1]); --j) {
+      const GroupParams t = p.group[j];
+      p.group[j] = p.group[j - 1];
+      p.group[j - 1] = t;
+    }
 
   const long long ns = (long long)n_layers * a.n_seq * ncol;
   if (a.n_tokens > 0) {
