@@ -190,11 +190,12 @@ struct TransformArgs {
   float lambda;
   float* c;
   int32_t* info;
-  double* workspace;         // [batch][n_seq*n_seq] when n_seq > kTransformLdsMax, else unused
+  double* workspace;         // [batch][n_seq*n_seq + n_seq] when n_seq > kTransformLdsMax, else unused
   float* ema_state = nullptr;  // reg_mode 2: [batch][2] trailing mean of tr(K)/m, number of minibatches seen
   float ema_decay = 0.f;
 };
 constexpr int kTransformLdsMax = 128;
+constexpr int kTransformWidePanelMax = 512;   // larger problems factor panels of 16 columns instead of 32 (the panel has to fit in LDS)
 hipError_t launch_transform(const TransformArgs& a, hipStream_t s);
 
 // Generalised (p, q, r) re-scaling of the per-sequence coefficients.

@@ -14,10 +14,14 @@
 // non-interacting derivation compares reg_l with the typical ||.||_F^2).
 // The m x m problem is tiny next to the
 // contractions around it, so one workgroup per problem works in fp64: a
-// right-looking Cholesky factorisation in LDS (m <= 128) or in a caller-provided
-// global scratch (larger m), then two triangular solves.  The result is the
-// unique solution; the eigendecomposition the interacting listing uses reaches
-// the same vector.  A non-positive pivot is reported, never clamped.
+// right-looking Cholesky factorisation in panels and two triangular solves.  The
+// matrix lives in LDS (m <= 128) or in a caller-provided global scratch (larger
+// m); the panel being factored is in LDS, column-major, and each thread holds one
+// of its rows in registers (one barrier per column); A rides along as one more
+// row of the matrix, which makes the forward solve part of the factorisation, and
+// the backward solve runs panel by panel as well.  The result is the unique
+// solution; the eigendecomposition the interacting listing uses reaches the same
+// vector.  A non-positive pivot is reported, never clamped.
 #include "common.h"
 #include "kernels.h"
 
@@ -36,6 +40,183 @@ __device__ double block_sum(double x, double* red /* [kThreads/64] */) {
 #pragma unroll
   for (int w = 0; w < kThreads / 64; ++w) s += red[w];
   return s;
+}
+
+// A value every lane holds alike, moved to scalar registers (the column entries all rows are updated with:
+// thirty-one doubles next to a 32-double row would not fit the vector registers of a 1024-thread workgroup).
+__device__ __forceinline__ double uniform_value(double x) {
+  const int lo = __builtin_amdgcn_readfirstlane(__double2loint(x));
+  const int hi = __builtin_amdgcn_readfirstlane(__double2hiint(x));
+  return __hiloint2double(hi, lo);
+}
+
+// Panel rows in LDS: one padding element after every 32 rows of a column, so that the trailing update's
+// lanes, which read groups of four consecutive rows 32 bytes apart, spread over all banks.
+__device__ __forceinline__ int panel_pos(int lr) { return lr + (lr >> 5); }
+__host__ __device__ constexpr int panel_stride(int m) { return ((m + 1) + ((m + 1) >> 5) + 1 + 3) & ~3; }
+
+// (K + reg I) c = A: M [m + 1, m] fp64 in LDS or global memory (row m holds A, then y), the panel of NB columns
+// in LDS as PT[column][row - k0] with row stride RS.  kThreads threads; c is left in cs.
+//
+// Panel step: thread t holds the panel rows t and t + kThreads (R = 2: only a 1025-row panel has the second;
+// the launch gives smaller problems enough threads for R = 1) in registers.  Per column kk: every row's entry goes to LDS, one barrier, then each thread reads the pivot and
+// the entries (q, kk) of the rows q > kk (the same addresses for all lanes) and eliminates column kk from its
+// rows with the unscaled entries, row[q] -= row[kk] * (q, kk) / pivot; its own entry of L is row[kk] / sqrt(pivot).
+// The upper triangle of the diagonal block is carried along and never read.  The trailing matrix (rows up to
+// and including the row of A) then takes the rank-NB update in 4 x 4 register blocks whose factors come from
+// the panel in LDS.
+template <int kThreads, int NB, int R>
+__device__ bool cholesky_solve(const float* __restrict__ K, const float* __restrict__ A, int m, double reg,
+                               double* __restrict__ M, double* cs /* LDS [m] */, double* PT /* LDS */, int* fail_col) {
+  const int tid = threadIdx.x;
+  const int RS = panel_stride(m);
+  // the whole square, so that every later read is of a defined value; the upper triangle never enters a result
+  for (int e = tid; e < m * m; e += kThreads) {
+    const int r = e / m, q = e - r * m;
+    M[e] = (double)K[e] + (r == q ? reg : 0.0);
+  }
+  for (int i = tid; i < m; i += kThreads) M[(size_t)m * m + i] = (double)A[i];
+  __syncthreads();
+
+  for (int k0 = 0; k0 < m; k0 += NB) {
+    const int nbk = m - k0 < NB ? m - k0 : NB;
+    const int nrows = m + 1 - k0;                        // rows k0 .. m
+    // panel -> LDS (a wave reads NB-element pieces of rows)
+    for (int e = tid; e < nrows * NB; e += kThreads) {
+      const int lr = e / NB, kk = e % NB;
+      if (kk < nbk) PT[kk * RS + panel_pos(lr)] = M[(size_t)(k0 + lr) * m + k0 + kk];
+    }
+    __syncthreads();
+    // the thread's rows (R = 2 only where m + 1 > kThreads) in registers; waves without a row only keep the barriers
+    const bool wave_has_rows = (tid & ~(kWave - 1)) < nrows;
+    double row[R][NB];
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int lr = tid + i * kThreads;
+#pragma unroll
+      for (int q = 0; q < NB; ++q) row[i][q] = (lr < nrows && q < nbk) ? PT[q * RS + panel_pos(lr)] : 0.0;
+    }
+    bool failed = false;                                           // uniform
+#pragma unroll
+    for (int kk = 0; kk < NB; ++kk) {
+      if (kk >= nbk || failed) continue;                           // no break: the loop has to unroll for row[][] to stay in registers
+      // column kk as the columns before it left it: every row's entry goes to the column's own place in LDS
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        const int lr = tid + i * kThreads;
+        if (lr < nrows) PT[kk * RS + panel_pos(lr)] = row[i][kk];
+      }
+      __syncthreads();
+      const double d = uniform_value(PT[kk * RS + panel_pos(kk)]);
+      if (!(d > 0.0)) { *fail_col = k0 + kk; failed = true; continue; }      // every thread reads the same value
+      if (!wave_has_rows) continue;
+      const double rsq = 1.0 / sqrt(d), rd = rsq * rsq;
+      double f[R];
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        f[i] = row[i][kk] * rd;
+        row[i][kk] *= rsq;                                         // the entry of L; the pivot's own row: d / sqrt(d)
+      }
+      // eight columns at a time, so that only eight of the column's entries are held at once
+#pragma unroll
+      for (int q0 = kk + 1; q0 < NB; q0 += 8) {
+        double b[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (q0 + j < NB) b[j] = uniform_value(PT[kk * RS + panel_pos(q0 + j)]);   // entry (q, kk); for q >= nbk a row below the block: unused
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (q0 + j < NB) row[i][q0 + j] -= f[i] * b[j];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (failed) return false;
+    __syncthreads();                                               // the last column has been read
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int lr = tid + i * kThreads;
+#pragma unroll
+      for (int q = 0; q < NB; ++q)
+        if (lr < nrows && q < nbk) PT[q * RS + panel_pos(lr)] = row[i][q];
+    }
+    __syncthreads();
+    for (int e = tid; e < nrows * NB; e += kThreads) {
+      const int lr = e / NB, kk = e % NB;
+      if (kk < nbk) M[(size_t)(k0 + lr) * m + k0 + kk] = PT[kk * RS + panel_pos(lr)];
+    }
+    // trailing update: rows t0 .. m (the row of A included), columns t0 .. min(row, m - 1)
+    const int t0 = k0 + nbk;
+    const int nbr = (m + 1 - t0 + 3) >> 2, nbq = (m - t0 + 3) >> 2;
+    for (int e = tid; e < nbr * nbq; e += kThreads) {
+      const int br = e / nbq, bq = e - br * nbq;
+      if (bq > br) continue;
+      const int r0 = t0 + 4 * br, q0 = t0 + 4 * bq;
+      int lr[4], lq[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lr[i] = panel_pos((r0 + i <= m ? r0 + i : m) - k0);
+        lq[i] = panel_pos((q0 + i < m ? q0 + i : m - 1) - k0);
+      }
+      double acc[4][4] = {};
+      for (int kk = 0; kk < nbk; ++kk) {
+        double a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = PT[kk * RS + lr[i]]; b[i] = PT[kk * RS + lq[i]]; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int r = r0 + i, q = q0 + j;
+          if (r <= m && q < m && (q <= r)) M[(size_t)r * m + q] -= acc[i][j];
+        }
+    }
+    __syncthreads();
+  }
+
+  // backward: L^T c = y (y is row m of M), last panel first.  The sums over the rows below a panel are split
+  // over kThreads / NB row groups and met in LDS; wave 0 then solves the panel's triangle, lane = column.
+  constexpr int RG = kThreads / NB;
+  double* red = PT;                                       // [RG][NB + 1]
+  double* tri = PT + RG * (NB + 1);                       // [NB][NB + 1]: the panel's diagonal block of L
+  const int kk = tid % NB, rg = tid / NB;
+  for (int k0 = ((m - 1) / NB) * NB; k0 >= 0; k0 -= NB) {
+    const int nbk = m - k0 < NB ? m - k0 : NB;
+    const int t0 = k0 + nbk;
+    double acc = 0.0;
+    if (kk < nbk)
+      for (int r = t0 + rg; r < m; r += RG) acc += M[(size_t)r * m + k0 + kk] * cs[r];
+    red[rg * (NB + 1) + kk] = acc;
+    for (int e = tid; e < NB * NB; e += kThreads) {
+      const int r = e / NB, q = e % NB;
+      if (r < nbk && q <= r) tri[r * (NB + 1) + q] = M[(size_t)(k0 + r) * m + k0 + q];
+    }
+    __syncthreads();
+    if (tid < kWave) {
+      const int lane = tid;
+      double v = 0.0;
+      if (lane < nbk) {
+        double sum = 0.0;
+        for (int g = 0; g < RG; ++g) sum += red[g * (NB + 1) + lane];
+        v = M[(size_t)m * m + k0 + lane] - sum;
+      }
+      double cv = 0.0;
+      for (int j = nbk - 1; j >= 0; --j) {
+        const double cj = __shfl(v, j, kWave) / tri[j * (NB + 1) + j];
+        if (lane == j) cv = cj;
+        if (lane < j) v -= tri[j * (NB + 1) + lane] * cj;
+      }
+      if (lane < nbk) cs[k0 + lane] = cv;
+    }
+    __syncthreads();
+  }
+  return true;
 }
 
 template <int kThreads>
@@ -94,80 +275,48 @@ __global__ __launch_bounds__(kThreads) void transform_kernel(const float* __rest
     return;
   }
 
-  // M = K + reg I (lower triangle), y, in LDS or global scratch.
-  double* M = gws ? gws + (size_t)prob * ((size_t)m * m + m) : reinterpret_cast<double*>(smem);
-  double* y = M + (size_t)m * m;
-  for (int e = tid; e < m * m; e += kThreads) {
-    const int r = e / m, q = e % m;
-    if (q <= r) M[e] = (double)K[e] + (r == q ? reg : 0.0);
+  if (gws) {
+    if constexpr (kThreads == 1024) {
+      double* Mg = gws + (size_t)prob * ((size_t)m * m + m);
+      double* PT = reinterpret_cast<double*>(smem);
+      int fail_col = 0;
+      const bool ok = m <= kTransformWidePanelMax ? cholesky_solve<1024, 32, 1>(K, A, m, reg, Mg, f2s, PT, &fail_col)
+                                                  : cholesky_solve<1024, 16, 2>(K, A, m, reg, Mg, f2s, PT, &fail_col);
+      for (int i = tid; i < m; i += kThreads) c[i] = ok ? (float)f2s[i] : __builtin_nanf("");
+      if (info && tid == 0) info[prob] = ok ? 0 : fail_col + 1;
+    }
+    return;
   }
-  for (int i = tid; i < m; i += kThreads) y[i] = (double)A[i];
-  __syncthreads();
 
-  // Right-looking Cholesky in panels of kPanel columns: the panel is factored column by column (updates
-  // confined to the panel), then the trailing matrix takes one rank-kPanel update, so the large matrix is
-  // swept m/kPanel times instead of m times.
-  constexpr int kPanel = 8;
-  for (int k0 = 0; k0 < m; k0 += kPanel) {
-    const int nb = m - k0 < kPanel ? m - k0 : kPanel;
-    for (int kk = 0; kk < nb; ++kk) {
-      const int k = k0 + kk;
-      const double d = M[(size_t)k * m + k];
-      if (!(d > 0.0)) {                       // uniform: every thread reads the same value
-        for (int i = tid; i < m; i += kThreads) c[i] = __builtin_nanf("");
-        if (info && tid == 0) info[prob] = k + 1;
-        return;
-      }
-      const double inv = 1.0 / sqrt(d);
-      __syncthreads();                        // everyone has read the pivot
-      for (int r = k + tid; r < m; r += kThreads) M[(size_t)r * m + k] *= inv;   // column k of L (M[k][k] -> sqrt(d))
-      __syncthreads();
-      const int ncol = k0 + nb - 1 - k;       // panel columns right of k
-      const int nrow = m - k - 1;
-      for (int e = tid; e < nrow * ncol; e += kThreads) {
-        const int r = k + 1 + e / ncol, q = k + 1 + e % ncol;
-        if (q <= r) M[(size_t)r * m + q] -= M[(size_t)r * m + k] * M[(size_t)q * m + k];
-      }
-      __syncthreads();
-    }
-    const int t0 = k0 + nb, rem = m - t0;     // trailing lower triangle, rows/cols t0..m-1
-    for (int e = tid; e < rem * rem; e += kThreads) {
-      const int r = t0 + e / rem, q = t0 + e % rem;
-      if (q <= r) {
-        double s = 0.0;
-        for (int kk = 0; kk < nb; ++kk) s += M[(size_t)r * m + k0 + kk] * M[(size_t)q * m + k0 + kk];
-        M[(size_t)r * m + q] -= s;
-      }
-    }
-    __syncthreads();
-  }
-  // forward: L y = A
-  for (int k = 0; k < m; ++k) {
-    const double yk = y[k] / M[(size_t)k * m + k];
-    __syncthreads();
-    if (tid == 0) y[k] = yk;
-    for (int r = k + 1 + tid; r < m; r += kThreads) y[r] -= M[(size_t)r * m + k] * yk;
-    __syncthreads();
-  }
-  // backward: L^T c = y
-  for (int k = m - 1; k >= 0; --k) {
-    const double ck = y[k] / M[(size_t)k * m + k];
-    __syncthreads();
-    if (tid == 0) y[k] = ck;
-    for (int r = tid; r < k; r += kThreads) y[r] -= M[(size_t)k * m + r] * ck;
-    __syncthreads();
-  }
-  for (int i = tid; i < m; i += kThreads) c[i] = (float)y[i];
-  if (info && tid == 0) info[prob] = 0;
+  // the matrix in LDS as well, panels of 16 columns
+  double* Ml = reinterpret_cast<double*>(smem);
+  int fail_col = 0;
+  const bool ok = cholesky_solve<kThreads, 16, 1>(K, A, m, reg, Ml, f2s, Ml + (size_t)(m + 1) * m, &fail_col);
+  for (int i = tid; i < m; i += kThreads) c[i] = ok ? (float)f2s[i] : __builtin_nanf("");
+  if (info && tid == 0) info[prob] = ok ? 0 : fail_col + 1;
 }
 
 }  // namespace
+
+// Dynamic LDS of the INTERACTING transform: the panel (32 columns up to kTransformWidePanelMax sequences in
+// global scratch, else 16) or what the backward solve keeps there instead (at most 1024 / 16 + 16 rows of 17),
+// and up to kTransformLdsMax sequences the matrix with the row of A in front of it.
+constexpr size_t transform_lds_bytes(int m) {
+  const bool lds = m <= kTransformLdsMax;
+  const int nb = (!lds && m <= kTransformWidePanelMax) ? 32 : 16;
+  size_t panel = (size_t)nb * panel_stride(m);
+  const size_t backward = nb == 32 ? (size_t)(32 + 32) * 33 : (size_t)(64 + 16) * 17;
+  if (panel < backward) panel = backward;
+  return ((lds ? (size_t)(m + 1) * m : 0) + panel) * sizeof(double);
+}
 
 template <int THREADS>
 hipError_t launch_transform_t(const TransformArgs& a, size_t smem, double* gws, hipStream_t s) {
   auto kern = transform_kernel<THREADS>;
   // once per process and instantiation (static initialisation is thread-safe); a failure is returned by every call
-  constexpr int max_smem = (int)(((size_t)kTransformLdsMax * kTransformLdsMax + kTransformLdsMax) * sizeof(double));
+  constexpr int max_smem = (int)transform_lds_bytes(kTransformLdsMax) > (int)transform_lds_bytes(kTransformWidePanelMax)
+                               ? (int)transform_lds_bytes(kTransformLdsMax) : (int)transform_lds_bytes(kTransformWidePanelMax);
+  static_assert(transform_lds_bytes(ISOPO_MAX_SEQ_TRANSFORM) <= (size_t)max_smem && max_smem + 8704 <= 160 * 1024, "LDS budget");
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, max_smem);
   if (attr != hipSuccess) return attr;
@@ -178,8 +327,7 @@ hipError_t launch_transform_t(const TransformArgs& a, size_t smem, double* gws, 
 
 hipError_t launch_transform(const TransformArgs& a, hipStream_t s) {
   const bool lds = a.n_seq <= kTransformLdsMax;
-  size_t smem = 0;
-  if (a.variant == 1 && lds) smem = ((size_t)a.n_seq * a.n_seq + a.n_seq) * sizeof(double);
+  const size_t smem = a.variant == 1 ? transform_lds_bytes(a.n_seq) : 0;
   double* gws = (a.variant == 1 && !lds) ? a.workspace : nullptr;
   // the trailing update of column k has (m-k)^2/2 independent elements: more threads for larger problems
   if (a.n_seq <= 48) return launch_transform_t<256>(a, smem, gws, s);
