@@ -366,7 +366,7 @@ def _random_gram(rng, m, rank_extra=8, scale=1.0):
     return (J @ J.T).astype(np.float32)
 
 
-@pytest.mark.parametrize("m", [1, 2, 4, 7, 8, 9, 16, 31, 32, 48, 49, 64, 96, 97, 128, 129, 200, 256])
+@pytest.mark.parametrize("m", [1, 2, 4, 7, 8, 9, 15, 16, 17, 31, 32, 33, 48, 49, 64, 96, 97, 128, 129, 200, 256, 300, 512, 513, 1024])
 @pytest.mark.parametrize("variant", ["fisher", "interacting"])
 def test_transform_sizes(gpu_device, m, variant):
     rng = np.random.default_rng(100 + m)
@@ -409,6 +409,32 @@ def test_transform_reports_not_positive_definite(gpu_device):
     Kz = np.diag([1.0, 0.0, 2.0]).astype(np.float32)
     c, info = isopo.transform(torch.from_numpy(Kz).to(gpu_device), torch.from_numpy(A[0]).to(gpu_device), "fisher", 0.0)
     assert c.cpu().numpy()[1] == 0.0 and np.all(np.isfinite(c.cpu().numpy()))
+
+
+@pytest.mark.parametrize("m,k", [(64, 16), (64, 17), (64, 40), (128, 128), (200, 32), (200, 33), (200, 150), (200, 200),
+                                 (600, 17), (600, 600), (1024, 1009)])
+def test_transform_failing_pivot_in_any_panel(gpu_device, m, k):
+    """The k-th pivot is exactly -1 (row and column k - 1 of a dense positive definite matrix are cleared, the
+    diagonal entry set to -1): info = k and a NaN fill, wherever k falls in the panels of the factorisation;
+    the other problem of the batch is solved."""
+    rng = np.random.default_rng(1000 * m + k)
+    good = _random_gram(rng, m)
+    bad = good.copy()
+    bad[k - 1, :] = 0.0
+    bad[:, k - 1] = 0.0
+    bad[k - 1, k - 1] = -1.0
+    K = np.stack([bad, good])
+    A = rng.standard_normal((2, m)).astype(np.float32)
+    c, info = isopo.transform(torch.from_numpy(K).to(gpu_device), torch.from_numpy(A).to(gpu_device), "interacting",
+                              1e-3, isopo.REG_ABSOLUTE)
+    torch.cuda.synchronize()
+    assert info.cpu().tolist() == [k, 0]
+    assert orc.coeff_interacting(bad, A[0], 1e-3, isopo.REG_ABSOLUTE)[1] == k
+    c = c.cpu().numpy()
+    assert np.all(np.isnan(c[0]))
+    ref, oinfo = orc.coeff_interacting(good, A[1], 1e-3, isopo.REG_ABSOLUTE)
+    assert oinfo == 0
+    assert_c_close(c[1], ref, 1e-5, f"m={m}, the solvable problem beside a failing one")
 
 
 def test_bad_arguments_on_device_calls(gpu_device):
