@@ -469,7 +469,9 @@ def main() -> int:
         t_tsg = timed(token_sample_step_group_calls, reps, 2, "token_samples_groups")
         t_ts2 = timed(token_sample_step_side_streams, reps, 2, "token_samples_side")
 
-        def variant_step(reg_mode=isopo.REG_REL_TRACE, beta=0.0, recompute=False):
+        dWs_bf16 = [torch.zeros(dW.shape, dtype=torch.bfloat16, device=dev) for dW in dWs]
+
+        def variant_step(reg_mode=isopo.REG_REL_TRACE, beta=0.0, recompute=False, bf16_dw=False):
             def fn():
                 for _ in range(sweeps):
                     for b in range(len(blocks)):
@@ -482,12 +484,18 @@ def main() -> int:
                             i = b * npj + j
                             if recompute:
                                 isopo.weighted_grad(layers[i], cb[b][j], None, beta, dWs[i], stream=stream)
+                            elif bf16_dw:
+                                isopo.weighted_grad_stash_bf16(layers[i], cb[b][j], wss[j], layouts[i], beta, dWs_bf16[i],
+                                                               stream=stream)
                             else:
                                 isopo.weighted_grad(layers[i], cb[b][j], wss[j], beta, dWs[i], stream=stream, layout=layouts[i])
             return fn
         t_abs = timed(variant_step(reg_mode=isopo.REG_ABSOLUTE), reps, 2, "absolute")
         t_beta = timed(variant_step(beta=1.0), reps, 2, "beta1")
         t_rec = timed(variant_step(recompute=True), reps, 2, "recompute")
+        t_bf = timed(variant_step(bf16_dw=True), reps, 2, "bf16_dw")
+        t_bf1 = timed(variant_step(beta=1.0, bf16_dw=True), reps, 2, "bf16_dw_beta1")
+        del dWs_bf16
         for dW in dWs:
             dW.zero_()          # beta = 1 accumulated into them
 
@@ -504,6 +512,8 @@ def main() -> int:
             f"{other}_from_stash_gram": entry(t_other, "other", total_flops),
             f"{args.variant}_absolute_lambda": entry(t_abs, "absolute", what="the headline route with reg = lambda as printed (numerically nil at these shapes: K_ii ~ 1e4..1e6)"),
             f"{args.variant}_beta_1": entry(t_beta, "beta1", what="the headline route accumulating into dW (mod.grad += of the listings): one more read of dW per projection"),
+            f"{args.variant}_bf16_dW": entry(t_bf, "bf16_dw", what="the headline route with dW written in bf16 (isopo_weighted_grad_stash_bf16: the gradient buffer of a bf16 parameter); the REINFORCE baseline it is set against still writes fp32"),
+            f"{args.variant}_bf16_dW_beta_1": entry(t_bf1, "bf16_dw_beta1", what="the same accumulating into the bf16 dW"),
             f"{args.variant}_without_stash": entry(t_rec, "recompute", what="isopo_layer_gram with no stash kept, then isopo_weighted_grad(c, stash = NULL): the weighted contraction from X and Delta again (the route for a workspace too small to keep the stash)"),
             "fisher_from_token_samples": entry(t_ts, "token_samples", ts_flops, n_samples=args.n_samples,
                                                what="isopo_fisher_samples_block once per block (the sets of projections sharing an input in one launch), then isopo_weighted_grad(c, stash = NULL) per projection: ONE weighted contraction, no stash, no scaled copy"),

@@ -271,6 +271,15 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
 isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
                                        isopo_stash_layout layout, float beta, float* dW, void* stream);
 
+/* isopo_weighted_grad_stash with dW [d_out, d_in] in bf16, the gradient buffer of a bf16 model's parameter
+ * (`mod.grad += ...` of both listings where `mod.weight` is bf16): the sums run in fp32 as before and
+ * dW = bf16(beta * dW + sum_i c_i G_i) is rounded once, to nearest even; with beta = 0 the result is the
+ * fp32 call's result rounded.  The pass is bound by HBM and by the lines of dW it writes back, of which
+ * there are half as many.  bf16 layers only (ISOPO_ERR_UNSUPPORTED otherwise); dW_bf16 device, 16-byte
+ * aligned, caller-owned; everything else as isopo_weighted_grad_stash. */
+isopo_status isopo_weighted_grad_stash_bf16(const isopo_layer* layer, const float* c, const void* stash,
+                                            isopo_stash_layout layout, float beta, void* dW_bf16, void* stream);
+
 /* The non-interacting update's coefficients with the paper's own Fisher-norm estimate (eq.
  * formal-F-norm; F_norm of the non-interacting listing): from n_samples sampled token rows j of the
  * microbatch (a0 = act_in[samples], g0 = grad_out[samples]),

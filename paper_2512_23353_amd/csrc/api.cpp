@@ -575,7 +575,7 @@ isopo_status isopo_weighted_grad(const isopo_layer* layer, const float* c, const
   const bool bf16 = layer->dtype == ISOPO_BF16;
   const long long D = (long long)layer->d_out * layer->d_in;
   if (stash) {
-    return launch_stash_weighted_sum(stash, bf16, D, D, layer->n_seq, c, beta, dW, s) == hipSuccess ? ISOPO_OK
+    return launch_stash_weighted_sum(stash, bf16, D, D, layer->n_seq, c, beta, dW, false, s) == hipSuccess ? ISOPO_OK
                                                                                                       : ISOPO_ERR_HIP;
   }
   SeqGradArgs a;
@@ -598,23 +598,39 @@ isopo_status isopo_stash_layout_of(const isopo_layer* layer, isopo_stash_layout*
   return ISOPO_OK;
 }
 
-isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
-                                       isopo_stash_layout layout, float beta, float* dW, void* stream) {
+// dW = beta dW + sum_i c_i G_i from a kept stash in either layout, dW in fp32 or bf16
+static isopo_status weighted_grad_from_stash(const isopo_layer* layer, const float* c, const void* stash,
+                                             isopo_stash_layout layout, float beta, void* dW, bool dw_bf16,
+                                             void* stream) {
   if (!enum_in(layout, ISOPO_STASH_ROW_MAJOR, ISOPO_STASH_TILE_ORDER)) return ISOPO_ERR_INVALID_ARG;
-  if (layout == ISOPO_STASH_ROW_MAJOR) {
-    if (!stash) return ISOPO_ERR_INVALID_ARG;
-    return isopo_weighted_grad(layer, c, stash, beta, dW, stream);
-  }
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
   if (!c || !stash || !dW || !aligned16(dW) || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
+  const bool bf16 = layer->dtype == ISOPO_BF16;
+  if (dw_bf16 && !bf16) return ISOPO_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (layout == ISOPO_STASH_ROW_MAJOR) {
+    const long long D = (long long)layer->d_out * layer->d_in;
+    return launch_stash_weighted_sum(stash, bf16, D, D, layer->n_seq, c, beta, dW, dw_bf16, s) == hipSuccess
+               ? ISOPO_OK : ISOPO_ERR_HIP;
+  }
   isopo_stash_layout have;
   int32_t tile;
   st = isopo_stash_layout_of(layer, &have, &tile);
   if (st != ISOPO_OK) return st;
   if (have != ISOPO_STASH_TILE_ORDER) return ISOPO_ERR_UNSUPPORTED;      // this layer's kept stash is row-major
-  return launch_stash_weighted_sum_tiled(stash, tile, layer->d_out, layer->d_in, layer->n_seq, c, beta, dW,
-                                         static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+  return launch_stash_weighted_sum_tiled(stash, tile, layer->d_out, layer->d_in, layer->n_seq, c, beta, dW, dw_bf16,
+                                         s) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
+                                       isopo_stash_layout layout, float beta, float* dW, void* stream) {
+  return weighted_grad_from_stash(layer, c, stash, layout, beta, dW, false, stream);
+}
+
+isopo_status isopo_weighted_grad_stash_bf16(const isopo_layer* layer, const float* c, const void* stash,
+                                            isopo_stash_layout layout, float beta, void* dW_bf16, void* stream) {
+  return weighted_grad_from_stash(layer, c, stash, layout, beta, dW_bf16, true, stream);
 }
 
 size_t isopo_weighted_grad_scratch(const isopo_layer* layer) {

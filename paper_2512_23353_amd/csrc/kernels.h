@@ -86,12 +86,13 @@ hipError_t launch_stash_gram_finish(const float* partials, bool bf16, int n_seq,
 int stash_gram_stream_slots();
 hipError_t launch_stash_gram_stream(const StashGramArgs& a, hipStream_t s);
 
-// dW[p] = beta*dW[p] + sum_i c[i] * stash[i][p],  p in [0, n_elem).
+// dW[p] = beta*dW[p] + sum_i c[i] * stash[i][p],  p in [0, n_elem).  dW fp32, or bf16 (dw_bf16; bf16 stash only:
+// fp32 sums, one rounding).
 hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq_stride, long long n_elem,
-                                     int n_seq, const float* c, float beta, float* dW, hipStream_t s);
+                                     int n_seq, const float* c, float beta, void* dW, bool dw_bf16, hipStream_t s);
 // The same from a bf16 stash in tile order (tile 256 or 128, d_out and d_in multiples of it); dW row-major.
 hipError_t launch_stash_weighted_sum_tiled(const void* stash, int tile, int d_out, int d_in, int n_seq, const float* c,
-                                           float beta, float* dW, hipStream_t s);
+                                           float beta, void* dW, bool dw_bf16, hipStream_t s);
 
 // Ghost Gram: K_ij = sum_{t in i, s in j} (x_t.x_s)(delta_t.delta_s).
 struct GhostArgs {

@@ -145,11 +145,11 @@ __global__ __launch_bounds__(1024) void stash_gram_finish_kernel(const float* __
   }
 }
 
-template <bool BF16>
+template <bool BF16, bool OUTB>
 __global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __restrict__ stash, long long seq_stride,
                                                                  long long n_vec, int n_seq,
                                                                  const float* __restrict__ c, float beta,
-                                                                 float* __restrict__ dW) {
+                                                                 void* __restrict__ dW_out) {
   constexpr int kV = BF16 ? 8 : 4;
   for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < n_vec;
        vi += (long long)gridDim.x * blockDim.x) {
@@ -176,15 +176,33 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __r
         s[0] += ci * f.x; s[1] += ci * f.y; s[2] += ci * f.z; s[3] += ci * f.w;
       }
     }
-    float* o = dW + vi * kV;
-#pragma unroll
-    for (int e = 0; e < kV; e += 4) {
-      float4 r = make_float4(s[e], s[e + 1], s[e + 2], s[e + 3]);
+    if constexpr (OUTB) {
+      // bf16 dW (bf16 stash only): the thread's eight values are one 16-byte vector
+      static_assert(!OUTB || BF16, "a bf16 dW is formed from a bf16 stash");
+      uint4* o = static_cast<uint4*>(dW_out) + vi;
+      unsigned w[4] = {0u, 0u, 0u, 0u};
       if (beta != 0.f) {
-        const float4 old = *reinterpret_cast<const float4*>(o + e);
-        r.x += beta * old.x; r.y += beta * old.y; r.z += beta * old.z; r.w += beta * old.w;
+        const uint4 old = *o;
+        w[0] = old.x; w[1] = old.y; w[2] = old.z; w[3] = old.w;
       }
-      *reinterpret_cast<float4*>(o + e) = r;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = s[2 * e] + beta * __builtin_bit_cast(float, w[e] << 16);
+        const float hi = s[2 * e + 1] + beta * __builtin_bit_cast(float, w[e] & 0xffff0000u);
+        w[e] = (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16);
+      }
+      *o = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+      float* o = static_cast<float*>(dW_out) + vi * kV;
+#pragma unroll
+      for (int e = 0; e < kV; e += 4) {
+        float4 r = make_float4(s[e], s[e + 1], s[e + 2], s[e + 3]);
+        if (beta != 0.f) {
+          const float4 old = *reinterpret_cast<const float4*>(o + e);
+          r.x += beta * old.x; r.y += beta * old.y; r.z += beta * old.z; r.w += beta * old.w;
+        }
+        *reinterpret_cast<float4*>(o + e) = r;
+      }
     }
   }
 }
@@ -192,11 +210,11 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_kernel(const void* __r
 // The same from a stash in tile order (see stash_tile_order_ok): a thread's eight values are four rows of
 // two columns of dW, 16 apart; a wave stores, per value, four rows' runs of 16 consecutive floats, and the
 // values q and q + 4 complete each other's 128-byte lines.
-template <int T>
+template <int T, bool OUTB>
 __global__ __launch_bounds__(256) void stash_weighted_sum_tiled_kernel(const void* __restrict__ stash, long long seq_stride,
                                                                        long long n_vec, int n_seq,
                                                                        const float* __restrict__ c, float beta,
-                                                                       float* __restrict__ dW, int d_in, int tiles_n) {
+                                                                       void* __restrict__ dW_out, int d_in, int tiles_n) {
   constexpr int NP = T / 64;                       // 16x32 pieces per 16-row strip of a quadrant
   constexpr int QV = (T / 2) * (T / 2) / 8;        // 16-byte vectors per quadrant
   constexpr int TV = T * T / 8;                    // ... per tile
@@ -223,10 +241,31 @@ __global__ __launch_bounds__(256) void stash_weighted_sum_tiled_kernel(const voi
     const int tile_m = (int)(tile / tiles_n), tile_n = (int)(tile % tiles_n);
     const int n0 = tile_n * T + (quad & 1) * (T / 2) + jp * 32 + (lane & 15);
     const int m0 = tile_m * T + (quad >> 1) * (T / 2) + strip * 16 + 4 * (lane >> 4);
+    if constexpr (OUTB) {
+      // bf16 dW: neighbouring lanes hold neighbouring columns; the even lane takes its neighbour's values of
+      // the left 16 columns and stores pairs there, the odd lane does the same for the right 16 columns
+      // (n_vec is a multiple of 64 for a stash in tile order, so every lane of a wave is here)
+      __bf16* dW = static_cast<__bf16*>(dW_out);
+      const bool odd = lane & 1;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      float* o = dW + (size_t)(m0 + (q & 3)) * d_in + n0 + 16 * (q >> 2);
-      *o = (beta != 0.f ? beta * *o : 0.f) + s[q];
+      for (int q = 0; q < 4; ++q) {
+        const float got = __shfl_xor(odd ? s[q] : s[q + 4], 1, kWave);
+        float lo = odd ? got : s[q], hi = odd ? s[q + 4] : got;
+        unsigned* o = reinterpret_cast<unsigned*>(dW + (size_t)(m0 + q) * d_in + (n0 & ~1) + (odd ? 16 : 0));
+        if (beta != 0.f) {
+          const unsigned old = *o;
+          lo += beta * __builtin_bit_cast(float, old << 16);
+          hi += beta * __builtin_bit_cast(float, old & 0xffff0000u);
+        }
+        *o = (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16);
+      }
+    } else {
+      float* dW = static_cast<float*>(dW_out);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        float* o = dW + (size_t)(m0 + (q & 3)) * d_in + n0 + 16 * (q >> 2);
+        *o = (beta != 0.f ? beta * *o : 0.f) + s[q];
+      }
     }
   }
 }
@@ -283,35 +322,45 @@ hipError_t launch_stash_gram_finish(const float* partials, bool bf16, int n_seq,
 }
 
 hipError_t launch_stash_weighted_sum(const void* stash, bool bf16, long long seq_stride, long long n_elem, int n_seq,
-                                     const float* c, float beta, float* dW, hipStream_t s) {
+                                     const float* c, float beta, void* dW, bool dw_bf16, hipStream_t s) {
   const long long n_vec = n_elem / (bf16 ? 8 : 4);
   if (n_vec <= 0) return hipSuccess;
+  if (dw_bf16 && !bf16) return hipErrorInvalidValue;
   // one 16-byte vector per thread (the kernel's loop strides over the rest of a stash beyond 2^39 elements)
   long long blocks = (n_vec + 255) / 256;
   if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
-  if (bf16)
-    hipLaunchKernelGGL((stash_weighted_sum_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
+  if (bf16 && dw_bf16)
+    hipLaunchKernelGGL((stash_weighted_sum_kernel<true, true>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
+                       n_vec, n_seq, c, beta, dW);
+  else if (bf16)
+    hipLaunchKernelGGL((stash_weighted_sum_kernel<true, false>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
                        n_vec, n_seq, c, beta, dW);
   else
-    hipLaunchKernelGGL((stash_weighted_sum_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
+    hipLaunchKernelGGL((stash_weighted_sum_kernel<false, false>), dim3((unsigned)blocks), dim3(256), 0, s, stash, seq_stride,
                        n_vec, n_seq, c, beta, dW);
   return hipGetLastError();
 }
 
+template <int T, bool OUTB>
+static hipError_t launch_tiled_t(const void* stash, long long D, long long n_vec, int n_seq, const float* c, float beta,
+                                 void* dW, int d_in, hipStream_t s) {
+  long long blocks = (n_vec + 255) / 256;
+  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
+  hipLaunchKernelGGL((stash_weighted_sum_tiled_kernel<T, OUTB>), dim3((unsigned)blocks), dim3(256), 0, s, stash, D, n_vec,
+                     n_seq, c, beta, dW, d_in, d_in / T);
+  return hipGetLastError();
+}
+
 hipError_t launch_stash_weighted_sum_tiled(const void* stash, int tile, int d_out, int d_in, int n_seq, const float* c,
-                                           float beta, float* dW, hipStream_t s) {
+                                           float beta, void* dW, bool dw_bf16, hipStream_t s) {
   if ((tile != 256 && tile != 128) || d_out % tile || d_in % tile) return hipErrorInvalidValue;
   const long long D = (long long)d_out * d_in, n_vec = D / 8;
   if (n_vec <= 0) return hipSuccess;
-  long long blocks = (n_vec + 255) / 256;
-  if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;
   if (tile == 256)
-    hipLaunchKernelGGL((stash_weighted_sum_tiled_kernel<256>), dim3((unsigned)blocks), dim3(256), 0, s, stash, D, n_vec,
-                       n_seq, c, beta, dW, d_in, d_in / tile);
-  else
-    hipLaunchKernelGGL((stash_weighted_sum_tiled_kernel<128>), dim3((unsigned)blocks), dim3(256), 0, s, stash, D, n_vec,
-                       n_seq, c, beta, dW, d_in, d_in / tile);
-  return hipGetLastError();
+    return dw_bf16 ? launch_tiled_t<256, true>(stash, D, n_vec, n_seq, c, beta, dW, d_in, s)
+                   : launch_tiled_t<256, false>(stash, D, n_vec, n_seq, c, beta, dW, d_in, s);
+  return dw_bf16 ? launch_tiled_t<128, true>(stash, D, n_vec, n_seq, c, beta, dW, d_in, s)
+                 : launch_tiled_t<128, false>(stash, D, n_vec, n_seq, c, beta, dW, d_in, s);
 }
 
 }  // namespace isopo

@@ -30,7 +30,7 @@ _PATHS = {"auto": GRAM_AUTO, "ghost": GRAM_GHOST, "materialised": GRAM_MATERIALI
 _PATH_NAMES = {v: k for k, v in _PATHS.items()}
 
 EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_plan", "isopo_layer_gram",
-           "isopo_stash_layout_of", "isopo_weighted_grad_stash", "isopo_seq_grads_stash",
+           "isopo_stash_layout_of", "isopo_weighted_grad_stash", "isopo_weighted_grad_stash_bf16", "isopo_seq_grads_stash",
            "isopo_transform_ema", "isopo_seq_grads_limited", "isopo_seq_grads",
            "isopo_stash_gram_workspace", "isopo_stash_gram", "isopo_transform_workspace",
            "isopo_transform", "isopo_transform_noalloc", "isopo_weighted_grad", "isopo_scale_rows",
@@ -107,6 +107,8 @@ def load() -> ctypes.CDLL:
     lib.isopo_stash_layout_of.restype = ctypes.c_int
     lib.isopo_weighted_grad_stash.argtypes = [lp, vp, vp, ctypes.c_int, f32, vp, vp]
     lib.isopo_weighted_grad_stash.restype = ctypes.c_int
+    lib.isopo_weighted_grad_stash_bf16.argtypes = [lp, vp, vp, ctypes.c_int, f32, vp, vp]
+    lib.isopo_weighted_grad_stash_bf16.restype = ctypes.c_int
     lib.isopo_scale_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int64, i32, vp, i32, vp, vp, vp]
     lib.isopo_scale_rows.restype = ctypes.c_int
     lib.isopo_fisher_samples_workspace.argtypes = [lp, i32]
@@ -388,6 +390,20 @@ def weighted_grad(layer: Layer, c: Optional[torch.Tensor], stash: Optional[torch
         return dW
     _check(load().isopo_weighted_grad(layer.ref(), _ptr(c), _ptr(stash), float(beta), dW.data_ptr(),
                                       _stream(stream)), "isopo_weighted_grad")
+    return dW
+
+
+def weighted_grad_stash_bf16(layer: Layer, c: torch.Tensor, stash: torch.Tensor, layout: int = 0, beta: float = 0.0,
+                             dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """dW [d_out, d_in] bf16 = bf16(beta dW + sum_i c_i G_i) from a kept stash in the given layout."""
+    if dW is None:
+        if beta != 0.0:
+            raise ValueError("beta != 0 needs an existing dW")
+        dW = torch.empty((layer.d_out, layer.d_in), dtype=torch.bfloat16, device=layer.device)
+    if dW.dtype != torch.bfloat16 or not dW.is_contiguous() or tuple(dW.shape) != (layer.d_out, layer.d_in):
+        raise ValueError("dW must be a contiguous bf16 [d_out, d_in] tensor")
+    _check(load().isopo_weighted_grad_stash_bf16(layer.ref(), _ptr(c), _ptr(stash), int(layout), float(beta),
+                                                 dW.data_ptr(), _stream(stream)), "isopo_weighted_grad_stash_bf16")
     return dW
 
 

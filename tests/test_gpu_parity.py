@@ -187,6 +187,43 @@ def test_stash_in_tile_order(gpu_device, case):
     assert torch.equal(isopo.weighted_grad(layer, c, ws_rm, layout=isopo.STASH_ROW_MAJOR), isopo.weighted_grad(layer, c, ws_rm))
 
 
+@pytest.mark.parametrize("case", TILE_ORDER_CASES[:2] + [("row_major_264x512", 264, 512, [40, 3, 0, 77, 130])],
+                         ids=lambda c: c[0])
+def test_weighted_grad_from_stash_into_bf16(gpu_device, case):
+    """dW in bf16 (`mod.grad +=` on a bf16 parameter): with beta = 0 the bits are the fp32 result's, rounded to
+    nearest even; with beta != 0 the old bf16 values enter in fp32 before the one rounding; the oracle's dW is met
+    within the bf16 tolerance.  Both layouts of the stash."""
+    name, d_in, d_out, lengths = case
+    prob = wl.custom_layer(d_in, d_out, lengths, dtype="bf16", seed=31, sigma_delta=1e-2, rho=0.3)
+    layer, A = to_device(prob, gpu_device)
+    layout, _ = isopo.stash_layout(layer)
+    assert layout == (isopo.STASH_ROW_MAJOR if name.startswith("row_major") else isopo.STASH_TILE_ORDER)
+    K, ws = isopo.layer_gram(layer, "materialised", keep_stash=isopo.KEEP_FAST)
+    c, info = isopo.transform(K, A, "interacting", 1e-2, isopo.REG_REL_TRACE)
+    full = isopo.weighted_grad(layer, c, ws, layout=layout)
+    half = isopo.weighted_grad_stash_bf16(layer, c, ws, layout)
+    torch.cuda.synchronize()
+    assert half.dtype == torch.bfloat16 and torch.equal(half, full.to(torch.bfloat16))
+    ref = oracle_step(prob, "interacting", 1e-2, isopo.REG_REL_TRACE)
+    assert_dW_close(half.float().cpu().numpy(), ref["dW"], TOL["bf16"], f"{name} bf16 dW", ref["dW_abs"])
+    # accumulation into an existing bf16 gradient
+    old = torch.from_numpy(np.random.default_rng(6).standard_normal((d_out, d_in)).astype(np.float32)).to(gpu_device)
+    old = (old * full.abs().mean()).to(torch.bfloat16)
+    for beta in (1.0, 0.5):
+        got = isopo.weighted_grad_stash_bf16(layer, c, ws, layout, beta, old.clone())
+        want = isopo.weighted_grad(layer, c, ws, beta, old.float(), layout=layout).to(torch.bfloat16)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"beta={beta}"
+    # fp32 layers have no bf16 gradient
+    prob32 = wl.custom_layer(64, 128, [5, 9], dtype="f32", seed=32)
+    layer32, _ = to_device(prob32, gpu_device)
+    stash32 = isopo.seq_grads(layer32)
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.weighted_grad_stash_bf16(layer32, torch.ones(2, device=gpu_device), stash32, isopo.STASH_ROW_MAJOR, 0.0,
+                                       torch.zeros((128, 64), dtype=torch.bfloat16, device=gpu_device))
+    assert e.value.status == 3
+
+
 def test_stash_layout_falls_back_to_row_major(gpu_device):
     """Dimensions that are not multiples of 256, or fp32 inputs: keep_stash = 2 leaves the row-major stash,
     and asking for tile order is refused."""

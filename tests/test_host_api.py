@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     lib = isopo.load()
     header = open(os.path.join(ROOT, "include", "isopo.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(isopo_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(isopo_[a-z0-9_]+)\s*\(", header))
     assert declared == set(isopo.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
