@@ -110,6 +110,12 @@ def _full_size_checks(prob, gpu_device, rng, *, full_k, k_pairs=(), lams=(1e-3,)
     c_rand = torch.from_numpy(rng.standard_normal(prob.n_seq).astype(np.float32)).to(gpu_device)
     dW_stash_r = isopo.weighted_grad(layer, c_rand, ws, layout=layout)
     dW_re = isopo.weighted_grad(layer, c_rand)                                # from X and Delta, no stash
+    if prob.dtype == "bf16":
+        # the bf16 gradient buffer: the fp32 sums above, rounded once (so the oracle checks of dW_stash below cover it)
+        dW_half = isopo.weighted_grad_stash_bf16(layer, c_int, ws, layout)
+        torch.cuda.synchronize()
+        assert torch.equal(dW_half, dW_stash.to(torch.bfloat16)), f"{prob.name}: bf16 dW"
+        del dW_half
     torch.cuda.synchronize()
     del ws
     Kh = K.cpu().numpy().astype(np.float64)
