@@ -600,16 +600,14 @@ isopo_status isopo_stash_layout_of(const isopo_layer* layer, isopo_stash_layout*
 
 // dW = beta dW + sum_i c_i G_i from a kept stash in either layout, dW in fp32 or bf16
 static isopo_status weighted_grad_from_stash(const isopo_layer* layer, const float* c, const void* stash,
-                                             isopo_stash_layout layout, float beta, void* dW, bool dw_bf16,
-                                             void* stream) {
-  if (!enum_in(layout, ISOPO_STASH_ROW_MAJOR, ISOPO_STASH_TILE_ORDER)) return ISOPO_ERR_INVALID_ARG;
+                                             bool tile_order, float beta, void* dW, bool dw_bf16, void* stream) {
   isopo_status st = check_layer(layer, true);
   if (st != ISOPO_OK) return st;
   if (!c || !stash || !dW || !aligned16(dW) || !aligned16(stash)) return ISOPO_ERR_INVALID_ARG;
   const bool bf16 = layer->dtype == ISOPO_BF16;
   if (dw_bf16 && !bf16) return ISOPO_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (layout == ISOPO_STASH_ROW_MAJOR) {
+  if (!tile_order) {
     const long long D = (long long)layer->d_out * layer->d_in;
     return launch_stash_weighted_sum(stash, bf16, D, D, layer->n_seq, c, beta, dW, dw_bf16, s) == hipSuccess
                ? ISOPO_OK : ISOPO_ERR_HIP;
@@ -625,12 +623,14 @@ static isopo_status weighted_grad_from_stash(const isopo_layer* layer, const flo
 
 isopo_status isopo_weighted_grad_stash(const isopo_layer* layer, const float* c, const void* stash,
                                        isopo_stash_layout layout, float beta, float* dW, void* stream) {
-  return weighted_grad_from_stash(layer, c, stash, layout, beta, dW, false, stream);
+  if (!enum_in(layout, ISOPO_STASH_ROW_MAJOR, ISOPO_STASH_TILE_ORDER)) return ISOPO_ERR_INVALID_ARG;
+  return weighted_grad_from_stash(layer, c, stash, layout == ISOPO_STASH_TILE_ORDER, beta, dW, false, stream);
 }
 
 isopo_status isopo_weighted_grad_stash_bf16(const isopo_layer* layer, const float* c, const void* stash,
                                             isopo_stash_layout layout, float beta, void* dW_bf16, void* stream) {
-  return weighted_grad_from_stash(layer, c, stash, layout, beta, dW_bf16, true, stream);
+  if (!enum_in(layout, ISOPO_STASH_ROW_MAJOR, ISOPO_STASH_TILE_ORDER)) return ISOPO_ERR_INVALID_ARG;
+  return weighted_grad_from_stash(layer, c, stash, layout == ISOPO_STASH_TILE_ORDER, beta, dW_bf16, true, stream);
 }
 
 size_t isopo_weighted_grad_scratch(const isopo_layer* layer) {

@@ -127,6 +127,9 @@ int main() {
     EXPECT(isopo_layer_gram_plan(&l, (isopo_gram_path)9, nullptr, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
     EXPECT(isopo_layer_gram(&l, ISOPO_GRAM_AUTO, nullptr, nullptr, 0, 0, nullptr) == ISOPO_ERR_INVALID_ARG);
     EXPECT(isopo_weighted_grad(&l, nullptr, nullptr, 0.f, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
+    EXPECT(isopo_weighted_grad_stash(&l, nullptr, nullptr, (isopo_stash_layout)7, 0.f, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
+    EXPECT(isopo_weighted_grad_stash_bf16(&l, nullptr, nullptr, ISOPO_STASH_ROW_MAJOR, 0.f, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
+    EXPECT(isopo_weighted_grad_stash_bf16(nullptr, nullptr, nullptr, ISOPO_STASH_TILE_ORDER, 0.f, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
     EXPECT(isopo_contraction_plan(&l, 1, nullptr) == ISOPO_ERR_INVALID_ARG);
     const std::vector<int32_t> bad1 = {1, 3, 7}, bad2 = {0, 5, 3}, bad3 = {0, 3, 6};
     for (const auto* b : {&bad1, &bad2, &bad3}) {
