@@ -12,8 +12,8 @@
 // factor * E[mean(D)]: the mean eigenvalue is the trace over m, so no
 // decomposition is needed for it); for FISHER it is mean_i ||g_i||_F^2 (the
 // non-interacting derivation compares reg_l with the typical ||.||_F^2).
-// The m x m problem is tiny next to the
-// contractions around it, so one workgroup per problem works in fp64: a
+// The m x m problem is tiny next to the contractions around it, so one
+// workgroup per problem works in fp64: a
 // right-looking Cholesky factorisation in panels and two triangular solves.  The
 // matrix lives in LDS (m <= 128) or in a caller-provided global scratch (larger
 // m); the panel being factored is in LDS, column-major, and each thread holds one
@@ -59,9 +59,10 @@ __host__ __device__ constexpr int panel_stride(int m) { return ((m + 1) + ((m + 
 // in LDS as PT[column][row - k0] with row stride RS.  kThreads threads; c is left in cs.
 //
 // Panel step: thread t holds the panel rows t and t + kThreads (R = 2: only a 1025-row panel has the second;
-// the launch gives smaller problems enough threads for R = 1) in registers.  Per column kk: every row's entry goes to LDS, one barrier, then each thread reads the pivot and
-// the entries (q, kk) of the rows q > kk (the same addresses for all lanes) and eliminates column kk from its
-// rows with the unscaled entries, row[q] -= row[kk] * (q, kk) / pivot; its own entry of L is row[kk] / sqrt(pivot).
+// the launch gives smaller problems enough threads for R = 1) in registers.  Per column kk: every row's entry
+// goes to LDS, one barrier, then each thread reads the pivot and the entries (q, kk) of the rows q > kk (the
+// same addresses for all lanes) and eliminates column kk from its rows with the unscaled entries,
+// row[q] -= row[kk] * (q, kk) / pivot; its own entry of L is row[kk] / sqrt(pivot).
 // The upper triangle of the diagonal block is carried along and never read.  The trailing matrix (rows up to
 // and including the row of A) then takes the rank-NB update in 4 x 4 register blocks whose factors come from
 // the panel in LDS.
