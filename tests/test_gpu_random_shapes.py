@@ -1,8 +1,10 @@
 """Seeded random shapes through every route of the HIP path against the oracle:
 dimensions that are not multiples of any tile size, sequences of length 0 and
 1 mixed with long ones, both dtypes, both Gram paths, both transforms, the
-stash-free update and the token-sample coefficients.  Three families: small
-layers, layers wide enough for the 256x256 tiles, and wide layers on few tokens."""
+stash-free update and the token-sample coefficients.  Four families: small
+layers, layers wide enough for the 256x256 tiles, wide layers on few tokens, and
+more than 128 short sequences on layers whose stash is kept in tile order (the
+Gram kernels and the transform for many sequences, the bf16 gradient buffer)."""
 import numpy as np
 import pytest
 import torch
@@ -18,6 +20,15 @@ pytestmark = pytest.mark.gpu
 
 def _draw_case(seed):
     rng = np.random.default_rng(seed)
+    if seed >= 300:
+        # many short sequences, dimensions that are multiples of 256: tile-order stash, the Gram kernels for 129 - 256
+        # and for more than 256 sequences, the transform's panels in global scratch
+        dtype = "bf16"
+        d_in = 256
+        d_out = int(rng.integers(1, 3)) * 256
+        n_seq = int(rng.integers(129, 257)) if seed % 2 == 0 else int(rng.integers(257, 330))
+        lengths = [int(rng.integers(0, 2)) if rng.random() < 0.1 else int(rng.integers(2, 48)) for _ in range(n_seq)]
+        return dtype, d_in, d_out, lengths
     if seed >= 200:
         # few tokens on a wide layer: the ghost launch cuts the features into ranges (64-feature tails included)
         dtype = "bf16"
@@ -48,7 +59,7 @@ def _draw_case(seed):
     return dtype, d_in, d_out, lengths
 
 
-@pytest.mark.parametrize("seed", list(range(24)) + list(range(100, 108)) + list(range(200, 206)))
+@pytest.mark.parametrize("seed", list(range(24)) + list(range(100, 108)) + list(range(200, 206)) + list(range(300, 304)))
 def test_random_shape(gpu_device, seed):
     dtype, d_in, d_out, lengths = _draw_case(seed)
     print(f"seed {seed}: {dtype} d_in={d_in} d_out={d_out} lengths={lengths}", flush=True)
@@ -69,6 +80,11 @@ def test_random_shape(gpu_device, seed):
         assert_dW_close(out["dW"].cpu().numpy(), ref["dW"], tol, what, ref["dW_abs"])
         cf, _ = isopo.transform(out["K"], A, "fisher", 1e-2, isopo.REG_REL_TRACE)
         assert_c_close(cf.cpu().numpy(), ref_f["c"], tol, what + "/fisher")
+        if path == "materialised" and dtype == "bf16":
+            # the bf16 gradient buffer from the same stash: the fp32 result rounded once
+            half = isopo.weighted_grad_stash_bf16(layer, out["c"], out["workspace"], out["stash_layout"])
+            torch.cuda.synchronize()
+            assert torch.equal(half, out["dW"].to(torch.bfloat16)), what + "/bf16 dW"
     # the stash-free routes with the oracle's own coefficients
     c_dev = torch.from_numpy(ref["c"].astype(np.float32)).to(gpu_device)
     c32 = c_dev.cpu().numpy().astype(np.float64)
