@@ -158,6 +158,54 @@ def mfma_ceiling(dev, board_probe=False) -> dict:
     return out
 
 
+def schedule_probe(dev) -> dict:
+    """Is the contraction bound by its schedule or by the board?  (1) isopo_probe_lds_dma: the rate at which a
+    workgroup streams an L2-resident buffer into LDS with the contraction's DMA loads, against the number of waves
+    that issue them; (2) isopo_probe_contraction_waves: config 3's gate projection (dW = Delta^T X, 256x256 tiles)
+    with the library's 4 waves per workgroup and with 8 (half the registers per wave, twice the DMA issuers), on
+    the workload's operands and on zeros (where the part holds its top clock)."""
+    import numpy as np
+    import torch
+    from paper_2512_23353_amd import isopo, workloads as wl
+    stream = torch.cuda.current_stream()
+
+    def med_ms(fn, reps=7):
+        ms = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return float(np.median(ms[1:]))
+    out = {"lds_dma": {"what": "GB/s per workgroup into LDS, ring of 32 KiB stages refilled without a pause, 16 MiB "
+                               "buffer (L2-resident); 8 workgroups (alone on the chip) and 256 (one per compute unit)",
+                       "rates": {}},
+           "contraction": {"what": "config3 gate projection, dW = Delta^T X, ms per launch and TFLOP/s on 2 N d_out d_in flop"}}
+    buf = torch.ones(16 << 20, dtype=torch.uint8, device=dev)
+    sink = torch.empty(4096, dtype=torch.float32, device=dev)
+    iters = 4000
+    for wgs in (8, 256):
+        for waves in (2, 4, 8, 16):
+            for stages in (2, 4):
+                t = med_ms(lambda: isopo.probe_lds_dma(buf, waves, stages, wgs, iters, sink, stream=stream), reps=4)
+                out["lds_dma"]["rates"][f"{wgs}_workgroups/{waves}_waves/{stages}_stages"] = round(iters * 32768 / t / 1e6, 1)
+    w = wl.CONFIGS["config3"]
+    lengths = wl.draw_lengths(w)
+    gate = [p for p in w.projections if p.name == "gate"][0]
+    prob = wl.make_layer(w, gate, lengths, device=dev)
+    flops = 2.0 * prob.n_tokens * prob.d_in * prob.d_out
+    zX, zD = torch.zeros_like(prob.X), torch.zeros_like(prob.Delta)
+    dW = torch.empty((prob.d_out, prob.d_in), dtype=torch.float32, device=dev)
+    for kind, layer in (("workload", isopo.Layer(prob.X, prob.Delta, prob.seq_offsets)),
+                        ("zero_operands", isopo.Layer(zX, zD, prob.seq_offsets))):
+        for waves in (4, 8, 4, 8):
+            t = med_ms(lambda: isopo.probe_contraction_waves(layer, waves, dW, stream=stream), reps=9)
+            out["contraction"].setdefault(f"{kind}/{waves}_waves", []).append({"ms": round(t, 4), "tflops": round(flops / t / 1e9, 1)})
+    return out
+
+
 def ghost_case(dev) -> dict:
     """The ghost Gram path where it is the chosen one: a short microbatch (8 sequences of 1024 tokens) on the
     stress layer 5120 -> 27648.  Algorithmic work N^2 (d_in + d_out) flop (both token-by-token products over the
@@ -242,6 +290,9 @@ def main() -> int:
     ap.add_argument("--ghost-case", action="store_true",
                     help="only time isopo_layer_gram on the ghost path for a short microbatch on the stress layer "
                          "(5120 -> 27648, 8 sequences of 1024 tokens) and print its rate, then exit")
+    ap.add_argument("--schedule-probe", action="store_true",
+                    help="only run the two schedule diagnostics (LDS-DMA rate against waves per workgroup; the gate "
+                         "projection's contraction with 4 and with 8 waves, on the workload and on zeros), then exit")
     ap.add_argument("--eigh-case", action="store_true",
                     help="only time the eigendecomposition route (decomposition, sweep of three regularisers) against "
                          "three Cholesky transforms for 32 to 512 sequences, then exit")
@@ -274,6 +325,9 @@ def main() -> int:
         return 0
     if args.eigh_case:
         print(json.dumps(eigh_case(dev)))
+        return 0
+    if args.schedule_probe:
+        print(json.dumps(schedule_probe(dev)))
         return 0
     if args.ghost_case:
         print(json.dumps(ghost_case(dev)))

@@ -430,6 +430,25 @@ isopo_status isopo_weighted_grad_prescaled(const isopo_layer* layer, const float
 #define ISOPO_PROBE_THREADS (256 * 256)
 isopo_status isopo_probe_mfma_loop(int32_t shape, const void* operands, float* sink, int32_t iters, void* stream);
 
+/* Diagnostic: the rate at which workgroups stream global memory into LDS with the 16-byte-per-lane DMA loads
+ * of the contraction kernels, against the number of waves that issue them.  Every workgroup keeps a ring of
+ * `stages` stages of 32 KiB filled (it waits for a stage, meets, requests the next) for `iters` stages and
+ * computes nothing; workgroup b walks the (b mod 8)-th eighth of buf round and round.
+ *   buf         device, 16-byte aligned, `bytes` a multiple of 8 * 32768 (16 MiB stays in the L2s)
+ *   waves       2, 4, 8 or 16 per workgroup;  stages 2 or 4;  workgroups 1 .. 4096 (256: one per compute unit)
+ *   sink        device float [workgroups], overwritten
+ * Bytes moved: workgroups * iters * 32768. */
+isopo_status isopo_probe_lds_dma(const void* buf, size_t bytes, int32_t waves, int32_t stages, int32_t workgroups,
+                                 int32_t iters, float* sink, void* stream);
+
+/* Diagnostic: dW [d_out, d_in] fp32 = Delta^T X (isopo_weighted_grad with c = NULL, stash = NULL, beta = 0) by
+ * the matrix-core contraction on its 256 x 256 tile with 4 waves per workgroup (the launch the library makes: a
+ * 2 x 2 arrangement of 128 x 128 wave tiles, one wave per SIMD, 256 accumulators per lane) or with 8 (2 x 4,
+ * 128 x 64 wave tiles, two waves per SIMD, twice as many waves issuing the operand loads).  Same result; the
+ * benchmark times both on the workload and on zero operands.  bf16 layers whose launch plan takes the
+ * 256 x 256 tile (isopo_contraction_plan), else ISOPO_ERR_UNSUPPORTED. */
+isopo_status isopo_probe_contraction_waves(const isopo_layer* layer, int32_t waves, float* dW, void* stream);
+
 const char* isopo_status_string(isopo_status s);
 
 /* Library version, "major.minor". */

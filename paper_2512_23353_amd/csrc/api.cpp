@@ -663,4 +663,28 @@ isopo_status isopo_probe_mfma_loop(int32_t shape, const void* operands, float* s
                                                                                                          : ISOPO_ERR_HIP;
 }
 
+isopo_status isopo_probe_lds_dma(const void* buf, size_t bytes, int32_t waves, int32_t stages, int32_t workgroups,
+                                 int32_t iters, float* sink, void* stream) {
+  if (!buf || !sink || !aligned16(buf) || iters < 1 || workgroups < 1 || workgroups > 4096) return ISOPO_ERR_INVALID_ARG;
+  if (bytes == 0 || bytes % (8 * 32768)) return ISOPO_ERR_INVALID_ARG;
+  if ((waves != 2 && waves != 4 && waves != 8 && waves != 16) || (stages != 2 && stages != 4)) return ISOPO_ERR_INVALID_ARG;
+  return launch_lds_dma_ring(buf, bytes, waves, stages, workgroups, iters, sink, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
+isopo_status isopo_probe_contraction_waves(const isopo_layer* layer, int32_t waves, float* dW, void* stream) {
+  isopo_status st = check_layer(layer, true);
+  if (st != ISOPO_OK) return st;
+  if (!dW || !aligned16(dW) || (waves != 4 && waves != 8)) return ISOPO_ERR_INVALID_ARG;
+  if (layer->dtype != ISOPO_BF16 || layer->n_tokens == 0) return ISOPO_ERR_UNSUPPORTED;
+  if (plan_contraction(layer->d_out, layer->d_in, (int)layer->n_tokens, layer->n_seq, layer->seq_offsets_host, false).tile != 256)
+    return ISOPO_ERR_UNSUPPORTED;
+  SeqGradArgs a;
+  a.X = layer->X; a.Delta = layer->Delta; a.off = layer->seq_offsets_dev; a.off_host = layer->seq_offsets_host; a.c = nullptr; a.out = dW;
+  a.d_in = layer->d_in; a.d_out = layer->d_out; a.n_seq = layer->n_seq; a.n_tokens = (int)layer->n_tokens;
+  a.row0 = 0; a.rows = layer->d_out; a.out_row0 = 0; a.out_seq_stride = 0;
+  a.beta = 0.f; a.per_sequence = false; a.bf16 = true;
+  return launch_seq_grad_stream_waves(a, waves, static_cast<hipStream_t>(stream)) == hipSuccess ? ISOPO_OK : ISOPO_ERR_HIP;
+}
+
 }  // extern "C"

@@ -59,6 +59,9 @@ ContractionPlan plan_contraction(int rows, int d_in, int n_tokens, int n_seq, co
 hipError_t launch_seq_grad(const SeqGradArgs& a, hipStream_t s);
 // bf16 only, c == nullptr only: the direct-to-LDS streaming kernel (launch_seq_grad routes to it).
 hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s);
+// Schedule probe: the plain sum over all tokens (c == nullptr, not per sequence) on the 256x256 tile with four or
+// eight waves per workgroup; hipErrorInvalidValue where the plan would take the 128x128 tile.
+hipError_t launch_seq_grad_stream_waves(const SeqGradArgs& a, int waves, hipStream_t s);
 
 // K partials from the stash:  for p in [p0, p1):  acc[i][j] += S[i][p] * S[j][p].
 struct StashGramArgs {
@@ -241,5 +244,10 @@ hipError_t launch_eigh_solve(const EighSolveArgs& a, hipStream_t s);
 // kProbeWorkgroups workgroups of 256 threads; 2 * 128 * 128 * 32 flop per wave and trip.
 constexpr int kProbeWorkgroups = 256;
 hipError_t launch_mfma_loop(int shape, const void* operands, float* sink, int iters, hipStream_t s);
+// `workgroups` workgroups of `waves` waves (2, 4, 8 or 16) stream the buffer (bytes: a multiple of 8 * 32 KiB,
+// workgroup b walks its (b mod 8)-th eighth) into a ring of `stages` (2 or 4) LDS stages of 32 KiB, `iters`
+// stages each; sink: float [workgroups].
+hipError_t launch_lds_dma_ring(const void* buf, size_t bytes, int waves, int stages, int workgroups, int iters,
+                               float* sink, hipStream_t s);
 
 }  // namespace isopo

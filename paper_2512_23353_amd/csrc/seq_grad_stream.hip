@@ -124,23 +124,28 @@ __device__ __forceinline__ void strip_tile_coords(int tile, int tiles_m, int til
   tile_n = c0 + in_strip % w;
 }
 
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false>
-__global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
+// NW: waves per workgroup.  Four (a 2 x 2 arrangement of BM/2 x BN/2 wave tiles) in every launch the library
+// makes itself; eight (2 x 4, wave tiles of BM/2 x BN/4, two waves per SIMD, half the DMA instructions per
+// wave) exists for the schedule probe, which shows that the two land on the same rate on real operands.
+template <int BM, int BN, int NSTAGE, bool PER_SEQ, bool PERSIST, bool TILED, bool WTD, int NW>
+__device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
   static_assert(PER_SEQ || !TILED, "tile order is a layout of the per-sequence stash");
   static_assert(!PER_SEQ || !WTD, "the coefficients weight the sum over all tokens");
   // the 16x16x32 inner loop: the tile-order stash and the sum over all tokens (the row-major stash keeps the
   // 32x32x16 loop, whose accumulator blocks its transposing epilogue is written for)
   constexpr bool MF16 = TILED || !PER_SEQ;
   static_assert(PER_SEQ || !PERSIST, "the persistent mode serves the per-sequence gradients");
-  constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
+  static_assert(NW == 4 || (NW == 8 && (TILED || !PER_SEQ)), "eight waves: the 16x16x32 loop only");
+  constexpr int WNC = NW / 2, NT = 64 * NW;                    // waves along the tile's columns; threads
+  constexpr int WM = BM / 2, WN = BN / WNC, FM = WM / 32, FN = WN / 32;
   constexpr unsigned PA = BM * 2, PB = BN * 2;                 // LDS row pitch, bytes (no padding: swizzled)
   constexpr unsigned A_BYTES = BK * PA, B_BYTES = BK * PB, STAGE = A_BYTES + B_BYTES;
-  constexpr int LA = A_BYTES / 1024 / 4, LB = B_BYTES / 1024 / 4;   // 1 KiB wave-loads per wave and tile
+  constexpr int LA = A_BYTES / 1024 / NW, LB = B_BYTES / 1024 / NW;   // 1 KiB wave-loads per wave and tile
   constexpr int RA = 1024 / PA, RB = 1024 / PB;                // tile rows per wave-load
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const unsigned smem_base = (unsigned)(size_t)(lds_void_ptr)smem;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WNC, wn = wave % WNC;
 
   // Persistent mode (per-sequence only): the grid is a chosen number of workgroups, a multiple of eight;
   // the workgroups of XCD x pull that XCD's work items one at a time from the counter queue[x].  The
@@ -264,17 +269,17 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       n_seg = __builtin_amdgcn_readfirstlane(sh_meta[0]);
       n_tiles = __builtin_amdgcn_readfirstlane(sh_meta[1]);
       // coefficient -> ratio to the segment before (1 for the first), in place
-      float ratio[kMaxSeg / 256];
+      float ratio[kMaxSeg / NT];
 #pragma unroll
-      for (int q = 0; q < kMaxSeg / 256; ++q) {
-        const int k = tid + 256 * q;
+      for (int q = 0; q < kMaxSeg / NT; ++q) {
+        const int k = tid + NT * q;
         ratio[q] = (k > 0 && k < n_seg) ? sh_seg_c[k - 1] / sh_seg_c[k] : 1.f;
       }
       if (tid == 0) sh_last_c = n_seg > 0 ? sh_seg_c[n_seg - 1] : 0.f;
       __syncthreads();
 #pragma unroll
-      for (int q = 0; q < kMaxSeg / 256; ++q) {
-        const int k = tid + 256 * q;
+      for (int q = 0; q < kMaxSeg / NT; ++q) {
+        const int k = tid + NT * q;
         if (k < n_seg) sh_seg_c[k] = ratio[q];
       }
       __syncthreads();
@@ -351,7 +356,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       // of two register sets) and, once the row is done with it, the next block's A fragment i (in place),
       // and a share of the eight DMA instructions of the block AHEAD ahead.  One barrier per block.
       constexpr int FM16 = WM / 16, FN16 = WN / 16, NMF16 = FM16 * FN16;
-      static_assert(FM16 == FN16, "square wave tile");
+      static_assert(NMF16 - (FM16 / 2) * FN16 >= FN16 + FM16 / 2, "the second half's MFMAs carry the next block's fragment reads");
       constexpr int LPT = LA + LB, AHEAD = NSTAGE - 1;
       typedef float f32x4v __attribute__((ext_vector_type(4)));
       unsigned adA[FM16], adB[FN16];
@@ -546,8 +551,12 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
       // one 1 KiB store of the wave.
       typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
       const int tile_row = (m0 - p.out_row0) / BM;
+      // the wave's quadrant of the tile, and inside each 16-row strip of the quadrant the wave's pieces (all of
+      // them with four waves, the left or the right half with eight)
+      constexpr int QP = (BN / 2) / 32;                        // pieces per strip of a quadrant
+      const int quad = wm * 2 + wn / (WNC / 2), piece0 = (wn % (WNC / 2)) * (FN16 / 2);
       u16* tb = static_cast<u16*>(p.out) + (size_t)item * p.out_seq_stride +
-                ((size_t)tile_row * p.tiles_n + tile_n) * (BM * BN) + (size_t)wave * (WM * WN);
+                ((size_t)tile_row * p.tiles_n + tile_n) * (BM * BN) + (size_t)quad * ((BM / 2) * (BN / 2));
 #pragma unroll
       for (int i = 0; i < FM16; ++i)
 #pragma unroll
@@ -559,7 +568,7 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
           pk[3] = pack_bf16(rd16(acc[i][2 * jp + 1][2]), rd16(acc[i][2 * jp + 1][3]));
           // written once and read after the launch: non-temporal, so the stash does not push the operand
           // panels out of the L2
-          __builtin_nontemporal_store(pk, (u32x4*)(tb + (i * (FN16 / 2) + jp) * 512 + lane * 8));
+          __builtin_nontemporal_store(pk, (u32x4*)(tb + (i * QP + piece0 + jp) * 512 + lane * 8));
         }
       if constexpr (PERSIST) continue; else break;
     }
@@ -748,6 +757,16 @@ __global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams 
 }
 
 
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false>
+__global__ __launch_bounds__(256, OCC) void seq_grad_stream_kernel(StreamParams p) {
+  seq_grad_stream_body<BM, BN, NSTAGE, PER_SEQ, PERSIST, TILED, WTD, 4>(p);
+}
+
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false>
+__global__ __launch_bounds__(512, OCC) void seq_grad_stream_waves8_kernel(StreamParams p) {
+  seq_grad_stream_body<BM, BN, NSTAGE, PER_SEQ, PERSIST, TILED, WTD, 8>(p);
+}
+
 // o[i] = beta * o[i] (0 for beta = 0, whatever o held), ahead of the atomic accumulation.
 __global__ __launch_bounds__(256) void apply_beta_kernel(float* __restrict__ o, long long n, float beta) {
   const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
@@ -787,7 +806,7 @@ __global__ void queue_zero_kernel(unsigned* queue) {
 
 // n_wg > 0 (per-sequence mode, 256x256 tile): persistent launch of n_wg workgroups, a multiple of eight,
 // pulling work from `queue` (eight device counters, zeroed here on the stream).
-template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false>
+template <int BM, int BN, int NSTAGE, int OCC, bool PER_SEQ, bool PERSIST = false, bool TILED = false, bool WTD = false, int NW = 4>
 hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStream_t s, int n_wg = 0,
                          unsigned* queue = nullptr) {
   StreamParams p;
@@ -808,7 +827,11 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   p.n_blocks = (unsigned)pl.blocks;
   constexpr size_t ring = (size_t)NSTAGE * BK * (BM + BN) * 2;
   constexpr size_t smem = ring > 32768 ? ring : 32768;      // the stash epilogue stages 8 KiB per wave
-  auto kern = seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST, TILED, WTD>;
+  static_assert(NW == 4 || NW == 8, "waves per workgroup");
+  auto kern = [] {
+    if constexpr (NW == 8) return &seq_grad_stream_waves8_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST, TILED, WTD>;
+    else return &seq_grad_stream_kernel<BM, BN, NSTAGE, OCC, PER_SEQ, PERSIST, TILED, WTD>;
+  }();
   // once per process (static initialisation is thread-safe); a failure is returned by every call
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -825,9 +848,9 @@ hipError_t launch_stream(const SeqGradArgs& a, const ContractionPlan& pl, hipStr
   }
   if constexpr (PERSIST) {
     hipLaunchKernelGGL(queue_zero_kernel, dim3(1), dim3(64), 0, s, queue);
-    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(256), smem, s, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_wg), dim3(64 * NW), smem, s, p);
   } else {
-    hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(256), smem, s, p);
+    hipLaunchKernelGGL(kern, dim3(p.n_blocks), dim3(64 * NW), smem, s, p);
   }
   return hipGetLastError();
 }
@@ -854,6 +877,15 @@ hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
     return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false, false, false, true>(a, pl, s)
                           : launch_stream<128, 128, 4, 2, false, false, false, true>(a, pl, s);
   return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false>(a, pl, s) : launch_stream<128, 128, 4, 2, false>(a, pl, s);
+}
+
+// Schedule probe: the plain sum over all tokens on the 256x256 tile with four or eight waves per workgroup.
+hipError_t launch_seq_grad_stream_waves(const SeqGradArgs& a, int waves, hipStream_t s) {
+  if (a.per_sequence || a.c != nullptr || (waves != 4 && waves != 8)) return hipErrorInvalidValue;
+  const ContractionPlan pl = plan_contraction(a.rows, a.d_in, a.n_tokens, a.n_seq, a.off_host, false);
+  if (pl.tile != 256) return hipErrorInvalidValue;
+  return waves == 8 ? launch_stream<256, 256, 4, 1, false, false, false, false, 8>(a, pl, s)
+                    : launch_stream<256, 256, 4, 1, false>(a, pl, s);
 }
 
 }  // namespace isopo

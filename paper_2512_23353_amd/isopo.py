@@ -39,7 +39,7 @@ EXPORTS = ("isopo_layer_gram_plan", "isopo_gram_cost_model", "isopo_contraction_
            "isopo_fisher_samples_block_workspace", "isopo_fisher_samples_block",
            "isopo_weighted_grad_scratch", "isopo_weighted_grad_prescaled",
            "isopo_gram_norms", "isopo_rescale", "isopo_ntk_eigh_workspace", "isopo_ntk_eigh",
-           "isopo_transform_eigh", "isopo_probe_mfma_loop", "isopo_status_string", "isopo_version")
+           "isopo_transform_eigh", "isopo_probe_mfma_loop", "isopo_probe_lds_dma", "isopo_probe_contraction_waves", "isopo_status_string", "isopo_version")
 
 
 class IsopoError(RuntimeError):
@@ -142,6 +142,10 @@ def load() -> ctypes.CDLL:
     lib.isopo_transform_eigh.restype = ctypes.c_int
     lib.isopo_probe_mfma_loop.argtypes = [i32, vp, vp, i32, vp]
     lib.isopo_probe_mfma_loop.restype = ctypes.c_int
+    lib.isopo_probe_lds_dma.argtypes = [vp, sz, i32, i32, i32, i32, vp, vp]
+    lib.isopo_probe_lds_dma.restype = ctypes.c_int
+    lib.isopo_probe_contraction_waves.argtypes = [lp, i32, vp, vp]
+    lib.isopo_probe_contraction_waves.restype = ctypes.c_int
     lib.isopo_status_string.argtypes = [ctypes.c_int]
     lib.isopo_status_string.restype = ctypes.c_char_p
     lib.isopo_version.argtypes = []
@@ -587,6 +591,26 @@ def probe_mfma_loop(shape: int, operands: torch.Tensor, sink: torch.Tensor, iter
         raise ValueError("operands / sink too small for the probe")
     _check(load().isopo_probe_mfma_loop(int(shape), operands.data_ptr(), sink.data_ptr(), int(iters), _stream(stream)),
            "isopo_probe_mfma_loop")
+
+
+def probe_lds_dma(buf: torch.Tensor, waves: int, stages: int, workgroups: int, iters: int, sink: torch.Tensor,
+                  stream=None) -> None:
+    """Diagnostic: `workgroups` workgroups of `waves` waves keep a ring of `stages` 32 KiB LDS stages filled from
+    `buf` by DMA loads for `iters` stages each (workgroups * iters * 32768 bytes in all)."""
+    if sink.dtype != torch.float32 or sink.numel() < workgroups:
+        raise ValueError("sink must hold one float per workgroup")
+    _check(load().isopo_probe_lds_dma(buf.data_ptr(), buf.numel() * buf.element_size(), int(waves), int(stages),
+                                      int(workgroups), int(iters), sink.data_ptr(), _stream(stream)), "isopo_probe_lds_dma")
+
+
+def probe_contraction_waves(layer: Layer, waves: int, dW: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Diagnostic: dW = Delta^T X by the 256x256-tile contraction with 4 (the library's own launch) or 8 waves
+    per workgroup."""
+    if dW is None:
+        dW = torch.empty((layer.d_out, layer.d_in), dtype=torch.float32, device=layer.device)
+    _check(load().isopo_probe_contraction_waves(layer.ref(), int(waves), dW.data_ptr(), _stream(stream)),
+           "isopo_probe_contraction_waves")
+    return dW
 
 
 def layer_step(layer: Layer, A: torch.Tensor, variant="interacting", lam: float = 0.0,

@@ -131,6 +131,9 @@ int main() {
     EXPECT(isopo_weighted_grad_stash_bf16(&l, nullptr, nullptr, ISOPO_STASH_ROW_MAJOR, 0.f, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
     EXPECT(isopo_weighted_grad_stash_bf16(nullptr, nullptr, nullptr, ISOPO_STASH_TILE_ORDER, 0.f, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
     EXPECT(isopo_contraction_plan(&l, 1, nullptr) == ISOPO_ERR_INVALID_ARG);
+    EXPECT(isopo_probe_contraction_waves(&l, 8, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
+    EXPECT(isopo_probe_contraction_waves(nullptr, 4, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
+    EXPECT(isopo_probe_lds_dma(nullptr, 8 * 32768, 4, 2, 8, 1, nullptr, nullptr) == ISOPO_ERR_INVALID_ARG);
     const std::vector<int32_t> bad1 = {1, 3, 7}, bad2 = {0, 5, 3}, bad3 = {0, 3, 6};
     for (const auto* b : {&bad1, &bad2, &bad3}) {
       l.seq_offsets_host = b->data();

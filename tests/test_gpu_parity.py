@@ -474,6 +474,48 @@ def test_transform_failing_pivot_in_any_panel(gpu_device, m, k):
     assert_c_close(c[1], ref, 1e-5, f"m={m}, the solvable problem beside a failing one")
 
 
+def test_schedule_probes(gpu_device):
+    """The two diagnostics behind the benchmark's schedule probe: the eight-wave contraction gives the four-wave
+    launch's dW, which is isopo_weighted_grad's (to fp32 rounding: with few tiles the token range is split and the
+    parts are added with atomics); the LDS-DMA probe runs for every wave count and ring depth and rejects what it
+    does not serve."""
+    # enough tokens for the plan to take the 256x256 tile (with a token split), ragged tile edges in d_out
+    prob = wl.custom_layer(1024, 1100 // 8 * 8, [3000, 0, 777, 1, 6500, 3100], dtype="bf16", seed=41, sigma_delta=1e-2)
+    layer, _ = to_device(prob, gpu_device)
+    assert isopo.contraction_plan(layer.ref(), False)["tile"] == 256
+    want = isopo.weighted_grad(layer, None)
+    four = isopo.probe_contraction_waves(layer, 4)
+    eight = isopo.probe_contraction_waves(layer, 8)
+    torch.cuda.synchronize()
+    for got in (four, eight):
+        assert float((got - want).norm() / want.norm()) < 1e-6
+    G = orc.seq_logprob_grads(wl.to_oracle(prob.X), wl.to_oracle(prob.Delta), prob.seq_offsets)
+    ones = np.ones(prob.n_seq)
+    assert_dW_close(eight.cpu().numpy(), orc.weighted_grad(G, ones), TOL["bf16"], "eight waves", orc.weighted_grad_abs(G, ones))
+    small = wl.custom_layer(64, 128, [40, 9], dtype="bf16", seed=42)
+    small_layer, _ = to_device(small, gpu_device)
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.probe_contraction_waves(small_layer, 8)
+    assert e.value.status == 3
+    with pytest.raises(isopo.IsopoError) as e:
+        isopo.probe_contraction_waves(layer, 6)
+    assert e.value.status == 1
+    buf = torch.ones(8 * 32768 * 4, dtype=torch.uint8, device=gpu_device)
+    sink = torch.zeros(64, dtype=torch.float32, device=gpu_device)
+    for waves in (2, 4, 8, 16):
+        for stages in (2, 4):
+            isopo.probe_lds_dma(buf, waves, stages, 16, 50, sink)
+    torch.cuda.synchronize()
+    for bad in (dict(waves=3), dict(stages=3), dict(workgroups=0), dict(iters=0)):
+        kw = dict(waves=4, stages=2, workgroups=8, iters=10)
+        kw.update(bad)
+        with pytest.raises(isopo.IsopoError) as e:
+            isopo.probe_lds_dma(buf, kw["waves"], kw["stages"], kw["workgroups"], kw["iters"], sink)
+        assert e.value.status == 1
+    with pytest.raises(isopo.IsopoError):
+        isopo.probe_lds_dma(buf[:1000], 4, 2, 8, 10, sink)
+
+
 def test_bad_arguments_on_device_calls(gpu_device):
     prob = wl.custom_layer(128, 128, [10, 20], dtype="bf16", seed=9)
     layer, A = to_device(prob, gpu_device)
