@@ -442,9 +442,10 @@ isopo_status isopo_probe_lds_dma(const void* buf, size_t bytes, int32_t waves, i
                                  int32_t iters, float* sink, void* stream);
 
 /* Diagnostic: dW [d_out, d_in] fp32 = Delta^T X (isopo_weighted_grad with c = NULL, stash = NULL, beta = 0) by
- * the matrix-core contraction on its 256 x 256 tile with 4 waves per workgroup (the launch the library makes: a
- * 2 x 2 arrangement of 128 x 128 wave tiles, one wave per SIMD, 256 accumulators per lane) or with 8 (2 x 4,
- * 128 x 64 wave tiles, two waves per SIMD, twice as many waves issuing the operand loads).  Same result; the
+ * the matrix-core contraction on its 256 x 256 tile with 4 waves per workgroup (a 2 x 2 arrangement of
+ * 128 x 128 wave tiles, one wave per SIMD, 256 accumulators per lane: what the per-sequence launch behind
+ * isopo_layer_gram uses) or with 8 (2 x 4, 128 x 64 wave tiles, two waves per SIMD, twice as many waves issuing
+ * the operand loads: what isopo_weighted_grad launches for the sums over all tokens).  Same result; the
  * benchmark times both on the workload and on zero operands.  bf16 layers whose launch plan takes the
  * 256 x 256 tile (isopo_contraction_plan), else ISOPO_ERR_UNSUPPORTED. */
 isopo_status isopo_probe_contraction_waves(const isopo_layer* layer, int32_t waves, float* dW, void* stream);

@@ -17,10 +17,11 @@
 //    transpose reads bank-conflict free.
 //  * Two inner loops.  The tile-order stash and the sum over all tokens use the
 //    16x16x32 MFMA (less energy per flop, and the part runs at its power cap): a
-//    token block is one K = 32 step of 64 MFMAs per wave; the eight DMA
-//    instructions of the block NSTAGE-1 ahead go out behind the first half of
-//    them, the barrier sits mid-block, the next block's fragments are read behind
-//    the second half.  The row-major stash keeps the 32x32x16 MFMA, whose
+//    token block is one K = 32 step of 64 MFMAs per wave (32 with eight waves per
+//    workgroup, which the sums over all tokens use on the 256x256 tile); the DMA
+//    instructions of the block NSTAGE-1 ahead (eight per wave, or four) go out
+//    behind the first half of them, the barrier sits mid-block, the next block's
+//    fragments are read behind the second half.  The row-major stash keeps the 32x32x16 MFMA, whose
 //    accumulator blocks its transposing epilogue is written for: fragments
 //    double-buffered in registers, the reads of the next half block interleaved
 //    one-to-one with the MFMAs of the current one, the DMA instructions between
@@ -124,9 +125,13 @@ __device__ __forceinline__ void strip_tile_coords(int tile, int tiles_m, int til
   tile_n = c0 + in_strip % w;
 }
 
-// NW: waves per workgroup.  Four (a 2 x 2 arrangement of BM/2 x BN/2 wave tiles) in every launch the library
-// makes itself; eight (2 x 4, wave tiles of BM/2 x BN/4, two waves per SIMD, half the DMA instructions per
-// wave) exists for the schedule probe, which shows that the two land on the same rate on real operands.
+// NW: waves per workgroup.  Four: a 2 x 2 arrangement of BM/2 x BN/2 wave tiles, one wave per SIMD on the
+// 256x256 tile with its accumulators pinned to the AGPRs.  Eight (16x16x32 loop only): 2 x 4, wave tiles of
+// BM/2 x BN/4, two waves per SIMD, 128 accumulators per lane in VGPRs, half the DMA instructions per wave, so
+// that twice as many waves issue operand loads.  On the workload's operands, where the board's power limit sets
+// the rate, the two are within a few per cent of each other: the per-sequence launch is no faster with eight
+// and keeps four; the sums over all tokens are 1 - 5 % faster with eight (more where the launch is not at the
+// power limit) and take eight on the 256x256 tile.
 template <int BM, int BN, int NSTAGE, bool PER_SEQ, bool PERSIST, bool TILED, bool WTD, int NW>
 __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
   static_assert(PER_SEQ || !TILED, "tile order is a layout of the per-sequence stash");
@@ -874,9 +879,10 @@ hipError_t launch_seq_grad_stream(const SeqGradArgs& a, hipStream_t s) {
   if (a.per_sequence)
     return pl.tile == 256 ? launch_stream<256, 256, 4, 1, true>(a, pl, s) : launch_stream<128, 128, 4, 2, true>(a, pl, s);
   if (a.c != nullptr)       // the weighted sum: segments of one sequence each, accumulators rescaled in between
-    return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false, false, false, true>(a, pl, s)
+    return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false, false, false, true, 8>(a, pl, s)
                           : launch_stream<128, 128, 4, 2, false, false, false, true>(a, pl, s);
-  return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false>(a, pl, s) : launch_stream<128, 128, 4, 2, false>(a, pl, s);
+  return pl.tile == 256 ? launch_stream<256, 256, 4, 1, false, false, false, false, 8>(a, pl, s)
+                        : launch_stream<128, 128, 4, 2, false>(a, pl, s);
 }
 
 // Schedule probe: the plain sum over all tokens on the 256x256 tile with four or eight waves per workgroup.
