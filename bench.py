@@ -162,8 +162,9 @@ def schedule_probe(dev) -> dict:
     """Is the contraction bound by its schedule or by the board?  (1) isopo_probe_lds_dma: the rate at which a
     workgroup streams an L2-resident buffer into LDS with the contraction's DMA loads, against the number of waves
     that issue them; (2) isopo_probe_contraction_waves: config 3's gate projection (dW = Delta^T X, 256x256 tiles)
-    with the library's 4 waves per workgroup and with 8 (half the registers per wave, twice the DMA issuers), on
-    the workload's operands and on zeros (where the part holds its top clock)."""
+    with 4 waves per workgroup (the per-sequence launch's shape) and with 8 (what the sums over all tokens launch:
+    half the registers per wave, twice the DMA issuers), on the workload's operands and on zeros (where the part
+    holds its top clock)."""
     import numpy as np
     import torch
     from paper_2512_23353_amd import isopo, workloads as wl

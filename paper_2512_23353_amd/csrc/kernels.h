@@ -34,7 +34,7 @@ struct SeqGradArgs {
   bool tile_order = false;
 };
 // The per-sequence bf16 contraction can leave its result in tile order: tiles of T x T outputs (T the plan's
-// tile, 256 or 128) in row-major tile order; inside a tile the four waves' (T/2 x T/2) quadrants one after the
+// tile, 256 or 128) in row-major tile order; inside a tile its four (T/2 x T/2) quadrants one after the
 // other (upper left, upper right, lower left, lower right); inside a quadrant its strips of 16 rows, top down,
 // each strip as pieces of 16 rows x 32 columns, left to right; a piece is 1 KiB, 16 bytes per lane l: its
 // element 8 l + q (q = 0..7) is row 4 (l / 16) + q % 4, column l % 16 + 16 (q / 4) of the piece.  That is what
