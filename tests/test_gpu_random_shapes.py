@@ -59,7 +59,7 @@ def _draw_case(seed):
     return dtype, d_in, d_out, lengths
 
 
-@pytest.mark.parametrize("seed", list(range(24)) + list(range(100, 108)) + list(range(200, 206)) + list(range(300, 304)))
+@pytest.mark.parametrize("seed", list(range(32)) + list(range(100, 112)) + list(range(200, 210)) + list(range(300, 306)))
 def test_random_shape(gpu_device, seed):
     dtype, d_in, d_out, lengths = _draw_case(seed)
     print(f"seed {seed}: {dtype} d_in={d_in} d_out={d_out} lengths={lengths}", flush=True)
