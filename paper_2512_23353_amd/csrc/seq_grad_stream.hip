@@ -74,17 +74,6 @@ struct StreamParams {
   unsigned* queue;                 // persistent mode: eight work counters, one per XCD, zero at launch
 };
 
-// Raw buffer descriptor over [base, base + bytes): loads beyond it return zero.
-__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
-  const unsigned long long a = (unsigned long long)base;
-  v4i r;
-  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-  r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));
-  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-  r[3] = 0x00020000;
-  return r;
-}
-
 // 16 bytes per lane from a buffer straight into LDS: lane l lands at lds_addr + 16*l.
 // Inline asm, so that the compiler's LDS-DMA tracking does not put a vmcnt(0) before
 // every later LDS read; the kernel orders them itself with s_waitcnt vmcnt(n) + s_barrier.
@@ -224,7 +213,9 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
     // unscaled, and where a new segment opens the accumulators are multiplied once by c_previous / c_new.
     // The epilogue multiplies by the last segment's coefficient.  No operand is scaled or rounded.
     constexpr int kMaxSeg = 1024;            // the library's limit on sequences per layer
-    struct Cursor { int k, tok, end, left; };
+    // What the loads take next: the address of the next token block's first row in Delta and in X, the rows
+    // left of the range it lies in (<= 0: an all-zero block); weighted sum: the segment and its blocks left.
+    struct Cursor { unsigned long long pa, pb; int rem, k, left; };
     [[maybe_unused]] int n_seg = 0;
     [[maybe_unused]] float last_c = 0.f;
     [[maybe_unused]] int* seg_tok = nullptr;
@@ -290,39 +281,60 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
       __syncthreads();
       last_c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sh_last_c)));
     }
-    // The next token block the loads take (they run ahead of the multiplications): first token row and valid
-    // rows (0: an all-zero block).  Every segment is walked in an even number of blocks, the last one all
-    // zero if need be, because the main loop takes two blocks per trip.  One branch per block, taken only
-    // where a segment ends (the wave has nothing else to issue while a branch resolves).
+    // The loads run ahead of the multiplications.  Their cursor moves on by one token block per step with two
+    // 64-bit additions (no multiplication of a token index by a row length on the way); the buffer descriptors
+    // of a block cover its valid rows only.  Weighted sum: every segment is walked in an even number of blocks,
+    // the last one all zero if need be, because the main loop takes two blocks per trip; one branch per block,
+    // taken only where a segment ends.
+    const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
+    auto uniform64 = [](unsigned long long a) {
+      const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a);
+      const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));
+      return ((unsigned long long)hi << 32) | lo;
+    };
+    auto range_open = [&](Cursor& cur, int tok, int rows) {
+      cur.pa = uniform64((unsigned long long)(p.Delta + (size_t)tok * p.d_out));
+      cur.pb = uniform64((unsigned long long)(p.X + (size_t)tok * p.d_in));
+      cur.rem = rows;
+    };
     auto segment_open = [&](Cursor& cur) {
       if (cur.k < n_seg) {
-        cur.tok = __builtin_amdgcn_readfirstlane(seg_tok[cur.k]);
-        cur.end = __builtin_amdgcn_readfirstlane(seg_end[cur.k]);
-        cur.left = ((cur.end - cur.tok + BK - 1) / BK + 1) & ~1;
+        const int tok = __builtin_amdgcn_readfirstlane(seg_tok[cur.k]);
+        const int len = __builtin_amdgcn_readfirstlane(seg_end[cur.k]) - tok;
+        range_open(cur, tok, len);
+        cur.left = ((len + BK - 1) / BK + 1) & ~1;
       } else {
-        cur.tok = 0; cur.end = 0; cur.left = 0x7fffffff;       // past the last segment: all-zero blocks
+        cur.rem = 0; cur.left = 0x7fffffff;                    // past the last segment: all-zero blocks
       }
     };
-    auto next_block = [&](Cursor& cur, int it, int& tok0, int& rows) {
-      if constexpr (WTD) {
-        const int rem = cur.end - cur.tok;
-        rows = rem < 0 ? 0 : (rem > BK ? BK : rem);
-        tok0 = rows > 0 ? cur.tok : 0;
-        cur.tok += BK;
-        if (__builtin_expect(--cur.left == 0, 0)) {
-          ++cur.k;
-          segment_open(cur);
-        }
-      } else {
-        tok0 = t0 + it * BK;
-        rows = n_rows - it * BK;
-        rows = rows < 0 ? 0 : (rows > BK ? BK : rows);
+    // descriptors of the cursor's block, then one block on
+    auto next_block = [&](Cursor& cur, v4i& ra, v4i& rb) {
+      int rows;
+      asm("s_max_i32 %0, %1, 0\n\ts_min_i32 %0, %0, %2" : "=s"(rows) : "s"(cur.rem), "n"(BK) : "scc");
+      ra[0] = (int)(unsigned)cur.pa; ra[1] = (int)((unsigned)(cur.pa >> 32) & 0xffffu);
+      ra[2] = (int)((unsigned)rows * rbA); ra[3] = 0x00020000;
+      rb[0] = (int)(unsigned)cur.pb; rb[1] = (int)((unsigned)(cur.pb >> 32) & 0xffffu);
+      rb[2] = (int)((unsigned)rows * rbB); rb[3] = 0x00020000;
+      cur.pa += (unsigned long long)BK * rbA;
+      cur.pb += (unsigned long long)BK * rbB;
+      cur.rem -= BK;
+      if constexpr (WTD) --cur.left;
+    };
+    // weighted sum, after next_block: on to the next segment once this one's blocks are out
+    [[maybe_unused]] auto segment_step = [&](Cursor& cur) {
+      if (__builtin_expect(cur.left == 0, 0)) {
+        ++cur.k;
+        segment_open(cur);
       }
     };
     Cursor ld;
-    ld.k = 0; ld.tok = 0; ld.end = 0; ld.left = 0;
-    if constexpr (WTD) segment_open(ld);
-    const unsigned rbA = (unsigned)p.d_out * 2u, rbB = (unsigned)p.d_in * 2u;
+    ld.k = 0; ld.left = 0;
+    if constexpr (WTD) {
+      ld.pa = 0; ld.pb = 0; ld.rem = 0;
+      segment_open(ld);
+    } else {
+      range_open(ld, t0, n_rows);
+    }
 
     // 16-byte column swizzle of token row r.  The 16x16x32 fragments (TILED) are read by lane groups whose
     // rows lie 8 apart, so that variant also moves rows 8..15 and 24..31 by two columns.
@@ -342,11 +354,10 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
     }
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     auto issue_loads = [&](int it) {
-      int tok0, rows;
-      next_block(ld, it, tok0, rows);
-      v4i ra = make_rsrc(p.Delta + (size_t)tok0 * p.d_out, (unsigned)rows * rbA);
-      v4i rb = make_rsrc(p.X + (size_t)tok0 * p.d_in, (unsigned)rows * rbB);
-      const unsigned stage = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+      v4i ra, rb;
+      next_block(ld, ra, rb);
+      if constexpr (WTD) segment_step(ld);
+      const unsigned stage = smem_base + ((unsigned)it % NSTAGE) * STAGE;
 #pragma unroll
       for (int q = 0; q < LA; ++q) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
 #pragma unroll
@@ -404,19 +415,32 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
         for (int i = 0; i < FM16; ++i) fa[i] = frag(smem_base + adA[i], PA);
 #pragma unroll
         for (int j = 0; j < FN16; ++j) fb[0][j] = frag(smem_base + adB[j], PB);
+        // The descriptors of the next block's loads are formed a block ahead, behind the barrier, so that this
+        // scalar work issues between MFMAs and not ahead of a block's first one.
+        constexpr bool PIPE = true;
+        [[maybe_unused]] v4i ra_n, rb_n;
+        if constexpr (PIPE) {
+          next_block(ld, ra_n, rb_n);
+          if constexpr (WTD) segment_step(ld);
+        }
         // LATE: the two waves of the lower tile half take the other of every two read slots, so that the LDS
         // serves two waves' fragment reads at a time, not four (compile-time, as CUR, so that the bodies stay
         // straight-line code)
-        auto token_block = [&](int it, auto cur_c, auto late_c) {
+        // SCALE (weighted sum only): 1 in a segment's first block, 2 in its last.  The accumulators change their
+        // unit from the previous segment's coefficient to this one's by a factor r; those of the first RB rows
+        // take it in the last block of the segment before, behind the MFMAs of the other rows, the others in
+        // this segment's first block, behind the MFMAs of the first RB rows: every accumulator is multiplied
+        // once between its last MFMA of one segment and its first of the next, and the matrix pipes never wait
+        // for the multiplications.
+        auto token_block = [&](int it, auto cur_c, auto late_c, auto scale_c, [[maybe_unused]] float r) {
           constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
           constexpr bool LATE = decltype(late_c)::value;
-          const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
-          const int nb = it + AHEAD;
-          int tok_nb, rows;
-          next_block(ld, nb, tok_nb, rows);
-          const v4i ra = make_rsrc(p.Delta + (size_t)tok_nb * p.d_out, (unsigned)rows * rbA);
-          const v4i rb = make_rsrc(p.X + (size_t)tok_nb * p.d_in, (unsigned)rows * rbB);
-          const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
+          constexpr int SCALE = decltype(scale_c)::value;
+          static_assert(SCALE == 0 || NMF16 * 4 <= 128, "the multiplications are written for accumulators in VGPRs");
+          const unsigned sn = smem_base + ((unsigned)(it + 1) % NSTAGE) * STAGE;
+          v4i ra, rb;                              // of block it + AHEAD
+          if constexpr (PIPE) { ra = ra_n; rb = rb_n; } else next_block(ld, ra, rb);
+          const unsigned stage = smem_base + ((unsigned)(it + AHEAD) % NSTAGE) * STAGE;
           // When the accumulator tile fills the AGPRs the MFMA is written as asm, so that every accumulator
           // stays where it is (left to itself the register allocator shuttles them through VGPRs).
 #define ISOPO_MFMA16(i, j)                                                                                            \
@@ -436,8 +460,17 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
             for (int j = 0; j < FN16; ++j) {
               const int idx = i * FN16 + j;
               ISOPO_MFMA16(i, j);
+              if constexpr (SCALE == 1) {
+#pragma unroll
+                for (int q = idx * REST / HEAD; q < (idx + 1) * REST / HEAD; ++q)
+                  acc[RB + q / FN16][q % FN16] = acc[RB + q / FN16][q % FN16] * r;
+              }
 #pragma unroll
               for (int q = idx * LPT / HEAD; q < (idx + 1) * LPT / HEAD; ++q) {
+                // builtin MFMAs (plain sum): the scheduler would move every load to the top of the block, ahead
+                // of the MFMAs.  (The weighted sum is faster without the pins: 6.02 against 6.15 ms on config 3's
+                // gate projection.)
+                if constexpr (NMF16 * 4 <= 128 && !WTD) __builtin_amdgcn_sched_barrier(0);
                 if (q < LA) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
                 else load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + (q - LA)) * 1024, offB[q - LA]);
               }
@@ -445,6 +478,12 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
           // block it + 1 has landed (this wave's part; the barrier makes it everyone's)
           __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 1) * LPT) & 15) | ((((AHEAD - 1) * LPT) >> 4) << 14));
           __builtin_amdgcn_s_barrier();
+          // the descriptors the next block's loads need: scalar work that issues between this half's MFMAs
+          // instead of ahead of the next block's first one
+          if constexpr (PIPE) {
+            next_block(ld, ra_n, rb_n);
+            if constexpr (WTD) segment_step(ld);
+          }
           // the other rows: behind their MFMAs the fragments of block it + 1, the B ones into the other register
           // set, the A ones in place: those of the first RB rows at once, the others as their rows end
 #pragma unroll
@@ -453,6 +492,11 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
             for (int j = 0; j < FN16; ++j) {
               ISOPO_MFMA16(i, j);
               const int k = (i - RB) * FN16 + j;                      // 0 .. REST - 1
+              if constexpr (SCALE == 2) {
+#pragma unroll
+                for (int q = k * HEAD / REST; q < (k + 1) * HEAD / REST; ++q)
+                  acc[q / FN16][q % FN16] = acc[q / FN16][q % FN16] * r;
+              }
               constexpr int PER = REST / (FN16 + RB);                 // MFMAs per fragment slot
               if (j == (LATE && PER > 1 ? 1 : 0) && i > RB) fa[i - 1] = frag(sn + adA[i - 1], PA);
               if (k % PER == (LATE ? 0 : PER - 1)) {
@@ -468,57 +512,33 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
         // block past the end, whose rows are all out of range and arrive as zeros
         auto walk = [&](auto late_c) {
           if constexpr (WTD) {
-            // segment by segment; where a segment opens the sum so far changes its unit from the previous
-            // segment's coefficient to this one's (ratio 1 for the first).  The multiplication sits between
-            // the inner loops, on every path, so that the accumulators stay where they are.
+            // segment by segment, each an even number of blocks (two at least): the first block and the last
+            // carry the change of unit (ratio 1 before the first segment and after the last)
+            constexpr std::integral_constant<int, 0> c0{};
+            constexpr std::integral_constant<int, 1> c1{};
+            constexpr std::integral_constant<int, 2> c2{};
+            auto ratio_of = [&](int k) {
+              return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seg_ratio[k])));
+            };
             int it = 0;
+            float r_in = 1.f;
             for (int k = 0; k < n_seg; ++k) {
-              const float r = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seg_ratio[k])));
               const int len = __builtin_amdgcn_readfirstlane(seg_end[k]) - __builtin_amdgcn_readfirstlane(seg_tok[k]);
               const int blocks = ((len + BK - 1) / BK + 1) & ~1;
-              if constexpr (NMF16 * 4 > 128) {
-                // by hand, in the accumulation registers: the MFMAs of the block before have retired (the
-                // hazard tracking does not see through the asm on either side)
-                asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-                // eight elements per statement, so that no instruction waits for the one before it
-#pragma unroll
-                for (int i = 0; i < FM16; ++i)
-#pragma unroll
-                  for (int jp = 0; jp < FN16; jp += 2) {
-                    float e0 = acc[i][jp][0], e1 = acc[i][jp][1], e2 = acc[i][jp][2], e3 = acc[i][jp][3];
-                    float e4 = acc[i][jp + 1][0], e5 = acc[i][jp + 1][1], e6 = acc[i][jp + 1][2], e7 = acc[i][jp + 1][3];
-                    float t0, t1, t2, t3, t4, t5, t6, t7;
-                    asm volatile(
-                        "v_accvgpr_read_b32 %8, %0\n\tv_accvgpr_read_b32 %9, %1\n\tv_accvgpr_read_b32 %10, %2\n\t"
-                        "v_accvgpr_read_b32 %11, %3\n\tv_accvgpr_read_b32 %12, %4\n\tv_accvgpr_read_b32 %13, %5\n\t"
-                        "v_accvgpr_read_b32 %14, %6\n\tv_accvgpr_read_b32 %15, %7\n\t"
-                        "v_mul_f32 %8, %16, %8\n\tv_mul_f32 %9, %16, %9\n\tv_mul_f32 %10, %16, %10\n\tv_mul_f32 %11, %16, %11\n\t"
-                        "v_mul_f32 %12, %16, %12\n\tv_mul_f32 %13, %16, %13\n\tv_mul_f32 %14, %16, %14\n\tv_mul_f32 %15, %16, %15\n\t"
-                        "v_accvgpr_write_b32 %0, %8\n\tv_accvgpr_write_b32 %1, %9\n\tv_accvgpr_write_b32 %2, %10\n\t"
-                        "v_accvgpr_write_b32 %3, %11\n\tv_accvgpr_write_b32 %4, %12\n\tv_accvgpr_write_b32 %5, %13\n\t"
-                        "v_accvgpr_write_b32 %6, %14\n\tv_accvgpr_write_b32 %7, %15"
-                        : "+a"(e0), "+a"(e1), "+a"(e2), "+a"(e3), "+a"(e4), "+a"(e5), "+a"(e6), "+a"(e7), "=&v"(t0),
-                          "=&v"(t1), "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7)
-                        : "s"(r));
-                    acc[i][jp][0] = e0; acc[i][jp][1] = e1; acc[i][jp][2] = e2; acc[i][jp][3] = e3;
-                    acc[i][jp + 1][0] = e4; acc[i][jp + 1][1] = e5; acc[i][jp + 1][2] = e6; acc[i][jp + 1][3] = e7;
-                  }
-                asm volatile("s_nop 7" ::: "memory");
-              } else {
-#pragma unroll
-                for (int i = 0; i < FM16; ++i)
-#pragma unroll
-                  for (int j = 0; j < FN16; ++j) acc[i][j] = acc[i][j] * r;
+              const float r_out = k + 1 < n_seg ? ratio_of(k + 1) : 1.f;
+              token_block(it, c0, late_c, c1, r_in);
+              for (int b = 2; b < blocks; b += 2, it += 2) {
+                token_block(it + 1, c1, late_c, c0, 0.f);
+                token_block(it + 2, c0, late_c, c0, 0.f);
               }
-              for (int b = 0; b < blocks; b += 2, it += 2) {
-                token_block(it, std::integral_constant<int, 0>{}, late_c);
-                token_block(it + 1, std::integral_constant<int, 1>{}, late_c);
-              }
+              token_block(it + 1, c1, late_c, c2, r_out);
+              it += 2;
+              r_in = r_out;
             }
           } else {
             for (int it = 0; it < n_tiles; it += 2) {
-              token_block(it, std::integral_constant<int, 0>{}, late_c);
-              token_block(it + 1, std::integral_constant<int, 1>{}, late_c);
+              token_block(it, std::integral_constant<int, 0>{}, late_c, std::integral_constant<int, 0>{}, 0.f);
+              token_block(it + 1, std::integral_constant<int, 1>{}, late_c, std::integral_constant<int, 0>{}, 0.f);
             }
           }
         };
@@ -648,7 +668,7 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
       // straight-line code)
       auto token_block = [&](int it, auto late_c) {
         constexpr bool LATE = decltype(late_c)::value;
-        const unsigned sb = smem_base + (unsigned)(it % NSTAGE) * STAGE;
+        const unsigned sb = smem_base + ((unsigned)it % NSTAGE) * STAGE;
         {
           // written out MFMA by MFMA: one fragment's reads behind each MFMA of this wave's read slots
 #pragma unroll
@@ -670,16 +690,13 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
         // reads of block it are complete: its stage may be overwritten after the barrier
         __builtin_amdgcn_s_waitcnt(0x0f70 | (((AHEAD - 2) * LPT) & 15) | ((((AHEAD - 2) * LPT) >> 4) << 14));
         __builtin_amdgcn_s_barrier();
-        const unsigned sn = smem_base + (unsigned)((it + 1) % NSTAGE) * STAGE;
+        const unsigned sn = smem_base + ((unsigned)(it + 1) % NSTAGE) * STAGE;
         // second half block: its 16 MFMAs carry the fragment reads of the next block's first half and the
         // DMA instructions of the block AHEAD ahead
         {
-          const int nb = it + AHEAD;
-          int tok_nb, rows;
-          next_block(ld, nb, tok_nb, rows);
-          const v4i ra = make_rsrc(p.Delta + (size_t)tok_nb * p.d_out, (unsigned)rows * rbA);
-          const v4i rb = make_rsrc(p.X + (size_t)tok_nb * p.d_in, (unsigned)rows * rbB);
-          const unsigned stage = smem_base + (unsigned)(nb % NSTAGE) * STAGE;
+          v4i ra, rb;
+          next_block(ld, ra, rb);
+          const unsigned stage = smem_base + ((unsigned)(it + AHEAD) % NSTAGE) * STAGE;
 #pragma unroll
           for (int i = 0; i < FM; ++i) {
 #pragma unroll
