@@ -7,7 +7,9 @@
 //    (16 bytes per lane, no VGPR staging, no LDS-write instructions).  The
 //    buffer descriptor covers exactly the rows of the current token block, so
 //    rows past the end of a sequence are out of range and arrive as zeros:
-//    ragged tails cost no branches.
+//    ragged tails cost no branches.  The loads' cursor moves on by additions, and
+//    a block's descriptors are formed one block ahead, between MFMAs: what
+//    stands ahead of a block's first MFMA every wave of the workgroup waits for.
 //  * LDS holds a ring of NSTAGE token blocks ([token][feature], the HBM layout).
 //    NSTAGE-1 blocks are in flight while one is multiplied; one s_barrier per block.
 //  * MFMA fragments need 8 consecutive tokens of one feature per lane; they come
