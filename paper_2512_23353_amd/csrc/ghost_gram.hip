@@ -16,6 +16,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace isopo {
 namespace {
 
@@ -179,8 +181,13 @@ constexpr int kGStageBytes = 2 * kGT * kGRowBytes;
 constexpr int kGRun = 64;                        // workgroups an XCD holds at a time: 32 compute units x 2
 static_assert(kGStages * kGStageBytes * 2 <= 160 * 1024, "two workgroups per compute unit share the LDS");
 
-__device__ __forceinline__ void ghost_load_lds16(const void* gptr, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from a buffer straight into LDS: lane l lands at lds_addr + 16 l.  Offsets at or beyond the
+// descriptor's byte count are out of range: nothing is fetched and zeros arrive.
+__device__ __forceinline__ void ghost_load_lds16(v4i rsrc, unsigned lds_addr, unsigned voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               : : "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
 }
 
 // 16-byte column c of LDS row `row` holds global column c ^ ghost_swizzle(row): sixteen consecutive rows read
@@ -197,57 +204,77 @@ __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restr
                                                    int k_end, f32x16 (&acc)[2][2]) {
   constexpr int COLS = kGRowBytes / 16, ROWS_PER_LOAD = 64 / COLS;      // one wave-load is 1 KiB of whole rows
   constexpr int LPW = 2 * kGT / ROWS_PER_LOAD / 4;                      // wave-loads per wave and stage
+  static_assert(kGStages == 2 && 4 * LPW * ROWS_PER_LOAD == 2 * kGT, "waves 0, 1 stage tile ti's rows, waves 2, 3 tile tj's");
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int wi = wave >> 1, wj = wave & 1;
-  const char* src[LPW];
-  int vec_off[LPW];
+  // The rows this wave stages belong to one tile; a buffer descriptor over that tile's valid rows lets the
+  // loads take a 32-bit offset per lane (one addition per load and stage; 64-bit addresses clamped lane by lane
+  // cost some sixty vector instructions per stage, as much issue time as the stage's MFMAs).  Rows past the
+  // last token are out of range and arrive as zeros; a 16-byte column past the row's end reads into the next
+  // row or out of range (the fragments of such columns are zeroed below).
+  const int row0 = (wave_s < 2 ? ti : tj) * kGT;
+  int rows_valid = n_tokens - row0;
+  rows_valid = rows_valid < 0 ? 0 : (rows_valid > kGT ? kGT : rows_valid);
+  const unsigned long long base = (unsigned long long)(M + (size_t)row0 * d);
+  v4i rsrc;
+  rsrc[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)base);
+  rsrc[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(base >> 32) & 0xffffu));
+  rsrc[2] = __builtin_amdgcn_readfirstlane((int)((unsigned)rows_valid * (unsigned)d * 2u));     // at most 128 rows of 64 Ki features
+  rsrc[3] = 0x00020000;
+  unsigned voff[LPW];
 #pragma unroll
   for (int q = 0; q < LPW; ++q) {
     const int row = (wave * LPW + q) * ROWS_PER_LOAD + lane / COLS;  // 0..255: tile ti's rows, then tile tj's
-    int tok = row < kGT ? ti * kGT + row : tj * kGT + (row - kGT);
-    if (tok >= n_tokens) tok = n_tokens - 1;                        // rows past the end are masked in the epilogue
-    src[q] = reinterpret_cast<const char*>(M + (size_t)tok * d);
-    vec_off[q] = ((lane % COLS) ^ ghost_swizzle(row)) * 16;
+    voff[q] = (unsigned)(row & (kGT - 1)) * (unsigned)d * 2u + (unsigned)k_begin * kGRowBytes +
+              (unsigned)(((lane % COLS) ^ ghost_swizzle(row)) * 16);
   }
-  auto issue = [&](int k) {
+  // the next slice of kGKW features into ring stage `stage` (look-ahead slices past k_end are never read)
+  auto issue = [&](int stage) {
 #pragma unroll
     for (int q = 0; q < LPW; ++q) {
-      long long byte = (long long)k * kGRowBytes + vec_off[q];
-      const long long last = ((long long)d - 8) * 2;
-      if (byte > last) byte = last;                                 // tail and look-ahead: stays inside the row
-      ghost_load_lds16(src[q] + byte, smem_base + (unsigned)((k - k_begin) % kGStages) * kGStageBytes +
-                                          (unsigned)(wave_s * LPW + q) * 1024);
+      ghost_load_lds16(rsrc, smem_base + (unsigned)stage * kGStageBytes + (unsigned)(wave_s * LPW + q) * 1024, voff[q]);
+      voff[q] += kGRowBytes;
     }
   };
-#pragma unroll
-  for (int s = 0; s < kGStages - 1; ++s) issue(k_begin + s);
+  issue(0);
   const int frow = lane & 31, half = lane >> 5;
-  for (int k = k_begin; k < k_end; ++k) {
-    __builtin_amdgcn_s_waitcnt(0x0f70 | (((kGStages - 2) * LPW) & 15) | ((((kGStages - 2) * LPW) >> 4) << 14));
+  // fragment addresses of the first 32-row block in stage 0: the second block (32 rows on, the same swizzle) and
+  // stage 1 are immediate offsets away
+  constexpr int KS = kGKW / 16;
+  static_assert(COLS == 8, "rows 32 apart share their swizzle");
+  unsigned ada[KS], adb[KS];
+#pragma unroll
+  for (int st = 0; st < KS; ++st) {
+    const int vec = st * 2 + half;
+    const int ra = wi * 64 + frow, rb = kGT + wj * 64 + frow;
+    ada[st] = smem_base + (unsigned)ra * kGRowBytes + (unsigned)((vec ^ ghost_swizzle(ra)) * 16);
+    adb[st] = smem_base + (unsigned)rb * kGRowBytes + (unsigned)((vec ^ ghost_swizzle(rb)) * 16);
+  }
+  // TAIL: the last slice of a feature count that is no multiple of kGKW (its own body, so that the full slices
+  // carry no selects)
+  auto stage_body = [&](int k, auto stage_c, auto tail_c) {
+    constexpr int STAGE = decltype(stage_c)::value;
+    constexpr bool TAIL = decltype(tail_c)::value;
+    __builtin_amdgcn_s_waitcnt(0x0f70);      // this wave's part of slice k has landed; the barrier makes it everyone's
     __builtin_amdgcn_s_barrier();
-    issue(k + kGStages - 1);
-    const unsigned sb = smem_base + (unsigned)((k - k_begin) % kGStages) * kGStageBytes;
-    const int valid = d - k * kGKW;
+    issue(STAGE ^ 1);
     // every 16-feature step has its own fragment registers, and the reads of step st + 1 are issued ahead of
     // the MFMAs of step st: with one or two waves per SIMD nothing else hides the LDS latency
-    constexpr int KS = kGKW / 16;
     v4u fa[KS][2], fb[KS][2];
 #pragma unroll
-    for (int st = 0; st < KS; ++st) {
-      const int vec = st * 2 + half;
+    for (int st = 0; st < KS; ++st)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const int ra = wi * 64 + b * 32 + frow, rb = kGT + wj * 64 + b * 32 + frow;
-        fa[st][b] = *(lds_v4u_ptr)(sb + (unsigned)ra * kGRowBytes + (unsigned)((vec ^ ghost_swizzle(ra)) * 16));
-        fb[st][b] = *(lds_v4u_ptr)(sb + (unsigned)rb * kGRowBytes + (unsigned)((vec ^ ghost_swizzle(rb)) * 16));
+        fa[st][b] = *(lds_v4u_ptr)(ada[st] + (unsigned)(STAGE * kGStageBytes + b * 32 * kGRowBytes));
+        fb[st][b] = *(lds_v4u_ptr)(adb[st] + (unsigned)(STAGE * kGStageBytes + b * 32 * kGRowBytes));
       }
-    }
-    if (valid < kGKW) {                          // the last stage of a feature count that is not a multiple of 64
+    if constexpr (TAIL) {
+      const int valid = d - k * kGKW;            // features of this slice that exist
 #pragma unroll
       for (int st = 0; st < KS; ++st)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          if ((st * 2 + half) * 8 >= valid) fa[st][b] = v4u{0u, 0u, 0u, 0u};
+          if ((st * 2 + half) * 8 >= valid) { fa[st][b] = v4u{0u, 0u, 0u, 0u}; fb[st][b] = v4u{0u, 0u, 0u, 0u}; }
     }
 #pragma unroll
     for (int st = 0; st < KS; ++st)
@@ -264,6 +291,21 @@ __device__ __forceinline__ void ghost_product_pass(const unsigned short* __restr
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       if (st + 2 < KS) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
     }
+  };
+  constexpr std::integral_constant<int, 0> s0{};
+  constexpr std::integral_constant<int, 1> s1{};
+  int k_full = d / kGKW;                       // slices [k_begin, k_full) are whole; at most one more follows
+  k_full = k_full < k_begin ? k_begin : (k_full > k_end ? k_end : k_full);
+  int k = k_begin;
+  for (; k + 1 < k_full; k += 2) {
+    stage_body(k, s0, std::false_type{});
+    stage_body(k + 1, s1, std::false_type{});
+  }
+  if (k < k_full) {
+    stage_body(k, s0, std::false_type{});
+    if (k + 1 < k_end) stage_body(k + 1, s1, std::true_type{});
+  } else if (k < k_end) {
+    stage_body(k, s0, std::true_type{});
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);
   __builtin_amdgcn_s_barrier();            // the ring is reused by the next pass
