@@ -469,10 +469,8 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
               }
 #pragma unroll
               for (int q = idx * LPT / HEAD; q < (idx + 1) * LPT / HEAD; ++q) {
-                // builtin MFMAs (plain sum): the scheduler would move every load to the top of the block, ahead
-                // of the MFMAs.  (The weighted sum is faster without the pins: 6.02 against 6.15 ms on config 3's
-                // gate projection.)
-                if constexpr (NMF16 * 4 <= 128 && !WTD) __builtin_amdgcn_sched_barrier(0);
+                // builtin MFMAs: the scheduler would move every load to the top of the block, ahead of the MFMAs
+                if constexpr (NMF16 * 4 <= 128) __builtin_amdgcn_sched_barrier(0);
                 if (q < LA) load_lds16(ra, stage + (unsigned)(wave_s * LA + q) * 1024, offA[q]);
                 else load_lds16(rb, stage + A_BYTES + (unsigned)(wave_s * LB + (q - LA)) * 1024, offB[q - LA]);
               }
@@ -482,10 +480,7 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
           __builtin_amdgcn_s_barrier();
           // the descriptors the next block's loads need: scalar work that issues between this half's MFMAs
           // instead of ahead of the next block's first one
-          if constexpr (PIPE) {
-            next_block(ld, ra_n, rb_n);
-            if constexpr (WTD) segment_step(ld);
-          }
+          if constexpr (PIPE) next_block(ld, ra_n, rb_n);
           // the other rows: behind their MFMAs the fragments of block it + 1, the B ones into the other register
           // set, the A ones in place: those of the first RB rows at once, the others as their rows end
 #pragma unroll
@@ -508,6 +503,10 @@ __device__ __forceinline__ void seq_grad_stream_body(const StreamParams& p) {
               }
             }
           fa[FM16 - 1] = frag(sn + adA[FM16 - 1], PA);
+          // weighted sum: the cursor's branch (taken where a segment ends) closes the block.  Behind the barrier
+          // it would cut the block in two there, with the scalar work of the second part standing between the
+          // barrier and the MFMAs that follow it.
+          if constexpr (WTD) segment_step(ld);
 #undef ISOPO_MFMA16
         };
         // two blocks per trip (the B fragments alternate between two register sets); an odd count runs one
