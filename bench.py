@@ -551,6 +551,22 @@ def main() -> int:
         t_bf = timed(variant_step(bf16_dw=True), reps, 2, "bf16_dw")
         t_bf1 = timed(variant_step(beta=1.0, bf16_dw=True), reps, 2, "bf16_dw_beta1")
         del dWs_bf16
+        # The headline step and the REINFORCE baseline replayed from HIP graphs: what the gaps between the step's
+        # launches cost (the library allocates nothing and clears its counters with kernels, so a caller may
+        # capture it).  One block only: the sweep of config 4 would be a graph of some thousand nodes.
+        t_gs = t_gr = None
+        if len(blocks) == 1 and sweeps == 1:
+            outer = stream
+            g_step, g_reinforce = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_step):
+                stream = torch.cuda.current_stream()       # the closures launch on the capturing stream
+                step()
+            with torch.cuda.graph(g_reinforce):
+                stream = torch.cuda.current_stream()
+                reinforce_step()
+            stream = outer
+            t_gs = timed(g_step.replay, reps, 2, "graph_step")
+            t_gr = timed(g_reinforce.replay, reps, 2, "graph_reinforce")
         for dW in dWs:
             dW.zero_()          # beta = 1 accumulated into them
 
@@ -577,6 +593,11 @@ def main() -> int:
             "fisher_from_token_samples_side_streams": entry(t_ts2, "token_samples_side", ts_flops, n_samples=args.n_samples,
                                                             what="the group calls on streams of their own, side by side, before the contractions on the launch stream"),
         }
+        if t_gs is not None:
+            variants[f"{args.variant}_replayed_from_hip_graph"] = entry(
+                t_gs, "graph_step", total_flops, reinforce_replayed_ms=t_gr * 1e3,
+                overhead_over_replayed_reinforce=t_gs / t_gr - 1.0,
+                what="the headline step and the REINFORCE baseline each captured once in a HIP graph and replayed: the same kernels without the host's launch gaps")
         if n_layers > 1:
             # The sweep with K and the stash formed once per layer: six transforms (both variants x three
             # lambdas) and six stash-weighted sums per projection, against ONE REINFORCE sweep.
